@@ -1,0 +1,359 @@
+"""TEST INFRASTRUCTURE ONLY: exact evaluation of the paper's I/O-bound expressions and of the
+tile-selection rule, in Python integers and rationals.
+
+Every function cites the passage it evaluates.  Quantities that contain a square root are
+returned as floats computed from an exact rational radicand; everything the GPU library's
+tuner is compared with bit-for-bit is an integer.
+
+Notation (paper -> here): W_ker,H_ker -> S,R (kernel width,height); C_in -> C; C_out -> K;
+W_out,H_out -> Q,P; mu -> stride; the paper's reuse number "R" -> rho; the paper's fast-memory
+size "S" -> Sf (elements); e -> e (Winograd output tile edge); r -> r.  A batch of N images
+(absent from the paper's formulas) multiplies the output plane: W_out*H_out -> N*P*Q.
+No code is shared with the GPU library.
+"""
+from fractions import Fraction
+from math import isqrt, sqrt
+
+DIRECT, WINO_F2, WINO_F4 = 0, 1, 2
+PATH_FMA, PATH_MFMA = 0, 1
+
+# ------------------------------------------------------------------------------------------
+# shapes
+# ------------------------------------------------------------------------------------------
+
+def out_extent(H, W, R, S, stride, pad):
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+
+
+def rho(R, S, stride):
+    """Maximum number of sliding windows that reuse one input element (Sec. 4.2, Eq. 'definition of R')."""
+    return Fraction(R * S, stride * stride)
+
+
+# ------------------------------------------------------------------------------------------
+# vertex counts
+# ------------------------------------------------------------------------------------------
+
+def summation_tree(k):
+    """(internal, output) vertices of a summation tree with k inputs (Sec. 4.2, first lemma)."""
+    return (k - 2 if k >= 2 else 0, 1)
+
+
+def linear_combination_tree(k):
+    """(internal, output) vertices of a linear-combination tree with k inputs (Sec. 4.3, first
+    lemma): k products plus the k-2 internal sums of a summation tree."""
+    return (k + summation_tree(k)[0], 1)
+
+
+def V_DC(N, C, P, Q, K, R, S):
+    """Internal + output vertices of the direct-convolution DAG (Sec. 4.2, second lemma)."""
+    return (2 * R * S * C - 1) * P * Q * K * N
+
+
+def V_WA_steps(C, e, r=3):
+    """Per (tile, output channel) vertex counts of the four Winograd steps, as the proof of the
+    vertex-count lemma of Sec. 4.3 lists them.  Returns a dict of integers."""
+    n = e + r - 1
+    return {
+        "input_transform": (2 * n * n - 1) * n * n * C,
+        "kernel_transform": (2 * r * r - 1) * n * n * C,
+        "products": n * n * C,
+        "channel_sums": (C - 1) * n * n,
+        "output_transform": (2 * n * n - 1) * e * e,
+    }
+
+
+def V_WA_lead(N, C, P, Q, K, e, r=3):
+    """Leading term of the Winograd vertex count, 2 W_out H_out C_out C_in (e+r-1)^4 / e^2."""
+    n = e + r - 1
+    return Fraction(2 * N * P * Q * K * C * n ** 4, e * e)
+
+
+# ------------------------------------------------------------------------------------------
+# T(S) bounds and lower bounds
+# ------------------------------------------------------------------------------------------
+
+def _sqrt_fraction(fr):
+    fr = Fraction(fr)
+    num, den = fr.numerator, fr.denominator
+    rn, rd = isqrt(num), isqrt(den)
+    if rn * rn == num and rd * rd == den:
+        return Fraction(rn, rd)          # exact when the radicand is a perfect square
+    return sqrt(num / den)
+
+
+def T_DC(Sf, rho_):
+    """Upper bound on a partition subset, T(S) <= 4 S sqrt(rho S) + S - 1 (Sec. 4.2, third lemma)."""
+    return 4 * Sf * _sqrt_fraction(rho_ * Sf) + Sf - 1
+
+
+def general_lower_bound(V, T_2S, Sf):
+    """Q >= S (|V| / T(2S) - 1)  (Sec. 4.1, theorem 'general I/O lower bound')."""
+    return Sf * (V / T_2S - 1)
+
+
+def Qlow_DC_explicit(N, C, P, Q, K, R, S, stride, Sf):
+    """The general bound with the direct-convolution vertex count and T bound substituted:
+    V / (8 sqrt(2 rho S) + 2 - 1/S) - S.   (The proof of the direct-convolution theorem prints
+    the trailing term as 1/S; carrying out the substitution gives S.)"""
+    root = _sqrt_fraction(2 * rho(R, S, stride) * Sf)
+    return V_DC(N, C, P, Q, K, R, S) / (8 * root + 2 - Fraction(1, Sf)) - Sf
+
+
+def Qlow_DC_lead(N, C, P, Q, K, R, S, stride, Sf):
+    """Leading term W_ker H_ker C_in W_out H_out C_out / (4 sqrt(2 rho S))  (Sec. 4.2 theorem)."""
+    return (R * S * C * P * Q * K * N) / (4 * _sqrt_fraction(2 * rho(R, S, stride) * Sf))
+
+
+def T_WA(Sf, e, r=3):
+    """T(S) = 2 (e+r-1)^3/(e r) S sqrt(S) + 6 (e+r-1)^2/(e r) S  (Sec. 4.3, T lemma)."""
+    n = e + r - 1
+    return Fraction(2 * n ** 3, e * r) * Sf * _sqrt_fraction(Sf) + Fraction(6 * n * n, e * r) * Sf
+
+
+def Qlow_WA_lead(N, C, P, Q, K, e, Sf, r=3):
+    """W_out H_out C_out C_in (e+r-1) r / (e sqrt(S))  (Sec. 4.3 theorem, as printed)."""
+    n = e + r - 1
+    return Fraction(N * P * Q * K * C * n * r, e) / _sqrt_fraction(Sf)
+
+
+# ------------------------------------------------------------------------------------------
+# dataflow I/O volumes (Sec. 5)
+# ------------------------------------------------------------------------------------------
+
+def Qread_DC_paper(C, P, Q, K, R, S, stride, x, y, z):
+    """(H_out W_out C_out / xyz) * H_ker W_ker C_in (z + xy/rho)   (Sec. 5.2, first display)."""
+    return Fraction(P * Q * K, x * y * z) * R * S * C * (z + Fraction(x * y) / rho(R, S, stride))
+
+
+def Qread_DC_min(C, P, Q, K, R, S, stride, xyz):
+    """Its lower envelope 2 H W C_out H_ker W_ker C_in sqrt(1/(rho xyz)), reached iff xy = rho z."""
+    return 2 * P * Q * K * R * S * C * _sqrt_fraction(1 / (rho(R, S, stride) * xyz))
+
+
+def Qread_WA_paper(C, P, Q, K, x, y, z, r=3):
+    """(H_out W_out C_out / xyz) * (xy C_in + z r^2 C_in)   (Sec. 5.3, first display)."""
+    return Fraction(P * Q * K, x * y * z) * (x * y * C + z * r * r * C)
+
+
+def Qread_WA_min(C, P, Q, K, xyz, r=3):
+    """Its lower envelope 2 r H W C_out C_in / sqrt(xyz), reached iff xy = r^2 z."""
+    return 2 * r * P * Q * K * C / _sqrt_fraction(xyz)
+
+
+def Q_DC_total(C, P, Q, K, R, S, stride, Sf, Np=1):
+    """2 H W C_out H_ker W_ker C_in / sqrt(rho S / N_p) + H W C_out   (Sec. 5.2, Eq. 'Q of actual DC')."""
+    return 2 * P * Q * K * R * S * C / _sqrt_fraction(rho(R, S, stride) * Fraction(Sf, Np)) + P * Q * K
+
+
+def Q_WA_total(C, P, Q, K, e, Sf, Np=1, r=3):
+    """2 H W C_out C_in r (e+r-1) / (e sqrt(S/N_p)) + H W C_out   (Sec. 5.3, last display)."""
+    n = e + r - 1
+    return Fraction(2 * P * Q * K * C * r * n, e) / _sqrt_fraction(Fraction(Sf, Np)) + P * Q * K
+
+
+def compulsory(N, C, H, W, K, R, S, P, Q):
+    """Every input and weight loaded once, every output stored once (Sec. 3.1)."""
+    return N * C * H * W + K * C * R * S + N * K * P * Q
+
+
+def bounds(shape, Sf):
+    """The figures the library's iolb_bounds reports, for comparison.  shape is a dict with
+    N,C,H,W,K,R,S,stride,pad,algo."""
+    s = shape
+    P, Q = out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
+    out = {"P": P, "Q": Q,
+           "compulsory_elems": compulsory(s["N"], s["C"], s["H"], s["W"], s["K"], s["R"], s["S"], P, Q),
+           "q_write_elems": s["N"] * s["K"] * P * Q}
+    if s["algo"] == DIRECT:
+        r_ = rho(s["R"], s["S"], s["stride"])
+        out["vertices"] = V_DC(s["N"], s["C"], P, Q, s["K"], s["R"], s["S"])
+        out["t_bound_2s"] = float(T_DC(2 * Sf, r_))
+        out["q_lower_lead"] = float(Qlow_DC_lead(s["N"], s["C"], P, Q, s["K"], s["R"], s["S"], s["stride"], Sf))
+        out["q_lower_explicit"] = float(Qlow_DC_explicit(s["N"], s["C"], P, Q, s["K"], s["R"], s["S"], s["stride"], Sf))
+        out["q_dataflow"] = float(Q_DC_total(s["C"], s["N"] * P, Q, s["K"], s["R"], s["S"], s["stride"], Sf))
+    else:
+        e = 2 if s["algo"] == WINO_F2 else 4
+        steps = V_WA_steps(s["C"], e)
+        tiles = s["N"] * (-(-P // e)) * (-(-Q // e))
+        out["vertices"] = tiles * s["K"] * sum(steps.values())
+        out["t_bound_2s"] = float(T_WA(2 * Sf, e))
+        out["q_lower_lead"] = float(Qlow_WA_lead(s["N"], s["C"], P, Q, s["K"], e, Sf))
+        out["q_lower_explicit"] = float(general_lower_bound(V_WA_lead(s["N"], s["C"], P, Q, s["K"], e),
+                                                            T_WA(2 * Sf, e), Sf))
+        out["q_dataflow"] = float(Q_WA_total(s["C"], s["N"] * P, Q, s["K"], e, Sf))
+    return out
+
+
+# ------------------------------------------------------------------------------------------
+# tile selection (the analytical tuner)
+# ------------------------------------------------------------------------------------------
+#
+# The searching domain is Table 1 of Sec. 6.2 read for a wave64 machine whose partial sums live
+# in registers and whose staging buffers live in LDS:
+#   * tile extents are factors of the output extents (b | N, x | W_out, y | H_out, z | C_out);
+#   * the resident output block must fit the accumulator registers of the workgroup,
+#     b x y z <= T * vgpr_budget                                   ("xyz <= S_b");
+#   * the optimality condition xy = rho z bounds the box:  z <= sqrt(S_b/rho), xy <= sqrt(S_b rho),
+#     with S_b the largest workgroup's accumulator capacity, 1024 * vgpr_budget;
+#   * the per-stage input tile x' * y' * alpha and the weight slab R S alpha z, double buffered,
+#     must fit lds_bytes (the LDS share of one workgroup, S_sm / 2 by default).
+# Among feasible tiles the rule minimises the read volume of the dataflow of Sec. 5.2 evaluated
+# exactly (true halo x' = stride (x-1) + S instead of x' ~ stride x), after making sure the grid
+# keeps the 256 compute units busy.
+
+N_CU = 256
+T_MAX = 1024
+T_CHOICES = (64, 128, 256, 512, 1024)
+EFF_CAP = 80
+
+
+def divisors(n):
+    return [d for d in range(1, n + 1) if n % d == 0]
+
+
+def _grid_efficiency_pct(nblocks):
+    rounds = -(-nblocks // N_CU)
+    return min((100 * nblocks) // (rounds * N_CU), EFF_CAP)
+
+
+def _pick_alpha(C, choices, per_alpha_bytes, lds_bytes):
+    """Channels per stage: least channel padding first, then the deepest stage that fits."""
+    best = None
+    for a in choices:
+        if per_alpha_bytes * a > lds_bytes:
+            continue
+        padded = -(-C // a) * a
+        key = (padded, -a)
+        if best is None or key < best[0]:
+            best = (key, a)
+    return None if best is None else best[1]
+
+
+def _wave_grids(MB, NB, vgpr_budget):
+    """All (waves_m, waves_n) that split MB x NB blocks of 32 x 32 outputs over whole waves."""
+    out = []
+    for wm in divisors(MB):
+        for wn in divisors(NB):
+            mbw, nbw = MB // wm, NB // wn
+            T = 64 * wm * wn
+            if mbw not in (1, 2) or mbw * nbw > 8 or T not in T_CHOICES:
+                continue
+            if 16 * mbw * nbw > vgpr_budget:
+                continue
+            out.append((T, mbw + nbw, wm, wn, 16 * mbw * nbw))
+    return out
+
+
+def _pow2ceil(v):
+    p = 1
+    while p < v:
+        p *= 2
+    return p
+
+
+def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
+    N, C, K, R, S, st = s["N"], s["C"], s["K"], s["R"], s["S"], s["stride"]
+    sb_max = T_MAX * vgpr_budget
+    cands = []
+    for b in divisors(N):
+        for x in divisors(Q):
+            for y in divisors(P):
+                npix = b * x * y
+                xp, yp = (x - 1) * st + S, (y - 1) * st + R
+                halo = b * xp * yp
+                for z in divisors(K):
+                    if use_f3 and not (z * z * R * S <= sb_max * st * st and
+                                       npix * npix * st * st <= sb_max * R * S):
+                        continue
+                    if path == PATH_MFMA:
+                        if npix % 32 or z % 32:
+                            continue
+                        grids = _wave_grids(z // 32, npix // 32, vgpr_budget)
+                        alpha = _pick_alpha(C, (16, 8, 4, 2), 8 * (halo + R * S * z), lds_bytes)
+                        lds_mult = 8
+                    else:
+                        if npix > 256:
+                            continue
+                        PL = max(_pow2ceil(npix), 16)
+                        grids = []
+                        for T in (64, 128, 256):
+                            if PL > T:
+                                continue
+                            KG = T // PL
+                            if z % KG or z // KG > 16 or z // KG > vgpr_budget:
+                                continue
+                            grids.append((T, 0, KG, 1, z // KG))
+                        alpha = _pick_alpha(C, (16, 8, 4, 2, 1), 4 * (halo + R * S * z), lds_bytes)
+                        lds_mult = 4
+                    if alpha is None or not grids:
+                        continue
+                    nblocks = (N // b) * (Q // x) * (P // y) * (K // z)
+                    qread = nblocks * C * (halo + R * S * z)
+                    T, _, wm, wn, acc = min(grids)
+                    key = (-_grid_efficiency_pct(nblocks), qread, abs(npix * st * st - R * S * z),
+                           -npix * z, -x, z, b, y, T)
+                    cands.append((key, dict(b=b, x=x, y=y, z=z, alpha=alpha, threads=T, waves_m=wm,
+                                            waves_n=wn, path=path, wt_mode=0,
+                                            lds_bytes_used=lds_mult * alpha * (halo + R * S * z),
+                                            acc_regs_per_thread=acc, q_read_elems=qread,
+                                            q_write_elems=N * K * P * Q)))
+    return cands
+
+
+def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
+    """Winograd: the resident block is one transformed plane of `tb` sub-domains by z output
+    channels (the channel-summation temporaries of step 3); per channel it reads tb transformed
+    inputs and z transformed weights, for each of the (e+r-1)^2 planes.  Reported as a strip of
+    tb sub-domains: b = 1, x = e * tb, y = e."""
+    N, C, K = s["N"], s["C"], s["K"]
+    n2 = (e + 2) * (e + 2)
+    tiles = N * (-(-P // e)) * (-(-Q // e))
+    sb_max = T_MAX * vgpr_budget
+    cands = []
+    tb_top = -(-tiles // 32) * 32
+    for tb in range(32, min(tb_top, 1024) + 1, 32):
+        for z in divisors(K):
+            if z % 32:
+                continue
+            if use_f3 and not (z * z <= sb_max and tb * tb <= sb_max):
+                continue
+            grids = _wave_grids(z // 32, tb // 32, vgpr_budget)
+            alpha = _pick_alpha(C, (16, 8, 4, 2), 8 * (tb + z), lds_bytes)
+            if alpha is None or not grids:
+                continue
+            nblocks = n2 * (-(-tiles // tb)) * (K // z)
+            qread = nblocks * C * (tb + z)
+            T, _, wm, wn, acc = min(grids)
+            key = (-_grid_efficiency_pct(nblocks), qread, abs(tb - z), -tb * z, z, T)
+            cands.append((key, dict(b=1, x=e * tb, y=e, z=z, alpha=alpha, threads=T, waves_m=wm,
+                                    waves_n=wn, path=PATH_MFMA, wt_mode=1,
+                                    lds_bytes_used=8 * alpha * (tb + z), acc_regs_per_thread=acc,
+                                    q_read_elems=qread, q_write_elems=N * K * P * Q)))
+    return cands
+
+
+def candidates(shape, lds_bytes=81920, vgpr_budget=128, use_f3=True):
+    """Every feasible tile with its ordering key (smaller is better); the MFMA path is preferred
+    whenever it has a feasible tile.  Also what the exhaustive sweep enumerates (use_f3=False)."""
+    s = shape
+    P, Q = out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
+    if P < 1 or Q < 1:
+        return []
+    if s["algo"] == DIRECT:
+        c = _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_MFMA, use_f3)
+        if not c:
+            c = _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
+        return c
+    e = 2 if s["algo"] == WINO_F2 else 4
+    return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3)
+
+
+def tune(shape, lds_bytes=81920, vgpr_budget=128):
+    """The tile the library's iolb_tune must return, or None when nothing fits."""
+    c = candidates(shape, lds_bytes, vgpr_budget, True)
+    if not c:
+        c = candidates(shape, lds_bytes, vgpr_budget, False)   # tiny layers: drop the box
+    if not c:
+        return None
+    return min(c, key=lambda kv: kv[0])[1]

@@ -1,0 +1,212 @@
+"""Pins for the bound/tuner oracle (oracle/iolb_oracle.py): hand-countable shapes, closed forms
+and equality cases the paper states, and an independently written feasibility/optimality check
+of the tile rule.  CPU only."""
+from fractions import Fraction
+from math import isclose, sqrt
+
+import pytest
+
+from oracle import iolb_oracle as o
+
+
+def shape(N, C, H, W, K, R=3, S=3, stride=1, pad=1, algo=o.DIRECT):
+    return dict(N=N, C=C, H=H, W=W, K=K, R=R, S=S, stride=stride, pad=pad, algo=algo)
+
+
+def test_tree_vertex_counts():
+    assert o.summation_tree(2) == (0, 1)             # Sec. 4.2: k inputs -> k-2 internal, 1 output
+    assert o.summation_tree(9) == (7, 1)
+    assert o.linear_combination_tree(4) == (6, 1)    # Sec. 4.3: 2k-2 internal, 1 output
+    assert o.linear_combination_tree(16) == (30, 1)
+
+
+def test_direct_vertex_count_hand_cases():
+    assert o.V_DC(1, 1, 5, 7, 3, 1, 1) == 5 * 7 * 3              # 1x1x1 kernel: the outputs only... (2*1-1)
+    assert o.V_DC(1, 1, 2, 2, 1, 2, 2) == 7 * 4                  # 4 products + 2 sums + 1 output each
+    # count the DAG of a tiny layer vertex by vertex
+    R, S, C, P, Q, K = 3, 2, 2, 2, 3, 2
+    per_output = R * S * C + sum(o.summation_tree(R * S * C))
+    assert o.V_DC(1, C, P, Q, K, R, S) == per_output * P * Q * K
+
+
+def test_rho():
+    assert o.rho(3, 3, 1) == 9
+    assert o.rho(11, 11, 4) == Fraction(121, 16)
+    assert o.rho(1, 1, 2) == Fraction(1, 4)
+
+
+def test_direct_bound_worked_example():
+    # rho = 9, S = 2, C = 2, 4x4 outputs, 2 kernels: every quantity is rational (2 rho S = 36)
+    N, C, P, Q, K, R, S, st, Sf = 1, 2, 4, 4, 2, 3, 3, 1, 2
+    V = o.V_DC(N, C, P, Q, K, R, S)
+    assert V == 35 * 32 == 1120
+    T4 = o.T_DC(2 * Sf, o.rho(R, S, st))
+    assert T4 == 4 * 4 * 6 + 4 - 1 == 99
+    general = o.general_lower_bound(V, T4, Sf)
+    explicit = o.Qlow_DC_explicit(N, C, P, Q, K, R, S, st, Sf)
+    assert general == explicit == Fraction(1120 * 2, 99) - 2          # both routes agree exactly
+    assert isclose(float(general), 20.6262626, rel_tol=1e-8)
+    lead = o.Qlow_DC_lead(N, C, P, Q, K, R, S, st, Sf)
+    assert lead == Fraction(9 * 2 * 16 * 2, 4 * 6)
+
+
+def test_direct_bound_general_equals_explicit_on_a_grid():
+    for j in (1, 2, 3, 5):
+        Sf = 2 * j * j                     # makes 2 rho S a perfect square for rho = 9
+        for C in (1, 3, 8):
+            V = o.V_DC(2, C, 6, 5, 4, 3, 3)
+            g = o.general_lower_bound(V, o.T_DC(2 * Sf, Fraction(9)), Sf)
+            assert g == o.Qlow_DC_explicit(2, C, 6, 5, 4, 3, 3, 1, Sf)
+
+
+def test_dataflow_equality_cases():
+    # direct: xy = rho z  (Sec. 5.2).  x = y = 12, z = 16, rho = 9:  z + xy/rho = 32 = 2 sqrt(xyz/rho)
+    C, P, Q, K = 8, 24, 24, 32
+    q = o.Qread_DC_paper(C, P, Q, K, 3, 3, 1, 12, 12, 16)
+    assert q == o.Qread_DC_min(C, P, Q, K, 3, 3, 1, 12 * 12 * 16)
+    assert q == Fraction(P * Q * K, 2304) * 9 * C * 32
+    for x, y, z in ((12, 12, 8), (24, 12, 8), (6, 12, 32), (12, 6, 32), (12, 12, 32)):
+        if x * y != 9 * z:
+            assert o.Qread_DC_paper(C, P, Q, K, 3, 3, 1, x, y, z) > \
+                   float(o.Qread_DC_min(C, P, Q, K, 3, 3, 1, x * y * z)) * (1 + 1e-12)
+    # Winograd: xy = r^2 z (Sec. 5.3): (xy + 9z)/(xyz) = 1/8 = 2*3/sqrt(2304)
+    qw = o.Qread_WA_paper(C, P, Q, K, 12, 12, 16)
+    assert qw == o.Qread_WA_min(C, P, Q, K, 2304) == Fraction(P * Q * K * C, 8)
+
+
+def test_dataflow_to_bound_ratios():
+    # leading term of the dataflow volume over the printed bound at equal fast memory
+    C, P, Q, K, Sf = 64, 56, 56, 64, 2 * 64 * 64
+    lead_df = float(o.Q_DC_total(C, P, Q, K, 3, 3, 1, Sf)) - P * Q * K
+    assert isclose(lead_df / float(o.Qlow_DC_lead(1, C, P, Q, K, 3, 3, 1, Sf)), 8 * sqrt(2), rel_tol=1e-12)
+    for e in (2, 4):
+        lead_w = float(o.Q_WA_total(C, P, Q, K, e, 4096)) - P * Q * K
+        assert isclose(lead_w / float(o.Qlow_WA_lead(1, C, P, Q, K, e, 4096)), 2.0, rel_tol=1e-12)
+
+
+def test_winograd_T_and_vertex_counts():
+    assert o.T_WA(16, 2) == Fraction(2 * 64, 6) * 16 * 4 + Fraction(6 * 16, 6) * 16
+    steps = o.V_WA_steps(C=10, e=2)
+    n = 4
+    assert steps["input_transform"] == 16 * sum(o.linear_combination_tree(16)) * 10
+    assert steps["kernel_transform"] == 16 * sum(o.linear_combination_tree(9)) * 10
+    assert steps["products"] == 160 and steps["channel_sums"] == 16 * sum(o.summation_tree(10))
+    assert steps["output_transform"] == 4 * sum(o.linear_combination_tree(16))
+    # the input transform carries the leading term 2 (e+r-1)^4 C per (tile, kernel)
+    big = o.V_WA_steps(C=10 ** 6, e=4)
+    lead = Fraction(2 * 6 ** 4 * 10 ** 6)
+    assert 1 < Fraction(sum(big.values())) / lead < Fraction(3, 2)
+    assert o.V_WA_lead(1, 3, 8, 8, 2, 4) == Fraction(2 * 64 * 2 * 3 * 6 ** 4, 16)
+
+
+def test_winograd_bound_leading_term():
+    v = o.Qlow_WA_lead(1, 64, 28, 28, 64, 2, 4096)
+    assert v == Fraction(28 * 28 * 64 * 64 * 4 * 3, 2 * 64)
+
+
+def test_compulsory():
+    assert o.compulsory(2, 3, 5, 7, 4, 3, 3, 5, 7) == 2 * 3 * 35 + 4 * 3 * 9 + 2 * 4 * 35
+
+
+# ---------------------------------------------------------------------------------------------
+# tile rule
+# ---------------------------------------------------------------------------------------------
+
+def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
+    """Constraints re-stated from the documentation of the rule, written independently."""
+    P, Q = o.out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
+    b, x, y, z, a, T = (cfg[k] for k in ("b", "x", "y", "z", "alpha", "threads"))
+    assert s["K"] % z == 0 and T in (64, 128, 256, 512, 1024)
+    assert cfg["lds_bytes_used"] <= lds_bytes and cfg["acc_regs_per_thread"] <= vgpr_budget
+    if s["algo"] == o.DIRECT:
+        assert s["N"] % b == 0 and Q % x == 0 and P % y == 0
+        halo = b * ((x - 1) * s["stride"] + s["S"]) * ((y - 1) * s["stride"] + s["R"])
+        per_stage = halo + s["R"] * s["S"] * z
+        blocks = (s["N"] // b) * (Q // x) * (P // y) * (s["K"] // z)
+        assert cfg["q_read_elems"] == blocks * s["C"] * per_stage
+        if cfg["path"] == o.PATH_MFMA:
+            assert (b * x * y) % 32 == 0 and z % 32 == 0 and a % 2 == 0
+            assert cfg["lds_bytes_used"] == 2 * 4 * a * per_stage
+            assert b * x * y * z == cfg["acc_regs_per_thread"] * T        # accumulators fill the lanes
+            assert T == 64 * cfg["waves_m"] * cfg["waves_n"]
+        else:
+            assert b * x * y <= 256 and cfg["lds_bytes_used"] == 4 * a * per_stage
+    else:
+        e = 2 if s["algo"] == o.WINO_F2 else 4
+        assert b == 1 and y == e and x % (32 * e) == 0 and z % 32 == 0
+        tb = x // e
+        assert tb * z == cfg["acc_regs_per_thread"] * T
+        assert cfg["lds_bytes_used"] == 8 * a * (tb + z)
+    assert cfg["q_write_elems"] == s["N"] * s["K"] * P * Q
+
+
+SHAPES = [shape(1, 16, 14, 14, 16), shape(8, 64, 28, 28, 64, algo=o.WINO_F2), shape(32, 64, 56, 56, 64),
+          shape(64, 256, 14, 14, 256, algo=o.WINO_F4), shape(64, 3, 224, 224, 64),
+          shape(64, 128, 112, 112, 128), shape(64, 512, 28, 28, 512), shape(16, 96, 27, 27, 256, 5, 5, 1, 2),
+          shape(16, 3, 227, 227, 96, 11, 11, 4, 0), shape(4, 32, 32, 32, 64, algo=o.WINO_F4),
+          shape(2, 8, 16, 16, 32, 1, 1, 1, 0), shape(3, 5, 9, 7, 6)]
+
+
+@pytest.mark.parametrize("s", SHAPES)
+@pytest.mark.parametrize("lds,vg", [(81920, 128), (32768, 64), (163840, 128)])
+def test_tile_rule_returns_a_feasible_tile(s, lds, vg):
+    cfg = o.tune(s, lds, vg)
+    if cfg is None:
+        assert not o.candidates(s, lds, vg, False)
+        return
+    _check_feasible(s, cfg, lds, vg)
+
+
+@pytest.mark.parametrize("s", SHAPES[:8])
+def test_tile_rule_minimises_read_volume_within_its_grid_class(s):
+    """Among candidates that keep the chip equally busy, none reads less than the pick."""
+    cfg = o.tune(s)
+    cands = o.candidates(s, use_f3=True) or o.candidates(s, use_f3=False)
+    best_eff = min(k[0] for k, _ in cands)
+    same = [c for k, c in cands if k[0] == best_eff]
+    assert cfg["q_read_elems"] == min(c["q_read_elems"] for c in same)
+
+
+def test_optimality_box_prunes_but_keeps_the_pick():
+    s = shape(64, 256, 56, 56, 256)
+    inside = o.candidates(s, use_f3=True)
+    everything = o.candidates(s, use_f3=False)
+    assert 0 < len(inside) < len(everything)
+    sb = o.T_MAX * 128
+    for _, c in inside:
+        assert c["z"] ** 2 * 9 <= sb and (c["b"] * c["x"] * c["y"]) ** 2 <= sb * 9      # z<=sqrt(Sb/rho), xy<=sqrt(Sb rho)
+
+
+def test_continuous_optimum_is_on_the_optimality_curve():
+    """With the paper's approximate halo (x' ~ x) the read volume over tiles of equal volume is
+    smallest where xy = rho z: check on S_b = 2304, rho = 9 that (xy, z) = (144, 16) wins."""
+    C, P, Q, K = 4, 24, 24, 32
+    best = None
+    for x in o.divisors(Q):
+        for y in o.divisors(P):
+            for z in o.divisors(K):
+                if x * y * z == 2304:
+                    v = o.Qread_DC_paper(C, P, Q, K, 3, 3, 1, x, y, z)
+                    if best is None or v < best[0]:
+                        best = (v, {(x * y, z)})
+                    elif v == best[0]:
+                        best[1].add((x * y, z))
+    assert best[1] == {(144, 16)}
+
+
+def test_more_lds_never_reads_more():
+    s = shape(64, 256, 56, 56, 256)
+    reads = [o.tune(s, lds, 128)["q_read_elems"] for lds in (24576, 40960, 81920, 163840)]
+    assert reads == sorted(reads, reverse=True)
+
+
+def test_no_tile_when_nothing_fits():
+    assert o.tune(shape(1, 16, 14, 14, 16), lds_bytes=16, vgpr_budget=128) is None
+
+
+def test_bounds_report():
+    s = shape(32, 64, 56, 56, 64)
+    r = o.bounds(s, 20480)
+    assert r["compulsory_elems"] == 32 * 64 * 3136 + 64 * 64 * 9 + 32 * 64 * 3136
+    assert r["vertices"] == (2 * 9 * 64 - 1) * 56 * 56 * 64 * 32
+    assert isclose(r["q_lower_lead"], 9 * 64 * 3136 * 64 * 32 / (4 * sqrt(2 * 9 * 20480)), rel_tol=1e-12)
