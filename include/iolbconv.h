@@ -1,0 +1,143 @@
+/*
+ * iolbconv -- forward 2-D convolution for AMD MI355X (gfx950), tiled by the red-blue-pebble
+ * I/O lower bound of "I/O Lower Bounds for Auto-tuning of Convolutions in CNNs".
+ *
+ * C ABI.  Every tensor pointer is a DEVICE pointer to dense fp32 data owned by the caller; the
+ * library never frees or keeps them.  All entry points return 0 on success or a negative
+ * IOLB_E* code; no exception crosses this boundary and nothing aborts.  Arguments are checked
+ * before anything is launched, so a call that fails validation writes nothing.
+ *
+ * Work is enqueued on the stream given to iolb_set_stream (the null stream by default) and
+ * the calls return without waiting for it.  One stream per host thread; calls that use the
+ * library's workspace and overlap on one GPU race.
+ *
+ * Symbols (paper -> here): W_in,H_in,C_in -> W,H,C;  C_out -> K;  W_ker,H_ker -> S,R;
+ * W_out,H_out -> Q,P;  mu -> stride;  e -> m.  A batch of N images shares the K kernels.
+ */
+#ifndef IOLBCONV_H
+#define IOLBCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IOLB_OK            0
+#define IOLB_EINVAL       -1   /* null pointer, non-positive extent, stride < 1, pad < 0, empty output */
+#define IOLB_EUNSUPPORTED -2   /* Winograd m outside {2,4}; algo outside the enum */
+#define IOLB_ENOTILE      -3   /* no tile fits the LDS / register budgets */
+#define IOLB_EWORKSPACE   -4   /* workspace missing or too small */
+#define IOLB_EHIP         -5   /* a HIP runtime call or launch failed; see iolb_last_hip_error */
+
+enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2 };
+enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1 };
+
+/* A convolution layer (Sec. 2.2).  Output extents are P = floor((H+2 pad-R)/stride)+1 and
+ * Q = floor((W+2 pad-S)/stride)+1.  For the Winograd algos R = S = 3 and stride = 1. */
+typedef struct iolb_shape {
+    int32_t N, C, H, W, K, R, S, stride, pad;
+    int32_t algo;               /* IOLB_DIRECT, IOLB_WINO_F2 or IOLB_WINO_F4 */
+} iolb_shape;
+
+/* A tile configuration: the output sub-block x * y * z of Sec. 5.2 (x along W_out, y along
+ * H_out, z along C_out) taken over b images, the channels per stage alpha, and the thread
+ * decomposition (Table 1 of Sec. 6.2: tile sizes and thread numbers).
+ * For the Winograd algos the block is a strip of x/m sub-domains of m x m outputs (b = 1,
+ * y = m) of one transformed plane.  All fields are exact integers. */
+typedef struct iolb_tile_config {
+    int32_t b, x, y, z;
+    int32_t alpha;               /* input channels staged per step of the channel loop */
+    int32_t threads;             /* workgroup size */
+    int32_t waves_m, waves_n;    /* MFMA path: wave grid over (z, pixels); FMA path: channel groups, 1 */
+    int32_t path;                /* IOLB_PATH_FMA or IOLB_PATH_MFMA */
+    int32_t wt_mode;             /* 0: raw R*S weights staged; 1: pre-transformed (m+2)^2 weights */
+    int32_t lds_bytes_used;      /* staging bytes the tile needs */
+    int32_t acc_regs_per_thread; /* partial sums held per lane */
+    int64_t q_read_elems;        /* modelled elements read by all workgroups (exact form of the
+                                    reading volume of Sec. 5.2 / 5.3 for this tile) */
+    int64_t q_write_elems;       /* N*K*P*Q: every output written once */
+} iolb_tile_config;
+
+/* Figures of the lower-bound theory for one layer at fast-memory size S_f (in elements). */
+typedef struct iolb_bounds_out {
+    int32_t P, Q;
+    int64_t vertices;            /* internal+output vertices of the DAG: Sec. 4.2 second lemma
+                                    (direct); per-step counts of the Sec. 4.3 lemma (Winograd) */
+    int64_t compulsory_elems;    /* N*C*H*W + K*C*R*S + N*K*P*Q (Sec. 3.1: each input loaded and
+                                    each output stored at least once) */
+    int64_t q_write_elems;
+    double  t_bound_2s;          /* T(2 S_f): Sec. 4.2 third lemma / Sec. 4.3 T lemma */
+    double  q_lower_lead;        /* leading term printed in the theorems of Sec. 4.2 / 4.3 */
+    double  q_lower_explicit;    /* S_f (|V|/T(2 S_f) - 1), the general theorem of Sec. 4.1 */
+    double  q_dataflow;          /* total volume of the near-optimal dataflow, Sec. 5.2 / 5.3, N_p = 1 */
+} iolb_bounds_out;
+
+/* Direct convolution (Sec. 2.2, dataflow of Sec. 5.2).
+ *   y[n,k,p,q] = sum_{c,r,s} xpad[n,c,p*stride+r-pad,q*stride+s-pad] * w[k,c,r,s]
+ * x: [N][C][H][W], w: [K][C][R][S], y: [N][K][P][Q]; cross-correlation, zero padding.
+ * y is fully overwritten; x and y must not overlap.  The tile comes from iolb_tune with the
+ * default budgets.  May grow the library's device workspace (one allocation, kept). */
+int conv_direct(const float* x, const float* w, float* y,
+                int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+
+/* Same, with the tile given by the caller (for sweeps).  cfg must be one that iolb_tune or
+ * iolb_enumerate produced for this shape; IOLB_EINVAL otherwise. */
+int conv_direct_cfg(const float* x, const float* w, float* y,
+                    int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                    const iolb_tile_config* cfg);
+
+/* Winograd F(m x m, 3 x 3) convolution (Sec. 2.3; four steps of Sec. 4.3), R = S = 3,
+ * stride 1, pad 1 (P = H, Q = W), m in {2, 4}.  Same layouts as conv_direct.  The transformed
+ * kernels, inputs and products live in the library's device workspace, grown on demand. */
+int conv_winograd(const float* x, const float* w, float* y,
+                  int N, int C, int H, int W, int K, int m);
+
+/* Bytes of workspace conv_winograd_ws needs for this layer (0 on invalid arguments). */
+size_t conv_winograd_workspace_bytes(int N, int C, int H, int W, int K, int m);
+
+/* conv_winograd with a caller-owned device workspace of at least that many bytes, 256-byte
+ * aligned.  cfg may be NULL (the tuned tile is used). */
+int conv_winograd_ws(const float* x, const float* w, float* y,
+                     int N, int C, int H, int W, int K, int m,
+                     void* workspace, size_t workspace_bytes, const iolb_tile_config* cfg);
+
+/* The analytical tuner (searching domain of Table 1, Sec. 6.2; objective: reading volume of
+ * the dataflow of Sec. 5.2 / 5.3).  Host only; shape and out are host pointers.
+ * lds_bytes: LDS available to one workgroup (0 = default 81920, half a compute unit's LDS, the
+ * "two blocks per multiprocessor" rule of Sec. 6.2).  vgpr_budget: accumulator registers per
+ * lane (0 = default 128).  IOLB_ENOTILE when nothing fits. */
+int iolb_tune(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, iolb_tile_config* out);
+
+/* Every feasible tile for the shape, best first (the domain the exhaustive sweep times).
+ * use_box != 0 applies the optimality-condition box z <= sqrt(S_b/rho), xy <= sqrt(S_b rho).
+ * Writes at most `capacity` entries to out (may be NULL) and returns the total count, or a
+ * negative code. */
+int64_t iolb_enumerate(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, int use_box,
+                       iolb_tile_config* out, int64_t capacity);
+
+/* Lower-bound figures for a layer at fast-memory size S_f elements.  Host only. */
+int iolb_bounds(const iolb_shape* shape, int64_t S_f_elems, iolb_bounds_out* out);
+
+/* Stream (a hipStream_t) later calls enqueue on; NULL selects the null stream. */
+int iolb_set_stream(void* hip_stream);
+
+/* Timing hook for benchmarks: when enabled, the main kernel of each conv call (the direct
+ * convolution kernel, or the Winograd batched product) is bracketed by HIP events on the
+ * call's stream.  iolb_timing_read waits for the recorded events, returns the number of
+ * launches timed since the last read and their total duration in milliseconds, and resets. */
+int iolb_timing_enable(int on);
+int iolb_timing_read(int* launches, float* total_ms);
+
+/* Frees the library's device workspace (it is otherwise kept until the process ends). */
+int iolb_release_workspace(void);
+
+const char* iolb_strerror(int code);
+/* Text of the last HIP error seen by this thread's calls ("" if none). */
+const char* iolb_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IOLBCONV_H */

@@ -241,6 +241,8 @@ def _wave_grids(MB, NB, vgpr_budget):
                 continue
             if 16 * mbw * nbw > vgpr_budget:
                 continue
+            if 16 * mbw * nbw + 64 > 131072 // T:      # register-file share of a lane, 64 kept for operands
+                continue
             out.append((T, mbw + nbw, wm, wn, 16 * mbw * nbw))
     return out
 

@@ -1,0 +1,215 @@
+"""Thin ctypes binding of libiolbconv.so: argument marshalling only.
+
+Every step of the convolution runs in the library's HIP kernels; torch is used for device
+memory and the current stream.  There is no CPU fallback: a missing library raises.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libiolbconv.so")
+
+DIRECT, WINO_F2, WINO_F4 = 0, 1, 2
+PATH_FMA, PATH_MFMA = 0, 1
+
+EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_winograd", "conv_winograd_workspace_bytes",
+           "conv_winograd_ws", "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_set_stream",
+           "iolb_timing_enable", "iolb_timing_read", "iolb_release_workspace", "iolb_strerror",
+           "iolb_last_hip_error"]
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad", "algo")]
+
+
+class TileConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("b", "x", "y", "z", "alpha", "threads", "waves_m", "waves_n",
+                                              "path", "wt_mode", "lds_bytes_used", "acc_regs_per_thread")] + \
+               [("q_read_elems", ctypes.c_int64), ("q_write_elems", ctypes.c_int64)]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+    @classmethod
+    def from_dict(cls, d):
+        return cls(**{n: int(d[n]) for n, _ in cls._fields_})
+
+
+class BoundsOut(ctypes.Structure):
+    _fields_ = [("P", ctypes.c_int32), ("Q", ctypes.c_int32), ("vertices", ctypes.c_int64),
+                ("compulsory_elems", ctypes.c_int64), ("q_write_elems", ctypes.c_int64),
+                ("t_bound_2s", ctypes.c_double), ("q_lower_lead", ctypes.c_double),
+                ("q_lower_explicit", ctypes.c_double), ("q_dataflow", ctypes.c_double)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class IolbError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("iolbconv error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libiolbconv.so is missing: run __graft_entry__.build() "
+                               "(python -m paper_2012_15667_amd.build) first")
+        L = ctypes.CDLL(LIB_PATH)
+        i, vp, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+        L.conv_direct.restype = i
+        L.conv_direct.argtypes = [vp, vp, vp] + [i] * 9
+        L.conv_direct_cfg.restype = i
+        L.conv_direct_cfg.argtypes = [vp, vp, vp] + [i] * 9 + [ctypes.POINTER(TileConfig)]
+        L.conv_winograd.restype = i
+        L.conv_winograd.argtypes = [vp, vp, vp] + [i] * 6
+        L.conv_winograd_workspace_bytes.restype = sz
+        L.conv_winograd_workspace_bytes.argtypes = [i] * 6
+        L.conv_winograd_ws.restype = i
+        L.conv_winograd_ws.argtypes = [vp, vp, vp] + [i] * 6 + [vp, sz, ctypes.POINTER(TileConfig)]
+        L.iolb_tune.restype = i
+        L.iolb_tune.argtypes = [ctypes.POINTER(Shape), sz, i, ctypes.POINTER(TileConfig)]
+        L.iolb_enumerate.restype = ctypes.c_int64
+        L.iolb_enumerate.argtypes = [ctypes.POINTER(Shape), sz, i, i, ctypes.POINTER(TileConfig), ctypes.c_int64]
+        L.iolb_bounds.restype = i
+        L.iolb_bounds.argtypes = [ctypes.POINTER(Shape), ctypes.c_int64, ctypes.POINTER(BoundsOut)]
+        L.iolb_set_stream.restype = i
+        L.iolb_set_stream.argtypes = [vp]
+        L.iolb_timing_enable.restype = i
+        L.iolb_timing_enable.argtypes = [i]
+        L.iolb_timing_read.restype = i
+        L.iolb_timing_read.argtypes = [ctypes.POINTER(i), ctypes.POINTER(ctypes.c_float)]
+        L.iolb_release_workspace.restype = i
+        L.iolb_release_workspace.argtypes = []
+        L.iolb_strerror.restype = ctypes.c_char_p
+        L.iolb_strerror.argtypes = [i]
+        L.iolb_last_hip_error.restype = ctypes.c_char_p
+        L.iolb_last_hip_error.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(code):
+    if code < 0:
+        L = lib()
+        text = L.iolb_strerror(int(code)).decode()
+        if code == -5:
+            text += ": " + L.iolb_last_hip_error().decode()
+        raise IolbError(int(code), text)
+    return code
+
+
+def make_shape(N, C, H, W, K, R=3, S=3, stride=1, pad=1, algo=DIRECT):
+    return Shape(N, C, H, W, K, R, S, stride, pad, algo)
+
+
+def iolb_tune(shape, lds_bytes=0, vgpr_budget=0):
+    """Tile the analytical tuner picks for `shape` (a Shape); returns a dict."""
+    out = TileConfig()
+    _check(lib().iolb_tune(ctypes.byref(shape), lds_bytes, vgpr_budget, ctypes.byref(out)))
+    return out.as_dict()
+
+
+def iolb_enumerate(shape, lds_bytes=0, vgpr_budget=0, use_box=True):
+    """Every feasible tile, best first, as a list of dicts."""
+    L = lib()
+    n = _check(L.iolb_enumerate(ctypes.byref(shape), lds_bytes, vgpr_budget, int(use_box), None, 0))
+    arr = (TileConfig * max(n, 1))()
+    _check(L.iolb_enumerate(ctypes.byref(shape), lds_bytes, vgpr_budget, int(use_box), arr, n))
+    return [arr[j].as_dict() for j in range(n)]
+
+
+def iolb_bounds(shape, Sf):
+    out = BoundsOut()
+    _check(lib().iolb_bounds(ctypes.byref(shape), int(Sf), ctypes.byref(out)))
+    return out.as_dict()
+
+
+def _use_current_stream():
+    import torch
+    _check(lib().iolb_set_stream(ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)))
+
+
+def _dev_f32(t, name):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError(name + " must be a contiguous float32 tensor on the GPU")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def conv_direct(x, w, stride=1, pad=0, y=None, cfg=None):
+    """y = direct convolution of x [N][C][H][W] with w [K][C][R][S] on the current stream."""
+    import torch
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    if y is None:
+        if stride < 1 or pad < 0 or H + 2 * pad < R or W + 2 * pad < S:
+            raise IolbError(-1, "invalid argument")
+        P = (H + 2 * pad - R) // stride + 1
+        Q = (W + 2 * pad - S) // stride + 1
+        y = torch.empty((N, K, P, Q), dtype=torch.float32, device=x.device)
+    _use_current_stream()
+    args = (_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, R, S, stride, pad)
+    if cfg is None:
+        _check(lib().conv_direct(*args))
+    else:
+        c = cfg if isinstance(cfg, TileConfig) else TileConfig.from_dict(cfg)
+        _check(lib().conv_direct_cfg(*args, ctypes.byref(c)))
+    return y
+
+
+def conv_winograd(x, w, m, y=None, cfg=None, workspace=None):
+    """y = Winograd F(m x m, 3 x 3) convolution (stride 1, pad 1) on the current stream."""
+    import torch
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C or R != 3 or S != 3:
+        raise ValueError("Winograd path needs 3x3 kernels with matching channels")
+    if y is None:
+        y = torch.empty((N, K, H, W), dtype=torch.float32, device=x.device)
+    elif tuple(y.shape) != (N, K, H, W):
+        raise ValueError("y has the wrong shape")
+    _use_current_stream()
+    L = lib()
+    if cfg is None and workspace is None:
+        _check(L.conv_winograd(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, m))
+        return y
+    need = L.conv_winograd_workspace_bytes(N, C, H, W, K, m)
+    if need == 0:
+        raise IolbError(-2, "unsupported Winograd layer")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    c = None
+    if cfg is not None:
+        c = ctypes.byref(cfg if isinstance(cfg, TileConfig) else TileConfig.from_dict(cfg))
+    _check(L.conv_winograd_ws(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, m,
+                              ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), c))
+    return y
+
+
+def winograd_workspace_bytes(N, C, H, W, K, m):
+    return int(lib().conv_winograd_workspace_bytes(N, C, H, W, K, m))
+
+
+def timing_enable(on=True):
+    _check(lib().iolb_timing_enable(int(on)))
+
+
+def timing_read():
+    """(launches, total_ms) of the main kernels timed since the last read."""
+    n = ctypes.c_int(0)
+    ms = ctypes.c_float(0)
+    _check(lib().iolb_timing_read(ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value
+
+
+def release_workspace():
+    _check(lib().iolb_release_workspace())

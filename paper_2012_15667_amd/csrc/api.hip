@@ -1,0 +1,385 @@
+// C-ABI layer: argument checks, tile selection, workspace, launches.  See include/iolbconv.h.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "iolbconv.h"
+#include "kernels.h"
+#include "tune.h"
+
+namespace {
+
+// A few zero words in device memory: the source of every padded element the LDS-direct loads fetch.
+__device__ __align__(256) float g_zero_words[64];
+
+thread_local hipStream_t t_stream = nullptr;
+thread_local std::string t_hip_error;
+
+int hip_fail(hipError_t e)
+{
+    t_hip_error = hipGetErrorString(e);
+    return IOLB_EHIP;
+}
+#define IOLB_HIP(call)                                \
+    do {                                              \
+        hipError_t e__ = (call);                      \
+        if (e__ != hipSuccess) return hip_fail(e__);  \
+    } while (0)
+
+struct DeviceState {
+    float* zeros = nullptr;
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+};
+std::mutex g_mutex;
+std::map<int, DeviceState> g_devices;
+
+int device_state(DeviceState** out)
+{
+    int dev = 0;
+    IOLB_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState& d = g_devices[dev];
+    if (!d.zeros) {
+        void* p = nullptr;
+        IOLB_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_zero_words)));
+        d.zeros = static_cast<float*>(p);
+    }
+    *out = &d;
+    return IOLB_OK;
+}
+
+// Library-owned workspace: one allocation per device, grown on demand, kept until released.
+int ensure_workspace(DeviceState* d, size_t bytes)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (d->ws_bytes >= bytes) return IOLB_OK;
+    if (d->ws) {
+        IOLB_HIP(hipDeviceSynchronize());      // earlier launches may still read the old buffer
+        IOLB_HIP(hipFree(d->ws));
+        d->ws = nullptr;
+        d->ws_bytes = 0;
+    }
+    IOLB_HIP(hipMalloc(&d->ws, bytes));
+    d->ws_bytes = bytes;
+    return IOLB_OK;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// ---- timing hook --------------------------------------------------------------------------
+bool g_timing = false;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
+
+struct MainKernelTimer {
+    hipEvent_t a = nullptr, b = nullptr;
+    bool on;
+    explicit MainKernelTimer(hipStream_t st) : on(g_timing)
+    {
+        if (!on) return;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
+        hipEventRecord(a, st);
+    }
+    void stop(hipStream_t st)
+    {
+        if (!on) return;
+        hipEventRecord(b, st);
+        g_events.emplace_back(a, b);
+    }
+};
+
+// ---- tile cache -----------------------------------------------------------------------------
+typedef std::tuple<int, int, int, int, int, int, int, int, int, int> ShapeKey;
+std::map<ShapeKey, iolb_tile_config> g_tiles;
+
+int tuned_tile(const iolb_shape& s, iolb_tile_config* cfg)
+{
+    const ShapeKey key(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.algo);
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        auto it = g_tiles.find(key);
+        if (it != g_tiles.end()) { *cfg = it->second; return IOLB_OK; }
+    }
+    const int rc = iolb::tune(s, 0, 0, cfg);
+    if (rc != IOLB_OK) return rc;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_tiles[key] = *cfg;
+    return IOLB_OK;
+}
+
+bool same_config(const iolb_tile_config& a, const iolb_tile_config& b)
+{
+    return a.b == b.b && a.x == b.x && a.y == b.y && a.z == b.z && a.alpha == b.alpha && a.threads == b.threads &&
+           a.waves_m == b.waves_m && a.waves_n == b.waves_n && a.path == b.path && a.wt_mode == b.wt_mode &&
+           a.lds_bytes_used == b.lds_bytes_used && a.acc_regs_per_thread == b.acc_regs_per_thread &&
+           a.q_read_elems == b.q_read_elems && a.q_write_elems == b.q_write_elems;
+}
+
+// A caller-supplied tile must be one the enumeration produces for this shape (any LDS budget up to the
+// whole compute unit), so that every kernel assumption about it holds.
+int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
+{
+    std::vector<iolb::Candidate> all;
+    const int rc = iolb::enumerate(s, 160 * 1024, 0, false, &all);
+    if (rc != IOLB_OK) return rc;
+    for (const auto& c : all) {
+        iolb_tile_config probe = c.cfg;
+        // alpha may be any smaller even stage depth than the enumeration's deepest one
+        if (cfg.alpha >= 1 && cfg.alpha <= c.cfg.alpha && (cfg.path == IOLB_PATH_FMA || cfg.alpha % 2 == 0) &&
+            c.cfg.alpha % cfg.alpha == 0) {
+            probe.alpha = cfg.alpha;
+            probe.lds_bytes_used = (int32_t)((int64_t)c.cfg.lds_bytes_used / c.cfg.alpha * cfg.alpha);
+        }
+        if (same_config(probe, cfg)) return IOLB_OK;
+    }
+    return IOLB_EINVAL;
+}
+
+int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, int P, int Q, const iolb_tile_config& cfg)
+{
+    DeviceState* dev = nullptr;
+    int rc = device_state(&dev);
+    if (rc != IOLB_OK) return rc;
+    iolb::DirectGeom g{};
+    g.N = s.N; g.C = s.C; g.H = s.H; g.W = s.W; g.K = s.K; g.R = s.R; g.S = s.S; g.stride = s.stride; g.pad = s.pad;
+    g.P = P; g.Q = Q;
+    g.b = cfg.b; g.tx = cfg.x; g.ty = cfg.y; g.z = cfg.z; g.alpha = cfg.alpha;
+    g.threads = cfg.threads; g.waves_m = cfg.waves_m; g.waves_n = cfg.waves_n;
+    g.per_thread = cfg.acc_regs_per_thread;
+    g.nbx = Q / cfg.x; g.nby = P / cfg.y; g.nbn = s.N / cfg.b; g.nbk = s.K / cfg.z;
+    g.xh = (cfg.x - 1) * s.stride + s.S;
+    g.yh = (cfg.y - 1) * s.stride + s.R;
+    g.halo = cfg.b * g.xh * g.yh;
+    if ((int64_t)g.nbx * g.nby * g.nbn * g.nbk > 0x7fffffffLL) return IOLB_EINVAL;
+    hipStream_t st = t_stream;
+    if (cfg.path == IOLB_PATH_MFMA) {
+        const size_t wbytes = sizeof(float) * (size_t)s.K * s.C * s.R * s.S;
+        rc = ensure_workspace(dev, align256(wbytes));
+        if (rc != IOLB_OK) return rc;
+        float* wt = static_cast<float*>(dev->ws);
+        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, s.C * s.R * s.S, st));
+        MainKernelTimer timer(st);
+        IOLB_HIP(iolb::launch_direct_mfma(x, wt, y, dev->zeros, g, st));
+        timer.stop(st);
+    } else {
+        MainKernelTimer timer(st);
+        IOLB_HIP(iolb::launch_direct_fma(x, w, y, g, st));
+        timer.stop(st);
+    }
+    return IOLB_OK;
+}
+
+int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGeom* g)
+{
+    const int m = s.algo == IOLB_WINO_F2 ? 2 : 4;
+    g->N = s.N; g->C = s.C; g->H = s.H; g->W = s.W; g->K = s.K; g->m = m;
+    g->th = (s.H + m - 1) / m;
+    g->tw = (s.W + m - 1) / m;
+    const int64_t tiles = (int64_t)s.N * g->th * g->tw;
+    g->tb = cfg.x / m;
+    g->z = cfg.z;
+    g->alpha = cfg.alpha;
+    g->waves_m = cfg.waves_m;
+    g->waves_n = cfg.waves_n;
+    const int64_t pitch = (tiles + g->tb - 1) / g->tb * g->tb;
+    const int64_t n2 = (int64_t)(m + 2) * (m + 2);
+    if (n2 * s.C * pitch >= (1LL << 31) || n2 * s.K * pitch >= (1LL << 31)) return IOLB_EINVAL;
+    g->tiles = (int)tiles;
+    g->tiles_pitch = (int)pitch;
+    return IOLB_OK;
+}
+
+struct WinoWorkspace {
+    size_t u_off, v_off, m_off, total;
+};
+WinoWorkspace winograd_layout(int C, int K, int m, int64_t tiles_pitch)
+{
+    const size_t n2 = (size_t)(m + 2) * (m + 2);
+    WinoWorkspace l;
+    l.u_off = 0;
+    l.v_off = l.u_off + align256(sizeof(float) * n2 * C * K);
+    l.m_off = l.v_off + align256(sizeof(float) * n2 * C * tiles_pitch);
+    l.total = l.m_off + align256(sizeof(float) * n2 * K * tiles_pitch);
+    return l;
+}
+
+int make_wino_shape(int N, int C, int H, int W, int K, int m, iolb_shape* s)
+{
+    if (m != 2 && m != 4) return IOLB_EUNSUPPORTED;
+    *s = iolb_shape{N, C, H, W, K, 3, 3, 1, 1, m == 2 ? IOLB_WINO_F2 : IOLB_WINO_F4};
+    int P = 0, Q = 0;
+    return iolb::validate_shape(*s, &P, &Q);
+}
+
+int run_winograd(const float* x, const float* w, float* y, const iolb_shape& s, const iolb_tile_config& cfg,
+                 void* ws, size_t ws_bytes)
+{
+    DeviceState* dev = nullptr;
+    int rc = device_state(&dev);
+    if (rc != IOLB_OK) return rc;
+    iolb::WinoGeom g{};
+    rc = winograd_geom(s, cfg, &g);
+    if (rc != IOLB_OK) return rc;
+    const WinoWorkspace l = winograd_layout(s.C, s.K, g.m, g.tiles_pitch);
+    if (!ws || ws_bytes < l.total || (reinterpret_cast<uintptr_t>(ws) & 255)) return IOLB_EWORKSPACE;
+    char* base = static_cast<char*>(ws);
+    float* U = reinterpret_cast<float*>(base + l.u_off);
+    float* V = reinterpret_cast<float*>(base + l.v_off);
+    float* M = reinterpret_cast<float*>(base + l.m_off);
+    hipStream_t st = t_stream;
+    IOLB_HIP(iolb::launch_wino_kernel_transform(w, U, g, st));
+    IOLB_HIP(iolb::launch_wino_input_transform(x, V, g, st));
+    MainKernelTimer timer(st);
+    IOLB_HIP(iolb::launch_wino_product(U, V, M, dev->zeros, g, st));
+    timer.stop(st);
+    IOLB_HIP(iolb::launch_wino_output_transform(M, y, g, st));
+    return IOLB_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_direct_cfg(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                    int stride, int pad, const iolb_tile_config* cfg)
+{
+    if (!x || !w || !y || !cfg) return IOLB_EINVAL;
+    const iolb_shape s{N, C, H, W, K, R, S, stride, pad, IOLB_DIRECT};
+    int P = 0, Q = 0;
+    int rc = iolb::validate_shape(s, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    rc = check_config(s, *cfg);
+    if (rc != IOLB_OK) return rc;
+    return run_direct(x, w, y, s, P, Q, *cfg);
+}
+
+int conv_direct(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                int stride, int pad)
+{
+    if (!x || !w || !y) return IOLB_EINVAL;
+    const iolb_shape s{N, C, H, W, K, R, S, stride, pad, IOLB_DIRECT};
+    int P = 0, Q = 0;
+    int rc = iolb::validate_shape(s, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    iolb_tile_config cfg;
+    rc = tuned_tile(s, &cfg);
+    if (rc != IOLB_OK) return rc;
+    return run_direct(x, w, y, s, P, Q, cfg);
+}
+
+size_t conv_winograd_workspace_bytes(int N, int C, int H, int W, int K, int m)
+{
+    iolb_shape s;
+    if (make_wino_shape(N, C, H, W, K, m, &s) != IOLB_OK) return 0;
+    // large enough for every tile the enumeration can produce: blocks hold at most 1024 sub-domains
+    const int64_t tiles = (int64_t)N * ((H + m - 1) / m) * ((W + m - 1) / m);
+    return winograd_layout(C, K, m, tiles + 1024).total;
+}
+
+int conv_winograd_ws(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m,
+                     void* workspace, size_t workspace_bytes, const iolb_tile_config* cfg)
+{
+    if (!x || !w || !y) return IOLB_EINVAL;
+    iolb_shape s;
+    int rc = make_wino_shape(N, C, H, W, K, m, &s);
+    if (rc != IOLB_OK) return rc;
+    iolb_tile_config tile;
+    if (cfg) {
+        rc = check_config(s, *cfg);
+        if (rc != IOLB_OK) return rc;
+        tile = *cfg;
+    } else {
+        rc = tuned_tile(s, &tile);
+        if (rc != IOLB_OK) return rc;
+    }
+    return run_winograd(x, w, y, s, tile, workspace, workspace_bytes);
+}
+
+int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m)
+{
+    if (!x || !w || !y) return IOLB_EINVAL;
+    iolb_shape s;
+    int rc = make_wino_shape(N, C, H, W, K, m, &s);
+    if (rc != IOLB_OK) return rc;
+    iolb_tile_config tile;
+    rc = tuned_tile(s, &tile);
+    if (rc != IOLB_OK) return rc;
+    const size_t bytes = conv_winograd_workspace_bytes(N, C, H, W, K, m);
+    DeviceState* dev = nullptr;
+    rc = device_state(&dev);
+    if (rc != IOLB_OK) return rc;
+    rc = ensure_workspace(dev, bytes);
+    if (rc != IOLB_OK) return rc;
+    return run_winograd(x, w, y, s, tile, dev->ws, dev->ws_bytes);
+}
+
+int iolb_set_stream(void* hip_stream)
+{
+    t_stream = static_cast<hipStream_t>(hip_stream);
+    return IOLB_OK;
+}
+
+int iolb_timing_enable(int on)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    g_timing = on != 0;
+    return IOLB_OK;
+}
+
+int iolb_timing_read(int* launches, float* total_ms)
+{
+    if (!launches || !total_ms) return IOLB_EINVAL;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    float sum = 0.f;
+    int count = 0;
+    int rc = IOLB_OK;
+    for (auto& ev : g_events) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(ev.second);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.first, ev.second);
+        if (e != hipSuccess) rc = hip_fail(e);
+        else { sum += ms; ++count; }
+        hipEventDestroy(ev.first);
+        hipEventDestroy(ev.second);
+    }
+    g_events.clear();
+    *launches = count;
+    *total_ms = sum;
+    return rc;
+}
+
+int iolb_release_workspace(void)
+{
+    int dev = 0;
+    IOLB_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lock(g_mutex);
+    auto it = g_devices.find(dev);
+    if (it == g_devices.end() || !it->second.ws) return IOLB_OK;
+    IOLB_HIP(hipDeviceSynchronize());
+    IOLB_HIP(hipFree(it->second.ws));
+    it->second.ws = nullptr;
+    it->second.ws_bytes = 0;
+    return IOLB_OK;
+}
+
+const char* iolb_strerror(int code)
+{
+    switch (code) {
+    case IOLB_OK: return "success";
+    case IOLB_EINVAL: return "invalid argument";
+    case IOLB_EUNSUPPORTED: return "unsupported algorithm or Winograd tile size";
+    case IOLB_ENOTILE: return "no tile fits the LDS / register budgets";
+    case IOLB_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case IOLB_EHIP: return "HIP runtime error (see iolb_last_hip_error)";
+    default: return "unknown error code";
+    }
+}
+
+const char* iolb_last_hip_error(void) { return t_hip_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,49 @@
+// Internal launch interface between the C-ABI layer and the gfx950 kernels.
+#ifndef IOLB_KERNELS_H
+#define IOLB_KERNELS_H
+
+#include <hip/hip_runtime.h>
+
+#include "iolbconv.h"
+
+namespace iolb {
+
+// Geometry of one direct-convolution launch: the layer, the output sub-block b * tx * ty * z of
+// Sec. 5.2 with its input tile xh * yh (x' * y' in the paper), and the block counts.
+struct DirectGeom {
+    int N, C, H, W, K, R, S, stride, pad, P, Q;
+    int b, tx, ty, z, alpha;
+    int threads;               // workgroup size
+    int waves_m, waves_n;      // MFMA path: wave grid; FMA path: channel groups, 1
+    int per_thread;            // FMA path: output channels per lane
+    int nbx, nby, nbn, nbk;    // blocks along W_out, H_out, batch, C_out
+    int xh, yh, halo;          // input tile extents and elements per channel (b * yh * xh)
+};
+
+// Re-layout w[K][C][R][S] -> wt[C][R][S][K] so that a stage's weight slab is contiguous in K.
+hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, hipStream_t st);
+
+hipError_t launch_direct_fma(const float* x, const float* w, float* y, const DirectGeom& g, hipStream_t st);
+// zeros: at least 16 bytes of device memory holding 0.0f (source of padded elements).
+hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const float* zeros,
+                              const DirectGeom& g, hipStream_t st);
+
+// Winograd F(m x m, 3 x 3), unfused: kernel transform, input transform, batched product over the
+// (m+2)^2 planes, output transform (steps 1-4 of Sec. 4.3).
+struct WinoGeom {
+    int N, C, H, W, K, m;      // P = H, Q = W (pad 1)
+    int th, tw;                // sub-domains along H_out and W_out
+    int tiles;                 // N * th * tw
+    int tiles_pitch;           // tiles rounded up to a whole number of blocks
+    int tb, z, alpha;          // block: tb sub-domains by z channels of one plane
+    int waves_m, waves_n;
+};
+hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom& g, hipStream_t st);
+hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom& g, hipStream_t st);
+hipError_t launch_wino_product(const float* U, const float* V, float* M, const float* zeros,
+                               const WinoGeom& g, hipStream_t st);
+hipError_t launch_wino_output_transform(const float* M, float* y, const WinoGeom& g, hipStream_t st);
+
+}  // namespace iolb
+
+#endif

@@ -1,0 +1,298 @@
+// Host-side analytical tuner and lower-bound figures (no GPU code in this file).
+//
+// The searching domain is Table 1 of Sec. 6.2 read for a wave64 machine whose partial sums
+// live in registers and whose staging buffers live in LDS; the objective is the reading volume
+// of the dataflow of Sec. 5.2 (direct) / Sec. 5.3 (Winograd) evaluated exactly for each tile.
+// All decisions are taken in 64-bit integers.
+#include "iolbconv.h"
+#include "tune.h"
+
+#include <algorithm>
+#include <array>
+#include <cmath>
+#include <cstdlib>
+#include <vector>
+
+namespace iolb {
+
+namespace {
+
+constexpr int64_t kComputeUnits = 256;   // grid-fill rule: a launch should keep every CU busy
+constexpr int64_t kMaxThreads = 1024;    // largest workgroup: bounds the optimality box
+constexpr int64_t kEffCap = 80;          // grid efficiency above this percentage is "good enough"
+
+std::vector<int> factors_of(int n) {
+    std::vector<int> f;
+    for (int d = 1; d <= n; ++d)
+        if (n % d == 0) f.push_back(d);
+    return f;
+}
+
+bool allowed_threads(int64_t t) { return t == 64 || t == 128 || t == 256 || t == 512 || t == 1024; }
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Percentage of compute-unit slots busy over the rounds the grid needs, capped.
+int64_t grid_efficiency(int64_t nblocks) {
+    const int64_t rounds = ceil_div(nblocks, kComputeUnits);
+    return std::min<int64_t>((100 * nblocks) / (rounds * kComputeUnits), kEffCap);
+}
+
+// Channels per stage: least zero-padding of C first, then the deepest stage that fits the LDS.
+int choose_alpha(int C, const int* choices, int nchoices, int64_t bytes_per_channel, int64_t lds_bytes) {
+    int best = 0;
+    int64_t best_padded = 0;
+    for (int i = 0; i < nchoices; ++i) {
+        const int a = choices[i];
+        if (bytes_per_channel * a > lds_bytes) continue;
+        const int64_t padded = ceil_div(C, a) * a;
+        if (best == 0 || padded < best_padded || (padded == best_padded && a > best)) {
+            best = a;
+            best_padded = padded;
+        }
+    }
+    return best;
+}
+
+struct WaveGrid {
+    int threads, reads, wm, wn, acc;
+    bool operator<(const WaveGrid& o) const {
+        return std::array<int, 5>{threads, reads, wm, wn, acc} <
+               std::array<int, 5>{o.threads, o.reads, o.wm, o.wn, o.acc};
+    }
+};
+
+// Best split of MB x NB blocks of 32 x 32 partial sums over whole waves: each wave owns
+// mbw x nbw blocks (mbw in {1,2}, at most 8 blocks = 128 accumulator registers).
+bool best_wave_grid(int MB, int NB, int vgpr_budget, WaveGrid* out) {
+    bool found = false;
+    for (int wm = 1; wm <= MB; ++wm) {
+        if (MB % wm) continue;
+        const int mbw = MB / wm;
+        if (mbw != 1 && mbw != 2) continue;
+        for (int wn = 1; wn <= NB; ++wn) {
+            if (NB % wn) continue;
+            const int nbw = NB / wn;
+            const int64_t threads = 64LL * wm * wn;
+            if (mbw * nbw > 8 || !allowed_threads(threads) || 16 * mbw * nbw > vgpr_budget) continue;
+            // a compute unit's register file holds 131072 lane-registers; leave 64 per lane for operands
+            if (16 * mbw * nbw + 64 > 131072 / threads) continue;
+            WaveGrid g{(int)threads, mbw + nbw, wm, wn, 16 * mbw * nbw};
+            if (!found || g < *out) *out = g;
+            found = true;
+        }
+    }
+    return found;
+}
+
+int pow2_at_least(int v) {
+    int p = 1;
+    while (p < v) p *= 2;
+    return p;
+}
+
+void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int vgpr_budget, int path,
+                       bool use_box, std::vector<Candidate>* out) {
+    static const int alphas_mfma[] = {16, 8, 4, 2};
+    static const int alphas_fma[] = {16, 8, 4, 2, 1};
+    const int64_t box = kMaxThreads * vgpr_budget;
+    const int64_t RS = (int64_t)s.R * s.S, st2 = (int64_t)s.stride * s.stride;
+    const auto fb = factors_of(s.N), fx = factors_of(Q), fy = factors_of(P), fz = factors_of(s.K);
+    for (int b : fb)
+        for (int x : fx)
+            for (int y : fy) {
+                const int64_t npix = (int64_t)b * x * y;
+                const int64_t xh = (int64_t)(x - 1) * s.stride + s.S, yh = (int64_t)(y - 1) * s.stride + s.R;
+                const int64_t halo = b * xh * yh;
+                for (int z : fz) {
+                    if (use_box && !((int64_t)z * z * RS <= box * st2 && npix * npix * st2 <= box * RS)) continue;
+                    const int64_t per_stage = halo + RS * z;
+                    WaveGrid g{};
+                    int alpha = 0;
+                    int lds_mult = 0;
+                    if (path == IOLB_PATH_MFMA) {
+                        if (npix % 32 || z % 32) continue;
+                        if (!best_wave_grid(z / 32, (int)(npix / 32), vgpr_budget, &g)) continue;
+                        alpha = choose_alpha(s.C, alphas_mfma, 4, 8 * per_stage, lds_bytes);
+                        lds_mult = 8;
+                    } else {
+                        if (npix > 256) continue;
+                        const int lanes = std::max(pow2_at_least((int)npix), 16);
+                        bool found = false;
+                        for (int T : {64, 128, 256}) {
+                            if (lanes > T) continue;
+                            const int groups = T / lanes;
+                            if (z % groups) continue;
+                            const int per_thread = z / groups;
+                            if (per_thread > 16 || per_thread > vgpr_budget) continue;
+                            g = WaveGrid{T, 0, groups, 1, per_thread};
+                            found = true;
+                            break;               // ascending T: the first is the smallest
+                        }
+                        if (!found) continue;
+                        alpha = choose_alpha(s.C, alphas_fma, 5, 4 * per_stage, lds_bytes);
+                        lds_mult = 4;
+                    }
+                    if (alpha == 0) continue;
+                    const int64_t nblocks = (int64_t)(s.N / b) * (Q / x) * (P / y) * (s.K / z);
+                    Candidate c{};
+                    c.cfg.b = b; c.cfg.x = x; c.cfg.y = y; c.cfg.z = z;
+                    c.cfg.alpha = alpha;
+                    c.cfg.threads = g.threads; c.cfg.waves_m = g.wm; c.cfg.waves_n = g.wn;
+                    c.cfg.path = path; c.cfg.wt_mode = 0;
+                    c.cfg.lds_bytes_used = (int32_t)(lds_mult * alpha * per_stage);
+                    c.cfg.acc_regs_per_thread = g.acc;
+                    c.cfg.q_read_elems = nblocks * s.C * per_stage;
+                    c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+                    c.key = {-grid_efficiency(nblocks), c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z),
+                             -npix * z, -(int64_t)x, z, b, y, g.threads};
+                    out->push_back(c);
+                }
+            }
+}
+
+// Winograd: the resident block is tb sub-domains by z output channels of ONE transformed plane
+// (the channel-summation temporaries of step 3); per channel it reads tb transformed inputs and
+// z transformed weights, for each of the (m+2)^2 planes.
+void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_bytes, int vgpr_budget,
+                         bool use_box, std::vector<Candidate>* out) {
+    static const int alphas[] = {16, 8, 4, 2};
+    const int64_t planes = (int64_t)(m + 2) * (m + 2);
+    const int64_t tiles = (int64_t)s.N * ceil_div(P, m) * ceil_div(Q, m);
+    const int64_t box = kMaxThreads * vgpr_budget;
+    const int64_t top = std::min<int64_t>(ceil_div(tiles, 32) * 32, 1024);
+    const auto fz = factors_of(s.K);
+    for (int64_t tb = 32; tb <= top; tb += 32)
+        for (int z : fz) {
+            if (z % 32) continue;
+            if (use_box && !((int64_t)z * z <= box && tb * tb <= box)) continue;
+            WaveGrid g{};
+            if (!best_wave_grid(z / 32, (int)(tb / 32), vgpr_budget, &g)) continue;
+            const int alpha = choose_alpha(s.C, alphas, 4, 8 * (tb + z), lds_bytes);
+            if (alpha == 0) continue;
+            const int64_t nblocks = planes * ceil_div(tiles, tb) * (s.K / z);
+            Candidate c{};
+            c.cfg.b = 1; c.cfg.x = (int32_t)(m * tb); c.cfg.y = m; c.cfg.z = z;
+            c.cfg.alpha = alpha;
+            c.cfg.threads = g.threads; c.cfg.waves_m = g.wm; c.cfg.waves_n = g.wn;
+            c.cfg.path = IOLB_PATH_MFMA; c.cfg.wt_mode = 1;
+            c.cfg.lds_bytes_used = (int32_t)(8 * alpha * (tb + z));
+            c.cfg.acc_regs_per_thread = g.acc;
+            c.cfg.q_read_elems = nblocks * s.C * (tb + z);
+            c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+            c.key = {-grid_efficiency(nblocks), c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0};
+            out->push_back(c);
+        }
+}
+
+}  // namespace
+
+int validate_shape(const iolb_shape& s, int* P, int* Q) {
+    if (s.N < 1 || s.C < 1 || s.H < 1 || s.W < 1 || s.K < 1 || s.R < 1 || s.S < 1 || s.stride < 1 || s.pad < 0)
+        return IOLB_EINVAL;
+    if (s.algo != IOLB_DIRECT && s.algo != IOLB_WINO_F2 && s.algo != IOLB_WINO_F4) return IOLB_EUNSUPPORTED;
+    if (s.algo != IOLB_DIRECT && (s.R != 3 || s.S != 3 || s.stride != 1)) return IOLB_EUNSUPPORTED;
+    if ((int64_t)s.H + 2LL * s.pad < s.R || (int64_t)s.W + 2LL * s.pad < s.S) return IOLB_EINVAL;
+    const int64_t p = ((int64_t)s.H + 2LL * s.pad - s.R) / s.stride + 1;
+    const int64_t q = ((int64_t)s.W + 2LL * s.pad - s.S) / s.stride + 1;
+    // tensors of up to 2^31 - 1 elements each
+    if ((int64_t)s.N * s.C * s.H * s.W >= (1LL << 31) || (int64_t)s.N * s.K * p * q >= (1LL << 31) ||
+        (int64_t)s.K * s.C * s.R * s.S >= (1LL << 31)) return IOLB_EINVAL;
+    *P = (int)p;
+    *Q = (int)q;
+    return IOLB_OK;
+}
+
+int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_box, std::vector<Candidate>* out) {
+    int P = 0, Q = 0;
+    const int rc = validate_shape(s, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    if (lds_bytes <= 0) lds_bytes = 81920;
+    if (vgpr_budget <= 0) vgpr_budget = 128;
+    out->clear();
+    if (s.algo == IOLB_DIRECT) {
+        direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_MFMA, use_box, out);
+        if (out->empty()) direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_FMA, use_box, out);
+    } else {
+        winograd_candidates(s, P, Q, s.algo == IOLB_WINO_F2 ? 2 : 4, lds_bytes, vgpr_budget, use_box, out);
+    }
+    std::sort(out->begin(), out->end(), [](const Candidate& a, const Candidate& b) { return a.key < b.key; });
+    return IOLB_OK;
+}
+
+int tune(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, iolb_tile_config* cfg) {
+    std::vector<Candidate> c;
+    int rc = enumerate(s, lds_bytes, vgpr_budget, true, &c);
+    if (rc != IOLB_OK) return rc;
+    if (c.empty()) {                       // tiny layers: nothing inside the box, search the whole domain
+        rc = enumerate(s, lds_bytes, vgpr_budget, false, &c);
+        if (rc != IOLB_OK) return rc;
+    }
+    if (c.empty()) return IOLB_ENOTILE;
+    *cfg = c.front().cfg;
+    return IOLB_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// lower-bound figures (Sec. 4 and Sec. 5), in double precision
+// ---------------------------------------------------------------------------------------
+int bounds(const iolb_shape& s, int64_t Sf, iolb_bounds_out* o) {
+    int P = 0, Q = 0;
+    const int rc = validate_shape(s, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    if (Sf < 1) return IOLB_EINVAL;
+    const double npq = (double)s.N * P * Q;
+    o->P = P;
+    o->Q = Q;
+    o->q_write_elems = (int64_t)s.N * s.K * P * Q;
+    o->compulsory_elems = (int64_t)s.N * s.C * s.H * s.W + (int64_t)s.K * s.C * s.R * s.S + o->q_write_elems;
+    const double S = (double)Sf;
+    if (s.algo == IOLB_DIRECT) {
+        const double RS = (double)s.R * s.S;
+        const double reuse = RS / ((double)s.stride * s.stride);      // Eq. "definition of R"
+        o->vertices = (2LL * s.R * s.S * s.C - 1) * (int64_t)s.N * P * Q * s.K;
+        const double S2 = 2.0 * S;
+        o->t_bound_2s = 4.0 * S2 * std::sqrt(reuse * S2) + S2 - 1.0;
+        o->q_lower_lead = RS * s.C * npq * s.K / (4.0 * std::sqrt(2.0 * reuse * S));
+        o->q_lower_explicit = S * ((double)o->vertices / o->t_bound_2s - 1.0);
+        o->q_dataflow = 2.0 * npq * s.K * RS * s.C / std::sqrt(reuse * S) + npq * s.K;
+    } else {
+        const int m = s.algo == IOLB_WINO_F2 ? 2 : 4;
+        const int64_t n = m + 2, n2 = n * n, r = 3;
+        const int64_t tiles = (int64_t)s.N * ceil_div(P, m) * ceil_div(Q, m);
+        const int64_t per_tile_k = (2 * n2 - 1) * n2 * s.C + (2 * r * r - 1) * n2 * s.C + n2 * s.C +
+                                   (int64_t)(s.C - 1) * n2 + (2 * n2 - 1) * m * m;
+        o->vertices = tiles * s.K * per_tile_k;
+        const double S2 = 2.0 * S;
+        const double er = (double)m * r;
+        o->t_bound_2s = 2.0 * (double)(n * n * n) / er * S2 * std::sqrt(S2) + 6.0 * (double)n2 / er * S2;
+        o->q_lower_lead = npq * s.K * s.C * (double)n * r / (m * std::sqrt(S));
+        const double v_lead = 2.0 * npq * s.K * s.C * (double)(n2 * n2) / ((double)m * m);
+        o->q_lower_explicit = S * (v_lead / o->t_bound_2s - 1.0);
+        o->q_dataflow = 2.0 * npq * s.K * s.C * r * (double)n / (m * std::sqrt(S)) + npq * s.K;
+    }
+    return IOLB_OK;
+}
+
+}  // namespace iolb
+
+extern "C" int iolb_tune(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, iolb_tile_config* out) {
+    if (!shape || !out || vgpr_budget < 0) return IOLB_EINVAL;
+    return iolb::tune(*shape, (int64_t)lds_bytes, vgpr_budget, out);
+}
+
+extern "C" int64_t iolb_enumerate(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, int use_box,
+                                  iolb_tile_config* out, int64_t capacity) {
+    if (!shape || vgpr_budget < 0 || capacity < 0) return IOLB_EINVAL;
+    std::vector<iolb::Candidate> c;
+    const int rc = iolb::enumerate(*shape, (int64_t)lds_bytes, vgpr_budget, use_box != 0, &c);
+    if (rc != IOLB_OK) return rc;
+    if (out)
+        for (int64_t i = 0; i < (int64_t)c.size() && i < capacity; ++i) out[i] = c[i].cfg;
+    return (int64_t)c.size();
+}
+
+extern "C" int iolb_bounds(const iolb_shape* shape, int64_t S_f_elems, iolb_bounds_out* out) {
+    if (!shape || !out) return IOLB_EINVAL;
+    return iolb::bounds(*shape, S_f_elems, out);
+}

@@ -1,0 +1,28 @@
+// Internal interface of the host-side tuner (shared by tune.cpp and the launch code).
+#ifndef IOLB_TUNE_H
+#define IOLB_TUNE_H
+
+#include "iolbconv.h"
+
+#include <array>
+#include <cstdint>
+#include <vector>
+
+namespace iolb {
+
+struct Candidate {
+    iolb_tile_config cfg;
+    std::array<int64_t, 9> key;   // lexicographic, smaller is better
+};
+
+// Checks a layer description and computes its output extents.
+int validate_shape(const iolb_shape& s, int* P, int* Q);
+// All feasible tiles, best first.
+int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_box, std::vector<Candidate>* out);
+// The best tile (box first, whole domain if the box is empty).
+int tune(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, iolb_tile_config* cfg);
+int bounds(const iolb_shape& s, int64_t Sf, iolb_bounds_out* o);
+
+}  // namespace iolb
+
+#endif

@@ -1,0 +1,328 @@
+// Winograd F(m x m, 3 x 3) convolution, m in {2, 4}: the four steps of Sec. 4.3 as four kernels.
+//
+//   step 1b  U[xi][c][k]  = (L K_{k,c} L^T)[xi]                    kernel transform
+//   step 1a  V[xi][c][t]  = (B I_{c,t} B^T)[xi]                    input transform, t = sub-domain index
+//   step 2+3 M[xi][k][t]  = sum_c U[xi][c][k] * V[xi][c][t]        element-wise product + channel sum,
+//                                                                   one GEMM per transformed plane xi,
+//                                                                   on the fp32 matrix cores
+//   step 4   y            = A M_{k,t} A^T  (valid m x m part)      output transform
+//
+// xi runs over the n*n = (m+2)^2 positions of a transformed tile.  Sub-domain t = (image, tile row,
+// tile column) in that order; tile (ti, tj) reads the n x n input window whose top-left corner is
+// (ti*m - 1, tj*m - 1), zero outside the image.
+//
+// The transform matrices are the Toom-Cook matrices for the points {0, 1, -1, inf} (m = 2) and
+// {0, 1, -1, 2, -2, inf} (m = 4).
+#include "kernels.h"
+
+namespace iolb {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(1))) const void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+template <int M> struct Mats;
+
+template <> struct Mats<2> {
+    static constexpr int n = 4;
+    static constexpr float B[4][4] = {{1, 0, -1, 0}, {0, 1, 1, 0}, {0, -1, 1, 0}, {0, 1, 0, -1}};
+    static constexpr float L[4][3] = {{1, 0, 0}, {0.5f, 0.5f, 0.5f}, {0.5f, -0.5f, 0.5f}, {0, 0, 1}};
+    static constexpr float A[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
+};
+template <> struct Mats<4> {
+    static constexpr int n = 6;
+    static constexpr float B[6][6] = {{4, 0, -5, 0, 1, 0},  {0, -4, -4, 1, 1, 0}, {0, 4, -4, -1, 1, 0},
+                                      {0, -2, -1, 2, 1, 0}, {0, 2, -1, -2, 1, 0}, {0, 4, 0, -5, 0, 1}};
+    static constexpr float L[6][3] = {{1.f / 4, 0, 0},
+                                      {-1.f / 6, -1.f / 6, -1.f / 6},
+                                      {-1.f / 6, 1.f / 6, -1.f / 6},
+                                      {1.f / 24, 1.f / 12, 1.f / 6},
+                                      {1.f / 24, -1.f / 12, 1.f / 6},
+                                      {0, 0, 1}};
+    static constexpr float A[4][6] = {{1, 1, 1, 1, 1, 0}, {0, 1, -1, 2, -2, 0}, {0, 1, 1, 4, 4, 0}, {0, 1, -1, 8, -8, 1}};
+};
+
+// out[ROWS][COLS] = Mx[ROWS][IN] * in[IN][COLS]; zero entries of the constant matrix cost nothing
+template <int ROWS, int IN, int COLS, typename MatT>
+__device__ __forceinline__ void left_mul(const MatT& Mx, const float (&in)[IN][COLS], float (&out)[ROWS][COLS])
+{
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i)
+#pragma unroll
+        for (int j = 0; j < COLS; ++j) {
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < IN; ++k)
+                if (Mx[i][k] != 0.f) s = (Mx[i][k] == 1.f) ? s + in[k][j] : (Mx[i][k] == -1.f) ? s - in[k][j]
+                                                                                                : __builtin_fmaf(Mx[i][k], in[k][j], s);
+            out[i][j] = s;
+        }
+}
+// out[ROWS][COLS] = in[ROWS][IN] * Mx[COLS][IN]^T
+template <int ROWS, int IN, int COLS, typename MatT>
+__device__ __forceinline__ void right_mul_t(const float (&in)[ROWS][IN], const MatT& Mx, float (&out)[ROWS][COLS])
+{
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i)
+#pragma unroll
+        for (int j = 0; j < COLS; ++j) {
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < IN; ++k)
+                if (Mx[j][k] != 0.f) s = (Mx[j][k] == 1.f) ? s + in[i][k] : (Mx[j][k] == -1.f) ? s - in[i][k]
+                                                                                                : __builtin_fmaf(Mx[j][k], in[i][k], s);
+            out[i][j] = s;
+        }
+}
+
+// step 1b: one lane per (c, k); k runs fastest so the writes of a wave are contiguous
+template <int M>
+__global__ void __launch_bounds__(256)
+kernel_transform(const float* __restrict__ w, float* __restrict__ U, int C, int K)
+{
+    constexpr int n = Mats<M>::n;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)C * K) return;
+    const int k = idx % K, c = idx / K;
+    float g[3][3];
+    const float* wp = w + ((size_t)k * C + c) * 9;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int j = 0; j < 3; ++j) g[i][j] = wp[i * 3 + j];
+    float t[n][3], u[n][n];
+    left_mul<n, 3, 3>(Mats<M>::L, g, t);
+    right_mul_t<n, 3, n>(t, Mats<M>::L, u);
+    const size_t plane = (size_t)C * K;
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+#pragma unroll
+        for (int j = 0; j < n; ++j) U[(size_t)(i * n + j) * plane + idx] = u[i][j];
+}
+
+// step 1a: one lane per (c, t); t runs fastest
+template <int M>
+__global__ void __launch_bounds__(256)
+input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
+{
+    constexpr int n = Mats<M>::n;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int c = blockIdx.y;
+    if (t >= g.tiles) return;
+    const int tj = t % g.tw, ti = (t / g.tw) % g.th, img = t / (g.tw * g.th);
+    const int h0 = ti * M - 1, w0 = tj * M - 1;
+    const float* xp = x + ((size_t)img * g.C + c) * g.H * g.W;
+    float d[n][n];
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+#pragma unroll
+        for (int j = 0; j < n; ++j) {
+            const int h = h0 + i, ww = w0 + j;
+            d[i][j] = (h >= 0 && h < g.H && ww >= 0 && ww < g.W) ? xp[(size_t)h * g.W + ww] : 0.f;
+        }
+    float tmp[n][n], v[n][n];
+    left_mul<n, n, n>(Mats<M>::B, d, tmp);
+    right_mul_t<n, n, n>(tmp, Mats<M>::B, v);
+    const size_t plane = (size_t)g.C * g.tiles_pitch;
+    float* vp = V + (size_t)c * g.tiles_pitch + t;
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+#pragma unroll
+        for (int j = 0; j < n; ++j) vp[(size_t)(i * n + j) * plane] = v[i][j];
+}
+
+// step 4: one lane per (k, t); t runs fastest
+template <int M>
+__global__ void __launch_bounds__(256)
+output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g)
+{
+    constexpr int n = Mats<M>::n;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int k = blockIdx.y;
+    if (t >= g.tiles) return;
+    const int tj = t % g.tw, ti = (t / g.tw) % g.th, img = t / (g.tw * g.th);
+    const size_t plane = (size_t)g.K * g.tiles_pitch;
+    const float* mp = Mp + (size_t)k * g.tiles_pitch + t;
+    float pi[n][n];
+#pragma unroll
+    for (int i = 0; i < n; ++i)
+#pragma unroll
+        for (int j = 0; j < n; ++j) pi[i][j] = mp[(size_t)(i * n + j) * plane];
+    float tmp[M][n], o[M][M];
+    left_mul<M, n, n>(Mats<M>::A, pi, tmp);
+    right_mul_t<M, n, M>(tmp, Mats<M>::A, o);
+    float* yp = y + ((size_t)img * g.K + k) * g.H * g.W;
+#pragma unroll
+    for (int i = 0; i < M; ++i)
+#pragma unroll
+        for (int j = 0; j < M; ++j) {
+            const int h = ti * M + i, ww = tj * M + j;
+            if (h < g.H && ww < g.W) yp[(size_t)h * g.W + ww] = o[i][j];
+        }
+}
+
+// steps 2+3: M[xi] (K x tiles) = U[xi]^T (C x K) . V[xi] (C x tiles), one workgroup per z x tb block
+// of one plane.  The block's partial sums (the temporaries of the channel summation) stay in registers
+// for the whole channel loop.  Per stage, alpha rows of U (z floats) and of V (tb floats) go to LDS with
+// 16-byte LDS-direct loads; two buffers alternate.  Lane halves feed the two k-slices of an MFMA with
+// channels c2 and c2 + alpha/2.
+template <int MBW, int NBW, int LB>
+__global__ void __launch_bounds__(LB)
+wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, float* __restrict__ Mp,
+                    const float* __restrict__ zeros, WinoGeom g)
+{
+    extern __shared__ float lds[];
+    const int tid = threadIdx.x, T = blockDim.x;
+    const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int nbk = g.K / g.z, nbt = g.tiles_pitch / g.tb;
+    int bid = blockIdx.x;
+    const int nblk = gridDim.x;
+    if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
+    const int kb = bid % nbk; bid /= nbk;
+    const int tbk = bid % nbt;
+    const int xi = bid / nbt;
+    const int k0 = kb * g.z, t0 = tbk * g.tb;
+    const float* Up = U + (size_t)xi * g.C * g.K + k0;
+    const float* Vp = V + (size_t)xi * g.C * g.tiles_pitch + t0;
+
+    const int half_c = g.alpha >> 1;
+    const int ufloats = g.alpha * g.z;
+    const int stage_floats = g.alpha * (g.z + g.tb);
+    const int wm_i = wave % g.waves_m, wn_i = wave / g.waves_m;
+    const int abase = half * half_c * g.z + wm_i * MBW * 32 + l32;
+    const int bbase = ufloats + half * half_c * g.tb + wn_i * NBW * 32 + l32;
+
+    floatx16 acc[MBW][NBW];
+#pragma unroll
+    for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.f;
+
+    const int z4 = g.z >> 2, t4 = g.tb >> 2;
+    auto issue_stage = [&](int c0, float* buf) {
+        for (int e = tid; e < g.alpha * z4; e += T) {
+            const int row = e / z4, k4 = e - row * z4;
+            const float* src = (c0 + row < g.C) ? Up + (size_t)(c0 + row) * g.K + k4 * 4 : zeros;
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(buf + __builtin_amdgcn_readfirstlane(e - lane) * 4), 16, 0, 0);
+        }
+        for (int e = tid; e < g.alpha * t4; e += T) {
+            const int row = e / t4, q4 = e - row * t4;
+            const float* src = (c0 + row < g.C) ? Vp + (size_t)(c0 + row) * g.tiles_pitch + q4 * 4 : zeros;
+            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(buf + ufloats + __builtin_amdgcn_readfirstlane(e - lane) * 4), 16, 0, 0);
+        }
+    };
+
+    const int nstages = (g.C + g.alpha - 1) / g.alpha;
+    issue_stage(0, lds);
+    for (int s = 0; s < nstages; ++s) {
+        __syncthreads();
+        const float* cur = lds + (s & 1) * stage_floats;
+        if (s + 1 < nstages) issue_stage((s + 1) * g.alpha, lds + ((s + 1) & 1) * stage_floats);
+        for (int c2 = 0; c2 < half_c; ++c2) {
+            float a[MBW], bv[NBW];
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb) a[mb] = cur[abase + c2 * g.z + mb * 32];
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb) bv[nb] = cur[bbase + c2 * g.tb + nb * 32];
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb], bv[nb], acc[mb][nb], 0, 0, 0);
+        }
+    }
+
+    float* mp = Mp + ((size_t)xi * g.K + k0) * g.tiles_pitch + t0;
+#pragma unroll
+    for (int nb = 0; nb < NBW; ++nb) {
+        const int tcol = (wn_i * NBW + nb) * 32 + l32;
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb) {
+            const int kbase = (wm_i * MBW + mb) * 32 + 4 * half;
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                mp[(size_t)(kbase + 8 * (i >> 2) + (i & 3)) * g.tiles_pitch + tcol] = acc[mb][nb][i];
+        }
+    }
+}
+
+template <int MBW, int NBW, int LB>
+hipError_t launch_product_one(const float* U, const float* V, float* Mp, const float* zeros, const WinoGeom& g,
+                              int grid, int threads, size_t shm, hipStream_t st)
+{
+    auto kern = wino_product_kernel<MBW, NBW, LB>;
+    static bool raised = false;
+    if (shm > 64 * 1024 && !raised) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), shm, st, U, V, Mp, zeros, g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom& g, hipStream_t st)
+{
+    const size_t n = (size_t)g.C * g.K;
+    const int grid = (int)((n + 255) / 256);
+    if (g.m == 2) hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.K);
+    else          hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.K);
+    return hipGetLastError();
+}
+
+hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom& g, hipStream_t st)
+{
+    if (g.C > 65535) return hipErrorInvalidValue;
+    dim3 grid((g.tiles + 255) / 256, g.C);
+    if (g.m == 2) hipLaunchKernelGGL(input_transform<2>, grid, dim3(256), 0, st, x, V, g);
+    else          hipLaunchKernelGGL(input_transform<4>, grid, dim3(256), 0, st, x, V, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeom& g, hipStream_t st)
+{
+    if (g.K > 65535) return hipErrorInvalidValue;
+    dim3 grid((g.tiles + 255) / 256, g.K);
+    if (g.m == 2) hipLaunchKernelGGL(output_transform<2>, grid, dim3(256), 0, st, Mp, y, g);
+    else          hipLaunchKernelGGL(output_transform<4>, grid, dim3(256), 0, st, Mp, y, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const float* zeros,
+                               const WinoGeom& g, hipStream_t st)
+{
+    if (g.tb % 32 || g.z % 32 || (g.alpha & 1) || g.K % g.z || g.tiles_pitch % g.tb) return hipErrorInvalidValue;
+    const int MB = g.z / 32, NB = g.tb / 32;
+    if (MB % g.waves_m || NB % g.waves_n) return hipErrorInvalidValue;
+    const int mbw = MB / g.waves_m, nbw = NB / g.waves_n;
+    const int threads = 64 * g.waves_m * g.waves_n;
+    if (threads > 1024 || 16 * mbw * nbw + 64 > 131072 / threads) return hipErrorInvalidValue;
+    const size_t shm = 2 * sizeof(float) * (size_t)g.alpha * (g.z + g.tb);
+    if (shm > 160 * 1024) return hipErrorInvalidValue;
+    const int n = g.m + 2;
+    const long long grid_ll = (long long)n * n * (g.K / g.z) * (g.tiles_pitch / g.tb);
+    if (grid_ll > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int grid = (int)grid_ll;
+#define IOLB_CASE(M_, N_)                                                                                      \
+    if (mbw == M_ && nbw == N_) {                                                                              \
+        if (threads <= 256) return launch_product_one<M_, N_, 256>(U, V, Mp, zeros, g, grid, threads, shm, st); \
+        if (threads <= 512) return launch_product_one<M_, N_, 512>(U, V, Mp, zeros, g, grid, threads, shm, st); \
+        if constexpr (M_ * N_ <= 4)                                                                            \
+            return launch_product_one<M_, N_, 1024>(U, V, Mp, zeros, g, grid, threads, shm, st);               \
+    }
+    IOLB_CASE(1, 1) IOLB_CASE(1, 2) IOLB_CASE(1, 3) IOLB_CASE(1, 4)
+    IOLB_CASE(1, 5) IOLB_CASE(1, 6) IOLB_CASE(1, 7) IOLB_CASE(1, 8)
+    IOLB_CASE(2, 1) IOLB_CASE(2, 2) IOLB_CASE(2, 3) IOLB_CASE(2, 4)
+#undef IOLB_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace iolb

@@ -1,0 +1,112 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, and its
+tuner / bound figures agree with the oracle (bit-exactly for every integer).  No GPU needed."""
+import os
+import re
+
+import pytest
+
+from oracle import iolb_oracle as o
+from paper_2012_15667_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "iolbconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b((?:conv|iolb)_[a-z_0-9]+)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    declared = _declared_symbols()
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_strerror():
+    L = B.lib()
+    assert L.iolb_strerror(0) == b"success"
+    assert b"tile" in L.iolb_strerror(-3)
+
+
+def _shape(N, C, H, W, K, R=3, S=3, stride=1, pad=1, algo=0):
+    return dict(N=N, C=C, H=H, W=W, K=K, R=R, S=S, stride=stride, pad=pad, algo=algo)
+
+
+SHAPES = [
+    _shape(1, 16, 14, 14, 16), _shape(8, 64, 28, 28, 64, algo=1), _shape(32, 64, 56, 56, 64),
+    _shape(64, 256, 14, 14, 256, algo=2), _shape(64, 256, 14, 14, 256), _shape(64, 3, 224, 224, 64),
+    _shape(64, 128, 112, 112, 128), _shape(64, 256, 56, 56, 256), _shape(64, 512, 28, 28, 512),
+    _shape(64, 3, 224, 224, 64, algo=1), _shape(64, 128, 112, 112, 128, algo=2), _shape(64, 512, 28, 28, 512, algo=1),
+    _shape(16, 3, 227, 227, 96, 11, 11, 4, 0), _shape(16, 96, 27, 27, 256, 5, 5, 1, 2),
+    _shape(16, 256, 13, 13, 384), _shape(16, 384, 13, 13, 256, algo=2), _shape(16, 256, 13, 13, 384, algo=1),
+    _shape(2, 8, 16, 16, 32, 1, 1, 1, 0), _shape(3, 5, 9, 7, 6), _shape(4, 32, 32, 32, 64), _shape(4, 32, 32, 32, 64, algo=2),
+    _shape(2, 6, 20, 12, 96, 3, 3, 2, 1), _shape(1, 1, 1, 1, 1, 1, 1, 1, 0), _shape(5, 7, 11, 13, 17, 2, 3, 1, 1),
+]
+BUDGETS = [(0, 0), (32768, 64), (163840, 128), (8192, 32)]
+
+
+@pytest.mark.parametrize("s", SHAPES)
+@pytest.mark.parametrize("lds,vg", BUDGETS)
+def test_tuner_bit_exact_against_oracle(s, lds, vg):
+    want = o.tune(s, lds or 81920, vg or 128)
+    sh = B.make_shape(**s)
+    if want is None:
+        with pytest.raises(B.IolbError) as e:
+            B.iolb_tune(sh, lds, vg)
+        assert e.value.code == -3
+    else:
+        assert B.iolb_tune(sh, lds, vg) == want
+
+
+@pytest.mark.parametrize("s", SHAPES[:9] + SHAPES[12:14] + SHAPES[18:])
+@pytest.mark.parametrize("box", [True, False])
+def test_enumeration_bit_exact_and_in_order(s, box):
+    want = [c for _, c in sorted(o.candidates(s, use_f3=box), key=lambda kc: kc[0])]
+    got = B.iolb_enumerate(B.make_shape(**s), 0, 0, box)
+    assert got == want
+
+
+def test_random_small_shapes_bit_exact():
+    import random
+    rnd = random.Random(5)
+    for _ in range(150):
+        R = rnd.choice([1, 2, 3, 5])
+        s = _shape(rnd.choice([1, 2, 4, 6, 8]), rnd.randint(1, 40), rnd.randint(5, 40), rnd.randint(5, 40),
+                   rnd.choice([8, 16, 24, 32, 64, 96]), R, rnd.choice([1, 2, 3]), rnd.choice([1, 2]), rnd.choice([0, 1, 2]))
+        if s["H"] + 2 * s["pad"] < s["R"] or s["W"] + 2 * s["pad"] < s["S"]:
+            continue
+        want = o.tune(s)
+        sh = B.make_shape(**s)
+        if want is None:
+            with pytest.raises(B.IolbError):
+                B.iolb_tune(sh)
+        else:
+            assert B.iolb_tune(sh) == want, s
+
+
+@pytest.mark.parametrize("s", SHAPES[:12])
+@pytest.mark.parametrize("Sf", [2, 20480, 40960, 44_000_000])
+def test_bounds_match_oracle(s, Sf):
+    got = B.iolb_bounds(B.make_shape(**s), Sf)
+    want = o.bounds(s, Sf)
+    for k in ("P", "Q", "vertices", "compulsory_elems", "q_write_elems"):
+        assert got[k] == want[k], k
+    for k in ("t_bound_2s", "q_lower_lead", "q_lower_explicit", "q_dataflow"):
+        assert got[k] == pytest.approx(want[k], rel=1e-12, abs=1e-9), k
+
+
+def test_invalid_arguments_are_rejected_without_a_gpu():
+    with pytest.raises(B.IolbError) as e:
+        B.iolb_tune(B.make_shape(0, 1, 4, 4, 1))
+    assert e.value.code == -1
+    with pytest.raises(B.IolbError) as e:
+        B.iolb_tune(B.make_shape(1, 1, 4, 4, 32, 5, 5, 1, 1, algo=1))
+    assert e.value.code == -2
+    with pytest.raises(B.IolbError) as e:
+        B.iolb_tune(B.make_shape(1, 1, 2, 2, 1, 5, 5, 1, 0))
+    assert e.value.code == -1
+    assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 3) == 0
+    assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 4) > 0

@@ -1,0 +1,205 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerances (max_i |g_i - r_i| / max(|r_i|, rms(r)), fp32 GPU result against the fp64 oracle):
+direct convolution 1e-4, Winograd 5e-3 (both F(2x2) and F(4x4)).
+"""
+import numpy as np
+import pytest
+
+from oracle.conv_oracle import conv_ref, conv_ref_points
+from paper_2012_15667_amd.inputs import CONFIGS, layer_inputs, make_inputs, sample_output_indices
+from tests.conftest import rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL_DIRECT = 1e-4
+TOL_WINO = 5e-3
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' on a CPU box)")
+    from paper_2012_15667_amd import binding
+    binding.lib()          # a missing library must fail loudly, never fall back
+    return torch, binding
+
+
+def _run_direct(gpu, x, w, stride, pad, cfg=None):
+    torch, B = gpu
+    y = B.conv_direct(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), stride, pad, cfg=cfg)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def _run_wino(gpu, x, w, m, cfg=None):
+    torch, B = gpu
+    y = B.conv_winograd(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), m, cfg=cfg)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+# ---------------------------------------------------------------------------------------------
+# direct convolution
+# ---------------------------------------------------------------------------------------------
+
+DIRECT_CASES = [
+    # N, C, H, W, K, R, S, stride, pad
+    (1, 16, 14, 14, 16, 3, 3, 1, 1),       # config 1 (FMA path)
+    (2, 8, 16, 16, 32, 3, 3, 1, 1),        # smallest MFMA tiles
+    (4, 24, 16, 32, 64, 3, 3, 1, 1),       # several tiles, C not a multiple of 16
+    (2, 5, 16, 16, 32, 3, 3, 1, 1),        # odd C: zero-padded last stage
+    (8, 32, 28, 28, 96, 3, 3, 1, 1),       # 7 | extents, K = 3 * 32
+    (3, 7, 9, 11, 6, 3, 3, 1, 1),          # ragged everything (FMA path)
+    (2, 3, 35, 35, 32, 11, 11, 4, 0),      # down-scaled AlexNet conv1: stride 4, no padding
+    (2, 12, 27, 27, 64, 5, 5, 1, 2),       # conv2-like: 5x5, pad 2
+    (4, 16, 13, 13, 64, 3, 3, 1, 1),       # conv3/4 extent 13 (prime)
+    (4, 16, 32, 32, 64, 1, 1, 1, 0),       # 1x1: a plain GEMM
+    (2, 8, 32, 32, 32, 3, 3, 2, 1),        # stride 2
+    (2, 8, 16, 16, 32, 2, 3, 1, 0),        # non-square kernel
+    (1, 4, 64, 64, 32, 3, 3, 1, 0),        # pad 0
+]
+
+
+@pytest.mark.parametrize("case", DIRECT_CASES)
+def test_direct_matches_oracle(gpu, case):
+    N, C, H, W, K, R, S, stride, pad = case
+    x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=100 + C + H)
+    ref = conv_ref(x, w, stride, pad)
+    got = _run_direct(gpu, x, w, stride, pad)
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL_DIRECT
+
+
+def test_direct_config1_and_config3(gpu):
+    for name in ("cfg1", "cfg3"):
+        L = CONFIGS[name]
+        x, w = layer_inputs(L)
+        ref = conv_ref(x, w, L.stride, L.pad)
+        got = _run_direct(gpu, x, w, L.stride, L.pad)
+        assert rel_err(got, ref) <= TOL_DIRECT, name
+
+
+def test_direct_delta_kernel_is_bit_exact(gpu):
+    x, _ = make_inputs(4, 32, 16, 16, 32, 3, 3, seed=9)
+    w = np.zeros((32, 32, 3, 3), dtype=np.float32)
+    for k in range(32):
+        w[k, k, 1, 1] = 1.0
+    got = _run_direct(gpu, x, w, 1, 1)
+    assert np.array_equal(got, x)
+
+
+def test_direct_every_enumerated_path_agrees(gpu):
+    """A sample of the tiles the exhaustive sweep times: each must give the same layer."""
+    torch, B = gpu
+    N, C, H, W, K = 4, 16, 28, 28, 64
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=77)
+    ref = conv_ref(x, w, 1, 1)
+    tiles = B.iolb_enumerate(B.make_shape(N, C, H, W, K), 0, 0, False)
+    assert len(tiles) > 10
+    step = max(1, len(tiles) // 12)
+    for cfg in tiles[::step]:
+        got = _run_direct(gpu, x, w, 1, 1, cfg=cfg)
+        assert rel_err(got, ref) <= TOL_DIRECT, cfg
+
+
+@pytest.mark.parametrize("name", ["cfg5a", "cfg5b", "cfg5c", "cfg5d"])
+def test_direct_full_size_sampled(gpu, name):
+    """Full-size VGG-style layers in the launch configuration the benchmark times; 4096 sampled
+    outputs (corners included) are recomputed one by one by the oracle."""
+    L = CONFIGS[name]
+    x, w = layer_inputs(L)
+    got = _run_direct(gpu, x, w, 1, 1)
+    idx = sample_output_indices(L.N, L.K, L.H, L.W, 4096, seed=L.seed)
+    ref = conv_ref_points(x, w, idx, 1, 1)
+    g = got[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+    assert rel_err(g, ref) <= TOL_DIRECT
+    assert np.isfinite(got).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# Winograd
+# ---------------------------------------------------------------------------------------------
+
+WINO_CASES = [
+    # m, N, C, H, W, K
+    (2, 2, 8, 8, 8, 32),
+    (2, 1, 6, 7, 9, 32),         # ragged sub-domains
+    (2, 4, 20, 28, 28, 64),
+    (4, 2, 8, 16, 16, 32),
+    (4, 3, 10, 14, 14, 64),      # 14 = 3.5 sub-domains of 4
+    (4, 2, 16, 13, 13, 96),      # AlexNet conv3/4 extent
+    (4, 1, 3, 5, 37, 32),        # smaller than one sub-domain in height; odd C
+]
+
+
+@pytest.mark.parametrize("case", WINO_CASES)
+def test_winograd_matches_direct_oracle(gpu, case):
+    m, N, C, H, W, K = case
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u11", "he", seed=200 + m + C)
+    ref = conv_ref(x, w, 1, 1)
+    got = _run_wino(gpu, x, w, m)
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL_WINO
+
+
+def test_winograd_config2_and_config4(gpu):
+    for name, m in (("cfg2", 2), ("cfg4", 4)):
+        L = CONFIGS[name]
+        x, w = layer_inputs(L)
+        ref = conv_ref(x, w, 1, 1)
+        got = _run_wino(gpu, x, w, m)
+        assert rel_err(got, ref) <= TOL_WINO, name
+
+
+def test_winograd_caller_workspace_and_tiles(gpu):
+    torch, B = gpu
+    m, N, C, H, W, K = 4, 4, 16, 16, 16, 64
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=31)
+    ref = conv_ref(x, w, 1, 1)
+    tiles = B.iolb_enumerate(B.make_shape(N, C, H, W, K, algo=B.WINO_F4), 0, 0, False)
+    step = max(1, len(tiles) // 6)
+    for cfg in tiles[::step]:
+        got = _run_wino(gpu, x, w, m, cfg=cfg)
+        assert rel_err(got, ref) <= TOL_WINO, cfg
+
+
+@pytest.mark.parametrize("name,m", [("cfg5a", 2), ("cfg5b", 4), ("cfg5c", 4), ("cfg5d", 2)])
+def test_winograd_full_size_sampled(gpu, name, m):
+    L = CONFIGS[name]
+    x, w = layer_inputs(L)
+    got = _run_wino(gpu, x, w, m)
+    idx = sample_output_indices(L.N, L.K, L.H, L.W, 4096, seed=L.seed + 50)
+    ref = conv_ref_points(x, w, idx, 1, 1)
+    g = got[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+    assert rel_err(g, ref) <= TOL_WINO
+    assert np.isfinite(got).all()
+
+
+# ---------------------------------------------------------------------------------------------
+# error paths (nothing is launched)
+# ---------------------------------------------------------------------------------------------
+
+def test_error_codes(gpu):
+    torch, B = gpu
+    x = torch.zeros((1, 4, 8, 8), device="cuda")
+    w = torch.zeros((32, 4, 3, 3), device="cuda")
+    y = torch.full((1, 32, 8, 8), 7.0, device="cuda")
+    with pytest.raises(B.IolbError) as e:
+        B.conv_winograd(x, w, 3, y=y)
+    assert e.value.code == -2
+    with pytest.raises(B.IolbError) as e:
+        B.conv_direct(x, w, 0, 1, y=y)
+    assert e.value.code == -1
+    bad = B.iolb_tune(B.make_shape(1, 4, 8, 8, 32))
+    bad["z"] = 5
+    with pytest.raises(B.IolbError) as e:
+        B.conv_direct(x, w, 1, 1, y=y, cfg=bad)
+    assert e.value.code == -1
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.IolbError) as e:
+        B.conv_winograd(x, w, 4, y=y, workspace=ws)
+    assert e.value.code == -4
+    torch.cuda.synchronize()
+    assert float(y.min()) == 7.0 and float(y.max()) == 7.0      # failed calls wrote nothing
