@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the forward convolution layer (direct and Winograd) on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic layers: every layer of the
+workload list below, each in the algorithm(s) named for it (tile pick, weight re-layout /
+Winograd transforms, the matrix-core kernel, the store).  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+# (config name, algorithms run in a step)
+WORKLOAD = [
+    ("cfg2", ["wino2"]),
+    ("cfg3", ["direct"]),
+    ("cfg4", ["wino4"]),
+    ("cfg5a", ["direct", "wino2", "wino4"]),
+    ("cfg5b", ["direct", "wino2", "wino4"]),
+    ("cfg5c", ["direct", "wino2", "wino4"]),
+    ("cfg5d", ["direct", "wino2", "wino4"]),
+]
+
+
+def direct_flops(L):
+    P = (L.H + 2 * L.pad - L.R) // L.stride + 1
+    Q = (L.W + 2 * L.pad - L.S) // L.stride + 1
+    return 2.0 * L.N * L.K * P * Q * L.C * L.R * L.S
+
+
+def wino_product_flops(L, m):
+    n = m + 2
+    tiles = L.N * (-(-L.H // m)) * (-(-L.W // m))
+    return 2.0 * n * n * tiles * L.C * L.K
+
+
+def cpu_baseline(budget_s=12.0):
+    """The CPU oracle as it stands, on a bounded sample: config 3 and config 4 whole, then images
+    of config 5c in groups of 8 until about `budget_s` seconds of oracle time have been spent."""
+    import numpy as np
+    from oracle.conv_oracle import conv_ref
+    from paper_2012_15667_amd.inputs import CONFIGS, layer_inputs
+    flops, secs, threads = 0.0, 0.0, 0
+    parts = []
+
+    def timed(L, x, w, label):
+        nonlocal flops, secs, threads
+        t0 = time.perf_counter()
+        _, threads = conv_ref(x, w, L.stride, L.pad, return_threads=True)
+        secs += time.perf_counter() - t0
+        flops += direct_flops(L) * (x.shape[0] / L.N)
+        parts.append(label)
+
+    for name in ("cfg3", "cfg4"):
+        L = CONFIGS[name]
+        x, w = layer_inputs(L)
+        timed(L, x, w, name)
+    L = CONFIGS["cfg5c"]
+    x, w = layer_inputs(L)
+    done = 0
+    while done < L.N and secs < budget_s:
+        timed(L, np.ascontiguousarray(x[done:done + 8]), w, "cfg5c[%d:%d]" % (done, done + 8))
+        done += 8
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": "fp64 7-loop oracle on config 3 and config 4 (whole layers) and the first %d images of "
+                      "config 5c: %.1f GFLOP in %.1f s" % (done, flops / 1e9, secs)}
+
+
+def read_traffic_note():
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary."""
+    path = os.path.join(ROOT, "profiles", "direct_mfma_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", default="", help="comma-separated subset of config names (profiling runs)")
+    ap.add_argument("--algos", default="", help="comma-separated subset of direct,wino2,wino4 (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (every figure is the one "
+              "GPU's throughput)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2012_15667_amd import binding as B
+    from paper_2012_15667_amd.inputs import CONFIGS, layer_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    torch.cuda.set_device(0)
+
+    only_layers = set(filter(None, args.layers.split(",")))
+    only_algos = set(filter(None, args.algos.split(",")))
+    jobs = []           # (Layer, algo, x, w, y)
+    for name, algos in WORKLOAD:
+        if only_layers and name not in only_layers:
+            continue
+        L = CONFIGS[name]
+        x, w = layer_inputs(L)
+        xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        yd = torch.empty((L.N, L.K, L.H, L.W), dtype=torch.float32, device="cuda")
+        for a in algos:
+            if only_algos and a not in only_algos:
+                continue
+            jobs.append((L, a, xd, wd, yd))
+    torch.cuda.synchronize()
+
+    def run(job):
+        L, a, xd, wd, yd = job
+        if a == "direct":
+            B.conv_direct(xd, wd, L.stride, L.pad, y=yd)
+        else:
+            B.conv_winograd(xd, wd, 2 if a == "wino2" else 4, y=yd)
+
+    def step():
+        for job in jobs:
+            run(job)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps steps, main kernels bracketed by HIP events ------------
+    B.timing_read(B.TIME_DIRECT); B.timing_read(B.TIME_WINO_PRODUCT)
+    B.timing_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    B.timing_enable(False)
+    n_direct, ms_direct = B.timing_read(B.TIME_DIRECT)
+    n_wino, ms_wino = B.timing_read(B.TIME_WINO_PRODUCT)
+
+    flops_step = sum(direct_flops(j[0]) for j in jobs)
+    direct_alg_flops = sum(direct_flops(j[0]) for j in jobs if j[1] == "direct")
+    wino_alg_flops = sum(wino_product_flops(j[0], 2 if j[1] == "wino2" else 4) for j in jobs if j[1] != "direct")
+
+    # ---- per-layer figures (outside the timed region) ------------------------------------------
+    layers = []
+    for job in jobs:
+        L, a = job[0], job[1]
+        reps = 5
+        run(job)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            run(job)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino4": B.WINO_F4}[a]
+        shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
+        tile = B.iolb_tune(shape)
+        bnd = B.iolb_bounds(shape, 40960)
+        layers.append({
+            "layer": L.name, "algo": a, "ms": round(ms, 4),
+            "tflops_direct_equiv": round(direct_flops(L) / ms / 1e9, 2),
+            "tile": {k: tile[k] for k in ("b", "x", "y", "z", "alpha", "threads", "path")},
+            "compulsory_MB": round(4 * bnd["compulsory_elems"] / 1e6, 2),
+            "io_lower_bound_lead_MB_at_160KB": round(4 * bnd["q_lower_lead"] / 1e6, 2),
+            "modelled_read_MB": round(4 * tile["q_read_elems"] / 1e6, 2),
+        })
+
+    ms_step = 1e3 * elapsed / args.steps
+    value = flops_step / (elapsed / args.steps) / 1e12
+    roofline = None
+    if n_direct:
+        achieved = direct_alg_flops * args.steps / (ms_direct * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "direct_mfma_kernel (all instantiations in the step)",
+                    "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
+                    "avg_launch_ms": round(ms_direct / n_direct, 4), "launches": n_direct,
+                    "traffic": read_traffic_note()}
+    wino_roofline = None
+    if n_wino:
+        achieved_w = wino_alg_flops * args.steps / (ms_wino * 1e-3) / 1e12
+        wino_roofline = {"bound": "mfma", "kernel": "wino_product_kernel (all instantiations in the step)",
+                         "achieved": round(achieved_w, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(achieved_w / PEAK_FP32_MFMA_TFLOPS, 4),
+                         "avg_launch_ms": round(ms_wino / n_wino, 4), "launches": n_wino}
+
+    out = {
+        "metric": "TFLOP/s per conv layer (direct & Winograd) + HBM bytes / I/O lower bound",
+        "value": round(value, 3), "unit": "TFLOP/s (direct-conv-equivalent FLOPs, whole step)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "configs 2-5: " + ", ".join("%s[%s]" % (j[0].name, j[1]) for j in jobs),
+                   "convs_per_step": len(jobs), "direct_equiv_gflop_per_step": round(flops_step / 1e9, 1)},
+        "roofline": roofline,
+        "roofline_winograd_product": wino_roofline,
+        "layers": layers,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

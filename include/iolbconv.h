@@ -123,12 +123,14 @@ int iolb_bounds(const iolb_shape* shape, int64_t S_f_elems, iolb_bounds_out* out
 /* Stream (a hipStream_t) later calls enqueue on; NULL selects the null stream. */
 int iolb_set_stream(void* hip_stream);
 
-/* Timing hook for benchmarks: when enabled, the main kernel of each conv call (the direct
- * convolution kernel, or the Winograd batched product) is bracketed by HIP events on the
- * call's stream.  iolb_timing_read waits for the recorded events, returns the number of
- * launches timed since the last read and their total duration in milliseconds, and resets. */
+/* Timing hook for benchmarks: when enabled, the main kernel of each conv call is bracketed by
+ * HIP events on the call's stream.  Kinds: the direct-convolution kernel (IOLB_TIME_DIRECT) and
+ * the Winograd batched product (IOLB_TIME_WINO_PRODUCT).  iolb_timing_read waits for the recorded
+ * events of one kind, returns how many launches were timed since the last read of that kind and
+ * their total duration in milliseconds, and forgets them. */
+enum { IOLB_TIME_DIRECT = 0, IOLB_TIME_WINO_PRODUCT = 1 };
 int iolb_timing_enable(int on);
-int iolb_timing_read(int* launches, float* total_ms);
+int iolb_timing_read(int kind, int* launches, float* total_ms);
 
 /* Frees the library's device workspace (it is otherwise kept until the process ends). */
 int iolb_release_workspace(void);

@@ -84,7 +84,7 @@ def lib():
         L.iolb_timing_enable.restype = i
         L.iolb_timing_enable.argtypes = [i]
         L.iolb_timing_read.restype = i
-        L.iolb_timing_read.argtypes = [ctypes.POINTER(i), ctypes.POINTER(ctypes.c_float)]
+        L.iolb_timing_read.argtypes = [i, ctypes.POINTER(i), ctypes.POINTER(ctypes.c_float)]
         L.iolb_release_workspace.restype = i
         L.iolb_release_workspace.argtypes = []
         L.iolb_strerror.restype = ctypes.c_char_p
@@ -150,12 +150,15 @@ def conv_direct(x, w, stride=1, pad=0, y=None, cfg=None):
     K, C2, R, S = w.shape
     if C2 != C:
         raise ValueError("channel mismatch")
-    if y is None:
-        if stride < 1 or pad < 0 or H + 2 * pad < R or W + 2 * pad < S:
-            raise IolbError(-1, "invalid argument")
-        P = (H + 2 * pad - R) // stride + 1
-        Q = (W + 2 * pad - S) // stride + 1
-        y = torch.empty((N, K, P, Q), dtype=torch.float32, device=x.device)
+    valid = stride >= 1 and pad >= 0 and H + 2 * pad >= R and W + 2 * pad >= S
+    if valid:
+        shape = (N, K, (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1)
+        if y is None:
+            y = torch.empty(shape, dtype=torch.float32, device=x.device)
+        elif tuple(y.shape) != shape:
+            raise ValueError("y has the wrong shape")
+    elif y is None:
+        raise IolbError(-1, "invalid argument")
     _use_current_stream()
     args = (_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, R, S, stride, pad)
     if cfg is None:
@@ -203,11 +206,14 @@ def timing_enable(on=True):
     _check(lib().iolb_timing_enable(int(on)))
 
 
-def timing_read():
-    """(launches, total_ms) of the main kernels timed since the last read."""
+TIME_DIRECT, TIME_WINO_PRODUCT = 0, 1
+
+
+def timing_read(kind):
+    """(launches, total_ms) of the main kernels of `kind` timed since the last read."""
     n = ctypes.c_int(0)
     ms = ctypes.c_float(0)
-    _check(lib().iolb_timing_read(ctypes.byref(n), ctypes.byref(ms)))
+    _check(lib().iolb_timing_read(kind, ctypes.byref(n), ctypes.byref(ms)))
     return n.value, ms.value
 
 

@@ -74,12 +74,13 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // ---- timing hook --------------------------------------------------------------------------
 bool g_timing = false;
-std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events[2];
 
 struct MainKernelTimer {
     hipEvent_t a = nullptr, b = nullptr;
     bool on;
-    explicit MainKernelTimer(hipStream_t st) : on(g_timing)
+    int kind;
+    MainKernelTimer(hipStream_t st, int kind_) : on(g_timing), kind(kind_)
     {
         if (!on) return;
         if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { on = false; return; }
@@ -89,7 +90,7 @@ struct MainKernelTimer {
     {
         if (!on) return;
         hipEventRecord(b, st);
-        g_events.emplace_back(a, b);
+        { std::lock_guard<std::mutex> lock(g_mutex); g_events[kind].emplace_back(a, b); }
     }
 };
 
@@ -163,11 +164,11 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
         if (rc != IOLB_OK) return rc;
         float* wt = static_cast<float*>(dev->ws);
         IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, s.C * s.R * s.S, st));
-        MainKernelTimer timer(st);
+        MainKernelTimer timer(st, IOLB_TIME_DIRECT);
         IOLB_HIP(iolb::launch_direct_mfma(x, wt, y, dev->zeros, g, st));
         timer.stop(st);
     } else {
-        MainKernelTimer timer(st);
+        MainKernelTimer timer(st, IOLB_TIME_DIRECT);
         IOLB_HIP(iolb::launch_direct_fma(x, w, y, g, st));
         timer.stop(st);
     }
@@ -234,7 +235,7 @@ int run_winograd(const float* x, const float* w, float* y, const iolb_shape& s, 
     hipStream_t st = t_stream;
     IOLB_HIP(iolb::launch_wino_kernel_transform(w, U, g, st));
     IOLB_HIP(iolb::launch_wino_input_transform(x, V, g, st));
-    MainKernelTimer timer(st);
+    MainKernelTimer timer(st, IOLB_TIME_WINO_PRODUCT);
     IOLB_HIP(iolb::launch_wino_product(U, V, M, dev->zeros, g, st));
     timer.stop(st);
     IOLB_HIP(iolb::launch_wino_output_transform(M, y, g, st));
@@ -331,14 +332,14 @@ int iolb_timing_enable(int on)
     return IOLB_OK;
 }
 
-int iolb_timing_read(int* launches, float* total_ms)
+int iolb_timing_read(int kind, int* launches, float* total_ms)
 {
-    if (!launches || !total_ms) return IOLB_EINVAL;
+    if (!launches || !total_ms || kind < 0 || kind > 1) return IOLB_EINVAL;
     std::lock_guard<std::mutex> lock(g_mutex);
     float sum = 0.f;
     int count = 0;
     int rc = IOLB_OK;
-    for (auto& ev : g_events) {
+    for (auto& ev : g_events[kind]) {
         float ms = 0.f;
         hipError_t e = hipEventSynchronize(ev.second);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev.first, ev.second);
@@ -347,7 +348,7 @@ int iolb_timing_read(int* launches, float* total_ms)
         hipEventDestroy(ev.first);
         hipEventDestroy(ev.second);
     }
-    g_events.clear();
+    g_events[kind].clear();
     *launches = count;
     *total_ms = sum;
     return rc;
