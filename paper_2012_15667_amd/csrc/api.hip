@@ -14,9 +14,6 @@
 
 namespace {
 
-// A few zero words in device memory: the source of every padded element the LDS-direct loads fetch.
-__device__ __align__(256) float g_zero_words[64];
-
 thread_local hipStream_t t_stream = nullptr;
 thread_local std::string t_hip_error;
 
@@ -32,7 +29,6 @@ int hip_fail(hipError_t e)
     } while (0)
 
 struct DeviceState {
-    float* zeros = nullptr;
     void* ws = nullptr;
     size_t ws_bytes = 0;
 };
@@ -44,13 +40,7 @@ int device_state(DeviceState** out)
     int dev = 0;
     IOLB_HIP(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lock(g_mutex);
-    DeviceState& d = g_devices[dev];
-    if (!d.zeros) {
-        void* p = nullptr;
-        IOLB_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_zero_words)));
-        d.zeros = static_cast<float*>(p);
-    }
-    *out = &d;
+    *out = &g_devices[dev];
     return IOLB_OK;
 }
 
@@ -159,13 +149,14 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     if ((int64_t)g.nbx * g.nby * g.nbn * g.nbk > 0x7fffffffLL) return IOLB_EINVAL;
     hipStream_t st = t_stream;
     if (cfg.path == IOLB_PATH_MFMA) {
-        const size_t wbytes = sizeof(float) * (size_t)s.K * s.C * s.R * s.S;
+        const int c_padded = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;     // whole stages
+        const size_t wbytes = sizeof(float) * (size_t)s.K * c_padded * s.R * s.S;
         rc = ensure_workspace(dev, align256(wbytes));
         if (rc != IOLB_OK) return rc;
         float* wt = static_cast<float*>(dev->ws);
-        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, s.C * s.R * s.S, st));
+        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, s.C * s.R * s.S, c_padded * s.R * s.S, st));
         MainKernelTimer timer(st, IOLB_TIME_DIRECT);
-        IOLB_HIP(iolb::launch_direct_mfma(x, wt, y, dev->zeros, g, st));
+        IOLB_HIP(iolb::launch_direct_mfma(x, wt, y, g, st));
         timer.stop(st);
     } else {
         MainKernelTimer timer(st, IOLB_TIME_DIRECT);
@@ -185,11 +176,12 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
     g->tb = cfg.x / m;
     g->z = cfg.z;
     g->alpha = cfg.alpha;
+    g->Cp = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;
     g->waves_m = cfg.waves_m;
     g->waves_n = cfg.waves_n;
     const int64_t pitch = (tiles + g->tb - 1) / g->tb * g->tb;
     const int64_t n2 = (int64_t)(m + 2) * (m + 2);
-    if (n2 * s.C * pitch >= (1LL << 31) || n2 * s.K * pitch >= (1LL << 31)) return IOLB_EINVAL;
+    if (n2 * g->Cp * pitch >= (1LL << 31) || n2 * s.K * pitch >= (1LL << 31)) return IOLB_EINVAL;
     g->tiles = (int)tiles;
     g->tiles_pitch = (int)pitch;
     return IOLB_OK;
@@ -226,7 +218,7 @@ int run_winograd(const float* x, const float* w, float* y, const iolb_shape& s, 
     iolb::WinoGeom g{};
     rc = winograd_geom(s, cfg, &g);
     if (rc != IOLB_OK) return rc;
-    const WinoWorkspace l = winograd_layout(s.C, s.K, g.m, g.tiles_pitch);
+    const WinoWorkspace l = winograd_layout(g.Cp, s.K, g.m, g.tiles_pitch);
     if (!ws || ws_bytes < l.total || (reinterpret_cast<uintptr_t>(ws) & 255)) return IOLB_EWORKSPACE;
     char* base = static_cast<char*>(ws);
     float* U = reinterpret_cast<float*>(base + l.u_off);
@@ -236,7 +228,7 @@ int run_winograd(const float* x, const float* w, float* y, const iolb_shape& s, 
     IOLB_HIP(iolb::launch_wino_kernel_transform(w, U, g, st));
     IOLB_HIP(iolb::launch_wino_input_transform(x, V, g, st));
     MainKernelTimer timer(st, IOLB_TIME_WINO_PRODUCT);
-    IOLB_HIP(iolb::launch_wino_product(U, V, M, dev->zeros, g, st));
+    IOLB_HIP(iolb::launch_wino_product(U, V, M, g, st));
     timer.stop(st);
     IOLB_HIP(iolb::launch_wino_output_transform(M, y, g, st));
     return IOLB_OK;
@@ -279,7 +271,7 @@ size_t conv_winograd_workspace_bytes(int N, int C, int H, int W, int K, int m)
     if (make_wino_shape(N, C, H, W, K, m, &s) != IOLB_OK) return 0;
     // large enough for every tile the enumeration can produce: blocks hold at most 1024 sub-domains
     const int64_t tiles = (int64_t)N * ((H + m - 1) / m) * ((W + m - 1) / m);
-    return winograd_layout(C, K, m, tiles + 1024).total;
+    return winograd_layout(C + 15, K, m, tiles + 1024).total;     // stages hold at most 16 channels
 }
 
 int conv_winograd_ws(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m,

@@ -15,30 +15,28 @@
 // Inside one MFMA the two k-slices are fed by lane halves: lanes 0-31 take channel c2, lanes 32-63 take
 // channel c2 + alpha/2, so that both halves use the same LDS offset per (r, s).
 #include "kernels.h"
+#include "lds_dma.h"
 
 namespace iolb {
+
+#ifdef IOLB_TRACE
+__device__ long long g_trace[8 * 16 * 4];
+#define IOLB_STAMP(k) do { if (lane == 0 && s >= 8 && s < 24) s_trace[(wave * 16 + (s - 8)) * 4 + (k)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define IOLB_STAMP(k) do {} while (0)
+#endif
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-__device__ __forceinline__ void load_to_lds_4(const float* src, float* lds_wave_base)
-{
-    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)lds_wave_base, 4, 0, 0);
-}
-__device__ __forceinline__ void load_to_lds_16(const float* src, float* lds_wave_base)
-{
-    __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)lds_wave_base, 16, 0, 0);
-}
-
-template <int MBW, int NBW, int LB>
+template <int MBW, int NBW, int LB, int RR, int SS>
 __global__ void __launch_bounds__(LB)
-direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y,
-                   const float* __restrict__ zeros, DirectGeom g)
+direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y, DirectGeom g)
 {
     extern __shared__ float lds[];
+#ifdef IOLB_TRACE
+    __shared__ long long s_trace[8 * 16 * 4];
+#endif
     const int tid = threadIdx.x, T = blockDim.x;
     const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -86,61 +84,176 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
             for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.f;
 
     const int gy0 = y0 * g.stride - g.pad, gx0 = x0 * g.stride - g.pad;
-    const int z4 = g.z >> 2;
-    const int w_vec = g.alpha * RS * z4;                    // 16-byte elements in the weight slab
-    const int yxh = g.yh * g.xh;
+    const int nwaves = T >> 6;
+    const int tile_rows = g.b * g.yh;                       // rows of the input tile per channel
+    const int nseg = (g.xh + 63) >> 6;                      // 64-lane segments per tile row
+    const float* wslab = wt + k0;                           // row (c*RS + rs) of the slab starts at wslab + row*K
 
+    // Elements of the tile that fall outside the image are zero in every stage: clear both buffers
+    // once, then only ever load the elements that exist.
+    for (int i = tid; i < 2 * stage_floats; i += T) lds[i] = 0.f;
+    __syncthreads();
+
+    // first (tile row, segment) item of this wave
+    const int im_first = wave / (nseg * g.yh);
+    const int hy_first = (wave % (nseg * g.yh)) / nseg, seg_first = wave % nseg;
+
+    // Stage c0..c0+alpha-1 into buf.  Weights: alpha*RS rows of z floats, whole rows per instruction.
+    // Input tile: one instruction per (tile row, 64-lane segment, channel); the row's base address is
+    // wave-uniform, lanes add their column.  Channels at or beyond C (last stage when alpha does not
+    // divide C) are zero rows in wt and are cleared here for the tile.
     auto issue_stage = [&](int c0, float* buf) {
-        // weights: slab row (c, rs) holds z contiguous floats of wt
-        for (int e = tid; e < w_vec; e += T) {
-            const int row = e / z4, k4 = e - row * z4;
-            const int ch = c0 + row / RS;
-            const float* src = (ch < g.C) ? wt + ((size_t)(c0 * RS + row) * g.K + k0 + k4 * 4) : zeros;
-            load_to_lds_16(src, buf + __builtin_amdgcn_readfirstlane(e - lane) * 4);
-        }
-        // input tile: element h of the tile for each staged channel
-        for (int h = tid; h < g.halo; h += T) {
-            const int im = h / yxh, r2 = h - im * yxh;
-            const int hy = r2 / g.xh, hx = r2 - hy * g.xh;
-            const int gy = gy0 + hy, gx = gx0 + hx;
-            const bool inside = gy >= 0 && gy < g.H && gx >= 0 && gx < g.W;
-            const float* src0 = x + ((size_t)(n0 + im) * g.C + c0) * HW + gy * g.W + gx;
-            float* dst = buf + wfloats + __builtin_amdgcn_readfirstlane(h - lane);
-            for (int c = 0; c < g.alpha; ++c) {
-                const float* src = (inside && c0 + c < g.C) ? src0 + (size_t)c * HW : zeros;
-                load_to_lds_4(src, dst + c * g.halo);
+        stage_rows(wslab + (size_t)c0 * RS * g.K, g.K, g.z >> 2, g.alpha * RS, buf, wave, nwaves, lane);
+        float* xbuf = buf + wfloats;
+        int im = im_first, hy = hy_first, seg = seg_first;
+        for (int item = wave; item < tile_rows * nseg; item += nwaves) {
+            const int gy = gy0 + hy;
+            const int hx = seg * 64 + lane, gx = gx0 + hx;
+            if (gy >= 0 && gy < g.H && hx < g.xh && gx >= 0 && gx < g.W) {
+                const float* rowp = x + (((size_t)(n0 + im) * g.C + c0) * g.H + gy) * g.W;
+                const unsigned dst = lds_byte_address(xbuf + (im * g.yh + hy) * g.xh + seg * 64);
+                for (int c = 0; c < g.alpha && c0 + c < g.C; ++c)
+                    lds_dma_load_4(rowp + (size_t)c * HW, 4u * (unsigned)gx, dst + 4u * (unsigned)(c * g.halo));
             }
+            // next item of this wave: advance (im, hy, seg) by nwaves segments
+            seg += nwaves;
+            while (seg >= nseg) { seg -= nseg; ++hy; }
+            while (hy >= g.yh) { hy -= g.yh; ++im; }
         }
+        if (c0 + g.alpha > g.C)
+            for (int i = (g.C - c0) * g.halo + tid; i < g.alpha * g.halo; i += T) xbuf[i] = 0.f;
     };
 
     const int nstages = (g.C + g.alpha - 1) / g.alpha;
+    const int nsteps = half_c * RS;
+    const int step_r = g.xh - (g.S - 1);                          // tile offset increments at a row wrap
+    const int step_c = g.halo - (g.R - 1) * g.xh - (g.S - 1);     // ... and at a channel wrap
+    // Waves w and w+4 share a SIMD.  Each stages its part of the NEXT stage from inside the multiply
+    // phase of the current one, the second group half a stage later than the first, so that while one
+    // wave of a SIMD is busy issuing loads the other keeps the matrix core fed.
+    const int issue_group = (wave >> 2) & 1;
+
+    auto interleave_step = [&]() {
+        constexpr int MF = MBW * NBW, RD = MBW + NBW, PAIRS = (RD + 1) / 2;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (MF - 1 >= PAIRS) {
+#pragma unroll
+            for (int i = 0; i < PAIRS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+            if constexpr (MF - 1 - PAIRS > 0) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1 - PAIRS, 0);
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+            if constexpr (MF > 1) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1, 0);
+        }
+    };
+    auto multiply = [&](const float (&am)[MBW], const float (&bm)[NBW]) {
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
+    };
+
     issue_stage(0, lds);
     for (int s = 0; s < nstages; ++s) {
+        IOLB_STAMP(0);
+        lds_dma_wait_all();
+        IOLB_STAMP(1);
         __syncthreads();                                    // stage s has landed; stage s-1 is consumed
+        IOLB_STAMP(2);
         float* cur = lds + (s & 1) * stage_floats;
-        if (s + 1 < nstages) issue_stage((s + 1) * g.alpha, lds + ((s + 1) & 1) * stage_floats);
+        float* nxt = lds + ((s + 1) & 1) * stage_floats;
+#ifdef IOLB_EXP_NOISSUE
+        const bool more = false;
+#else
+        const bool more = s + 1 < nstages;
+#endif
+        const int c0_next = (s + 1) * g.alpha;
 
-        for (int c2 = 0; c2 < half_c; ++c2) {
-            const float* wrow = cur + abase + c2 * RS * g.z;
-            const int xoff_c = c2 * g.halo;
-            for (int r = 0; r < g.R; ++r) {
-                for (int sx = 0; sx < g.S; ++sx) {
-                    float a[MBW], bv[NBW];
+        bool done = false;
+        if constexpr (RR > 0) {
+            // Kernel extents known at compile time: the R*S steps of a channel pair are unrolled, so a
+            // step costs its LDS reads and a couple of address adds.  Bodies of two channel pairs keep
+            // the two operand register sets in phase; an odd number of pairs takes the general loop.
+            constexpr int RSc = RR * SS, BODY = 2 * RSc;
+            if ((half_c & 1) == 0) {
+                const int nbodies = half_c >> 1;
+                float fa[2][MBW], fb[2][NBW];
+                auto fetch = [&](int set, int bi, int t) {
+                    const int cl = t / RSc, rs = t % RSc, r = rs / SS, sx = rs % SS;
+                    const float* wp = cur + abase + ((2 * bi + cl) * RSc + rs) * g.z;
+                    const int sc = (2 * bi + cl) * g.halo + r * g.xh;
 #pragma unroll
-                    for (int mb = 0; mb < MBW; ++mb) a[mb] = wrow[mb * 32];
-                    const int xo = xoff_c + r * g.xh + sx;
+                    for (int mb = 0; mb < MBW; ++mb) fa[set][mb] = wp[mb * 32];
 #pragma unroll
-                    for (int nb = 0; nb < NBW; ++nb) bv[nb] = cur[bbase[nb] + xo];
+                    for (int nb = 0; nb < NBW; ++nb) fb[set][nb] = cur[bbase[nb] + sc + sx];
+                };
+                fetch(0, 0, 0);
+                for (int bi = 0; bi < nbodies; ++bi) {
+                    const int bnext = (bi + 1 < nbodies) ? bi + 1 : 0;   // after the last body: wrap, read and drop
 #pragma unroll
-                    for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-                        for (int nb = 0; nb < NBW; ++nb)
-                            acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb], bv[nb], acc[mb][nb], 0, 0, 0);
-                    wrow += g.z;
+                    for (int t = 0; t < BODY; ++t) {
+                        if (t == 0 || t == RSc) {
+                            if (more && bi == 0 && issue_group == (t == 0 ? 0 : 1)) issue_stage(c0_next, nxt);
+                        }
+                        if (t + 1 < BODY) fetch((t + 1) & 1, bi, t + 1);
+                        else              fetch(0, bnext, 0);
+                        multiply(fa[t & 1], fb[t & 1]);
+                        // Issue order inside the step: one MFMA, then the LDS reads of step t+1 two at a
+                        // time between the following MFMAs.  A wave then never has an MFMA-free stretch,
+                        // so two waves of a SIMD cannot both be off the matrix core at once.
+                        interleave_step();
+                    }
                 }
+                done = true;
             }
         }
+        if (!done) {
+            // General loop: steps j = (c2, r, s) flattened, two per iteration with two operand register
+            // sets; an odd step count is rounded up with a step whose weights are forced to zero.  After
+            // the last step the fetch wraps to step 0 (read and dropped).
+            const float* wrow = cur + abase;
+            int r = 0, sx = 0, xo = 0;              // position of the NEXT step to fetch
+            float a[MBW], bv[NBW], a1[MBW], b1[NBW];
+            auto fetch = [&](float (&an)[MBW], float (&bn)[NBW], bool last) {
+#pragma unroll
+                for (int mb = 0; mb < MBW; ++mb) an[mb] = wrow[mb * 32];
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb) bn[nb] = cur[bbase[nb] + xo];
+                // advance (r, s), the tile offset xo = c2*halo + r*xh + s and the weight row without branches
+                const int wrap_s = (sx + 1 == g.S), wrap_r = wrap_s & (r + 1 == g.R);
+                xo = last ? 0 : xo + (wrap_r ? step_c : (wrap_s ? step_r : 1));
+                wrow = last ? cur + abase : wrow + g.z;
+                sx = wrap_s ? 0 : sx + 1;
+                r = wrap_r ? 0 : r + wrap_s;
+            };
+            const int issue_at = issue_group ? ((nsteps >> 1) & ~1) : 0;
+            fetch(a, bv, nsteps == 1);
+#pragma unroll 1
+            for (int j = 0; j < nsteps; j += 2) {
+                if (more && j == issue_at) issue_stage(c0_next, nxt);
+                fetch(a1, b1, j + 2 >= nsteps);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(a, bv);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(a, bv, j + 3 >= nsteps);
+                if (j + 1 >= nsteps) {
+#pragma unroll
+                    for (int mb = 0; mb < MBW; ++mb) a1[mb] = 0.f;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(a1, b1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        IOLB_STAMP(3);
     }
+#ifdef IOLB_TRACE
+    __syncthreads();
+    if (blockIdx.x == 0) for (int i = tid; i < 8 * 16 * 4; i += T) g_trace[i] = s_trace[i];
+#endif
 
     // each partial sum is complete: write the block once.  Register i of a 32 x 32 block holds
     // channel 8*(i/4) + 4*half + i%4 of pixel l32.
@@ -157,9 +270,10 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     }
 }
 
-// w[K][CRS] -> wt[CRS][K] through a 32 x 33 LDS tile: both sides coalesced.
+// w[K][CRS] -> wt[rows][K] through a 32 x 33 LDS tile: both sides coalesced.  rows >= CRS; the rows
+// beyond CRS (channels added to fill the last stage) are written as zeros.
 __global__ void __launch_bounds__(256)
-weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int K, int CRS)
+weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int K, int CRS, int rows)
 {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
@@ -171,15 +285,15 @@ weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int 
     __syncthreads();
     for (int j = ty; j < 32; j += 8) {
         const int c = c0 + j, k = k0 + tx;
-        if (c < CRS && k < K) wt[(size_t)c * K + k] = tile[tx][j];
+        if (c < rows && k < K) wt[(size_t)c * K + k] = tile[tx][j];
     }
 }
 
-template <int MBW, int NBW, int LB>
-hipError_t launch_one(const float* x, const float* wt, float* y, const float* zeros, const DirectGeom& g,
+template <int MBW, int NBW, int LB, int RR, int SS>
+hipError_t launch_one(const float* x, const float* wt, float* y, const DirectGeom& g,
                       size_t shm, hipStream_t st)
 {
-    auto kern = direct_mfma_kernel<MBW, NBW, LB>;
+    auto kern = direct_mfma_kernel<MBW, NBW, LB, RR, SS>;
     static bool raised = false;               // dynamic LDS above 64 KB needs an opt-in, once per kernel
     if (shm > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -187,21 +301,27 @@ hipError_t launch_one(const float* x, const float* wt, float* y, const float* ze
         raised = true;
     }
     const int grid = g.nbk * g.nbx * g.nby * g.nbn;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(g.threads), shm, st, x, wt, y, zeros, g);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(g.threads), shm, st, x, wt, y, g);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, hipStream_t st)
+#ifdef IOLB_TRACE
+extern "C" int iolb_debug_trace(long long* host)
 {
-    dim3 grid((CRS + 31) / 32, (K + 31) / 32);
-    hipLaunchKernelGGL(weight_relayout_kernel, grid, dim3(256), 0, st, w, wt, K, CRS);
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(long long) * 8 * 16 * 4);
+}
+#endif
+
+hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int rows, hipStream_t st)
+{
+    dim3 grid((rows + 31) / 32, (K + 31) / 32);
+    hipLaunchKernelGGL(weight_relayout_kernel, grid, dim3(256), 0, st, w, wt, K, CRS, rows);
     return hipGetLastError();
 }
 
-hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const float* zeros,
-                              const DirectGeom& g, hipStream_t st)
+hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st)
 {
     const int npix = g.b * g.tx * g.ty;
     if (npix % 32 || g.z % 32 || (g.alpha & 1) || g.threads != 64 * g.waves_m * g.waves_n) return hipErrorInvalidValue;
@@ -214,11 +334,17 @@ hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const f
     // the register file of a compute unit holds 131072 lane-registers: a workgroup of T threads gets
     // 131072 / T per lane, of which 16 * mbw * nbw are partial sums
     if (16 * mbw * nbw + 64 > 131072 / g.threads) return hipErrorInvalidValue;
-#define IOLB_CASE(M_, N_)                                                                        \
-    if (mbw == M_ && nbw == N_) {                                                                \
-        if (g.threads <= 256) return launch_one<M_, N_, 256>(x, wt, y, zeros, g, shm, st);       \
-        if (g.threads <= 512) return launch_one<M_, N_, 512>(x, wt, y, zeros, g, shm, st);       \
-        if constexpr (M_ * N_ <= 4) return launch_one<M_, N_, 1024>(x, wt, y, zeros, g, shm, st); \
+#define IOLB_CASE(M_, N_)                                                                              \
+    if (mbw == M_ && nbw == N_) {                                                                      \
+        if (g.R == 3 && g.S == 3) {                                                                    \
+            if (g.threads <= 256) return launch_one<M_, N_, 256, 3, 3>(x, wt, y, g, shm, st);          \
+            if (g.threads <= 512) return launch_one<M_, N_, 512, 3, 3>(x, wt, y, g, shm, st);          \
+            if constexpr (M_ * N_ <= 4) return launch_one<M_, N_, 1024, 3, 3>(x, wt, y, g, shm, st);   \
+        } else {                                                                                       \
+            if (g.threads <= 256) return launch_one<M_, N_, 256, 0, 0>(x, wt, y, g, shm, st);          \
+            if (g.threads <= 512) return launch_one<M_, N_, 512, 0, 0>(x, wt, y, g, shm, st);          \
+            if constexpr (M_ * N_ <= 4) return launch_one<M_, N_, 1024, 0, 0>(x, wt, y, g, shm, st);   \
+        }                                                                                              \
     }
     IOLB_CASE(1, 1) IOLB_CASE(1, 2) IOLB_CASE(1, 3) IOLB_CASE(1, 4)
     IOLB_CASE(1, 5) IOLB_CASE(1, 6) IOLB_CASE(1, 7) IOLB_CASE(1, 8)

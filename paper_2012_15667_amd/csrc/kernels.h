@@ -20,18 +20,19 @@ struct DirectGeom {
     int xh, yh, halo;          // input tile extents and elements per channel (b * yh * xh)
 };
 
-// Re-layout w[K][C][R][S] -> wt[C][R][S][K] so that a stage's weight slab is contiguous in K.
-hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, hipStream_t st);
+// Re-layout w[K][C][R][S] -> wt[rows][K] (rows >= CRS = C*R*S; rows beyond CRS are zero) so that a
+// stage's weight slab is a run of rows contiguous in K.
+hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int rows, hipStream_t st);
 
 hipError_t launch_direct_fma(const float* x, const float* w, float* y, const DirectGeom& g, hipStream_t st);
-// zeros: at least 16 bytes of device memory holding 0.0f (source of padded elements).
-hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const float* zeros,
-                              const DirectGeom& g, hipStream_t st);
+// wt: re-laid-out weights with ceil(C/alpha)*alpha*R*S rows.
+hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st);
 
 // Winograd F(m x m, 3 x 3), unfused: kernel transform, input transform, batched product over the
 // (m+2)^2 planes, output transform (steps 1-4 of Sec. 4.3).
 struct WinoGeom {
     int N, C, H, W, K, m;      // P = H, Q = W (pad 1)
+    int Cp;                    // C rounded up to whole stages: U and V carry zero rows for c in [C, Cp)
     int th, tw;                // sub-domains along H_out and W_out
     int tiles;                 // N * th * tw
     int tiles_pitch;           // tiles rounded up to a whole number of blocks
@@ -40,8 +41,7 @@ struct WinoGeom {
 };
 hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom& g, hipStream_t st);
-hipError_t launch_wino_product(const float* U, const float* V, float* M, const float* zeros,
-                               const WinoGeom& g, hipStream_t st);
+hipError_t launch_wino_product(const float* U, const float* V, float* M, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_output_transform(const float* M, float* y, const WinoGeom& g, hipStream_t st);
 
 }  // namespace iolb

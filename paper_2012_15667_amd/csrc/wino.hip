@@ -14,14 +14,13 @@
 // The transform matrices are the Toom-Cook matrices for the points {0, 1, -1, inf} (m = 2) and
 // {0, 1, -1, 2, -2, inf} (m = 4).
 #include "kernels.h"
+#include "lds_dma.h"
 
 namespace iolb {
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __attribute__((address_space(1))) const void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
 
 template <int M> struct Mats;
 
@@ -80,22 +79,22 @@ __device__ __forceinline__ void right_mul_t(const float (&in)[ROWS][IN], const M
 // step 1b: one lane per (c, k); k runs fastest so the writes of a wave are contiguous
 template <int M>
 __global__ void __launch_bounds__(256)
-kernel_transform(const float* __restrict__ w, float* __restrict__ U, int C, int K)
+kernel_transform(const float* __restrict__ w, float* __restrict__ U, int C, int Cp, int K)
 {
     constexpr int n = Mats<M>::n;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)C * K) return;
+    if (idx >= (size_t)Cp * K) return;
     const int k = idx % K, c = idx / K;
     float g[3][3];
     const float* wp = w + ((size_t)k * C + c) * 9;
 #pragma unroll
     for (int i = 0; i < 3; ++i)
 #pragma unroll
-        for (int j = 0; j < 3; ++j) g[i][j] = wp[i * 3 + j];
+        for (int j = 0; j < 3; ++j) g[i][j] = (c < C) ? wp[i * 3 + j] : 0.f;     // rows [C, Cp) are zero
     float t[n][3], u[n][n];
     left_mul<n, 3, 3>(Mats<M>::L, g, t);
     right_mul_t<n, 3, n>(t, Mats<M>::L, u);
-    const size_t plane = (size_t)C * K;
+    const size_t plane = (size_t)Cp * K;
 #pragma unroll
     for (int i = 0; i < n; ++i)
 #pragma unroll
@@ -120,12 +119,12 @@ input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
 #pragma unroll
         for (int j = 0; j < n; ++j) {
             const int h = h0 + i, ww = w0 + j;
-            d[i][j] = (h >= 0 && h < g.H && ww >= 0 && ww < g.W) ? xp[(size_t)h * g.W + ww] : 0.f;
+            d[i][j] = (c < g.C && h >= 0 && h < g.H && ww >= 0 && ww < g.W) ? xp[(size_t)h * g.W + ww] : 0.f;
         }
     float tmp[n][n], v[n][n];
     left_mul<n, n, n>(Mats<M>::B, d, tmp);
     right_mul_t<n, n, n>(tmp, Mats<M>::B, v);
-    const size_t plane = (size_t)g.C * g.tiles_pitch;
+    const size_t plane = (size_t)g.Cp * g.tiles_pitch;
     float* vp = V + (size_t)c * g.tiles_pitch + t;
 #pragma unroll
     for (int i = 0; i < n; ++i)
@@ -170,8 +169,7 @@ output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g
 // channels c2 and c2 + alpha/2.
 template <int MBW, int NBW, int LB>
 __global__ void __launch_bounds__(LB)
-wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, float* __restrict__ Mp,
-                    const float* __restrict__ zeros, WinoGeom g)
+wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, float* __restrict__ Mp, WinoGeom g)
 {
     extern __shared__ float lds[];
     const int tid = threadIdx.x, T = blockDim.x;
@@ -186,8 +184,8 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
     const int tbk = bid % nbt;
     const int xi = bid / nbt;
     const int k0 = kb * g.z, t0 = tbk * g.tb;
-    const float* Up = U + (size_t)xi * g.C * g.K + k0;
-    const float* Vp = V + (size_t)xi * g.C * g.tiles_pitch + t0;
+    const float* Up = U + (size_t)xi * g.Cp * g.K + k0;
+    const float* Vp = V + (size_t)xi * g.Cp * g.tiles_pitch + t0;
 
     const int half_c = g.alpha >> 1;
     const int ufloats = g.alpha * g.z;
@@ -204,37 +202,60 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.f;
 
-    const int z4 = g.z >> 2, t4 = g.tb >> 2;
+    const int nwaves = T >> 6;
+    // rows [C, Cp) of U and V are zero, so every stage is alpha whole rows
     auto issue_stage = [&](int c0, float* buf) {
-        for (int e = tid; e < g.alpha * z4; e += T) {
-            const int row = e / z4, k4 = e - row * z4;
-            const float* src = (c0 + row < g.C) ? Up + (size_t)(c0 + row) * g.K + k4 * 4 : zeros;
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(buf + __builtin_amdgcn_readfirstlane(e - lane) * 4), 16, 0, 0);
-        }
-        for (int e = tid; e < g.alpha * t4; e += T) {
-            const int row = e / t4, q4 = e - row * t4;
-            const float* src = (c0 + row < g.C) ? Vp + (size_t)(c0 + row) * g.tiles_pitch + q4 * 4 : zeros;
-            __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(buf + ufloats + __builtin_amdgcn_readfirstlane(e - lane) * 4), 16, 0, 0);
-        }
+        stage_rows(Up + (size_t)c0 * g.K, g.K, g.z >> 2, g.alpha, buf, wave, nwaves, lane);
+        stage_rows(Vp + (size_t)c0 * g.tiles_pitch, g.tiles_pitch, g.tb >> 2, g.alpha, buf + ufloats, wave, nwaves, lane);
     };
 
     const int nstages = (g.C + g.alpha - 1) / g.alpha;
     issue_stage(0, lds);
     for (int s = 0; s < nstages; ++s) {
+        lds_dma_wait_all();
         __syncthreads();
         const float* cur = lds + (s & 1) * stage_floats;
         if (s + 1 < nstages) issue_stage((s + 1) * g.alpha, lds + ((s + 1) & 1) * stage_floats);
-        for (int c2 = 0; c2 < half_c; ++c2) {
-            float a[MBW], bv[NBW];
+        // operands of channel step c2+1 are fetched before the MFMAs of step c2 are issued; after the
+        // last step the fetch wraps to step 0 (read and dropped)
+        const float* ap = cur + abase;
+        const float* bp = cur + bbase;
+        float a[MBW], bv[NBW];
+        auto fetch = [&](float (&an)[MBW], float (&bn)[NBW], bool last) {
 #pragma unroll
-            for (int mb = 0; mb < MBW; ++mb) a[mb] = cur[abase + c2 * g.z + mb * 32];
+            for (int mb = 0; mb < MBW; ++mb) an[mb] = ap[mb * 32];
 #pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) bv[nb] = cur[bbase + c2 * g.tb + nb * 32];
+            for (int nb = 0; nb < NBW; ++nb) bn[nb] = bp[nb * 32];
+            ap = last ? cur + abase : ap + g.z;
+            bp = last ? cur + bbase : bp + g.tb;
+        };
+        auto multiply = [&](const float (&am)[MBW], const float (&bm)[NBW]) {
 #pragma unroll
             for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < NBW; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mb], bv[nb], acc[mb][nb], 0, 0, 0);
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
+        };
+        // two register sets, two steps per iteration; an odd step count is rounded up with a step
+        // whose A operand is forced to zero
+        float a1[MBW], b1[NBW];
+        fetch(a, bv, half_c == 1);
+#pragma unroll 1
+        for (int j = 0; j < half_c; j += 2) {
+            // sched_barrier(0): nothing may be moved across, so the LDS reads of the next step are
+            // issued before the MFMAs of the current one and have their whole duration to land
+            fetch(a1, b1, j + 2 >= half_c);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(a, bv);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(a, bv, j + 3 >= half_c);
+            if (j + 1 >= half_c) {
+#pragma unroll
+                for (int mb = 0; mb < MBW; ++mb) a1[mb] = 0.f;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -253,7 +274,7 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
 }
 
 template <int MBW, int NBW, int LB>
-hipError_t launch_product_one(const float* U, const float* V, float* Mp, const float* zeros, const WinoGeom& g,
+hipError_t launch_product_one(const float* U, const float* V, float* Mp, const WinoGeom& g,
                               int grid, int threads, size_t shm, hipStream_t st)
 {
     auto kern = wino_product_kernel<MBW, NBW, LB>;
@@ -263,7 +284,7 @@ hipError_t launch_product_one(const float* U, const float* V, float* Mp, const f
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), shm, st, U, V, Mp, zeros, g);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), shm, st, U, V, Mp, g);
     return hipGetLastError();
 }
 
@@ -271,17 +292,17 @@ hipError_t launch_product_one(const float* U, const float* V, float* Mp, const f
 
 hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom& g, hipStream_t st)
 {
-    const size_t n = (size_t)g.C * g.K;
+    const size_t n = (size_t)g.Cp * g.K;
     const int grid = (int)((n + 255) / 256);
-    if (g.m == 2) hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.K);
-    else          hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.K);
+    if (g.m == 2) hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K);
+    else          hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K);
     return hipGetLastError();
 }
 
 hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom& g, hipStream_t st)
 {
-    if (g.C > 65535) return hipErrorInvalidValue;
-    dim3 grid((g.tiles + 255) / 256, g.C);
+    if (g.Cp > 65535) return hipErrorInvalidValue;
+    dim3 grid((g.tiles + 255) / 256, g.Cp);
     if (g.m == 2) hipLaunchKernelGGL(input_transform<2>, grid, dim3(256), 0, st, x, V, g);
     else          hipLaunchKernelGGL(input_transform<4>, grid, dim3(256), 0, st, x, V, g);
     return hipGetLastError();
@@ -296,10 +317,10 @@ hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeo
     return hipGetLastError();
 }
 
-hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const float* zeros,
-                               const WinoGeom& g, hipStream_t st)
+hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const WinoGeom& g, hipStream_t st)
 {
-    if (g.tb % 32 || g.z % 32 || (g.alpha & 1) || g.K % g.z || g.tiles_pitch % g.tb) return hipErrorInvalidValue;
+    if (g.tb % 32 || g.z % 32 || (g.alpha & 1) || g.K % g.z || g.tiles_pitch % g.tb || g.Cp % g.alpha || g.Cp < g.C)
+        return hipErrorInvalidValue;
     const int MB = g.z / 32, NB = g.tb / 32;
     if (MB % g.waves_m || NB % g.waves_n) return hipErrorInvalidValue;
     const int mbw = MB / g.waves_m, nbw = NB / g.waves_n;
@@ -313,10 +334,10 @@ hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const 
     const int grid = (int)grid_ll;
 #define IOLB_CASE(M_, N_)                                                                                      \
     if (mbw == M_ && nbw == N_) {                                                                              \
-        if (threads <= 256) return launch_product_one<M_, N_, 256>(U, V, Mp, zeros, g, grid, threads, shm, st); \
-        if (threads <= 512) return launch_product_one<M_, N_, 512>(U, V, Mp, zeros, g, grid, threads, shm, st); \
+        if (threads <= 256) return launch_product_one<M_, N_, 256>(U, V, Mp, g, grid, threads, shm, st); \
+        if (threads <= 512) return launch_product_one<M_, N_, 512>(U, V, Mp, g, grid, threads, shm, st); \
         if constexpr (M_ * N_ <= 4)                                                                            \
-            return launch_product_one<M_, N_, 1024>(U, V, Mp, zeros, g, grid, threads, shm, st);               \
+            return launch_product_one<M_, N_, 1024>(U, V, Mp, g, grid, threads, shm, st);               \
     }
     IOLB_CASE(1, 1) IOLB_CASE(1, 2) IOLB_CASE(1, 3) IOLB_CASE(1, 4)
     IOLB_CASE(1, 5) IOLB_CASE(1, 6) IOLB_CASE(1, 7) IOLB_CASE(1, 8)

@@ -1,0 +1,98 @@
+"""Exhaustive tile sweep: times every tile `iolb_enumerate` yields for a layer (optionally a
+sample of them) and reports where the analytical tuner's pick ranks.
+
+This is the measured check of the tuner: the paper prunes its searching domain with the
+optimality condition and then searches by measurement (Sec. 6.2); here the pick is analytical and
+the measurement is the audit.
+
+    python -m paper_2012_15667_amd.sweep --layer cfg3 [--algo direct|wino2|wino4] [--max 200] [--alphas]
+"""
+import argparse
+import json
+import sys
+
+
+def time_call(torch, fn, reps):
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def sweep(layer_name, algo="direct", max_tiles=0, reps=3, vary_alpha=False, use_box=False, lds_bytes=0):
+    import torch
+    from . import binding as B
+    from .inputs import CONFIGS, layer_inputs
+
+    L = CONFIGS[layer_name]
+    x, w = layer_inputs(L)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino4": B.WINO_F4}[algo]
+    shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
+    pick = B.iolb_tune(shape)
+    tiles = B.iolb_enumerate(shape, lds_bytes, 0, use_box)
+    if max_tiles and len(tiles) > max_tiles:
+        step = len(tiles) / float(max_tiles)
+        tiles = [tiles[int(i * step)] for i in range(max_tiles)]
+    if pick not in tiles:
+        tiles.insert(0, pick)
+    if vary_alpha:
+        extra = []
+        for t in tiles:
+            a = t["alpha"] // 2
+            while a >= 2:
+                v = dict(t)
+                v["lds_bytes_used"] = t["lds_bytes_used"] // t["alpha"] * a
+                v["alpha"] = a
+                extra.append(v)
+                a //= 2
+        tiles = tiles + extra
+    P = (L.H + 2 * L.pad - L.R) // L.stride + 1
+    Q = (L.W + 2 * L.pad - L.S) // L.stride + 1
+    y = torch.empty((L.N, L.K, P, Q), dtype=torch.float32, device="cuda")
+    ws = None
+    if algo != "direct":
+        ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, 2 if algo == "wino2" else 4),
+                         dtype=torch.uint8, device="cuda")
+    flops = 2.0 * L.N * L.K * P * Q * L.C * L.R * L.S
+    rows = []
+    for t in tiles:
+        if algo == "direct":
+            fn = lambda: B.conv_direct(xd, wd, L.stride, L.pad, y=y, cfg=t)
+        else:
+            fn = lambda: B.conv_winograd(xd, wd, 2 if algo == "wino2" else 4, y=y, cfg=t, workspace=ws)
+        ms = time_call(torch, fn, reps)
+        rows.append((ms, t))
+        print("%8.4f ms %7.2f TF  b=%d x=%d y=%d z=%d a=%d T=%d wm=%d wn=%d lds=%d qread=%d%s" % (
+            ms, flops / ms / 1e9, t["b"], t["x"], t["y"], t["z"], t["alpha"], t["threads"], t["waves_m"],
+            t["waves_n"], t["lds_bytes_used"], t["q_read_elems"], "  <== tuner pick" if t == pick else ""), flush=True)
+    rows.sort(key=lambda r: r[0])
+    pick_ms = [ms for ms, t in rows if t == pick][0]
+    rank = 1 + [t for _, t in rows].index(pick)
+    summary = {"layer": layer_name, "algo": algo, "tiles_timed": len(rows), "pick_rank": rank,
+               "pick_ms": round(pick_ms, 4), "best_ms": round(rows[0][0], 4),
+               "pick_over_best": round(pick_ms / rows[0][0], 3), "best_tile": rows[0][1], "pick": pick}
+    print(json.dumps(summary))
+    return summary
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--layer", default="cfg3")
+    ap.add_argument("--algo", default="direct")
+    ap.add_argument("--max", type=int, default=0, help="time at most this many tiles (evenly spaced in tuner order)")
+    ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--alphas", action="store_true", help="also time each tile with shallower stages")
+    ap.add_argument("--box", action="store_true", help="only tiles inside the optimality-condition box")
+    ap.add_argument("--lds", type=int, default=0, help="LDS budget per workgroup for the enumeration")
+    a = ap.parse_args()
+    sweep(a.layer, a.algo, a.max, a.reps, a.alphas, a.box, a.lds)
+
+
+if __name__ == "__main__":
+    sys.exit(main())
