@@ -272,7 +272,7 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                         if npix % 32 or z % 32:
                             continue
                         grids = _wave_grids(z // 32, npix // 32, vgpr_budget)
-                        alpha = _pick_alpha(C, (16, 8, 4, 2), 8 * (halo + R * S * z), lds_bytes)
+                        alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), lds_bytes)
                         lds_mult = 8
                     else:
                         if npix > 256:
@@ -321,7 +321,7 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
             if use_f3 and not (z * z <= sb_max and tb * tb <= sb_max):
                 continue
             grids = _wave_grids(z // 32, tb // 32, vgpr_budget)
-            alpha = _pick_alpha(C, (16, 8, 4, 2), 8 * (tb + z), lds_bytes)
+            alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes)
             if alpha is None or not grids:
                 continue
             nblocks = n2 * (-(-tiles // tb)) * (K // z)

@@ -120,8 +120,8 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
     if (rc != IOLB_OK) return rc;
     for (const auto& c : all) {
         iolb_tile_config probe = c.cfg;
-        // alpha may be any smaller even stage depth than the enumeration's deepest one
-        if (cfg.alpha >= 1 && cfg.alpha <= c.cfg.alpha && (cfg.path == IOLB_PATH_FMA || cfg.alpha % 2 == 0) &&
+        // alpha may be any shallower stage depth than the enumeration's (a multiple of 4 on the MFMA path)
+        if (cfg.alpha >= 1 && cfg.alpha <= c.cfg.alpha && (cfg.path == IOLB_PATH_FMA || cfg.alpha % 4 == 0) &&
             c.cfg.alpha % cfg.alpha == 0) {
             probe.alpha = cfg.alpha;
             probe.lds_bytes_used = (int32_t)((int64_t)c.cfg.lds_bytes_used / c.cfg.alpha * cfg.alpha);

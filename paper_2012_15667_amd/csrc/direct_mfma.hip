@@ -172,48 +172,40 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
 #endif
         const int c0_next = (s + 1) * g.alpha;
 
-        bool done = false;
         if constexpr (RR > 0) {
             // Kernel extents known at compile time: the R*S steps of a channel pair are unrolled, so a
-            // step costs its LDS reads and a couple of address adds.  Bodies of two channel pairs keep
-            // the two operand register sets in phase; an odd number of pairs takes the general loop.
+            // step costs its LDS reads and a couple of address adds.  A body is two channel pairs (alpha
+            // is a multiple of 4), which keeps the two operand register sets in phase.
             constexpr int RSc = RR * SS, BODY = 2 * RSc;
-            if ((half_c & 1) == 0) {
-                const int nbodies = half_c >> 1;
-                float fa[2][MBW], fb[2][NBW];
-                auto fetch = [&](int set, int bi, int t) {
-                    const int cl = t / RSc, rs = t % RSc, r = rs / SS, sx = rs % SS;
-                    const float* wp = cur + abase + ((2 * bi + cl) * RSc + rs) * g.z;
-                    const int sc = (2 * bi + cl) * g.halo + r * g.xh;
+            const int nbodies = half_c >> 1;
+            float fa[2][MBW], fb[2][NBW];
+            auto fetch = [&](int set, int bi, int t) {
+                const int cl = t / RSc, rs = t % RSc, r = rs / SS, sx = rs % SS;
+                const float* wp = cur + abase + ((2 * bi + cl) * RSc + rs) * g.z;
+                const int sc = (2 * bi + cl) * g.halo + r * g.xh;
 #pragma unroll
-                    for (int mb = 0; mb < MBW; ++mb) fa[set][mb] = wp[mb * 32];
+                for (int mb = 0; mb < MBW; ++mb) fa[set][mb] = wp[mb * 32];
 #pragma unroll
-                    for (int nb = 0; nb < NBW; ++nb) fb[set][nb] = cur[bbase[nb] + sc + sx];
-                };
-                fetch(0, 0, 0);
-                for (int bi = 0; bi < nbodies; ++bi) {
-                    const int bnext = (bi + 1 < nbodies) ? bi + 1 : 0;   // after the last body: wrap, read and drop
+                for (int nb = 0; nb < NBW; ++nb) fb[set][nb] = cur[bbase[nb] + sc + sx];
+            };
+            fetch(0, 0, 0);
+            for (int bi = 0; bi < nbodies; ++bi) {
+                const int bnext = (bi + 1 < nbodies) ? bi + 1 : 0;   // after the last body: wrap, read and drop
 #pragma unroll
-                    for (int t = 0; t < BODY; ++t) {
-                        if (t == 0 || t == RSc) {
-                            if (more && bi == 0 && issue_group == (t == 0 ? 0 : 1)) issue_stage(c0_next, nxt);
-                        }
-                        if (t + 1 < BODY) fetch((t + 1) & 1, bi, t + 1);
-                        else              fetch(0, bnext, 0);
-                        multiply(fa[t & 1], fb[t & 1]);
-                        // Issue order inside the step: one MFMA, then the LDS reads of step t+1 two at a
-                        // time between the following MFMAs.  A wave then never has an MFMA-free stretch,
-                        // so two waves of a SIMD cannot both be off the matrix core at once.
-                        interleave_step();
+                for (int t = 0; t < BODY; ++t) {
+                    if (t == 0 || t == RSc) {
+                        if (more && bi == 0 && issue_group == (t == 0 ? 0 : 1)) issue_stage(c0_next, nxt);
                     }
+                    if (t + 1 < BODY) fetch((t + 1) & 1, bi, t + 1);
+                    else              fetch(0, bnext, 0);
+                    multiply(fa[t & 1], fb[t & 1]);
+                    interleave_step();
                 }
-                done = true;
             }
-        }
-        if (!done) {
+        } else {
             // General loop: steps j = (c2, r, s) flattened, two per iteration with two operand register
-            // sets; an odd step count is rounded up with a step whose weights are forced to zero.  After
-            // the last step the fetch wraps to step 0 (read and dropped).
+            // sets (alpha is a multiple of 4, so the count is even).  After the last step the fetch wraps
+            // to step 0 (read and dropped).
             const float* wrow = cur + abase;
             int r = 0, sx = 0, xo = 0;              // position of the NEXT step to fetch
             float a[MBW], bv[NBW], a1[MBW], b1[NBW];
@@ -230,22 +222,16 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
                 r = wrap_r ? 0 : r + wrap_s;
             };
             const int issue_at = issue_group ? ((nsteps >> 1) & ~1) : 0;
-            fetch(a, bv, nsteps == 1);
+            fetch(a, bv, false);
 #pragma unroll 1
             for (int j = 0; j < nsteps; j += 2) {
                 if (more && j == issue_at) issue_stage(c0_next, nxt);
-                fetch(a1, b1, j + 2 >= nsteps);
-                __builtin_amdgcn_sched_barrier(0);
+                fetch(a1, b1, false);
                 multiply(a, bv);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch(a, bv, j + 3 >= nsteps);
-                if (j + 1 >= nsteps) {
-#pragma unroll
-                    for (int mb = 0; mb < MBW; ++mb) a1[mb] = 0.f;
-                }
-                __builtin_amdgcn_sched_barrier(0);
+                interleave_step();
+                fetch(a, bv, j + 2 >= nsteps);
                 multiply(a1, b1);
-                __builtin_amdgcn_sched_barrier(0);
+                interleave_step();
             }
         }
         IOLB_STAMP(3);
@@ -324,7 +310,7 @@ hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int
 hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st)
 {
     const int npix = g.b * g.tx * g.ty;
-    if (npix % 32 || g.z % 32 || (g.alpha & 1) || g.threads != 64 * g.waves_m * g.waves_n) return hipErrorInvalidValue;
+    if (npix % 32 || g.z % 32 || (g.alpha & 3) || g.threads != 64 * g.waves_m * g.waves_n) return hipErrorInvalidValue;
     const int MB = g.z / 32, NB = npix / 32;
     if (MB % g.waves_m || NB % g.waves_n) return hipErrorInvalidValue;
     const int mbw = MB / g.waves_m, nbw = NB / g.waves_n;

@@ -93,7 +93,7 @@ int pow2_at_least(int v) {
 
 void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int vgpr_budget, int path,
                        bool use_box, std::vector<Candidate>* out) {
-    static const int alphas_mfma[] = {16, 8, 4, 2};
+    static const int alphas_mfma[] = {16, 8, 4};       // whole channel quads: two per lane half
     static const int alphas_fma[] = {16, 8, 4, 2, 1};
     const int64_t box = kMaxThreads * vgpr_budget;
     const int64_t RS = (int64_t)s.R * s.S, st2 = (int64_t)s.stride * s.stride;
@@ -113,7 +113,7 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                     if (path == IOLB_PATH_MFMA) {
                         if (npix % 32 || z % 32) continue;
                         if (!best_wave_grid(z / 32, (int)(npix / 32), vgpr_budget, &g)) continue;
-                        alpha = choose_alpha(s.C, alphas_mfma, 4, 8 * per_stage, lds_bytes);
+                        alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage, lds_bytes);
                         lds_mult = 8;
                     } else {
                         if (npix > 256) continue;
@@ -156,7 +156,7 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
 // z transformed weights, for each of the (m+2)^2 planes.
 void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_bytes, int vgpr_budget,
                          bool use_box, std::vector<Candidate>* out) {
-    static const int alphas[] = {16, 8, 4, 2};
+    static const int alphas[] = {16, 8, 4};
     const int64_t planes = (int64_t)(m + 2) * (m + 2);
     const int64_t tiles = (int64_t)s.N * ceil_div(P, m) * ceil_div(Q, m);
     const int64_t box = kMaxThreads * vgpr_budget;
@@ -168,7 +168,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             if (use_box && !((int64_t)z * z <= box && tb * tb <= box)) continue;
             WaveGrid g{};
             if (!best_wave_grid(z / 32, (int)(tb / 32), vgpr_budget, &g)) continue;
-            const int alpha = choose_alpha(s.C, alphas, 4, 8 * (tb + z), lds_bytes);
+            const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z), lds_bytes);
             if (alpha == 0) continue;
             const int64_t nblocks = planes * ceil_div(tiles, tb) * (s.K / z);
             Candidate c{};

@@ -210,17 +210,49 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
     };
 
     const int nstages = (g.C + g.alpha - 1) / g.alpha;
+    // waves w and w+4 share a SIMD: the second group stages the next buffer half a stage later than the
+    // first, so that one of the two always has MFMAs to issue
+    const int issue_group = (wave >> 2) & 1;
+    const int issue_at = issue_group ? ((half_c >> 1) & ~1) : 0;
+
+    auto multiply = [&](const float (&am)[MBW], const float (&bm)[NBW]) {
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
+    };
+    // issue order inside a step: one MFMA, then the LDS reads of the next step two at a time between the
+    // following MFMAs, so that a wave never has an MFMA-free stretch
+    auto interleave_step = [&]() {
+        constexpr int MF = MBW * NBW, RD = MBW + NBW, PAIRS = (RD + 1) / 2;
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if constexpr (MF - 1 >= PAIRS) {
+#pragma unroll
+            for (int i = 0; i < PAIRS; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+            if constexpr (MF - 1 - PAIRS > 0) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1 - PAIRS, 0);
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+            if constexpr (MF > 1) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1, 0);
+        }
+    };
+
     issue_stage(0, lds);
     for (int s = 0; s < nstages; ++s) {
         lds_dma_wait_all();
         __syncthreads();
         const float* cur = lds + (s & 1) * stage_floats;
-        if (s + 1 < nstages) issue_stage((s + 1) * g.alpha, lds + ((s + 1) & 1) * stage_floats);
-        // operands of channel step c2+1 are fetched before the MFMAs of step c2 are issued; after the
-        // last step the fetch wraps to step 0 (read and dropped)
+        float* nxt = lds + ((s + 1) & 1) * stage_floats;
+        const bool more = s + 1 < nstages;
+        const int c0_next = (s + 1) * g.alpha;
+        // operands of channel step j+1 are fetched while the MFMAs of step j are issued (two register
+        // sets, two steps per iteration); after the last step the fetch wraps to step 0 (read, dropped)
         const float* ap = cur + abase;
         const float* bp = cur + bbase;
-        float a[MBW], bv[NBW];
+        float a[MBW], bv[NBW], a1[MBW], b1[NBW];
         auto fetch = [&](float (&an)[MBW], float (&bn)[NBW], bool last) {
 #pragma unroll
             for (int mb = 0; mb < MBW; ++mb) an[mb] = ap[mb * 32];
@@ -229,33 +261,16 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
             ap = last ? cur + abase : ap + g.z;
             bp = last ? cur + bbase : bp + g.tb;
         };
-        auto multiply = [&](const float (&am)[MBW], const float (&bm)[NBW]) {
-#pragma unroll
-            for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < NBW; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
-        };
-        // two register sets, two steps per iteration; an odd step count is rounded up with a step
-        // whose A operand is forced to zero
-        float a1[MBW], b1[NBW];
-        fetch(a, bv, half_c == 1);
+        fetch(a, bv, false);
 #pragma unroll 1
-        for (int j = 0; j < half_c; j += 2) {
-            // sched_barrier(0): nothing may be moved across, so the LDS reads of the next step are
-            // issued before the MFMAs of the current one and have their whole duration to land
-            fetch(a1, b1, j + 2 >= half_c);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < half_c; j += 2) {       // alpha is a multiple of 4: an even number of steps
+            if (more && j == issue_at) issue_stage(c0_next, nxt);
+            fetch(a1, b1, false);
             multiply(a, bv);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(a, bv, j + 3 >= half_c);
-            if (j + 1 >= half_c) {
-#pragma unroll
-                for (int mb = 0; mb < MBW; ++mb) a1[mb] = 0.f;
-            }
-            __builtin_amdgcn_sched_barrier(0);
+            interleave_step();
+            fetch(a, bv, j + 2 >= half_c);
             multiply(a1, b1);
-            __builtin_amdgcn_sched_barrier(0);
+            interleave_step();
         }
     }
 
@@ -319,7 +334,7 @@ hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeo
 
 hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const WinoGeom& g, hipStream_t st)
 {
-    if (g.tb % 32 || g.z % 32 || (g.alpha & 1) || g.K % g.z || g.tiles_pitch % g.tb || g.Cp % g.alpha || g.Cp < g.C)
+    if (g.tb % 32 || g.z % 32 || (g.alpha & 3) || g.K % g.z || g.tiles_pitch % g.tb || g.Cp % g.alpha || g.Cp < g.C)
         return hipErrorInvalidValue;
     const int MB = g.z / 32, NB = g.tb / 32;
     if (MB % g.waves_m || NB % g.waves_n) return hipErrorInvalidValue;

@@ -45,7 +45,7 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=3, vary_alpha=False, use_
         extra = []
         for t in tiles:
             a = t["alpha"] // 2
-            while a >= 2:
+            while a >= 4:
                 v = dict(t)
                 v["lds_bytes_used"] = t["lds_bytes_used"] // t["alpha"] * a
                 v["alpha"] = a

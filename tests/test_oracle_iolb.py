@@ -125,7 +125,7 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
         blocks = (s["N"] // b) * (Q // x) * (P // y) * (s["K"] // z)
         assert cfg["q_read_elems"] == blocks * s["C"] * per_stage
         if cfg["path"] == o.PATH_MFMA:
-            assert (b * x * y) % 32 == 0 and z % 32 == 0 and a % 2 == 0
+            assert (b * x * y) % 32 == 0 and z % 32 == 0 and a % 4 == 0
             assert cfg["lds_bytes_used"] == 2 * 4 * a * per_stage
             assert b * x * y * z == cfg["acc_regs_per_thread"] * T        # accumulators fill the lanes
             assert T == 64 * cfg["waves_m"] * cfg["waves_n"]
