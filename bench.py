@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", default="", help="comma-separated subset of config names (profiling runs)")
     ap.add_argument("--algos", default="", help="comma-separated subset of direct,wino2,wino4 (profiling runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (known size) to calibrate rocprofv3 FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (every figure is the one "
@@ -109,6 +111,16 @@ def main():
         sys.exit(2)
     B.lib()
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        n = 1 << 28                                   # 2^28 fp32 = 1 GiB read + 1 GiB written per copy
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 4 * n, "copy_bytes_written": 4 * n, "copies": 3}))
+        return
 
     only_layers = set(filter(None, args.layers.split(",")))
     only_algos = set(filter(None, args.algos.split(",")))

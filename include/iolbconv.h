@@ -105,8 +105,9 @@ int conv_winograd_ws(const float* x, const float* w, float* y,
 
 /* The analytical tuner (searching domain of Table 1, Sec. 6.2; objective: reading volume of
  * the dataflow of Sec. 5.2 / 5.3).  Host only; shape and out are host pointers.
- * lds_bytes: LDS available to one workgroup (0 = default 81920, half a compute unit's LDS, the
- * "two blocks per multiprocessor" rule of Sec. 6.2).  vgpr_budget: accumulator registers per
+ * lds_bytes: LDS available to one workgroup; 0 = automatic: 81920 (half a compute unit's LDS, the
+ * "two blocks per multiprocessor" rule of Sec. 6.2), or the whole LDS for tiles whose registers
+ * allow only one workgroup per compute unit anyway.  vgpr_budget: accumulator registers per
  * lane (0 = default 128).  IOLB_ENOTILE when nothing fits. */
 int iolb_tune(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, iolb_tile_config* out);
 

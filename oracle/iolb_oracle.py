@@ -197,13 +197,26 @@ def bounds(shape, Sf):
 #   * the optimality condition xy = rho z bounds the box:  z <= sqrt(S_b/rho), xy <= sqrt(S_b rho),
 #     with S_b the largest workgroup's accumulator capacity, 1024 * vgpr_budget;
 #   * the per-stage input tile x' * y' * alpha and the weight slab R S alpha z, double buffered,
-#     must fit lds_bytes (the LDS share of one workgroup, S_sm / 2 by default).
+#     must fit lds_bytes (the LDS share of one workgroup; when 0, S_sm / 2, or S_sm if the tile's
+#     registers allow only one workgroup per compute unit anyway).
 # Among feasible tiles the rule minimises the read volume of the dataflow of Sec. 5.2 evaluated
 # exactly (true halo x' = stride (x-1) + S instead of x' ~ stride x), after making sure the grid
 # keeps the 256 compute units busy.
 
 N_CU = 256
 T_MAX = 1024
+LDS_CU = 160 * 1024 - 256      # LDS of a compute unit, minus a small reserve for alignment
+REGS_PER_LANE = 512            # registers per lane of a SIMD (4 SIMDs x 64 lanes x 512 = 131072 per CU)
+
+
+def _auto_lds_budget(T, acc):
+    """LDS share of one workgroup when the caller gives none: half a compute unit's LDS (two blocks
+    per multiprocessor, Sec. 6.2) -- unless the tile's registers already limit the compute unit to one
+    workgroup, in which case halving the LDS would buy nothing and the whole LDS is used."""
+    waves_per_simd = max(T // 256, 1)
+    two_fit = 2 * waves_per_simd * (acc + 64) <= REGS_PER_LANE
+    return 81920 if two_fit else LDS_CU
+
 T_CHOICES = (64, 128, 256, 512, 1024)
 EFF_CAP = 80
 
@@ -272,7 +285,11 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                         if npix % 32 or z % 32:
                             continue
                         grids = _wave_grids(z // 32, npix // 32, vgpr_budget)
-                        alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), lds_bytes)
+                        alpha = None
+                        if grids:
+                            T0, _, _, _, acc0 = min(grids)
+                            budget = lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0)
+                            alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), budget)
                         lds_mult = 8
                     else:
                         if npix > 256:
@@ -286,7 +303,7 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                             if z % KG or z // KG > 16 or z // KG > vgpr_budget:
                                 continue
                             grids.append((T, 0, KG, 1, z // KG))
-                        alpha = _pick_alpha(C, (16, 8, 4, 2, 1), 4 * (halo + R * S * z), lds_bytes)
+                        alpha = _pick_alpha(C, (16, 8, 4, 2, 1), 4 * (halo + R * S * z), lds_bytes or 81920)
                         lds_mult = 4
                     if alpha is None or not grids:
                         continue
@@ -321,8 +338,11 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
             if use_f3 and not (z * z <= sb_max and tb * tb <= sb_max):
                 continue
             grids = _wave_grids(z // 32, tb // 32, vgpr_budget)
-            alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes)
-            if alpha is None or not grids:
+            if not grids:
+                continue
+            T0, _, _, _, acc0 = min(grids)
+            alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0))
+            if alpha is None:
                 continue
             nblocks = n2 * (-(-tiles // tb)) * (K // z)
             qread = nblocks * C * (tb + z)
@@ -335,7 +355,7 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
     return cands
 
 
-def candidates(shape, lds_bytes=81920, vgpr_budget=128, use_f3=True):
+def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True):
     """Every feasible tile with its ordering key (smaller is better); the MFMA path is preferred
     whenever it has a feasible tile.  Also what the exhaustive sweep enumerates (use_f3=False)."""
     s = shape
@@ -351,7 +371,7 @@ def candidates(shape, lds_bytes=81920, vgpr_budget=128, use_f3=True):
     return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3)
 
 
-def tune(shape, lds_bytes=81920, vgpr_budget=128):
+def tune(shape, lds_bytes=0, vgpr_budget=128):
     """The tile the library's iolb_tune must return, or None when nothing fits."""
     c = candidates(shape, lds_bytes, vgpr_budget, True)
     if not c:

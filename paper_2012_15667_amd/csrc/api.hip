@@ -1,6 +1,7 @@
 // C-ABI layer: argument checks, tile selection, workspace, launches.  See include/iolbconv.h.
 #include <hip/hip_runtime.h>
 
+#include <array>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -112,9 +113,21 @@ bool same_config(const iolb_tile_config& a, const iolb_tile_config& b)
 }
 
 // A caller-supplied tile must be one the enumeration produces for this shape (any LDS budget up to the
-// whole compute unit), so that every kernel assumption about it holds.
+// whole compute unit), so that every kernel assumption about it holds.  Accepted (shape, tile) pairs are
+// remembered: sweeps call the same tile many times.
+typedef std::tuple<ShapeKey, std::array<int64_t, 14>> CheckedKey;
+std::map<CheckedKey, bool> g_checked;
+
 int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
 {
+    const CheckedKey key(ShapeKey(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.algo),
+                         std::array<int64_t, 14>{cfg.b, cfg.x, cfg.y, cfg.z, cfg.alpha, cfg.threads, cfg.waves_m,
+                                                 cfg.waves_n, cfg.path, cfg.wt_mode, cfg.lds_bytes_used,
+                                                 cfg.acc_regs_per_thread, cfg.q_read_elems, cfg.q_write_elems});
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        if (g_checked.count(key)) return IOLB_OK;
+    }
     std::vector<iolb::Candidate> all;
     const int rc = iolb::enumerate(s, 160 * 1024, 0, false, &all);
     if (rc != IOLB_OK) return rc;
@@ -126,7 +139,11 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
             probe.alpha = cfg.alpha;
             probe.lds_bytes_used = (int32_t)((int64_t)c.cfg.lds_bytes_used / c.cfg.alpha * cfg.alpha);
         }
-        if (same_config(probe, cfg)) return IOLB_OK;
+        if (same_config(probe, cfg)) {
+            std::lock_guard<std::mutex> lock(g_mutex);
+            g_checked[key] = true;
+            return IOLB_OK;
+        }
     }
     return IOLB_EINVAL;
 }

@@ -20,6 +20,17 @@ namespace {
 constexpr int64_t kComputeUnits = 256;   // grid-fill rule: a launch should keep every CU busy
 constexpr int64_t kMaxThreads = 1024;    // largest workgroup: bounds the optimality box
 constexpr int64_t kEffCap = 80;          // grid efficiency above this percentage is "good enough"
+constexpr int64_t kLdsPerCu = 160 * 1024 - 256;   // LDS of a compute unit, minus a small reserve for alignment
+constexpr int64_t kLdsHalf = 81920;      // "two blocks per multiprocessor" share (Sec. 6.2)
+
+// LDS share of one workgroup when the caller gives none: half a compute unit's LDS, unless the tile's
+// registers already limit the compute unit to one workgroup (then halving the LDS buys nothing).
+int64_t auto_lds_budget(int threads, int acc)
+{
+    const int64_t waves_per_simd = std::max(threads / 256, 1);
+    const bool two_fit = 2 * waves_per_simd * (acc + 64) <= 512;
+    return two_fit ? kLdsHalf : kLdsPerCu;
+}
 
 std::vector<int> factors_of(int n) {
     std::vector<int> f;
@@ -113,7 +124,8 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                     if (path == IOLB_PATH_MFMA) {
                         if (npix % 32 || z % 32) continue;
                         if (!best_wave_grid(z / 32, (int)(npix / 32), vgpr_budget, &g)) continue;
-                        alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage, lds_bytes);
+                        alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage,
+                                             lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
                         lds_mult = 8;
                     } else {
                         if (npix > 256) continue;
@@ -130,7 +142,7 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                             break;               // ascending T: the first is the smallest
                         }
                         if (!found) continue;
-                        alpha = choose_alpha(s.C, alphas_fma, 5, 4 * per_stage, lds_bytes);
+                        alpha = choose_alpha(s.C, alphas_fma, 5, 4 * per_stage, lds_bytes ? lds_bytes : kLdsHalf);
                         lds_mult = 4;
                     }
                     if (alpha == 0) continue;
@@ -168,7 +180,8 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             if (use_box && !((int64_t)z * z <= box && tb * tb <= box)) continue;
             WaveGrid g{};
             if (!best_wave_grid(z / 32, (int)(tb / 32), vgpr_budget, &g)) continue;
-            const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z), lds_bytes);
+            const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z),
+                                           lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
             if (alpha == 0) continue;
             const int64_t nblocks = planes * ceil_div(tiles, tb) * (s.K / z);
             Candidate c{};
@@ -207,7 +220,7 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
     int P = 0, Q = 0;
     const int rc = validate_shape(s, &P, &Q);
     if (rc != IOLB_OK) return rc;
-    if (lds_bytes <= 0) lds_bytes = 81920;
+    if (lds_bytes < 0) lds_bytes = 0;       // 0: per-tile automatic budget
     if (vgpr_budget <= 0) vgpr_budget = 128;
     out->clear();
     if (s.algo == IOLB_DIRECT) {
