@@ -12,8 +12,7 @@ OBJ_DIR = os.path.join(ROOT, "_build")
 SOURCES = ["api.hip", "direct_fma.hip", "direct_mfma.hip", "wino.hip", "tune.cpp"]
 # packed fp32 VALU forms are disabled on purpose: plain v_fma_f32 only
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-EXTRA = os.environ.get("IOLB_EXTRA_HIPCC_FLAGS", "").split()
-COMMON = EXTRA + ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
           "-Wno-unused-command-line-argument"]
 
 

@@ -6,25 +6,26 @@
 // implicit GEMM:  acc[z][npix] += W[z][alpha*R*S] * X[alpha*R*S][npix], where X is never materialised:
 // each lane reads its pixel's window straight out of the LDS-resident input tile xh * yh.
 //
-// Per stage of alpha channels the workgroup stages, with LDS-direct loads (no registers in between),
-//   - the weight slab  [alpha][R*S][z]  from the re-laid-out weights wt[C][R*S][K], 16 bytes per lane;
-//   - the input tile   [alpha][b][yh][xh], element-wise, padded elements fetched from a zero word.
-// Two LDS buffers alternate: the loads of stage s+1 are in flight while stage s is multiplied.
+// Per stage of alpha channels (a multiple of 4) the workgroup stages, with LDS-direct loads (no
+// registers in between),
+//   - the weight slab  [alpha][R*S][z]  from the re-laid-out weights wt[C'][R*S][K] (C' = C rounded up
+//     to whole stages, the extra rows zero), whole rows per instruction, 16 bytes per lane;
+//   - the input tile   [alpha][b][yh][xh], one instruction per (tile row, 64-column segment, channel):
+//     the row's base address is wave-uniform, lanes add their column.  Elements outside the image are
+//     never loaded: both LDS buffers are cleared once and those positions stay zero.
+// Two LDS buffers alternate.  The loads of stage s+1 are issued from inside the multiply phase of
+// stage s, by the two waves of a SIMD half a stage apart, so that the matrix core always has a wave
+// that is multiplying.
 //
 // Wave layout: waves_m x waves_n waves; a wave owns MBW x NBW blocks of 32 x 32 partial sums.
 // Inside one MFMA the two k-slices are fed by lane halves: lanes 0-31 take channel c2, lanes 32-63 take
-// channel c2 + alpha/2, so that both halves use the same LDS offset per (r, s).
+// channel c2 + alpha/2, so that both halves use the same LDS offset per (r, s).  The LDS reads of step
+// j+1 are interleaved between the MFMAs of step j (an MFMA blocks its wave's issue while it runs, so
+// a wave must never have a stretch without one).
 #include "kernels.h"
 #include "lds_dma.h"
 
 namespace iolb {
-
-#ifdef IOLB_TRACE
-__device__ long long g_trace[8 * 16 * 4];
-#define IOLB_STAMP(k) do { if (lane == 0 && s >= 8 && s < 24) s_trace[(wave * 16 + (s - 8)) * 4 + (k)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define IOLB_STAMP(k) do {} while (0)
-#endif
 
 namespace {
 
@@ -34,9 +35,6 @@ __global__ void __launch_bounds__(LB)
 direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y, DirectGeom g)
 {
     extern __shared__ float lds[];
-#ifdef IOLB_TRACE
-    __shared__ long long s_trace[8 * 16 * 4];
-#endif
     const int tid = threadIdx.x, T = blockDim.x;
     const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -158,18 +156,11 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
 
     issue_stage(0, lds);
     for (int s = 0; s < nstages; ++s) {
-        IOLB_STAMP(0);
         lds_dma_wait_all();
-        IOLB_STAMP(1);
         __syncthreads();                                    // stage s has landed; stage s-1 is consumed
-        IOLB_STAMP(2);
         float* cur = lds + (s & 1) * stage_floats;
         float* nxt = lds + ((s + 1) & 1) * stage_floats;
-#ifdef IOLB_EXP_NOISSUE
-        const bool more = false;
-#else
         const bool more = s + 1 < nstages;
-#endif
         const int c0_next = (s + 1) * g.alpha;
 
         if constexpr (RR > 0) {
@@ -234,12 +225,7 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
                 interleave_step();
             }
         }
-        IOLB_STAMP(3);
     }
-#ifdef IOLB_TRACE
-    __syncthreads();
-    if (blockIdx.x == 0) for (int i = tid; i < 8 * 16 * 4; i += T) g_trace[i] = s_trace[i];
-#endif
 
     // each partial sum is complete: write the block once.  Register i of a 32 x 32 block holds
     // channel 8*(i/4) + 4*half + i%4 of pixel l32.
@@ -292,13 +278,6 @@ hipError_t launch_one(const float* x, const float* wt, float* y, const DirectGeo
 }
 
 }  // namespace
-
-#ifdef IOLB_TRACE
-extern "C" int iolb_debug_trace(long long* host)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), sizeof(long long) * 8 * 16 * 4);
-}
-#endif
 
 hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int rows, hipStream_t st)
 {
