@@ -219,6 +219,7 @@ def _auto_lds_budget(T, acc):
 
 T_CHOICES = (64, 128, 256, 512, 1024)
 EFF_CAP = 80
+IDLE_OK_PCT = 5      # up to this share of idle pixel slots a ragged tile counts as a full one
 
 
 def divisors(n):
@@ -244,19 +245,26 @@ def _pick_alpha(C, choices, per_alpha_bytes, lds_bytes):
 
 
 def _wave_grids(MB, NB, vgpr_budget):
-    """All (waves_m, waves_n) that split MB x NB blocks of 32 x 32 outputs over whole waves."""
+    """All wave grids for MB x NB blocks of 32 x 32 outputs: a wave owns mbw x nbw blocks (mbw in {1,2},
+    at most 8 blocks); waves_m divides MB, waves_n = ceil(NB / nbw) -- the last wave column may own
+    blocks past the tile, which stay idle.  Ordered by idle blocks first, then workgroup size."""
     out = []
     for wm in divisors(MB):
-        for wn in divisors(NB):
-            mbw, nbw = MB // wm, NB // wn
+        mbw = MB // wm
+        if mbw not in (1, 2):
+            continue
+        for nbw in range(1, 9):
+            if mbw * nbw > 8 or nbw > NB:
+                continue
+            wn = -(-NB // nbw)
             T = 64 * wm * wn
-            if mbw not in (1, 2) or mbw * nbw > 8 or T not in T_CHOICES:
+            if T not in T_CHOICES:
                 continue
             if 16 * mbw * nbw > vgpr_budget:
                 continue
             if 16 * mbw * nbw + 64 > 131072 // T:      # register-file share of a lane, 64 kept for operands
                 continue
-            out.append((T, mbw + nbw, wm, wn, 16 * mbw * nbw))
+            out.append((wn * nbw - NB, T, mbw + nbw, wm, wn, 16 * mbw * nbw))
     return out
 
 
@@ -282,12 +290,12 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                                        npix * npix * st * st <= sb_max * R * S):
                         continue
                     if path == PATH_MFMA:
-                        if npix % 32 or z % 32:
+                        if z % 32:
                             continue
-                        grids = _wave_grids(z // 32, npix // 32, vgpr_budget)
+                        grids = _wave_grids(z // 32, -(-npix // 32), vgpr_budget)
                         alpha = None
                         if grids:
-                            T0, _, _, _, acc0 = min(grids)
+                            _, T0, _, _, _, acc0 = min(grids)
                             budget = lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0)
                             alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), budget)
                         lds_mult = 8
@@ -302,15 +310,19 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                             KG = T // PL
                             if z % KG or z // KG > 16 or z // KG > vgpr_budget:
                                 continue
-                            grids.append((T, 0, KG, 1, z // KG))
+                            grids.append((0, T, 0, KG, 1, z // KG))
                         alpha = _pick_alpha(C, (16, 8, 4, 2, 1), 4 * (halo + R * S * z), lds_bytes or 81920)
                         lds_mult = 4
                     if alpha is None or not grids:
                         continue
                     nblocks = (N // b) * (Q // x) * (P // y) * (K // z)
                     qread = nblocks * C * (halo + R * S * z)
-                    T, _, wm, wn, acc = min(grids)
-                    key = (-_grid_efficiency_pct(nblocks), qread, abs(npix * st * st - R * S * z),
+                    _, T, _, wm, wn, acc = min(grids)
+                    # share of the workgroup's matrix-core work spent on pixels past the tile (path 1 only)
+                    slots = (acc // 16 // (z // 32 // wm) * wn * 32) if path == PATH_MFMA else npix
+                    idle_pct = (100 * (slots - npix)) // slots
+                    key = (-_grid_efficiency_pct(nblocks), 0 if idle_pct <= IDLE_OK_PCT else idle_pct, qread,
+                           abs(npix * st * st - R * S * z),
                            -npix * z, -x, z, b, y, T)
                     cands.append((key, dict(b=b, x=x, y=y, z=z, alpha=alpha, threads=T, waves_m=wm,
                                             waves_n=wn, path=path, wt_mode=0,
@@ -337,16 +349,16 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
                 continue
             if use_f3 and not (z * z <= sb_max and tb * tb <= sb_max):
                 continue
-            grids = _wave_grids(z // 32, tb // 32, vgpr_budget)
+            grids = [g for g in _wave_grids(z // 32, tb // 32, vgpr_budget) if g[0] == 0]   # tb is free: no idle blocks
             if not grids:
                 continue
-            T0, _, _, _, acc0 = min(grids)
+            _, T0, _, _, _, acc0 = min(grids)
             alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0))
             if alpha is None:
                 continue
             nblocks = n2 * (-(-tiles // tb)) * (K // z)
             qread = nblocks * C * (tb + z)
-            T, _, wm, wn, acc = min(grids)
+            _, T, _, wm, wn, acc = min(grids)
             key = (-_grid_efficiency_pct(nblocks), qread, abs(tb - z), -tb * z, z, T)
             cands.append((key, dict(b=1, x=e * tb, y=e, z=z, alpha=alpha, threads=T, waves_m=wm,
                                     waves_n=wn, path=PATH_MFMA, wt_mode=1,

@@ -1,7 +1,7 @@
 // Direct convolution on the fp32 matrix cores (v_mfma_f32_32x32x2_f32), dataflow of Sec. 5.2.
 //
-// One workgroup owns an output sub-block of b images * ty rows * tx columns (npix pixels, a multiple
-// of 32) by z output channels (a multiple of 32) and keeps its partial sums in accumulator registers
+// One workgroup owns an output sub-block of b images * ty rows * tx columns (npix pixels, cut into
+// blocks of 32, the last one possibly ragged) by z output channels (a multiple of 32) and keeps its partial sums in accumulator registers
 // for the whole channel loop; they are written to HBM once.  The contraction over (c, r, s) runs as an
 // implicit GEMM:  acc[z][npix] += W[z][alpha*R*S] * X[alpha*R*S][npix], where X is never materialised:
 // each lane reads its pixel's window straight out of the LDS-resident input tile xh * yh.
@@ -59,11 +59,17 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     const int wm_i = wave % g.waves_m, wn_i = wave / g.waves_m;
 
     // per-lane read bases inside a stage buffer
+    // A tile whose pixel count is not a multiple of 32 (or does not fill the wave grid) leaves pixel slots
+    // idle: they read the tile's last pixel and store nothing.
     int bbase[NBW], pimg[NBW], ppy[NBW], ppx[NBW];
+    bool pvalid[NBW];
     const int txy = g.tx * g.ty;
+    const int npix = g.b * txy;
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
-        const int pix = (wn_i * NBW + nb) * 32 + l32;
+        const int slot = (wn_i * NBW + nb) * 32 + l32;
+        pvalid[nb] = slot < npix;
+        const int pix = pvalid[nb] ? slot : npix - 1;
         pimg[nb] = pix / txy;
         const int rem = pix % txy;
         ppy[nb] = rem / g.tx;
@@ -232,6 +238,7 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     const size_t PQ = (size_t)g.P * g.Q;
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
+        if (!pvalid[nb]) continue;
         float* yp = y + ((size_t)(n0 + pimg[nb]) * g.K + k0) * PQ + (size_t)(y0 + ppy[nb]) * g.Q + x0 + ppx[nb];
 #pragma unroll
         for (int mb = 0; mb < MBW; ++mb) {
@@ -289,10 +296,10 @@ hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int
 hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st)
 {
     const int npix = g.b * g.tx * g.ty;
-    if (npix % 32 || g.z % 32 || (g.alpha & 3) || g.threads != 64 * g.waves_m * g.waves_n) return hipErrorInvalidValue;
-    const int MB = g.z / 32, NB = npix / 32;
-    if (MB % g.waves_m || NB % g.waves_n) return hipErrorInvalidValue;
-    const int mbw = MB / g.waves_m, nbw = NB / g.waves_n;
+    if (g.z % 32 || (g.alpha & 3) || g.threads != 64 * g.waves_m * g.waves_n) return hipErrorInvalidValue;
+    const int MB = g.z / 32, NB = (npix + 31) / 32;          // a ragged last block is masked in the kernel
+    if (MB % g.waves_m || g.waves_n > NB) return hipErrorInvalidValue;
+    const int mbw = MB / g.waves_m, nbw = (NB + g.waves_n - 1) / g.waves_n;
     const size_t stage = ((size_t)g.alpha * ((size_t)g.R * g.S * g.z + g.halo) + 3) & ~(size_t)3;
     const size_t shm = 2 * stage * sizeof(float);
     if (shm > 160 * 1024) return hipErrorInvalidValue;

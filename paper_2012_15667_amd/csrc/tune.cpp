@@ -20,6 +20,7 @@ namespace {
 constexpr int64_t kComputeUnits = 256;   // grid-fill rule: a launch should keep every CU busy
 constexpr int64_t kMaxThreads = 1024;    // largest workgroup: bounds the optimality box
 constexpr int64_t kEffCap = 80;          // grid efficiency above this percentage is "good enough"
+constexpr int64_t kIdleOkPct = 5;        // a ragged tile with up to this share of idle pixel slots counts as full
 constexpr int64_t kLdsPerCu = 160 * 1024 - 256;   // LDS of a compute unit, minus a small reserve for alignment
 constexpr int64_t kLdsHalf = 81920;      // "two blocks per multiprocessor" share (Sec. 6.2)
 
@@ -66,29 +67,32 @@ int choose_alpha(int C, const int* choices, int nchoices, int64_t bytes_per_chan
 }
 
 struct WaveGrid {
-    int threads, reads, wm, wn, acc;
+    int idle, threads, reads, wm, wn, acc;
     bool operator<(const WaveGrid& o) const {
-        return std::array<int, 5>{threads, reads, wm, wn, acc} <
-               std::array<int, 5>{o.threads, o.reads, o.wm, o.wn, o.acc};
+        return std::array<int, 6>{idle, threads, reads, wm, wn, acc} <
+               std::array<int, 6>{o.idle, o.threads, o.reads, o.wm, o.wn, o.acc};
     }
 };
 
-// Best split of MB x NB blocks of 32 x 32 partial sums over whole waves: each wave owns
-// mbw x nbw blocks (mbw in {1,2}, at most 8 blocks = 128 accumulator registers).
-bool best_wave_grid(int MB, int NB, int vgpr_budget, WaveGrid* out) {
+// Best wave grid for MB x NB blocks of 32 x 32 partial sums: a wave owns mbw x nbw blocks (mbw in {1,2},
+// at most 8 blocks = 128 accumulator registers); waves_m divides MB, waves_n = ceil(NB / nbw) -- the last
+// wave column may own blocks past the tile, which stay idle.  Fewest idle blocks first, then the smallest
+// workgroup.
+bool best_wave_grid(int MB, int NB, int vgpr_budget, bool exact_only, WaveGrid* out) {
     bool found = false;
     for (int wm = 1; wm <= MB; ++wm) {
         if (MB % wm) continue;
         const int mbw = MB / wm;
         if (mbw != 1 && mbw != 2) continue;
-        for (int wn = 1; wn <= NB; ++wn) {
-            if (NB % wn) continue;
-            const int nbw = NB / wn;
+        for (int nbw = 1; nbw <= 8 && nbw <= NB; ++nbw) {
+            if (mbw * nbw > 8) continue;
+            const int wn = (NB + nbw - 1) / nbw;
+            if (exact_only && wn * nbw != NB) continue;
             const int64_t threads = 64LL * wm * wn;
-            if (mbw * nbw > 8 || !allowed_threads(threads) || 16 * mbw * nbw > vgpr_budget) continue;
+            if (!allowed_threads(threads) || 16 * mbw * nbw > vgpr_budget) continue;
             // a compute unit's register file holds 131072 lane-registers; leave 64 per lane for operands
             if (16 * mbw * nbw + 64 > 131072 / threads) continue;
-            WaveGrid g{(int)threads, mbw + nbw, wm, wn, 16 * mbw * nbw};
+            WaveGrid g{wn * nbw - NB, (int)threads, mbw + nbw, wm, wn, 16 * mbw * nbw};
             if (!found || g < *out) *out = g;
             found = true;
         }
@@ -122,8 +126,8 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                     int alpha = 0;
                     int lds_mult = 0;
                     if (path == IOLB_PATH_MFMA) {
-                        if (npix % 32 || z % 32) continue;
-                        if (!best_wave_grid(z / 32, (int)(npix / 32), vgpr_budget, &g)) continue;
+                        if (z % 32) continue;
+                        if (!best_wave_grid(z / 32, (int)((npix + 31) / 32), vgpr_budget, false, &g)) continue;
                         alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage,
                                              lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
                         lds_mult = 8;
@@ -137,7 +141,7 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                             if (z % groups) continue;
                             const int per_thread = z / groups;
                             if (per_thread > 16 || per_thread > vgpr_budget) continue;
-                            g = WaveGrid{T, 0, groups, 1, per_thread};
+                            g = WaveGrid{0, T, 0, groups, 1, per_thread};
                             found = true;
                             break;               // ascending T: the first is the smallest
                         }
@@ -156,8 +160,11 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                     c.cfg.acc_regs_per_thread = g.acc;
                     c.cfg.q_read_elems = nblocks * s.C * per_stage;
                     c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
-                    c.key = {-grid_efficiency(nblocks), c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z),
-                             -npix * z, -(int64_t)x, z, b, y, g.threads};
+                    // share of the workgroup's matrix-core work spent on pixels past the tile (MFMA path only)
+                    const int64_t slots = path == IOLB_PATH_MFMA ? (int64_t)(g.acc / 16 / (z / 32 / g.wm)) * g.wn * 32 : npix;
+                    const int64_t idle_pct = (100 * (slots - npix)) / slots;
+                    c.key = {-grid_efficiency(nblocks), idle_pct <= kIdleOkPct ? 0 : idle_pct, c.cfg.q_read_elems,
+                             std::llabs(npix * st2 - RS * z), -npix * z, -(int64_t)x, z, b, y, g.threads};
                     out->push_back(c);
                 }
             }
@@ -179,7 +186,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             if (z % 32) continue;
             if (use_box && !((int64_t)z * z <= box && tb * tb <= box)) continue;
             WaveGrid g{};
-            if (!best_wave_grid(z / 32, (int)(tb / 32), vgpr_budget, &g)) continue;
+            if (!best_wave_grid(z / 32, (int)(tb / 32), vgpr_budget, true, &g)) continue;    // tb is free: no idle blocks
             const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z),
                                            lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
             if (alpha == 0) continue;
@@ -193,7 +200,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             c.cfg.acc_regs_per_thread = g.acc;
             c.cfg.q_read_elems = nblocks * s.C * (tb + z);
             c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
-            c.key = {-grid_efficiency(nblocks), c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0};
+            c.key = {-grid_efficiency(nblocks), 0, c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0};
             out->push_back(c);
         }
 }

@@ -12,7 +12,7 @@ namespace iolb {
 
 struct Candidate {
     iolb_tile_config cfg;
-    std::array<int64_t, 9> key;   // lexicographic, smaller is better
+    std::array<int64_t, 10> key;   // lexicographic, smaller is better
 };
 
 // Checks a layer description and computes its output extents.

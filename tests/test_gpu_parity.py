@@ -118,6 +118,44 @@ def test_direct_full_size_sampled(gpu, name):
     assert np.isfinite(got).all()
 
 
+@pytest.mark.parametrize("name", ["alex1", "alex2", "alex3", "alex4"])
+def test_direct_alexnet_rows_full_size_sampled(gpu, name):
+    """The AlexNet rows of Table 2 (11x11 stride 4, 5x5 pad 2, 3x3 on 13x13) at batch 16."""
+    L = CONFIGS[name]
+    x, w = layer_inputs(L)
+    got = _run_direct(gpu, x, w, L.stride, L.pad)
+    N, K, P, Q = got.shape
+    idx = sample_output_indices(N, K, P, Q, 4096, seed=L.seed)
+    ref = conv_ref_points(x, w, idx, L.stride, L.pad)
+    g = got[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+    assert rel_err(g, ref) <= TOL_DIRECT
+    assert np.isfinite(got).all()
+
+
+def test_direct_is_reproducible_bit_for_bit(gpu):
+    """Each output block is owned by one workgroup and summed in a fixed order: no run-to-run noise."""
+    x, w = make_inputs(8, 32, 28, 28, 64, 3, 3, "u01", "he", seed=5)
+    a = _run_direct(gpu, x, w, 1, 1)
+    b = _run_direct(gpu, x, w, 1, 1)
+    assert np.array_equal(a, b)
+
+
+def test_direct_shallower_stages_agree(gpu):
+    """The same tile with alpha = 16, 8, 4 (C = 24 is padded to whole stages differently each time)."""
+    torch, B = gpu
+    N, C, H, W, K = 4, 24, 28, 28, 64
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=6)
+    ref = conv_ref(x, w, 1, 1)
+    tile = B.iolb_enumerate(B.make_shape(N, C, H, W, K), 163840, 0, False)[0]
+    assert tile["path"] == B.PATH_MFMA
+    a = tile["alpha"]
+    while a >= 4:
+        cfg = dict(tile, alpha=a, lds_bytes_used=tile["lds_bytes_used"] // tile["alpha"] * a)
+        got = _run_direct(gpu, x, w, 1, 1, cfg=cfg)
+        assert rel_err(got, ref) <= TOL_DIRECT, a
+        a //= 2
+
+
 # ---------------------------------------------------------------------------------------------
 # Winograd
 # ---------------------------------------------------------------------------------------------
@@ -165,7 +203,7 @@ def test_winograd_caller_workspace_and_tiles(gpu):
         assert rel_err(got, ref) <= TOL_WINO, cfg
 
 
-@pytest.mark.parametrize("name,m", [("cfg5a", 2), ("cfg5b", 4), ("cfg5c", 4), ("cfg5d", 2)])
+@pytest.mark.parametrize("name,m", [("cfg5a", 2), ("cfg5b", 4), ("cfg5c", 4), ("cfg5d", 2), ("alex3", 4), ("alex4", 2)])
 def test_winograd_full_size_sampled(gpu, name, m):
     L = CONFIGS[name]
     x, w = layer_inputs(L)
