@@ -12,8 +12,9 @@ import json
 import sys
 
 
-def time_call(torch, fn, reps):
-    fn()
+def time_call(torch, fn, reps, warmup=2):
+    for _ in range(warmup):
+        fn()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
@@ -24,7 +25,7 @@ def time_call(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-def sweep(layer_name, algo="direct", max_tiles=0, reps=3, vary_alpha=False, use_box=False, lds_bytes=0):
+def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_box=False, lds_bytes=0):
     import torch
     from . import binding as B
     from .inputs import CONFIGS, layer_inputs
@@ -86,7 +87,7 @@ def main():
     ap.add_argument("--layer", default="cfg3")
     ap.add_argument("--algo", default="direct")
     ap.add_argument("--max", type=int, default=0, help="time at most this many tiles (evenly spaced in tuner order)")
-    ap.add_argument("--reps", type=int, default=3)
+    ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--alphas", action="store_true", help="also time each tile with shallower stages")
     ap.add_argument("--box", action="store_true", help="only tiles inside the optimality-condition box")
     ap.add_argument("--lds", type=int, default=0, help="LDS budget per workgroup for the enumeration")

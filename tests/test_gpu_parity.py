@@ -215,6 +215,31 @@ def test_winograd_full_size_sampled(gpu, name, m):
     assert np.isfinite(got).all()
 
 
+def test_measured_autotuner_returns_a_valid_fast_tile(gpu):
+    """The measured tuning loop on a small layer: the tile it returns is one of the domain, gives the
+    right layer, and is not slower than the analytical pick by more than timing noise allows."""
+    torch, B = gpu
+    from paper_2012_15667_amd import autotune as A
+    from paper_2012_15667_amd.sweep import time_call
+    N, C, H, W, K = 8, 32, 28, 28, 64
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=8)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    shape = B.make_shape(N, C, H, W, K)
+    dom = A.with_stage_depths(B.iolb_enumerate(shape, 163840, 0, True), 4)
+    y = torch.empty((N, K, H, W), dtype=torch.float32, device="cuda")
+
+    def measure(cfg):
+        return time_call(torch, lambda: B.conv_direct(xd, wd, 1, 1, y=y, cfg=cfg), 3)
+
+    pick = B.iolb_tune(shape)
+    best, best_ms, history = A.autotune(dom, measure, n_s=6, patience=2, max_iterations=6, seed=3, seeds=[pick])
+    assert A._key(best) in {A._key(c) for c in dom}
+    assert history[-1][0] <= len(dom)
+    assert best_ms <= measure(pick) * 1.25
+    got = _run_direct(gpu, x, w, 1, 1, cfg=best)
+    assert rel_err(got, conv_ref(x, w, 1, 1)) <= TOL_DIRECT
+
+
 # ---------------------------------------------------------------------------------------------
 # error paths (nothing is launched)
 # ---------------------------------------------------------------------------------------------
