@@ -26,13 +26,14 @@ extern "C" {
 
 #define IOLB_OK            0
 #define IOLB_EINVAL       -1   /* null pointer, non-positive extent, stride < 1, pad < 0, empty output */
-#define IOLB_EUNSUPPORTED -2   /* Winograd m outside {2,4}; algo outside the enum */
+#define IOLB_EUNSUPPORTED -2   /* Winograd m outside {2,4}; algo or layout outside its enum */
 #define IOLB_ENOTILE      -3   /* no tile fits the LDS / register budgets */
 #define IOLB_EWORKSPACE   -4   /* workspace missing or too small */
 #define IOLB_EHIP         -5   /* a HIP runtime call or launch failed; see iolb_last_hip_error */
 
 enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2 };
 enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1 };
+enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1 };   /* per image: channels outermost / innermost */
 
 /* A convolution layer (Sec. 2.2).  Output extents are P = floor((H+2 pad-R)/stride)+1 and
  * Q = floor((W+2 pad-S)/stride)+1.  For the Winograd algos R = S = 3 and stride = 1. */
@@ -87,6 +88,14 @@ int conv_direct(const float* x, const float* w, float* y,
 int conv_direct_cfg(const float* x, const float* w, float* y,
                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                     const iolb_tile_config* cfg);
+
+/* Direct convolution with the tensor layout as a parameter (the layout entry of the searching
+ * domain, Table 1 of Sec. 6.2).  IOLB_LAYOUT_CHW: as conv_direct.  IOLB_LAYOUT_HWC:
+ * x: [N][H][W][C], y: [N][P][Q][K].  w is [K][C][R][S] for both.  cfg may be NULL (the tuned
+ * tile is used; tiles do not depend on the layout).  Other layout values: IOLB_EUNSUPPORTED. */
+int conv_direct_layout(const float* x, const float* w, float* y,
+                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                       int layout, const iolb_tile_config* cfg);
 
 /* Winograd F(m x m, 3 x 3) convolution (Sec. 2.3; four steps of Sec. 4.3), R = S = 3,
  * stride 1, pad 1 (P = H, Q = W), m in {2, 4}.  Same layouts as conv_direct.  The transformed

@@ -80,3 +80,12 @@ def conv_ref_points(x, w, idx, stride=1, pad=0):
     if rc < 0:
         raise ValueError("conv_ref_points_f64 rejected the arguments")
     return out
+
+
+def conv_ref_hwc(x_hwc, w, stride=1, pad=0):
+    """The same definition for tensors stored channels-innermost (the HWC layout of Table 1,
+    Sec. 6.2): x_hwc[n,h,w,c], result y[n,p,q,k]; w stays [k,c,r,s].  Only the index order
+    differs, so the tensors are permuted around conv_ref."""
+    x = np.ascontiguousarray(np.transpose(np.asarray(x_hwc), (0, 3, 1, 2)))
+    y = conv_ref(x, w, stride, pad)
+    return np.ascontiguousarray(np.transpose(y, (0, 2, 3, 1)))

@@ -11,7 +11,10 @@ Three parts, as in Sec. 6.1:
 The loop model training -> configuration searching -> dataset updating (Sec. 6.3) stops when the best
 measured time has not improved for `patience` iterations.
 
-    python -m paper_2012_15667_amd.autotune --layer alex3 --algo direct [--no-box]
+    python -m paper_2012_15667_amd.autotune --layer alex3 --algo direct [--no-box] [--layouts]
+
+With --layouts the tensor layout (CHW or HWC, Table 1) is one more parameter of the domain: every tile is
+a candidate in both layouts and the engine reports which layout its best configuration uses.
 """
 import argparse
 import json
@@ -25,7 +28,8 @@ FEATURES = ("b", "x", "y", "z", "alpha", "threads", "waves_m", "waves_n", "lds_b
 
 def features(cfg):
     """Numeric description of a configuration for the cost model (logs of the integer fields)."""
-    return [math.log2(max(1, cfg[k])) for k in FEATURES] + [math.log2(max(1, cfg["b"] * cfg["x"] * cfg["y"]))]
+    return [math.log2(max(1, cfg[k])) for k in FEATURES] + [math.log2(max(1, cfg["b"] * cfg["x"] * cfg["y"])),
+                                                            float(cfg.get("layout", 0))]
 
 
 def with_stage_depths(tiles, min_alpha=4):
@@ -42,19 +46,31 @@ def with_stage_depths(tiles, min_alpha=4):
     return out
 
 
+def with_layouts(tiles):
+    """Each configuration in both tensor layouts (0: channels outermost, 1: channels innermost)."""
+    return [dict(t, layout=l) for t in tiles for l in (0, 1)]
+
+
+PARAMS = ("b", "x", "y", "z", "alpha", "layout")
+
+
+def _params(cfg):
+    return tuple(cfg.get(p, 0) for p in PARAMS)
+
+
 def _key(cfg):
-    return tuple(cfg[k] for k in ("b", "x", "y", "z", "alpha", "threads", "waves_m", "waves_n", "path"))
+    return tuple(cfg[k] for k in ("b", "x", "y", "z", "alpha", "threads", "waves_m", "waves_n", "path")) + \
+        (cfg.get("layout", 0),)
 
 
 def neighbours(index, cfg):
-    """Configurations of the domain that differ from cfg in ONE of (b, x, y, z, alpha) by one step of
-    that parameter's sorted value list.  `index` maps parameter tuples to domain entries."""
+    """Configurations of the domain that differ from cfg in ONE of (b, x, y, z, alpha, layout) by one
+    step of that parameter's sorted value list.  `index` maps parameter tuples to domain entries."""
     out = []
-    params = ("b", "x", "y", "z", "alpha")
-    cur = tuple(cfg[p] for p in params)
-    for i, p in enumerate(params):
+    cur = _params(cfg)
+    for i, p in enumerate(PARAMS):
         values = index["values"][p]
-        j = values.index(cfg[p])
+        j = values.index(cur[i])
         for jj in (j - 1, j + 1):
             if 0 <= jj < len(values):
                 cand = list(cur)
@@ -66,9 +82,8 @@ def neighbours(index, cfg):
 
 
 def build_index(dom):
-    params = ("b", "x", "y", "z", "alpha")
-    return {"values": {p: sorted({c[p] for c in dom}) for p in params},
-            "by_params": {tuple(c[p] for p in params): c for c in dom}}
+    return {"values": {p: sorted({c.get(p, 0) for c in dom}) for p in PARAMS},
+            "by_params": {_params(c): c for c in dom}}
 
 
 class CostModel:
@@ -179,7 +194,7 @@ def autotune(dom, measure, n_s=8, patience=4, max_iterations=40, seed=0, seeds=(
 # GPU front end
 # ---------------------------------------------------------------------------------------------
 
-def gpu_domain_and_measure(layer_name, algo, use_box=True, reps=3):
+def gpu_domain_and_measure(layer_name, algo, use_box=True, reps=3, layouts=False):
     import torch
     from . import binding as B
     from .inputs import CONFIGS, layer_inputs
@@ -200,8 +215,15 @@ def gpu_domain_and_measure(layer_name, algo, use_box=True, reps=3):
     if algo != "direct":
         ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, 2 if algo == "wino2" else 4),
                          dtype=torch.uint8, device="cuda")
+    if layouts and algo == "direct":
+        dom = with_layouts(dom)
+        x_hwc = xd.permute(0, 2, 3, 1).contiguous()
+        y_hwc = torch.empty((L.N, P, Q, L.K), dtype=torch.float32, device="cuda")
 
     def measure(cfg):
+        if algo == "direct" and cfg.get("layout", 0) == 1:
+            return time_call(torch, lambda: B.conv_direct_layout(x_hwc, wd, L.stride, L.pad, B.LAYOUT_HWC, y=y_hwc,
+                                                                 cfg=cfg), reps)
         if algo == "direct":
             return time_call(torch, lambda: B.conv_direct(xd, wd, L.stride, L.pad, y=y, cfg=cfg), reps)
         return time_call(torch, lambda: B.conv_winograd(xd, wd, 2 if algo == "wino2" else 4, y=y, cfg=cfg,
@@ -215,13 +237,14 @@ def main():
     ap.add_argument("--layer", default="alex3")
     ap.add_argument("--algo", default="direct")
     ap.add_argument("--no-box", action="store_true", help="search the whole domain, not only the optimality box")
+    ap.add_argument("--layouts", action="store_true", help="the tensor layout (CHW / HWC) is part of the domain")
     ap.add_argument("--n-s", type=int, default=8)
     ap.add_argument("--patience", type=int, default=4)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--exhaustive", action="store_true", help="also time every configuration for comparison")
     a = ap.parse_args()
     from . import binding as B
-    shape, pick, dom, measure = gpu_domain_and_measure(a.layer, a.algo, not a.no_box)
+    shape, pick, dom, measure = gpu_domain_and_measure(a.layer, a.algo, not a.no_box, layouts=a.layouts)
     full = with_stage_depths(B.iolb_enumerate(shape, 163840, 0, False), 4 if dom and dom[0]["path"] == 1 else 1)
     seeds = [c for c in dom if all(c[k] == pick[k] for k in ("b", "x", "y", "z", "alpha"))]
     best, best_ms, history = autotune(dom, measure, a.n_s, a.patience, seed=a.seed, seeds=seeds)

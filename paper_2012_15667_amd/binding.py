@@ -11,8 +11,9 @@ LIB_PATH = os.path.join(_PKG, "libiolbconv.so")
 
 DIRECT, WINO_F2, WINO_F4 = 0, 1, 2
 PATH_FMA, PATH_MFMA = 0, 1
+LAYOUT_CHW, LAYOUT_HWC = 0, 1
 
-EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_winograd", "conv_winograd_workspace_bytes",
+EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_workspace_bytes",
            "conv_winograd_ws", "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_set_stream",
            "iolb_timing_enable", "iolb_timing_read", "iolb_release_workspace", "iolb_strerror",
            "iolb_last_hip_error"]
@@ -67,6 +68,8 @@ def lib():
         L.conv_direct.argtypes = [vp, vp, vp] + [i] * 9
         L.conv_direct_cfg.restype = i
         L.conv_direct_cfg.argtypes = [vp, vp, vp] + [i] * 9 + [ctypes.POINTER(TileConfig)]
+        L.conv_direct_layout.restype = i
+        L.conv_direct_layout.argtypes = [vp, vp, vp] + [i] * 10 + [ctypes.POINTER(TileConfig)]
         L.conv_winograd.restype = i
         L.conv_winograd.argtypes = [vp, vp, vp] + [i] * 6
         L.conv_winograd_workspace_bytes.restype = sz
@@ -166,6 +169,36 @@ def conv_direct(x, w, stride=1, pad=0, y=None, cfg=None):
     else:
         c = cfg if isinstance(cfg, TileConfig) else TileConfig.from_dict(cfg)
         _check(lib().conv_direct_cfg(*args, ctypes.byref(c)))
+    return y
+
+
+def conv_direct_layout(x, w, stride=1, pad=0, layout=LAYOUT_HWC, y=None, cfg=None):
+    """Direct convolution with the tensor layout given: LAYOUT_CHW as conv_direct; LAYOUT_HWC takes
+    x [N][H][W][C] and returns y [N][P][Q][K].  w is [K][C][R][S] for both."""
+    import torch
+    if layout == LAYOUT_HWC:
+        N, H, W, C = x.shape
+    else:
+        N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    valid = stride >= 1 and pad >= 0 and H + 2 * pad >= R and W + 2 * pad >= S
+    if valid:
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        shape = (N, P, Q, K) if layout == LAYOUT_HWC else (N, K, P, Q)
+        if y is None:
+            y = torch.empty(shape, dtype=torch.float32, device=x.device)
+        elif tuple(y.shape) != shape:
+            raise ValueError("y has the wrong shape")
+    elif y is None:
+        raise IolbError(-1, "invalid argument")
+    _use_current_stream()
+    c = None
+    if cfg is not None:
+        c = ctypes.byref(cfg if isinstance(cfg, TileConfig) else TileConfig.from_dict(cfg))
+    _check(lib().conv_direct_layout(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, R, S,
+                                    stride, pad, int(layout), c))
     return y
 
 

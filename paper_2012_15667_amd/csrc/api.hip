@@ -148,7 +148,8 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
     return IOLB_EINVAL;
 }
 
-int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, int P, int Q, const iolb_tile_config& cfg)
+int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, int P, int Q, const iolb_tile_config& cfg,
+               int layout = IOLB_LAYOUT_CHW)
 {
     DeviceState* dev = nullptr;
     int rc = device_state(&dev);
@@ -163,6 +164,7 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     g.xh = (cfg.x - 1) * s.stride + s.S;
     g.yh = (cfg.y - 1) * s.stride + s.R;
     g.halo = cfg.b * g.xh * g.yh;
+    g.hwc = layout == IOLB_LAYOUT_HWC;
     if ((int64_t)g.nbx * g.nby * g.nbn * g.nbk > 0x7fffffffLL) return IOLB_EINVAL;
     hipStream_t st = t_stream;
     if (cfg.path == IOLB_PATH_MFMA) {
@@ -173,7 +175,7 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
         float* wt = static_cast<float*>(dev->ws);
         IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, s.C * s.R * s.S, c_padded * s.R * s.S, st));
         MainKernelTimer timer(st, IOLB_TIME_DIRECT);
-        IOLB_HIP(iolb::launch_direct_mfma(x, wt, y, g, st));
+        IOLB_HIP(g.hwc ? iolb::launch_direct_mfma_hwc(x, wt, y, g, st) : iolb::launch_direct_mfma(x, wt, y, g, st));
         timer.stop(st);
     } else {
         MainKernelTimer timer(st, IOLB_TIME_DIRECT);
@@ -280,6 +282,27 @@ int conv_direct(const float* x, const float* w, float* y, int N, int C, int H, i
     rc = tuned_tile(s, &cfg);
     if (rc != IOLB_OK) return rc;
     return run_direct(x, w, y, s, P, Q, cfg);
+}
+
+int conv_direct_layout(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                       int stride, int pad, int layout, const iolb_tile_config* cfg)
+{
+    if (!x || !w || !y) return IOLB_EINVAL;
+    if (layout != IOLB_LAYOUT_CHW && layout != IOLB_LAYOUT_HWC) return IOLB_EUNSUPPORTED;
+    const iolb_shape s{N, C, H, W, K, R, S, stride, pad, IOLB_DIRECT};
+    int P = 0, Q = 0;
+    int rc = iolb::validate_shape(s, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    iolb_tile_config tile;
+    if (cfg) {
+        rc = check_config(s, *cfg);
+        if (rc != IOLB_OK) return rc;
+        tile = *cfg;
+    } else {
+        rc = tuned_tile(s, &tile);
+        if (rc != IOLB_OK) return rc;
+    }
+    return run_direct(x, w, y, s, P, Q, tile, layout);
 }
 
 size_t conv_winograd_workspace_bytes(int N, int C, int H, int W, int K, int m)

@@ -5,6 +5,8 @@
 // its partial sums in registers for the whole channel loop.  Each stage copies alpha channels of the
 // input tile xh * yh (zero-filled outside the image) and the matching weight slab into LDS, then
 // every lane updates its pixel for `per_thread` output channels.  Outputs are written once.
+// Both tensor layouts (channels outermost or innermost, g.hwc) share the kernel; the weights are
+// w[K][C][R][S] in either case.
 #include "kernels.h"
 
 namespace iolb {
@@ -48,7 +50,8 @@ direct_fma_kernel(const float* __restrict__ x, const float* __restrict__ w, floa
             const int gy = gy0 + hy, gx = gx0 + hx;
             float v = 0.f;
             if (c0 + c < g.C && gy >= 0 && gy < g.H && gx >= 0 && gx < g.W)
-                v = x[(((size_t)(n0 + im) * g.C + c0 + c) * g.H + gy) * g.W + gx];
+                v = g.hwc ? x[(((size_t)(n0 + im) * g.H + gy) * g.W + gx) * g.C + c0 + c]
+                          : x[(((size_t)(n0 + im) * g.C + c0 + c) * g.H + gy) * g.W + gx];
             xs[i] = v;
         }
         for (int i = tid; i < g.alpha * RS * g.z; i += T) {
@@ -76,7 +79,8 @@ direct_fma_kernel(const float* __restrict__ x, const float* __restrict__ w, floa
         for (int j = 0; j < ZT; ++j) {
             if (j < g.per_thread) {
                 const int k = k0 + kg * g.per_thread + j;
-                y[(((size_t)(n0 + img) * g.K + k) * g.P + y0 + py) * g.Q + x0 + px] = acc[j];
+                if (g.hwc) y[(((size_t)(n0 + img) * g.P + y0 + py) * g.Q + x0 + px) * g.K + k] = acc[j];
+                else       y[(((size_t)(n0 + img) * g.K + k) * g.P + y0 + py) * g.Q + x0 + px] = acc[j];
             }
         }
     }

@@ -1,253 +1,10 @@
-// Direct convolution on the fp32 matrix cores (v_mfma_f32_32x32x2_f32), dataflow of Sec. 5.2.
-//
-// One workgroup owns an output sub-block of b images * ty rows * tx columns (npix pixels, cut into
-// blocks of 32, the last one possibly ragged) by z output channels (a multiple of 32) and keeps its partial sums in accumulator registers
-// for the whole channel loop; they are written to HBM once.  The contraction over (c, r, s) runs as an
-// implicit GEMM:  acc[z][npix] += W[z][alpha*R*S] * X[alpha*R*S][npix], where X is never materialised:
-// each lane reads its pixel's window straight out of the LDS-resident input tile xh * yh.
-//
-// Per stage of alpha channels (a multiple of 4) the workgroup stages, with LDS-direct loads (no
-// registers in between),
-//   - the weight slab  [alpha][R*S][z]  from the re-laid-out weights wt[C'][R*S][K] (C' = C rounded up
-//     to whole stages, the extra rows zero), whole rows per instruction, 16 bytes per lane;
-//   - the input tile   [alpha][b][yh][xh], one instruction per (tile row, 64-column segment, channel):
-//     the row's base address is wave-uniform, lanes add their column.  Elements outside the image are
-//     never loaded: both LDS buffers are cleared once and those positions stay zero.
-// Two LDS buffers alternate.  The loads of stage s+1 are issued from inside the multiply phase of
-// stage s, by the two waves of a SIMD half a stage apart, so that the matrix core always has a wave
-// that is multiplying.
-//
-// Wave layout: waves_m x waves_n waves; a wave owns MBW x NBW blocks of 32 x 32 partial sums.
-// Inside one MFMA the two k-slices are fed by lane halves: lanes 0-31 take channel c2, lanes 32-63 take
-// channel c2 + alpha/2, so that both halves use the same LDS offset per (r, s).  The LDS reads of step
-// j+1 are interleaved between the MFMAs of step j (an MFMA blocks its wave's issue while it runs, so
-// a wave must never have a stretch without one).
-#include "kernels.h"
-#include "lds_dma.h"
+// Direct convolution on the matrix cores, x[N][C][H][W] -> y[N][K][P][Q] instantiations, and the
+// weight re-layout pre-pass shared by both tensor layouts.
+#include "direct_mfma_impl.h"
 
 namespace iolb {
 
 namespace {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-template <int MBW, int NBW, int LB, int RR, int SS>
-__global__ void __launch_bounds__(LB)
-direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y, DirectGeom g)
-{
-    extern __shared__ float lds[];
-    const int tid = threadIdx.x, T = blockDim.x;
-    const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-
-    // consecutive workgroup ids are dealt round-robin to the 8 XCDs; remap so that each XCD (one L2)
-    // works on a contiguous range of blocks, whose channel blocks share the same input tile
-    int bid = blockIdx.x;
-    const int nblk = gridDim.x;
-    if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
-    const int kb = bid % g.nbk; bid /= g.nbk;
-    const int xb = bid % g.nbx; bid /= g.nbx;
-    const int yb = bid % g.nby;
-    const int nb_ = bid / g.nby;
-    const int k0 = kb * g.z, x0 = xb * g.tx, y0 = yb * g.ty, n0 = nb_ * g.b;
-
-    const int RS = g.R * g.S;
-    const int HW = g.H * g.W;
-    const int wfloats = g.alpha * RS * g.z;                 // weight slab, multiple of 32 floats
-    const int stage_floats = (wfloats + g.alpha * g.halo + 3) & ~3;
-    const int half_c = g.alpha >> 1;
-
-    const int wm_i = wave % g.waves_m, wn_i = wave / g.waves_m;
-
-    // per-lane read bases inside a stage buffer
-    // A tile whose pixel count is not a multiple of 32 (or does not fill the wave grid) leaves pixel slots
-    // idle: they read the tile's last pixel and store nothing.
-    int bbase[NBW], pimg[NBW], ppy[NBW], ppx[NBW];
-    bool pvalid[NBW];
-    const int txy = g.tx * g.ty;
-    const int npix = g.b * txy;
-#pragma unroll
-    for (int nb = 0; nb < NBW; ++nb) {
-        const int slot = (wn_i * NBW + nb) * 32 + l32;
-        pvalid[nb] = slot < npix;
-        const int pix = pvalid[nb] ? slot : npix - 1;
-        pimg[nb] = pix / txy;
-        const int rem = pix % txy;
-        ppy[nb] = rem / g.tx;
-        ppx[nb] = rem % g.tx;
-        bbase[nb] = wfloats + half * half_c * g.halo + pimg[nb] * g.yh * g.xh + ppy[nb] * g.stride * g.xh +
-                    ppx[nb] * g.stride;
-    }
-    const int abase = half * half_c * RS * g.z + wm_i * MBW * 32 + l32;
-
-    floatx16 acc[MBW][NBW];
-#pragma unroll
-    for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NBW; ++nb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.f;
-
-    const int gy0 = y0 * g.stride - g.pad, gx0 = x0 * g.stride - g.pad;
-    const int nwaves = T >> 6;
-    const int tile_rows = g.b * g.yh;                       // rows of the input tile per channel
-    const int nseg = (g.xh + 63) >> 6;                      // 64-lane segments per tile row
-    const float* wslab = wt + k0;                           // row (c*RS + rs) of the slab starts at wslab + row*K
-
-    // Elements of the tile that fall outside the image are zero in every stage: clear both buffers
-    // once, then only ever load the elements that exist.
-    for (int i = tid; i < 2 * stage_floats; i += T) lds[i] = 0.f;
-    __syncthreads();
-
-    // first (tile row, segment) item of this wave
-    const int im_first = wave / (nseg * g.yh);
-    const int hy_first = (wave % (nseg * g.yh)) / nseg, seg_first = wave % nseg;
-
-    // Stage c0..c0+alpha-1 into buf.  Weights: alpha*RS rows of z floats, whole rows per instruction.
-    // Input tile: one instruction per (tile row, 64-lane segment, channel); the row's base address is
-    // wave-uniform, lanes add their column.  Channels at or beyond C (last stage when alpha does not
-    // divide C) are zero rows in wt and are cleared here for the tile.
-    auto issue_stage = [&](int c0, float* buf) {
-        stage_rows(wslab + (size_t)c0 * RS * g.K, g.K, g.z >> 2, g.alpha * RS, buf, wave, nwaves, lane);
-        float* xbuf = buf + wfloats;
-        int im = im_first, hy = hy_first, seg = seg_first;
-        for (int item = wave; item < tile_rows * nseg; item += nwaves) {
-            const int gy = gy0 + hy;
-            const int hx = seg * 64 + lane, gx = gx0 + hx;
-            if (gy >= 0 && gy < g.H && hx < g.xh && gx >= 0 && gx < g.W) {
-                const float* rowp = x + (((size_t)(n0 + im) * g.C + c0) * g.H + gy) * g.W;
-                const unsigned dst = lds_byte_address(xbuf + (im * g.yh + hy) * g.xh + seg * 64);
-                for (int c = 0; c < g.alpha && c0 + c < g.C; ++c)
-                    lds_dma_load_4(rowp + (size_t)c * HW, 4u * (unsigned)gx, dst + 4u * (unsigned)(c * g.halo));
-            }
-            // next item of this wave: advance (im, hy, seg) by nwaves segments
-            seg += nwaves;
-            while (seg >= nseg) { seg -= nseg; ++hy; }
-            while (hy >= g.yh) { hy -= g.yh; ++im; }
-        }
-        if (c0 + g.alpha > g.C)
-            for (int i = (g.C - c0) * g.halo + tid; i < g.alpha * g.halo; i += T) xbuf[i] = 0.f;
-    };
-
-    const int nstages = (g.C + g.alpha - 1) / g.alpha;
-    const int nsteps = half_c * RS;
-    const int step_r = g.xh - (g.S - 1);                          // tile offset increments at a row wrap
-    const int step_c = g.halo - (g.R - 1) * g.xh - (g.S - 1);     // ... and at a channel wrap
-    // Waves w and w+4 share a SIMD.  Each stages its part of the NEXT stage from inside the multiply
-    // phase of the current one, the second group half a stage later than the first, so that while one
-    // wave of a SIMD is busy issuing loads the other keeps the matrix core fed.
-    const int issue_group = (wave >> 2) & 1;
-
-    auto interleave_step = [&]() {
-        constexpr int MF = MBW * NBW, RD = MBW + NBW, PAIRS = (RD + 1) / 2;
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if constexpr (MF - 1 >= PAIRS) {
-#pragma unroll
-            for (int i = 0; i < PAIRS; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            }
-            if constexpr (MF - 1 - PAIRS > 0) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1 - PAIRS, 0);
-        } else {
-            __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
-            if constexpr (MF > 1) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1, 0);
-        }
-    };
-    auto multiply = [&](const float (&am)[MBW], const float (&bm)[NBW]) {
-#pragma unroll
-        for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NBW; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
-    };
-
-    issue_stage(0, lds);
-    for (int s = 0; s < nstages; ++s) {
-        lds_dma_wait_all();
-        __syncthreads();                                    // stage s has landed; stage s-1 is consumed
-        float* cur = lds + (s & 1) * stage_floats;
-        float* nxt = lds + ((s + 1) & 1) * stage_floats;
-        const bool more = s + 1 < nstages;
-        const int c0_next = (s + 1) * g.alpha;
-
-        if constexpr (RR > 0) {
-            // Kernel extents known at compile time: the R*S steps of a channel pair are unrolled, so a
-            // step costs its LDS reads and a couple of address adds.  A body is two channel pairs (alpha
-            // is a multiple of 4), which keeps the two operand register sets in phase.
-            constexpr int RSc = RR * SS, BODY = 2 * RSc;
-            const int nbodies = half_c >> 1;
-            float fa[2][MBW], fb[2][NBW];
-            auto fetch = [&](int set, int bi, int t) {
-                const int cl = t / RSc, rs = t % RSc, r = rs / SS, sx = rs % SS;
-                const float* wp = cur + abase + ((2 * bi + cl) * RSc + rs) * g.z;
-                const int sc = (2 * bi + cl) * g.halo + r * g.xh;
-#pragma unroll
-                for (int mb = 0; mb < MBW; ++mb) fa[set][mb] = wp[mb * 32];
-#pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) fb[set][nb] = cur[bbase[nb] + sc + sx];
-            };
-            fetch(0, 0, 0);
-            for (int bi = 0; bi < nbodies; ++bi) {
-                const int bnext = (bi + 1 < nbodies) ? bi + 1 : 0;   // after the last body: wrap, read and drop
-#pragma unroll
-                for (int t = 0; t < BODY; ++t) {
-                    if (t == 0 || t == RSc) {
-                        if (more && bi == 0 && issue_group == (t == 0 ? 0 : 1)) issue_stage(c0_next, nxt);
-                    }
-                    if (t + 1 < BODY) fetch((t + 1) & 1, bi, t + 1);
-                    else              fetch(0, bnext, 0);
-                    multiply(fa[t & 1], fb[t & 1]);
-                    interleave_step();
-                }
-            }
-        } else {
-            // General loop: steps j = (c2, r, s) flattened, two per iteration with two operand register
-            // sets (alpha is a multiple of 4, so the count is even).  After the last step the fetch wraps
-            // to step 0 (read and dropped).
-            const float* wrow = cur + abase;
-            int r = 0, sx = 0, xo = 0;              // position of the NEXT step to fetch
-            float a[MBW], bv[NBW], a1[MBW], b1[NBW];
-            auto fetch = [&](float (&an)[MBW], float (&bn)[NBW], bool last) {
-#pragma unroll
-                for (int mb = 0; mb < MBW; ++mb) an[mb] = wrow[mb * 32];
-#pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) bn[nb] = cur[bbase[nb] + xo];
-                // advance (r, s), the tile offset xo = c2*halo + r*xh + s and the weight row without branches
-                const int wrap_s = (sx + 1 == g.S), wrap_r = wrap_s & (r + 1 == g.R);
-                xo = last ? 0 : xo + (wrap_r ? step_c : (wrap_s ? step_r : 1));
-                wrow = last ? cur + abase : wrow + g.z;
-                sx = wrap_s ? 0 : sx + 1;
-                r = wrap_r ? 0 : r + wrap_s;
-            };
-            const int issue_at = issue_group ? ((nsteps >> 1) & ~1) : 0;
-            fetch(a, bv, false);
-#pragma unroll 1
-            for (int j = 0; j < nsteps; j += 2) {
-                if (more && j == issue_at) issue_stage(c0_next, nxt);
-                fetch(a1, b1, false);
-                multiply(a, bv);
-                interleave_step();
-                fetch(a, bv, j + 2 >= nsteps);
-                multiply(a1, b1);
-                interleave_step();
-            }
-        }
-    }
-
-    // each partial sum is complete: write the block once.  Register i of a 32 x 32 block holds
-    // channel 8*(i/4) + 4*half + i%4 of pixel l32.
-    const size_t PQ = (size_t)g.P * g.Q;
-#pragma unroll
-    for (int nb = 0; nb < NBW; ++nb) {
-        if (!pvalid[nb]) continue;
-        float* yp = y + ((size_t)(n0 + pimg[nb]) * g.K + k0) * PQ + (size_t)(y0 + ppy[nb]) * g.Q + x0 + ppx[nb];
-#pragma unroll
-        for (int mb = 0; mb < MBW; ++mb) {
-            const int kbase = (wm_i * MBW + mb) * 32 + 4 * half;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) yp[(size_t)(kbase + 8 * (i >> 2) + (i & 3)) * PQ] = acc[mb][nb][i];
-        }
-    }
-}
 
 // w[K][CRS] -> wt[rows][K] through a 32 x 33 LDS tile: both sides coalesced.  rows >= CRS; the rows
 // beyond CRS (channels added to fill the last stage) are written as zeros.
@@ -268,22 +25,6 @@ weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int 
     }
 }
 
-template <int MBW, int NBW, int LB, int RR, int SS>
-hipError_t launch_one(const float* x, const float* wt, float* y, const DirectGeom& g,
-                      size_t shm, hipStream_t st)
-{
-    auto kern = direct_mfma_kernel<MBW, NBW, LB, RR, SS>;
-    static bool raised = false;               // dynamic LDS above 64 KB needs an opt-in, once per kernel
-    if (shm > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
-    const int grid = g.nbk * g.nbx * g.nby * g.nbn;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(g.threads), shm, st, x, wt, y, g);
-    return hipGetLastError();
-}
-
 }  // namespace
 
 hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int rows, hipStream_t st)
@@ -295,34 +36,7 @@ hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int
 
 hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st)
 {
-    const int npix = g.b * g.tx * g.ty;
-    if (g.z % 32 || (g.alpha & 3) || g.threads != 64 * g.waves_m * g.waves_n) return hipErrorInvalidValue;
-    const int MB = g.z / 32, NB = (npix + 31) / 32;          // a ragged last block is masked in the kernel
-    if (MB % g.waves_m || g.waves_n > NB) return hipErrorInvalidValue;
-    const int mbw = MB / g.waves_m, nbw = (NB + g.waves_n - 1) / g.waves_n;
-    const size_t stage = ((size_t)g.alpha * ((size_t)g.R * g.S * g.z + g.halo) + 3) & ~(size_t)3;
-    const size_t shm = 2 * stage * sizeof(float);
-    if (shm > 160 * 1024) return hipErrorInvalidValue;
-    // the register file of a compute unit holds 131072 lane-registers: a workgroup of T threads gets
-    // 131072 / T per lane, of which 16 * mbw * nbw are partial sums
-    if (16 * mbw * nbw + 64 > 131072 / g.threads) return hipErrorInvalidValue;
-#define IOLB_CASE(M_, N_)                                                                              \
-    if (mbw == M_ && nbw == N_) {                                                                      \
-        if (g.R == 3 && g.S == 3) {                                                                    \
-            if (g.threads <= 256) return launch_one<M_, N_, 256, 3, 3>(x, wt, y, g, shm, st);          \
-            if (g.threads <= 512) return launch_one<M_, N_, 512, 3, 3>(x, wt, y, g, shm, st);          \
-            if constexpr (M_ * N_ <= 4) return launch_one<M_, N_, 1024, 3, 3>(x, wt, y, g, shm, st);   \
-        } else {                                                                                       \
-            if (g.threads <= 256) return launch_one<M_, N_, 256, 0, 0>(x, wt, y, g, shm, st);          \
-            if (g.threads <= 512) return launch_one<M_, N_, 512, 0, 0>(x, wt, y, g, shm, st);          \
-            if constexpr (M_ * N_ <= 4) return launch_one<M_, N_, 1024, 0, 0>(x, wt, y, g, shm, st);   \
-        }                                                                                              \
-    }
-    IOLB_CASE(1, 1) IOLB_CASE(1, 2) IOLB_CASE(1, 3) IOLB_CASE(1, 4)
-    IOLB_CASE(1, 5) IOLB_CASE(1, 6) IOLB_CASE(1, 7) IOLB_CASE(1, 8)
-    IOLB_CASE(2, 1) IOLB_CASE(2, 2) IOLB_CASE(2, 3) IOLB_CASE(2, 4)
-#undef IOLB_CASE
-    return hipErrorInvalidValue;
+    return launch_direct_mfma_layout<false>(x, wt, y, g, st);
 }
 
 }  // namespace iolb

@@ -18,6 +18,7 @@ struct DirectGeom {
     int per_thread;            // FMA path: output channels per lane
     int nbx, nby, nbn, nbk;    // blocks along W_out, H_out, batch, C_out
     int xh, yh, halo;          // input tile extents and elements per channel (b * yh * xh)
+    int hwc;                   // 0: x[N][C][H][W], y[N][K][P][Q];  1: x[N][H][W][C], y[N][P][Q][K]
 };
 
 // Re-layout w[K][C][R][S] -> wt[rows][K] (rows >= CRS = C*R*S; rows beyond CRS are zero) so that a
@@ -27,6 +28,8 @@ hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int
 hipError_t launch_direct_fma(const float* x, const float* w, float* y, const DirectGeom& g, hipStream_t st);
 // wt: re-laid-out weights with ceil(C/alpha)*alpha*R*S rows.
 hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st);
+// The same for the channels-innermost tensor layout (g.hwc = 1).
+hipError_t launch_direct_mfma_hwc(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st);
 
 // Winograd F(m x m, 3 x 3), unfused: kernel transform, input transform, batched product over the
 // (m+2)^2 planes, output transform (steps 1-4 of Sec. 4.3).

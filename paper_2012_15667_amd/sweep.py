@@ -5,7 +5,9 @@ This is the measured check of the tuner: the paper prunes its searching domain w
 optimality condition and then searches by measurement (Sec. 6.2); here the pick is analytical and
 the measurement is the audit.
 
-    python -m paper_2012_15667_amd.sweep --layer cfg3 [--algo direct|wino2|wino4] [--max 200] [--alphas]
+    python -m paper_2012_15667_amd.sweep --layer cfg3 [--algo direct|direct_hwc|wino2|wino4] [--max 200] [--alphas]
+
+`direct_hwc` times the same tiles on channels-innermost tensors (conv_direct_layout).
 """
 import argparse
 import json
@@ -33,7 +35,10 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
     L = CONFIGS[layer_name]
     x, w = layer_inputs(L)
     xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
-    algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino4": B.WINO_F4}[algo]
+    hwc = algo == "direct_hwc"
+    if hwc:
+        xd = xd.permute(0, 2, 3, 1).contiguous()
+    algo_id = {"direct": B.DIRECT, "direct_hwc": B.DIRECT, "wino2": B.WINO_F2, "wino4": B.WINO_F4}[algo]
     shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
     pick = B.iolb_tune(shape)
     tiles = B.iolb_enumerate(shape, lds_bytes, 0, use_box)
@@ -55,9 +60,9 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
         tiles = tiles + extra
     P = (L.H + 2 * L.pad - L.R) // L.stride + 1
     Q = (L.W + 2 * L.pad - L.S) // L.stride + 1
-    y = torch.empty((L.N, L.K, P, Q), dtype=torch.float32, device="cuda")
+    y = torch.empty((L.N, P, Q, L.K) if hwc else (L.N, L.K, P, Q), dtype=torch.float32, device="cuda")
     ws = None
-    if algo != "direct":
+    if algo in ("wino2", "wino4"):
         ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, 2 if algo == "wino2" else 4),
                          dtype=torch.uint8, device="cuda")
     flops = 2.0 * L.N * L.K * P * Q * L.C * L.R * L.S
@@ -65,6 +70,8 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
     for t in tiles:
         if algo == "direct":
             fn = lambda: B.conv_direct(xd, wd, L.stride, L.pad, y=y, cfg=t)
+        elif hwc:
+            fn = lambda: B.conv_direct_layout(xd, wd, L.stride, L.pad, B.LAYOUT_HWC, y=y, cfg=t)
         else:
             fn = lambda: B.conv_winograd(xd, wd, 2 if algo == "wino2" else 4, y=y, cfg=t, workspace=ws)
         ms = time_call(torch, fn, reps)

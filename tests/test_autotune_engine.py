@@ -58,3 +58,21 @@ def test_seeds_are_measured_first_and_never_lost():
     seed_cfg = dom[0]
     best, best_ms, _ = A.autotune(dom, _synthetic_ms, n_s=4, patience=1, max_iterations=1, seed=2, seeds=[seed_cfg])
     assert best_ms <= _synthetic_ms(seed_cfg)
+
+
+def test_layout_is_a_parameter_of_the_domain():
+    """Table 1 lists the tensor layout among the tunables: with it in the domain, a neighbour step may flip
+    the layout alone, and the search settles on the layout that the measurements favour."""
+    dom = A.with_layouts(_domain())
+    assert len({A._key(c) for c in dom}) == len(dom)
+    idx = A.build_index(dom)
+    c = dom[len(dom) // 2]
+    flips = [n for n in A.neighbours(idx, c) if n["layout"] != c["layout"]]
+    assert len(flips) == 1 and all(flips[0][p] == c[p] for p in ("b", "x", "y", "z", "alpha"))
+
+    def measure(cfg):
+        return _synthetic_ms(cfg) * (0.8 if cfg["layout"] == 1 else 1.0)
+
+    best, best_ms, _ = A.autotune(dom, measure, n_s=8, patience=4, seed=3)
+    assert best["layout"] == 1
+    assert best_ms <= min(measure(c) for c in dom) * 1.03

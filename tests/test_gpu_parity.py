@@ -6,7 +6,7 @@ direct convolution 1e-4, Winograd 5e-3 (both F(2x2) and F(4x4)).
 import numpy as np
 import pytest
 
-from oracle.conv_oracle import conv_ref, conv_ref_points
+from oracle.conv_oracle import conv_ref, conv_ref_hwc, conv_ref_points
 from paper_2012_15667_amd.inputs import CONFIGS, layer_inputs, make_inputs, sample_output_indices
 from tests.conftest import rel_err
 
@@ -157,6 +157,69 @@ def test_direct_shallower_stages_agree(gpu):
 
 
 # ---------------------------------------------------------------------------------------------
+# direct convolution, channels-innermost tensors (the HWC layout of Table 1)
+# ---------------------------------------------------------------------------------------------
+
+def _to_hwc(a):
+    return np.ascontiguousarray(np.transpose(a, (0, 2, 3, 1)))
+
+
+def _run_direct_hwc(gpu, x_hwc, w, stride, pad, cfg=None):
+    torch, B = gpu
+    y = B.conv_direct_layout(torch.from_numpy(x_hwc).cuda(), torch.from_numpy(w).cuda(), stride, pad,
+                             B.LAYOUT_HWC, cfg=cfg)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("case", DIRECT_CASES)
+def test_direct_hwc_matches_oracle(gpu, case):
+    N, C, H, W, K, R, S, stride, pad = case
+    x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=300 + C + H)
+    x_hwc = _to_hwc(x)
+    ref = conv_ref_hwc(x_hwc, w, stride, pad)
+    got = _run_direct_hwc(gpu, x_hwc, w, stride, pad)
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL_DIRECT
+
+
+def test_direct_hwc_equals_chw_bit_for_bit(gpu):
+    """Both layouts stage the same LDS tile and sum in the same order: identical bits, permuted."""
+    torch, B = gpu
+    x, w = make_inputs(8, 24, 28, 28, 64, 3, 3, "u01", "he", seed=8)
+    a = _run_direct(gpu, x, w, 1, 1)
+    b = _run_direct_hwc(gpu, _to_hwc(x), w, 1, 1)
+    assert np.array_equal(_to_hwc(a), b)
+    c = B.conv_direct_layout(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), 1, 1, B.LAYOUT_CHW)
+    assert np.array_equal(c.cpu().numpy(), a)
+
+
+def test_direct_hwc_enumerated_tiles_agree(gpu):
+    torch, B = gpu
+    N, C, H, W, K = 4, 16, 28, 28, 64
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=78)
+    x_hwc = _to_hwc(x)
+    ref = conv_ref_hwc(x_hwc, w, 1, 1)
+    tiles = B.iolb_enumerate(B.make_shape(N, C, H, W, K), 0, 0, False)
+    for cfg in tiles[::max(1, len(tiles) // 12)]:
+        got = _run_direct_hwc(gpu, x_hwc, w, 1, 1, cfg=cfg)
+        assert rel_err(got, ref) <= TOL_DIRECT, cfg
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg5a", "cfg5c", "alex1", "alex2"])
+def test_direct_hwc_full_size_sampled(gpu, name):
+    L = CONFIGS[name]
+    x, w = layer_inputs(L)
+    got = _run_direct_hwc(gpu, _to_hwc(x), w, L.stride, L.pad)
+    N, P, Q, K = got.shape
+    idx = sample_output_indices(N, K, P, Q, 4096, seed=L.seed)
+    ref = conv_ref_points(x, w, idx, L.stride, L.pad)
+    g = got[idx[:, 0], idx[:, 2], idx[:, 3], idx[:, 1]]
+    assert rel_err(g, ref) <= TOL_DIRECT
+    assert np.isfinite(got).all()
+
+
+# ---------------------------------------------------------------------------------------------
 # Winograd
 # ---------------------------------------------------------------------------------------------
 
@@ -243,6 +306,21 @@ def test_measured_autotuner_returns_a_valid_fast_tile(gpu):
 # ---------------------------------------------------------------------------------------------
 # error paths (nothing is launched)
 # ---------------------------------------------------------------------------------------------
+
+def test_layout_error_codes(gpu):
+    torch, B = gpu
+    x = torch.zeros((1, 8, 8, 4), dtype=torch.float32, device="cuda")
+    w = torch.zeros((32, 4, 3, 3), dtype=torch.float32, device="cuda")
+    y = torch.zeros((1, 8, 8, 32), dtype=torch.float32, device="cuda")
+    L = B.lib()
+    import ctypes
+    args = [ctypes.c_void_p(t.data_ptr()) for t in (x, w, y)] + [1, 4, 8, 8, 32, 3, 3, 1, 1]
+    assert L.conv_direct_layout(*args, 2, None) == -2
+    assert L.conv_direct_layout(*args, -1, None) == -2
+    assert L.conv_direct_layout(None, *args[1:], 1, None) == -1
+    assert L.conv_direct_layout(*args, 1, None) == 0
+    torch.cuda.synchronize()
+
 
 def test_error_codes(gpu):
     torch, B = gpu

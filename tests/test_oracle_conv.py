@@ -6,7 +6,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from oracle.conv_oracle import conv_ref, conv_ref_points, out_extent
+from oracle.conv_oracle import conv_ref, conv_ref_hwc, conv_ref_points, out_extent
 from paper_2012_15667_amd.inputs import make_inputs, sample_output_indices
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "conv_hand_cases.txt")
@@ -89,6 +89,30 @@ def test_brute_force_exact_small_integers(N, C, H, W, K, R, S, stride, pad):
     assert y.shape == ref.shape
     for got, want in zip(y.ravel(), ref.ravel()):
         assert Fraction(float(got)) == want          # small integers: fp64 is exact
+
+
+@pytest.mark.parametrize("N,C,H,W,K,R,S,stride,pad", [(2, 3, 5, 6, 4, 3, 3, 1, 1), (1, 2, 7, 5, 3, 3, 2, 2, 0)])
+def test_hwc_layout_brute_force_in_its_own_index_order(N, C, H, W, K, R, S, stride, pad):
+    """Channels-innermost tensors: y[n,p,q,k] = sum x[n, p*stride+r-pad, q*stride+s-pad, c] w[k,c,r,s],
+    summed here directly on the HWC arrays (small integers, exact)."""
+    rng = np.random.default_rng(11)
+    x = rng.integers(-4, 5, size=(N, H, W, C)).astype(np.float32)
+    w = rng.integers(-3, 4, size=(K, C, R, S)).astype(np.float32)
+    y = conv_ref_hwc(x, w, stride, pad)
+    P, Q = out_extent(H, W, R, S, stride, pad)
+    assert y.shape == (N, P, Q, K)
+    for n in range(N):
+        for p in range(P):
+            for q in range(Q):
+                for k in range(K):
+                    acc = 0
+                    for r in range(R):
+                        for s in range(S):
+                            h, ww = p * stride + r - pad, q * stride + s - pad
+                            if 0 <= h < H and 0 <= ww < W:
+                                for c in range(C):
+                                    acc += int(x[n, h, ww, c]) * int(w[k, c, r, s])
+                    assert y[n, p, q, k] == acc
 
 
 def test_delta_kernel_reproduces_input_bitwise():
