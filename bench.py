@@ -97,7 +97,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", default="", help="comma-separated subset of config names (profiling runs)")
-    ap.add_argument("--algos", default="", help="comma-separated subset of direct,wino2,wino4 (profiling runs)")
+    ap.add_argument("--algos", default="", help="comma-separated subset of direct,wino2,wino3,wino4,wino6 (profiling runs; wino3 and wino6 are not part of the default step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (known size) to calibrate rocprofv3 FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -147,7 +147,7 @@ def main():
         if a == "direct":
             B.conv_direct(xd, wd, L.stride, L.pad, y=yd)
         else:
-            B.conv_winograd(xd, wd, 2 if a == "wino2" else 4, y=yd)
+            B.conv_winograd(xd, wd, int(a[4:]), y=yd)
 
     def step():
         for job in jobs:
@@ -172,7 +172,7 @@ def main():
 
     flops_step = sum(direct_flops(j[0]) for j in jobs)
     direct_alg_flops = sum(direct_flops(j[0]) for j in jobs if j[1] == "direct")
-    wino_alg_flops = sum(wino_product_flops(j[0], 2 if j[1] == "wino2" else 4) for j in jobs if j[1] != "direct")
+    wino_alg_flops = sum(wino_product_flops(j[0], int(j[1][4:])) for j in jobs if j[1] != "direct")
 
     # ---- per-layer figures (outside the timed region) ------------------------------------------
     layers = []
@@ -188,7 +188,7 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / reps
-        algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino4": B.WINO_F4}[a]
+        algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino3": B.WINO_F3, "wino4": B.WINO_F4, "wino6": B.WINO_F6}[a]
         shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
         tile = B.iolb_tune(shape)
         bnd = B.iolb_bounds(shape, 40960)

@@ -26,12 +26,12 @@ extern "C" {
 
 #define IOLB_OK            0
 #define IOLB_EINVAL       -1   /* null pointer, non-positive extent, stride < 1, pad < 0, empty output */
-#define IOLB_EUNSUPPORTED -2   /* Winograd m outside {2,4}; algo or layout outside its enum */
+#define IOLB_EUNSUPPORTED -2   /* Winograd m outside {2,3,4,6}; algo or layout outside its enum */
 #define IOLB_ENOTILE      -3   /* no tile fits the LDS / register budgets */
 #define IOLB_EWORKSPACE   -4   /* workspace missing or too small */
 #define IOLB_EHIP         -5   /* a HIP runtime call or launch failed; see iolb_last_hip_error */
 
-enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2 };
+enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2, IOLB_WINO_F3 = 3, IOLB_WINO_F6 = 4 };
 enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1 };
 enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1 };   /* per image: channels outermost / innermost */
 
@@ -39,7 +39,7 @@ enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1 };   /* per image: channels oute
  * Q = floor((W+2 pad-S)/stride)+1.  For the Winograd algos R = S = 3 and stride = 1. */
 typedef struct iolb_shape {
     int32_t N, C, H, W, K, R, S, stride, pad;
-    int32_t algo;               /* IOLB_DIRECT, IOLB_WINO_F2 or IOLB_WINO_F4 */
+    int32_t algo;               /* IOLB_DIRECT or IOLB_WINO_F2 / _F3 / _F4 / _F6 (m = 2, 3, 4, 6) */
 } iolb_shape;
 
 /* A tile configuration: the output sub-block x * y * z of Sec. 5.2 (x along W_out, y along
@@ -98,7 +98,8 @@ int conv_direct_layout(const float* x, const float* w, float* y,
                        int layout, const iolb_tile_config* cfg);
 
 /* Winograd F(m x m, 3 x 3) convolution (Sec. 2.3; four steps of Sec. 4.3), R = S = 3,
- * stride 1, pad 1 (P = H, Q = W), m in {2, 4}.  Same layouts as conv_direct.  The transformed
+ * stride 1, pad 1 (P = H, Q = W), m in {2, 3, 4, 6} (Sec. 2.3 names e = 2 and e = 3; larger m
+ * trades more rounding error for fewer multiplications).  Same layouts as conv_direct.  The transformed
  * kernels, inputs and products live in the library's device workspace, grown on demand. */
 int conv_winograd(const float* x, const float* w, float* y,
                   int N, int C, int H, int W, int K, int m);
@@ -129,6 +130,11 @@ int64_t iolb_enumerate(const iolb_shape* shape, size_t lds_bytes, int vgpr_budge
 
 /* Lower-bound figures for a layer at fast-memory size S_f elements.  Host only. */
 int iolb_bounds(const iolb_shape* shape, int64_t S_f_elems, iolb_bounds_out* out);
+
+/* The constant transform matrices the Winograd kernels use for F(m x m, 3 x 3) (Sec. 2.3: input
+ * transform B d B^T, kernel transform L g L^T, output transform A M A^T), row-major into host
+ * arrays A[m][m+2], L[m+2][3], B[m+2][m+2].  Host only.  IOLB_EUNSUPPORTED for other m. */
+int iolb_winograd_matrices(int m, float* A, float* L, float* B);
 
 /* Stream (a hipStream_t) later calls enqueue on; NULL selects the null stream. */
 int iolb_set_stream(void* hip_stream);

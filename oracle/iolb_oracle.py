@@ -14,7 +14,8 @@ No code is shared with the GPU library.
 from fractions import Fraction
 from math import isqrt, sqrt
 
-DIRECT, WINO_F2, WINO_F4 = 0, 1, 2
+DIRECT, WINO_F2, WINO_F4, WINO_F3, WINO_F6 = 0, 1, 2, 3, 4
+WINO_E = {WINO_F2: 2, WINO_F3: 3, WINO_F4: 4, WINO_F6: 6}     # output tile extent e of each Winograd algo id
 PATH_FMA, PATH_MFMA = 0, 1
 
 # ------------------------------------------------------------------------------------------
@@ -173,7 +174,7 @@ def bounds(shape, Sf):
         out["q_lower_explicit"] = float(Qlow_DC_explicit(s["N"], s["C"], P, Q, s["K"], s["R"], s["S"], s["stride"], Sf))
         out["q_dataflow"] = float(Q_DC_total(s["C"], s["N"] * P, Q, s["K"], s["R"], s["S"], s["stride"], Sf))
     else:
-        e = 2 if s["algo"] == WINO_F2 else 4
+        e = WINO_E[s["algo"]]
         steps = V_WA_steps(s["C"], e)
         tiles = s["N"] * (-(-P // e)) * (-(-Q // e))
         out["vertices"] = tiles * s["K"] * sum(steps.values())
@@ -379,7 +380,7 @@ def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True):
         if not c:
             c = _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
         return c
-    e = 2 if s["algo"] == WINO_F2 else 4
+    e = WINO_E[s["algo"]]
     return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3)
 
 

@@ -203,7 +203,7 @@ def gpu_domain_and_measure(layer_name, algo, use_box=True, reps=3, layouts=False
     L = CONFIGS[layer_name]
     x, w = layer_inputs(L)
     xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
-    algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino4": B.WINO_F4}[algo]
+    algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino3": B.WINO_F3, "wino4": B.WINO_F4, "wino6": B.WINO_F6}[algo]
     shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
     pick = B.iolb_tune(shape)
     tiles = B.iolb_enumerate(shape, 163840, 0, use_box)
@@ -213,7 +213,7 @@ def gpu_domain_and_measure(layer_name, algo, use_box=True, reps=3, layouts=False
     y = torch.empty((L.N, L.K, P, Q), dtype=torch.float32, device="cuda")
     ws = None
     if algo != "direct":
-        ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, 2 if algo == "wino2" else 4),
+        ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, int(algo[4:])),
                          dtype=torch.uint8, device="cuda")
     if layouts and algo == "direct":
         dom = with_layouts(dom)
@@ -226,7 +226,7 @@ def gpu_domain_and_measure(layer_name, algo, use_box=True, reps=3, layouts=False
                                                                  cfg=cfg), reps)
         if algo == "direct":
             return time_call(torch, lambda: B.conv_direct(xd, wd, L.stride, L.pad, y=y, cfg=cfg), reps)
-        return time_call(torch, lambda: B.conv_winograd(xd, wd, 2 if algo == "wino2" else 4, y=y, cfg=cfg,
+        return time_call(torch, lambda: B.conv_winograd(xd, wd, int(algo[4:]), y=y, cfg=cfg,
                                                         workspace=ws), reps)
 
     return shape, pick, dom, measure

@@ -9,12 +9,13 @@ import os
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libiolbconv.so")
 
-DIRECT, WINO_F2, WINO_F4 = 0, 1, 2
+DIRECT, WINO_F2, WINO_F4, WINO_F3, WINO_F6 = 0, 1, 2, 3, 4
+WINO_ALGO = {2: WINO_F2, 3: WINO_F3, 4: WINO_F4, 6: WINO_F6}     # algo id of F(m x m, 3 x 3)
 PATH_FMA, PATH_MFMA = 0, 1
 LAYOUT_CHW, LAYOUT_HWC = 0, 1
 
 EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_workspace_bytes",
-           "conv_winograd_ws", "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_set_stream",
+           "conv_winograd_ws", "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
            "iolb_timing_enable", "iolb_timing_read", "iolb_release_workspace", "iolb_strerror",
            "iolb_last_hip_error"]
 
@@ -82,6 +83,8 @@ def lib():
         L.iolb_enumerate.argtypes = [ctypes.POINTER(Shape), sz, i, i, ctypes.POINTER(TileConfig), ctypes.c_int64]
         L.iolb_bounds.restype = i
         L.iolb_bounds.argtypes = [ctypes.POINTER(Shape), ctypes.c_int64, ctypes.POINTER(BoundsOut)]
+        L.iolb_winograd_matrices.restype = i
+        L.iolb_winograd_matrices.argtypes = [i, vp, vp, vp]
         L.iolb_set_stream.restype = i
         L.iolb_set_stream.argtypes = [vp]
         L.iolb_timing_enable.restype = i
@@ -132,6 +135,18 @@ def iolb_bounds(shape, Sf):
     out = BoundsOut()
     _check(lib().iolb_bounds(ctypes.byref(shape), int(Sf), ctypes.byref(out)))
     return out.as_dict()
+
+
+def iolb_winograd_matrices(m):
+    """(A, L, B) the Winograd kernels use for F(m x m, 3 x 3), as nested lists of floats."""
+    n = m + 2
+    A = (ctypes.c_float * (max(m, 1) * n))()
+    Lm = (ctypes.c_float * (n * 3))()
+    Bm = (ctypes.c_float * (n * n))()
+    _check(lib().iolb_winograd_matrices(m, A, Lm, Bm))
+    return ([[A[i * n + j] for j in range(n)] for i in range(m)],
+            [[Lm[i * 3 + j] for j in range(3)] for i in range(n)],
+            [[Bm[i * n + j] for j in range(n)] for i in range(n)])
 
 
 def _use_current_stream():

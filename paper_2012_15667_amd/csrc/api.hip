@@ -12,6 +12,7 @@
 #include "iolbconv.h"
 #include "kernels.h"
 #include "tune.h"
+#include "wino_mats.h"
 
 namespace {
 
@@ -187,7 +188,7 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
 
 int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGeom* g)
 {
-    const int m = s.algo == IOLB_WINO_F2 ? 2 : 4;
+    const int m = iolb::winograd_m(s.algo);
     g->N = s.N; g->C = s.C; g->H = s.H; g->W = s.W; g->K = s.K; g->m = m;
     g->th = (s.H + m - 1) / m;
     g->tw = (s.W + m - 1) / m;
@@ -222,8 +223,15 @@ WinoWorkspace winograd_layout(int C, int K, int m, int64_t tiles_pitch)
 
 int make_wino_shape(int N, int C, int H, int W, int K, int m, iolb_shape* s)
 {
-    if (m != 2 && m != 4) return IOLB_EUNSUPPORTED;
-    *s = iolb_shape{N, C, H, W, K, 3, 3, 1, 1, m == 2 ? IOLB_WINO_F2 : IOLB_WINO_F4};
+    int algo = 0;
+    switch (m) {
+    case 2: algo = IOLB_WINO_F2; break;
+    case 3: algo = IOLB_WINO_F3; break;
+    case 4: algo = IOLB_WINO_F4; break;
+    case 6: algo = IOLB_WINO_F6; break;
+    default: return IOLB_EUNSUPPORTED;
+    }
+    *s = iolb_shape{N, C, H, W, K, 3, 3, 1, 1, algo};
     int P = 0, Q = 0;
     return iolb::validate_shape(*s, &P, &Q);
 }
@@ -349,6 +357,29 @@ int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H,
     rc = ensure_workspace(dev, bytes);
     if (rc != IOLB_OK) return rc;
     return run_winograd(x, w, y, s, tile, dev->ws, dev->ws_bytes);
+}
+
+int iolb_winograd_matrices(int m, float* A, float* L, float* B)
+{
+    if (!A || !L || !B) return IOLB_EINVAL;
+    auto copy = [&](auto mats) {
+        using Mt = decltype(mats);
+        constexpr int n = Mt::n;
+        for (int i = 0; i < n - 2; ++i)
+            for (int j = 0; j < n; ++j) A[i * n + j] = Mt::A[i][j];
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < 3; ++j) L[i * 3 + j] = Mt::L[i][j];
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) B[i * n + j] = Mt::B[i][j];
+    };
+    switch (m) {
+    case 2: copy(iolb::Mats<2>{}); break;
+    case 3: copy(iolb::Mats<3>{}); break;
+    case 4: copy(iolb::Mats<4>{}); break;
+    case 6: copy(iolb::Mats<6>{}); break;
+    default: return IOLB_EUNSUPPORTED;
+    }
+    return IOLB_OK;
 }
 
 int iolb_set_stream(void* hip_stream)

@@ -207,10 +207,20 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
 
 }  // namespace
 
+int winograd_m(int algo) {
+    switch (algo) {
+    case IOLB_WINO_F2: return 2;
+    case IOLB_WINO_F3: return 3;
+    case IOLB_WINO_F4: return 4;
+    case IOLB_WINO_F6: return 6;
+    default: return 0;
+    }
+}
+
 int validate_shape(const iolb_shape& s, int* P, int* Q) {
     if (s.N < 1 || s.C < 1 || s.H < 1 || s.W < 1 || s.K < 1 || s.R < 1 || s.S < 1 || s.stride < 1 || s.pad < 0)
         return IOLB_EINVAL;
-    if (s.algo != IOLB_DIRECT && s.algo != IOLB_WINO_F2 && s.algo != IOLB_WINO_F4) return IOLB_EUNSUPPORTED;
+    if (s.algo != IOLB_DIRECT && winograd_m(s.algo) == 0) return IOLB_EUNSUPPORTED;
     if (s.algo != IOLB_DIRECT && (s.R != 3 || s.S != 3 || s.stride != 1)) return IOLB_EUNSUPPORTED;
     if ((int64_t)s.H + 2LL * s.pad < s.R || (int64_t)s.W + 2LL * s.pad < s.S) return IOLB_EINVAL;
     const int64_t p = ((int64_t)s.H + 2LL * s.pad - s.R) / s.stride + 1;
@@ -234,7 +244,7 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
         direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_MFMA, use_box, out);
         if (out->empty()) direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_FMA, use_box, out);
     } else {
-        winograd_candidates(s, P, Q, s.algo == IOLB_WINO_F2 ? 2 : 4, lds_bytes, vgpr_budget, use_box, out);
+        winograd_candidates(s, P, Q, winograd_m(s.algo), lds_bytes, vgpr_budget, use_box, out);
     }
     std::sort(out->begin(), out->end(), [](const Candidate& a, const Candidate& b) { return a.key < b.key; });
     return IOLB_OK;
@@ -277,7 +287,7 @@ int bounds(const iolb_shape& s, int64_t Sf, iolb_bounds_out* o) {
         o->q_lower_explicit = S * ((double)o->vertices / o->t_bound_2s - 1.0);
         o->q_dataflow = 2.0 * npq * s.K * RS * s.C / std::sqrt(reuse * S) + npq * s.K;
     } else {
-        const int m = s.algo == IOLB_WINO_F2 ? 2 : 4;
+        const int m = winograd_m(s.algo);
         const int64_t n = m + 2, n2 = n * n, r = 3;
         const int64_t tiles = (int64_t)s.N * ceil_div(P, m) * ceil_div(Q, m);
         const int64_t per_tile_k = (2 * n2 - 1) * n2 * s.C + (2 * r * r - 1) * n2 * s.C + n2 * s.C +

@@ -15,6 +15,8 @@ struct Candidate {
     std::array<int64_t, 10> key;   // lexicographic, smaller is better
 };
 
+// Output tile extent m of a Winograd algo id, 0 for anything else.
+int winograd_m(int algo);
 // Checks a layer description and computes its output extents.
 int validate_shape(const iolb_shape& s, int* P, int* Q);
 // All feasible tiles, best first.

@@ -1,4 +1,4 @@
-// Winograd F(m x m, 3 x 3) convolution, m in {2, 4}: the four steps of Sec. 4.3 as four kernels.
+// Winograd F(m x m, 3 x 3) convolution, m in {2, 3, 4, 6}: the four steps of Sec. 4.3 as four kernels.
 //
 //   step 1b  U[xi][c][k]  = (L K_{k,c} L^T)[xi]                    kernel transform
 //   step 1a  V[xi][c][t]  = (B I_{c,t} B^T)[xi]                    input transform, t = sub-domain index
@@ -11,37 +11,16 @@
 // tile column) in that order; tile (ti, tj) reads the n x n input window whose top-left corner is
 // (ti*m - 1, tj*m - 1), zero outside the image.
 //
-// The transform matrices are the Toom-Cook matrices for the points {0, 1, -1, inf} (m = 2) and
-// {0, 1, -1, 2, -2, inf} (m = 4).
+// The transform matrices (wino_mats.h) are compile-time constants: zeros and +-1 cost nothing.
 #include "kernels.h"
 #include "lds_dma.h"
+#include "wino_mats.h"
 
 namespace iolb {
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-template <int M> struct Mats;
-
-template <> struct Mats<2> {
-    static constexpr int n = 4;
-    static constexpr float B[4][4] = {{1, 0, -1, 0}, {0, 1, 1, 0}, {0, -1, 1, 0}, {0, 1, 0, -1}};
-    static constexpr float L[4][3] = {{1, 0, 0}, {0.5f, 0.5f, 0.5f}, {0.5f, -0.5f, 0.5f}, {0, 0, 1}};
-    static constexpr float A[2][4] = {{1, 1, 1, 0}, {0, 1, -1, -1}};
-};
-template <> struct Mats<4> {
-    static constexpr int n = 6;
-    static constexpr float B[6][6] = {{4, 0, -5, 0, 1, 0},  {0, -4, -4, 1, 1, 0}, {0, 4, -4, -1, 1, 0},
-                                      {0, -2, -1, 2, 1, 0}, {0, 2, -1, -2, 1, 0}, {0, 4, 0, -5, 0, 1}};
-    static constexpr float L[6][3] = {{1.f / 4, 0, 0},
-                                      {-1.f / 6, -1.f / 6, -1.f / 6},
-                                      {-1.f / 6, 1.f / 6, -1.f / 6},
-                                      {1.f / 24, 1.f / 12, 1.f / 6},
-                                      {1.f / 24, -1.f / 12, 1.f / 6},
-                                      {0, 0, 1}};
-    static constexpr float A[4][6] = {{1, 1, 1, 1, 1, 0}, {0, 1, -1, 2, -2, 0}, {0, 1, 1, 4, 4, 0}, {0, 1, -1, 8, -8, 1}};
-};
 
 // out[ROWS][COLS] = Mx[ROWS][IN] * in[IN][COLS]; zero entries of the constant matrix cost nothing
 template <int ROWS, int IN, int COLS, typename MatT>
@@ -309,8 +288,13 @@ hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom
 {
     const size_t n = (size_t)g.Cp * g.K;
     const int grid = (int)((n + 255) / 256);
-    if (g.m == 2) hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K);
-    else          hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K);
+    switch (g.m) {
+    case 2: hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
+    case 3: hipLaunchKernelGGL(kernel_transform<3>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
+    case 4: hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
+    case 6: hipLaunchKernelGGL(kernel_transform<6>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
@@ -318,8 +302,13 @@ hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom&
 {
     if (g.Cp > 65535) return hipErrorInvalidValue;
     dim3 grid((g.tiles + 255) / 256, g.Cp);
-    if (g.m == 2) hipLaunchKernelGGL(input_transform<2>, grid, dim3(256), 0, st, x, V, g);
-    else          hipLaunchKernelGGL(input_transform<4>, grid, dim3(256), 0, st, x, V, g);
+    switch (g.m) {
+    case 2: hipLaunchKernelGGL(input_transform<2>, grid, dim3(256), 0, st, x, V, g); break;
+    case 3: hipLaunchKernelGGL(input_transform<3>, grid, dim3(256), 0, st, x, V, g); break;
+    case 4: hipLaunchKernelGGL(input_transform<4>, grid, dim3(256), 0, st, x, V, g); break;
+    case 6: hipLaunchKernelGGL(input_transform<6>, grid, dim3(256), 0, st, x, V, g); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
@@ -327,8 +316,13 @@ hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeo
 {
     if (g.K > 65535) return hipErrorInvalidValue;
     dim3 grid((g.tiles + 255) / 256, g.K);
-    if (g.m == 2) hipLaunchKernelGGL(output_transform<2>, grid, dim3(256), 0, st, Mp, y, g);
-    else          hipLaunchKernelGGL(output_transform<4>, grid, dim3(256), 0, st, Mp, y, g);
+    switch (g.m) {
+    case 2: hipLaunchKernelGGL(output_transform<2>, grid, dim3(256), 0, st, Mp, y, g); break;
+    case 3: hipLaunchKernelGGL(output_transform<3>, grid, dim3(256), 0, st, Mp, y, g); break;
+    case 4: hipLaunchKernelGGL(output_transform<4>, grid, dim3(256), 0, st, Mp, y, g); break;
+    case 6: hipLaunchKernelGGL(output_transform<6>, grid, dim3(256), 0, st, Mp, y, g); break;
+    default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

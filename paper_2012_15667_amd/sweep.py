@@ -5,7 +5,7 @@ This is the measured check of the tuner: the paper prunes its searching domain w
 optimality condition and then searches by measurement (Sec. 6.2); here the pick is analytical and
 the measurement is the audit.
 
-    python -m paper_2012_15667_amd.sweep --layer cfg3 [--algo direct|direct_hwc|wino2|wino4] [--max 200] [--alphas]
+    python -m paper_2012_15667_amd.sweep --layer cfg3 [--algo direct|direct_hwc|wino2|wino3|wino4|wino6] [--max 200] [--alphas]
 
 `direct_hwc` times the same tiles on channels-innermost tensors (conv_direct_layout).
 """
@@ -38,7 +38,7 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
     hwc = algo == "direct_hwc"
     if hwc:
         xd = xd.permute(0, 2, 3, 1).contiguous()
-    algo_id = {"direct": B.DIRECT, "direct_hwc": B.DIRECT, "wino2": B.WINO_F2, "wino4": B.WINO_F4}[algo]
+    algo_id = {"direct": B.DIRECT, "direct_hwc": B.DIRECT, "wino2": B.WINO_F2, "wino3": B.WINO_F3, "wino4": B.WINO_F4, "wino6": B.WINO_F6}[algo]
     shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
     pick = B.iolb_tune(shape)
     tiles = B.iolb_enumerate(shape, lds_bytes, 0, use_box)
@@ -62,8 +62,8 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
     Q = (L.W + 2 * L.pad - L.S) // L.stride + 1
     y = torch.empty((L.N, P, Q, L.K) if hwc else (L.N, L.K, P, Q), dtype=torch.float32, device="cuda")
     ws = None
-    if algo in ("wino2", "wino4"):
-        ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, 2 if algo == "wino2" else 4),
+    if algo.startswith("wino"):
+        ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, int(algo[4:])),
                          dtype=torch.uint8, device="cuda")
     flops = 2.0 * L.N * L.K * P * Q * L.C * L.R * L.S
     rows = []
@@ -73,7 +73,7 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
         elif hwc:
             fn = lambda: B.conv_direct_layout(xd, wd, L.stride, L.pad, B.LAYOUT_HWC, y=y, cfg=t)
         else:
-            fn = lambda: B.conv_winograd(xd, wd, 2 if algo == "wino2" else 4, y=y, cfg=t, workspace=ws)
+            fn = lambda: B.conv_winograd(xd, wd, int(algo[4:]), y=y, cfg=t, workspace=ws)
         ms = time_call(torch, fn, reps)
         rows.append((ms, t))
         print("%8.4f ms %7.2f TF  b=%d x=%d y=%d z=%d a=%d T=%d wm=%d wn=%d lds=%d qread=%d%s" % (

@@ -44,6 +44,8 @@ SHAPES = [
     _shape(16, 256, 13, 13, 384), _shape(16, 384, 13, 13, 256, algo=2), _shape(16, 256, 13, 13, 384, algo=1),
     _shape(2, 8, 16, 16, 32, 1, 1, 1, 0), _shape(3, 5, 9, 7, 6), _shape(4, 32, 32, 32, 64), _shape(4, 32, 32, 32, 64, algo=2),
     _shape(2, 6, 20, 12, 96, 3, 3, 2, 1), _shape(1, 1, 1, 1, 1, 1, 1, 1, 0), _shape(5, 7, 11, 13, 17, 2, 3, 1, 1),
+    _shape(64, 256, 56, 56, 256, algo=4), _shape(64, 128, 112, 112, 128, algo=3), _shape(8, 64, 28, 28, 64, algo=3),
+    _shape(4, 20, 13, 17, 96, algo=4),
 ]
 BUDGETS = [(0, 0), (32768, 64), (163840, 128), (8192, 32)]
 
@@ -87,7 +89,7 @@ def test_random_small_shapes_bit_exact():
             assert B.iolb_tune(sh) == want, s
 
 
-@pytest.mark.parametrize("s", SHAPES[:12])
+@pytest.mark.parametrize("s", SHAPES[:12] + SHAPES[24:])
 @pytest.mark.parametrize("Sf", [2, 20480, 40960, 44_000_000])
 def test_bounds_match_oracle(s, Sf):
     got = B.iolb_bounds(B.make_shape(**s), Sf)
@@ -108,5 +110,26 @@ def test_invalid_arguments_are_rejected_without_a_gpu():
     with pytest.raises(B.IolbError) as e:
         B.iolb_tune(B.make_shape(1, 1, 2, 2, 1, 5, 5, 1, 0))
     assert e.value.code == -1
-    assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 3) == 0
+    assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 5) == 0
+    assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 3) > 0
     assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 4) > 0
+
+
+@pytest.mark.parametrize("m", [2, 3, 4, 6])
+def test_library_winograd_matrices_satisfy_the_defining_identity(m):
+    """The constants compiled into the Winograd kernels: for output i, tap j and input k,
+    sum_xi A[i][xi] L[xi][j] B[xi][k] = [k == i + j]  (1-D F(m, 3); the 2-D transforms nest it).
+    Checked on the library's own floats, no oracle involved."""
+    from fractions import Fraction
+    A, Lm, Bm = B.iolb_winograd_matrices(m)
+    n = m + 2
+    assert len(A) == m and len(Lm) == n and len(Bm) == n
+    for i in range(m):
+        for j in range(3):
+            for k in range(n):
+                s = sum(Fraction(A[i][xi]) * Fraction(Lm[xi][j]) * Fraction(Bm[xi][k]) for xi in range(n))
+                scale = sum(abs(Fraction(A[i][xi]) * Fraction(Lm[xi][j]) * Fraction(Bm[xi][k])) for xi in range(n))
+                assert abs(s - (1 if k == i + j else 0)) <= Fraction(1, 10**6) * max(1, scale), (i, j, k)
+    with pytest.raises(B.IolbError) as e:
+        B.iolb_winograd_matrices(5)
+    assert e.value.code == -2

@@ -1,7 +1,7 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
 
 Tolerances (max_i |g_i - r_i| / max(|r_i|, rms(r)), fp32 GPU result against the fp64 oracle):
-direct convolution 1e-4, Winograd 5e-3 (both F(2x2) and F(4x4)).
+direct convolution 1e-4, Winograd 5e-3 (F(2x2), F(3x3), F(4x4) and F(6x6)).
 """
 import numpy as np
 import pytest
@@ -232,6 +232,13 @@ WINO_CASES = [
     (4, 3, 10, 14, 14, 64),      # 14 = 3.5 sub-domains of 4
     (4, 2, 16, 13, 13, 96),      # AlexNet conv3/4 extent
     (4, 1, 3, 5, 37, 32),        # smaller than one sub-domain in height; odd C
+    (3, 2, 8, 18, 18, 32),
+    (3, 3, 10, 14, 14, 64),      # 14 = 4.67 sub-domains of 3
+    (3, 1, 3, 5, 37, 32),
+    (6, 2, 8, 24, 24, 32),
+    (6, 3, 10, 14, 14, 64),      # 14 = 2.33 sub-domains of 6
+    (6, 2, 16, 13, 13, 96),
+    (6, 1, 3, 5, 37, 32),        # smaller than one sub-domain in height; odd C
 ]
 
 
@@ -266,7 +273,8 @@ def test_winograd_caller_workspace_and_tiles(gpu):
         assert rel_err(got, ref) <= TOL_WINO, cfg
 
 
-@pytest.mark.parametrize("name,m", [("cfg5a", 2), ("cfg5b", 4), ("cfg5c", 4), ("cfg5d", 2), ("alex3", 4), ("alex4", 2)])
+@pytest.mark.parametrize("name,m", [("cfg5a", 2), ("cfg5b", 4), ("cfg5c", 4), ("cfg5d", 2), ("alex3", 4), ("alex4", 2),
+                                    ("cfg5c", 6), ("cfg5d", 3), ("cfg4", 6), ("alex4", 3)])
 def test_winograd_full_size_sampled(gpu, name, m):
     L = CONFIGS[name]
     x, w = layer_inputs(L)
@@ -328,7 +336,7 @@ def test_error_codes(gpu):
     w = torch.zeros((32, 4, 3, 3), device="cuda")
     y = torch.full((1, 32, 8, 8), 7.0, device="cuda")
     with pytest.raises(B.IolbError) as e:
-        B.conv_winograd(x, w, 3, y=y)
+        B.conv_winograd(x, w, 5, y=y)
     assert e.value.code == -2
     with pytest.raises(B.IolbError) as e:
         B.conv_direct(x, w, 0, 1, y=y)

@@ -79,7 +79,7 @@ def test_dataflow_to_bound_ratios():
     C, P, Q, K, Sf = 64, 56, 56, 64, 2 * 64 * 64
     lead_df = float(o.Q_DC_total(C, P, Q, K, 3, 3, 1, Sf)) - P * Q * K
     assert isclose(lead_df / float(o.Qlow_DC_lead(1, C, P, Q, K, 3, 3, 1, Sf)), 8 * sqrt(2), rel_tol=1e-12)
-    for e in (2, 4):
+    for e in (2, 3, 4, 6):
         lead_w = float(o.Q_WA_total(C, P, Q, K, e, 4096)) - P * Q * K
         assert isclose(lead_w / float(o.Qlow_WA_lead(1, C, P, Q, K, e, 4096)), 2.0, rel_tol=1e-12)
 
@@ -134,7 +134,7 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
         else:
             assert b * x * y <= 256 and cfg["lds_bytes_used"] == 4 * a * per_stage
     else:
-        e = 2 if s["algo"] == o.WINO_F2 else 4
+        e = o.WINO_E[s["algo"]]
         assert b == 1 and y == e and x % (32 * e) == 0 and z % 32 == 0
         tb = x // e
         assert tb * z == cfg["acc_regs_per_thread"] * T
@@ -146,7 +146,8 @@ SHAPES = [shape(1, 16, 14, 14, 16), shape(8, 64, 28, 28, 64, algo=o.WINO_F2), sh
           shape(64, 256, 14, 14, 256, algo=o.WINO_F4), shape(64, 3, 224, 224, 64),
           shape(64, 128, 112, 112, 128), shape(64, 512, 28, 28, 512), shape(16, 96, 27, 27, 256, 5, 5, 1, 2),
           shape(16, 3, 227, 227, 96, 11, 11, 4, 0), shape(4, 32, 32, 32, 64, algo=o.WINO_F4),
-          shape(2, 8, 16, 16, 32, 1, 1, 1, 0), shape(3, 5, 9, 7, 6)]
+          shape(2, 8, 16, 16, 32, 1, 1, 1, 0), shape(3, 5, 9, 7, 6),
+          shape(64, 256, 56, 56, 256, algo=o.WINO_F6), shape(8, 64, 28, 28, 64, algo=o.WINO_F3)]
 
 
 @pytest.mark.parametrize("s", SHAPES)

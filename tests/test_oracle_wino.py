@@ -32,7 +32,7 @@ def test_1d_identity_on_basis_vectors_exact(e):
             assert y == want
 
 
-@pytest.mark.parametrize("e", [2, 4])
+@pytest.mark.parametrize("e", [2, 3, 4, 6])
 def test_2d_tile_exact_small_integers(e):
     """A (L g L^T (.) B d B^T) A^T equals the e x e correlation outputs of one tile, exactly."""
     r, n = 3, e + 2
@@ -58,13 +58,13 @@ def test_2d_tile_exact_small_integers(e):
 
 def test_multiplication_counts():
     # F(e x e, 3 x 3) spends (e+2)^2 multiplications per tile where the definition spends 9 e^2
-    for e, want in ((2, 16), (4, 36)):
+    for e, want in ((2, 16), (3, 25), (4, 36), (6, 64)):
         A, B, L = winograd_matrices(e)
         assert len(B) ** 2 == want < 9 * e * e
 
 
 def test_input_transform_is_integer_valued_for_integer_points():
-    for e in (2, 4):
+    for e in (2, 3, 4):        # e = 6 uses the points +-1/2
         _, B, _ = winograd_matrices(e)
         assert all(v.denominator == 1 for row in B for v in row)
 
@@ -88,6 +88,11 @@ def test_rejects_repeated_points():
     (4, 1, 4, 13, 13, 3),      # AlexNet conv3/4 extent
     (4, 1, 2, 16, 12, 2),
     (4, 1, 3, 3, 5, 2),        # smaller than one tile
+    (3, 2, 4, 9, 12, 3),
+    (3, 1, 3, 14, 13, 2),      # ragged: neither extent a multiple of 3
+    (6, 1, 3, 12, 18, 2),
+    (6, 2, 2, 14, 13, 3),      # ragged: 14 = 2.33 tiles of 6
+    (6, 1, 2, 4, 5, 2),        # smaller than one tile
 ])
 def test_winograd_layer_matches_direct_oracle_fp64(e, N, C, H, W, K):
     x, w = make_inputs(N, C, H, W, K, 3, 3, seed=31 + e)
