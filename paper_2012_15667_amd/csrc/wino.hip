@@ -16,43 +16,71 @@
 #include "lds_dma.h"
 #include "wino_mats.h"
 
+#include <type_traits>
+#include <utility>
+
 namespace iolb {
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-// out[ROWS][COLS] = Mx[ROWS][IN] * in[IN][COLS]; zero entries of the constant matrix cost nothing
-template <int ROWS, int IN, int COLS, typename MatT>
-__device__ __forceinline__ void left_mul(const MatT& Mx, const float (&in)[IN][COLS], float (&out)[ROWS][COLS])
+// Compile-time loops: the body receives its index as an integral constant, so that a matrix coefficient
+// read with it is a constant expression (a plain unrolled loop leaves the coefficient a run-time value,
+// and every "is it zero / one" test becomes a branch).
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
 {
-#pragma unroll
-    for (int i = 0; i < ROWS; ++i)
-#pragma unroll
-        for (int j = 0; j < COLS; ++j) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// which constant matrix of Mats<M> a product uses
+struct UseA { template <int M> static constexpr float at(int i, int k) { return Mats<M>::A[i][k]; } };
+struct UseB { template <int M> static constexpr float at(int i, int k) { return Mats<M>::B[i][k]; } };
+struct UseL { template <int M> static constexpr float at(int i, int k) { return Mats<M>::L[i][k]; } };
+
+// s += coef * v with the coefficient known at compile time: zeros vanish, +-1 are an add / subtract
+template <int M, class Sel, int I, int K>
+__device__ __forceinline__ void accumulate(float& s, bool& first, float v)
+{
+    constexpr float coef = Sel::template at<M>(I, K);
+    if constexpr (coef != 0.f) {
+        if (first) s = (coef == 1.f) ? v : (coef == -1.f) ? -v : coef * v;
+        else       s = (coef == 1.f) ? s + v : (coef == -1.f) ? s - v : __builtin_fmaf(coef, v, s);
+        first = false;
+    }
+}
+
+// out[ROWS][COLS] = Mx[ROWS][IN] * in[IN][COLS], Mx = Sel's matrix of Mats<M>
+template <int M, class Sel, int ROWS, int IN, int COLS>
+__device__ __forceinline__ void left_mul(const float (&in)[IN][COLS], float (&out)[ROWS][COLS])
+{
+    static_for<ROWS>([&](auto i) {
+        static_for<COLS>([&](auto j) {
             float s = 0.f;
-#pragma unroll
-            for (int k = 0; k < IN; ++k)
-                if (Mx[i][k] != 0.f) s = (Mx[i][k] == 1.f) ? s + in[k][j] : (Mx[i][k] == -1.f) ? s - in[k][j]
-                                                                                                : __builtin_fmaf(Mx[i][k], in[k][j], s);
+            bool first = true;
+            static_for<IN>([&](auto k) { accumulate<M, Sel, decltype(i)::value, decltype(k)::value>(s, first, in[k][j]); });
             out[i][j] = s;
-        }
+        });
+    });
 }
 // out[ROWS][COLS] = in[ROWS][IN] * Mx[COLS][IN]^T
-template <int ROWS, int IN, int COLS, typename MatT>
-__device__ __forceinline__ void right_mul_t(const float (&in)[ROWS][IN], const MatT& Mx, float (&out)[ROWS][COLS])
+template <int M, class Sel, int ROWS, int IN, int COLS>
+__device__ __forceinline__ void right_mul_t(const float (&in)[ROWS][IN], float (&out)[ROWS][COLS])
 {
-#pragma unroll
-    for (int i = 0; i < ROWS; ++i)
-#pragma unroll
-        for (int j = 0; j < COLS; ++j) {
+    static_for<ROWS>([&](auto i) {
+        static_for<COLS>([&](auto j) {
             float s = 0.f;
-#pragma unroll
-            for (int k = 0; k < IN; ++k)
-                if (Mx[j][k] != 0.f) s = (Mx[j][k] == 1.f) ? s + in[i][k] : (Mx[j][k] == -1.f) ? s - in[i][k]
-                                                                                                : __builtin_fmaf(Mx[j][k], in[i][k], s);
+            bool first = true;
+            static_for<IN>([&](auto k) { accumulate<M, Sel, decltype(j)::value, decltype(k)::value>(s, first, in[i][k]); });
             out[i][j] = s;
-        }
+        });
+    });
 }
 
 // step 1b: one lane per (c, k); k runs fastest so the writes of a wave are contiguous
@@ -71,8 +99,8 @@ kernel_transform(const float* __restrict__ w, float* __restrict__ U, int C, int 
 #pragma unroll
         for (int j = 0; j < 3; ++j) g[i][j] = (c < C) ? wp[i * 3 + j] : 0.f;     // rows [C, Cp) are zero
     float t[n][3], u[n][n];
-    left_mul<n, 3, 3>(Mats<M>::L, g, t);
-    right_mul_t<n, 3, n>(t, Mats<M>::L, u);
+    left_mul<M, UseL, n, 3, 3>(g, t);
+    right_mul_t<M, UseL, n, 3, n>(t, u);
     const size_t plane = (size_t)Cp * K;
 #pragma unroll
     for (int i = 0; i < n; ++i)
@@ -80,8 +108,12 @@ kernel_transform(const float* __restrict__ w, float* __restrict__ U, int C, int 
         for (int j = 0; j < n; ++j) U[(size_t)(i * n + j) * plane + idx] = u[i][j];
 }
 
-// step 1a: one lane per (c, t); t runs fastest
-template <int M>
+// step 1a: one lane per (c, t); t runs fastest.  VEC (m = 2 or 4, W a multiple of m, x aligned to
+// 4m bytes): a lane loads the m columns under its own sub-domain as one aligned vector per row and takes
+// the two border columns from its neighbour lanes (the sub-domains left and right of it), which replaces
+// m + 2 strided 4-byte loads per row by one wide one; only the lanes at a wave boundary load their border
+// column themselves.
+template <int M, bool VEC>
 __global__ void __launch_bounds__(256)
 input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
 {
@@ -93,16 +125,62 @@ input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
     const int h0 = ti * M - 1, w0 = tj * M - 1;
     const float* xp = x + ((size_t)img * g.C + c) * g.H * g.W;
     float d[n][n];
+    if constexpr (VEC) {
+        typedef float vec __attribute__((ext_vector_type(M)));
+        const int lane = threadIdx.x & 63;
+        const bool own_left = tj > 0 && lane == 0, own_right = tj + 1 < g.tw && lane == 63;
+        // all loads first, without branches (rows outside the image or channels past C read a clamped
+        // address and are zeroed afterwards), so that they are in flight together
+        const int cc = c < g.C ? c : g.C - 1;
+        const float* xc = x + ((size_t)img * g.C + cc) * g.H * g.W + w0 + 1;     // first own column: a multiple of m
+        vec mid[n];
+        float bl[n], br[n];
 #pragma unroll
-    for (int i = 0; i < n; ++i)
-#pragma unroll
-        for (int j = 0; j < n; ++j) {
-            const int h = h0 + i, ww = w0 + j;
-            d[i][j] = (c < g.C && h >= 0 && h < g.H && ww >= 0 && ww < g.W) ? xp[(size_t)h * g.W + ww] : 0.f;
+        for (int i = 0; i < n; ++i) {
+            const int h = h0 + i, hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
+            mid[i] = *reinterpret_cast<const vec*>(xc + (size_t)hc * g.W);
+            bl[i] = br[i] = 0.f;
         }
+        if (own_left) {
+#pragma unroll
+            for (int i = 0; i < n; ++i) {
+                const int h = h0 + i, hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
+                bl[i] = xc[(size_t)hc * g.W - 1];
+            }
+        }
+        if (own_right) {
+#pragma unroll
+            for (int i = 0; i < n; ++i) {
+                const int h = h0 + i, hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h);
+                br[i] = xc[(size_t)hc * g.W + M];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < n; ++i) {
+            const int h = h0 + i;
+            const bool row = c < g.C && h >= 0 && h < g.H;
+            float left = __shfl_up(mid[i][M - 1], 1), right = __shfl_down(mid[i][0], 1);
+            if (own_left) left = bl[i];
+            if (own_right) right = br[i];
+            if (tj == 0) left = 0.f;
+            if (tj + 1 == g.tw) right = 0.f;
+            d[i][0] = row ? left : 0.f;
+#pragma unroll
+            for (int j = 0; j < M; ++j) d[i][j + 1] = row ? mid[i][j] : 0.f;
+            d[i][n - 1] = row ? right : 0.f;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < n; ++i)
+#pragma unroll
+            for (int j = 0; j < n; ++j) {
+                const int h = h0 + i, ww = w0 + j;
+                d[i][j] = (c < g.C && h >= 0 && h < g.H && ww >= 0 && ww < g.W) ? xp[(size_t)h * g.W + ww] : 0.f;
+            }
+    }
     float tmp[n][n], v[n][n];
-    left_mul<n, n, n>(Mats<M>::B, d, tmp);
-    right_mul_t<n, n, n>(tmp, Mats<M>::B, v);
+    left_mul<M, UseB, n, n, n>(d, tmp);
+    right_mul_t<M, UseB, n, n, n>(tmp, v);
     const size_t plane = (size_t)g.Cp * g.tiles_pitch;
     float* vp = V + (size_t)c * g.tiles_pitch + t;
 #pragma unroll
@@ -111,8 +189,9 @@ input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
         for (int j = 0; j < n; ++j) vp[(size_t)(i * n + j) * plane] = v[i][j];
 }
 
-// step 4: one lane per (k, t); t runs fastest
-template <int M>
+// step 4: one lane per (k, t); t runs fastest.  VEC (m = 2 or 4, W a multiple of m, y aligned to 4m
+// bytes): each of the m output rows of a sub-domain is one aligned vector store.
+template <int M, bool VEC>
 __global__ void __launch_bounds__(256)
 output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g)
 {
@@ -129,16 +208,26 @@ output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g
 #pragma unroll
         for (int j = 0; j < n; ++j) pi[i][j] = mp[(size_t)(i * n + j) * plane];
     float tmp[M][n], o[M][M];
-    left_mul<M, n, n>(Mats<M>::A, pi, tmp);
-    right_mul_t<M, n, M>(tmp, Mats<M>::A, o);
+    left_mul<M, UseA, M, n, n>(pi, tmp);
+    right_mul_t<M, UseA, M, n, M>(tmp, o);
     float* yp = y + ((size_t)img * g.K + k) * g.H * g.W;
 #pragma unroll
-    for (int i = 0; i < M; ++i)
+    for (int i = 0; i < M; ++i) {
+        const int h = ti * M + i;
+        if constexpr (VEC) {
+            typedef float vec __attribute__((ext_vector_type(M)));
+            vec v;
 #pragma unroll
-        for (int j = 0; j < M; ++j) {
-            const int h = ti * M + i, ww = tj * M + j;
-            if (h < g.H && ww < g.W) yp[(size_t)h * g.W + ww] = o[i][j];
+            for (int j = 0; j < M; ++j) v[j] = o[i][j];
+            if (h < g.H) *reinterpret_cast<vec*>(yp + (size_t)h * g.W + tj * M) = v;
+        } else {
+#pragma unroll
+            for (int j = 0; j < M; ++j) {
+                const int ww = tj * M + j;
+                if (h < g.H && ww < g.W) yp[(size_t)h * g.W + ww] = o[i][j];
+            }
         }
+    }
 }
 
 // steps 2+3: M[xi] (K x tiles) = U[xi]^T (C x K) . V[xi] (C x tiles), one workgroup per z x tb block
@@ -302,11 +391,18 @@ hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom&
 {
     if (g.Cp > 65535) return hipErrorInvalidValue;
     dim3 grid((g.tiles + 255) / 256, g.Cp);
+    const bool vec = g.W % g.m == 0 && (reinterpret_cast<uintptr_t>(x) & (4 * g.m - 1)) == 0;
     switch (g.m) {
-    case 2: hipLaunchKernelGGL(input_transform<2>, grid, dim3(256), 0, st, x, V, g); break;
-    case 3: hipLaunchKernelGGL(input_transform<3>, grid, dim3(256), 0, st, x, V, g); break;
-    case 4: hipLaunchKernelGGL(input_transform<4>, grid, dim3(256), 0, st, x, V, g); break;
-    case 6: hipLaunchKernelGGL(input_transform<6>, grid, dim3(256), 0, st, x, V, g); break;
+    case 2:
+        if (vec) hipLaunchKernelGGL((input_transform<2, true>), grid, dim3(256), 0, st, x, V, g);
+        else     hipLaunchKernelGGL((input_transform<2, false>), grid, dim3(256), 0, st, x, V, g);
+        break;
+    case 3: hipLaunchKernelGGL((input_transform<3, false>), grid, dim3(256), 0, st, x, V, g); break;
+    case 4:
+        if (vec) hipLaunchKernelGGL((input_transform<4, true>), grid, dim3(256), 0, st, x, V, g);
+        else     hipLaunchKernelGGL((input_transform<4, false>), grid, dim3(256), 0, st, x, V, g);
+        break;
+    case 6: hipLaunchKernelGGL((input_transform<6, false>), grid, dim3(256), 0, st, x, V, g); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -316,11 +412,18 @@ hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeo
 {
     if (g.K > 65535) return hipErrorInvalidValue;
     dim3 grid((g.tiles + 255) / 256, g.K);
+    const bool vec = g.W % g.m == 0 && (reinterpret_cast<uintptr_t>(y) & (4 * g.m - 1)) == 0;
     switch (g.m) {
-    case 2: hipLaunchKernelGGL(output_transform<2>, grid, dim3(256), 0, st, Mp, y, g); break;
-    case 3: hipLaunchKernelGGL(output_transform<3>, grid, dim3(256), 0, st, Mp, y, g); break;
-    case 4: hipLaunchKernelGGL(output_transform<4>, grid, dim3(256), 0, st, Mp, y, g); break;
-    case 6: hipLaunchKernelGGL(output_transform<6>, grid, dim3(256), 0, st, Mp, y, g); break;
+    case 2:
+        if (vec) hipLaunchKernelGGL((output_transform<2, true>), grid, dim3(256), 0, st, Mp, y, g);
+        else     hipLaunchKernelGGL((output_transform<2, false>), grid, dim3(256), 0, st, Mp, y, g);
+        break;
+    case 3: hipLaunchKernelGGL((output_transform<3, false>), grid, dim3(256), 0, st, Mp, y, g); break;
+    case 4:
+        if (vec) hipLaunchKernelGGL((output_transform<4, true>), grid, dim3(256), 0, st, Mp, y, g);
+        else     hipLaunchKernelGGL((output_transform<4, false>), grid, dim3(256), 0, st, Mp, y, g);
+        break;
+    case 6: hipLaunchKernelGGL((output_transform<6, false>), grid, dim3(256), 0, st, Mp, y, g); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
