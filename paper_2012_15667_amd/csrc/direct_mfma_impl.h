@@ -39,6 +39,9 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// chunks of 64 input-tile elements whose load offsets a wave keeps in registers (flat staging)
+constexpr int FLAT_CHUNKS = 8;
 template <int MBW, int NBW, int LB, int RR, int SS, bool HWC>
 __global__ void __launch_bounds__(LB)
 direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y, DirectGeom g)
@@ -107,39 +110,77 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     for (int i = tid; i < 2 * stage_floats; i += T) lds[i] = 0.f;
     __syncthreads();
 
+    // Input-tile staging comes in two forms.
+    //  - flat (g.flat): the tile of one channel is halo contiguous LDS floats (rows back to back); chunk
+    //    q = 64 consecutive floats of it is one instruction whose lanes each fetch their own element, so
+    //    narrow tile rows share an instruction.  A lane's global offset does not depend on the stage, so
+    //    the offsets of the (at most FLAT_CHUNKS) chunks a wave owns are computed once; a lane whose
+    //    element lies outside the image (or past the tile) never loads.
+    //  - by rows: one instruction per (tile row, 64-column segment, channel), the row's base address
+    //    wave-uniform, lanes add their column; used when a wave would own more chunks than it has
+    //    registers for.
+    const int nchunks = (g.halo + 63) >> 6;
+    unsigned flat_off[FLAT_CHUNKS];
+    if (g.flat) {
+#pragma unroll
+        for (int j = 0; j < FLAT_CHUNKS; ++j) {
+            const int e = (wave + j * nwaves) * 64 + lane;
+            flat_off[j] = ~0u;
+            if (e < g.halo) {
+                const int im = e / (g.yh * g.xh), rem = e % (g.yh * g.xh);
+                const int gy = gy0 + rem / g.xh, gx = gx0 + rem % g.xh;
+                if (gy >= 0 && gy < g.H && gx >= 0 && gx < g.W)
+                    flat_off[j] = HWC ? 4u * (unsigned)(((im * g.H + gy) * g.W + gx) * g.C)
+                                      : 4u * (unsigned)(im * g.C * HW + gy * g.W + gx);
+            }
+        }
+    }
     // first (tile row, segment) item of this wave
     const int im_first = wave / (nseg * g.yh);
     const int hy_first = (wave % (nseg * g.yh)) / nseg, seg_first = wave % nseg;
 
     // Stage c0..c0+alpha-1 into buf.  Weights: alpha*RS rows of z floats, whole rows per instruction.
-    // Input tile: one instruction per (tile row, 64-lane segment, channel); the row's base address is
-    // wave-uniform, lanes add their column.  Channels at or beyond C (last stage when alpha does not
-    // divide C) are zero rows in wt and are cleared here for the tile.
+    // Channels at or beyond C (last stage when alpha does not divide C) are zero rows in wt and are
+    // cleared here for the tile.
     auto issue_stage = [&](int c0, float* buf) {
         stage_rows(wslab + (size_t)c0 * RS * g.K, g.K, g.z >> 2, g.alpha * RS, buf, wave, nwaves, lane);
         float* xbuf = buf + wfloats;
-        int im = im_first, hy = hy_first, seg = seg_first;
-        for (int item = wave; item < tile_rows * nseg; item += nwaves) {
-            const int gy = gy0 + hy;
-            const int hx = seg * 64 + lane, gx = gx0 + hx;
-            if (gy >= 0 && gy < g.H && hx < g.xh && gx >= 0 && gx < g.W) {
-                const unsigned dst = lds_byte_address(xbuf + (im * g.yh + hy) * g.xh + seg * 64);
-                if constexpr (!HWC) {
-                    const float* rowp = x + (((size_t)(n0 + im) * g.C + c0) * g.H + gy) * g.W;
+        if (g.flat) {
+            const float* cbase = HWC ? x + (size_t)n0 * HW * g.C + c0 : x + ((size_t)n0 * g.C + c0) * HW;
+            const int cstep = HWC ? 1 : HW;
+            const unsigned dst0 = lds_byte_address(xbuf) + 256u * (unsigned)wave;
+#pragma unroll
+            for (int j = 0; j < FLAT_CHUNKS; ++j) {
+                if (wave + j * nwaves < nchunks && flat_off[j] != ~0u) {
+                    const unsigned dst = dst0 + 256u * (unsigned)(j * nwaves);
                     for (int c = 0; c < g.alpha && c0 + c < g.C; ++c)
-                        lds_dma_load_4(rowp + (size_t)c * HW, 4u * (unsigned)gx, dst + 4u * (unsigned)(c * g.halo));
-                } else {
-                    // channels innermost: the lanes of a row segment are C floats apart
-                    const float* rowp = x + ((size_t)(n0 + im) * g.H + gy) * g.W * g.C + c0;
-                    const unsigned off = 4u * (unsigned)gx * (unsigned)g.C;
-                    for (int c = 0; c < g.alpha && c0 + c < g.C; ++c)
-                        lds_dma_load_4(rowp + c, off, dst + 4u * (unsigned)(c * g.halo));
+                        lds_dma_load_4(cbase + (size_t)c * cstep, flat_off[j], dst + 4u * (unsigned)(c * g.halo));
                 }
             }
-            // next item of this wave: advance (im, hy, seg) by nwaves segments
-            seg += nwaves;
-            while (seg >= nseg) { seg -= nseg; ++hy; }
-            while (hy >= g.yh) { hy -= g.yh; ++im; }
+        } else {
+            int im = im_first, hy = hy_first, seg = seg_first;
+            for (int item = wave; item < tile_rows * nseg; item += nwaves) {
+                const int gy = gy0 + hy;
+                const int hx = seg * 64 + lane, gx = gx0 + hx;
+                if (gy >= 0 && gy < g.H && hx < g.xh && gx >= 0 && gx < g.W) {
+                    const unsigned dst = lds_byte_address(xbuf + (im * g.yh + hy) * g.xh + seg * 64);
+                    if constexpr (!HWC) {
+                        const float* rowp = x + (((size_t)(n0 + im) * g.C + c0) * g.H + gy) * g.W;
+                        for (int c = 0; c < g.alpha && c0 + c < g.C; ++c)
+                            lds_dma_load_4(rowp + (size_t)c * HW, 4u * (unsigned)gx, dst + 4u * (unsigned)(c * g.halo));
+                    } else {
+                        // channels innermost: the lanes of a row segment are C floats apart
+                        const float* rowp = x + ((size_t)(n0 + im) * g.H + gy) * g.W * g.C + c0;
+                        const unsigned off = 4u * (unsigned)gx * (unsigned)g.C;
+                        for (int c = 0; c < g.alpha && c0 + c < g.C; ++c)
+                            lds_dma_load_4(rowp + c, off, dst + 4u * (unsigned)(c * g.halo));
+                    }
+                }
+                // next item of this wave: advance (im, hy, seg) by nwaves segments
+                seg += nwaves;
+                while (seg >= nseg) { seg -= nseg; ++hy; }
+                while (hy >= g.yh) { hy -= g.yh; ++im; }
+            }
         }
         if (c0 + g.alpha > g.C)
             for (int i = (g.C - c0) * g.halo + tid; i < g.alpha * g.halo; i += T) xbuf[i] = 0.f;
@@ -292,7 +333,12 @@ hipError_t launch_one(const float* x, const float* wt, float* y, const DirectGeo
         raised = true;
     }
     const int grid = g.nbk * g.nbx * g.nby * g.nbn;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(g.threads), shm, st, x, wt, y, g);
+    DirectGeom gl = g;
+    // flat staging needs every chunk of a wave in its FLAT_CHUNKS registers and 32-bit byte offsets
+    const long long nchunks = ((long long)g.halo + 63) / 64, nwaves = g.threads / 64;
+    const long long span = 4LL * g.b * g.C * g.H * g.W;
+    gl.flat = (nchunks + nwaves - 1) / nwaves <= FLAT_CHUNKS && span < (1LL << 32);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(g.threads), shm, st, x, wt, y, gl);
     return hipGetLastError();
 }
 

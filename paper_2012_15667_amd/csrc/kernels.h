@@ -18,6 +18,7 @@ struct DirectGeom {
     int per_thread;            // FMA path: output channels per lane
     int nbx, nby, nbn, nbk;    // blocks along W_out, H_out, batch, C_out
     int xh, yh, halo;          // input tile extents and elements per channel (b * yh * xh)
+    int flat;                  // MFMA path, set by the launcher: input tile staged in flat 64-element chunks
     int hwc;                   // 0: x[N][C][H][W], y[N][K][P][Q];  1: x[N][H][W][C], y[N][P][Q][K]
 };
 

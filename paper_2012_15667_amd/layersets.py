@@ -1,0 +1,173 @@
+"""Layer sets for the widening experiments of Sec. 7: the convolution layers of whole networks and the
+shape sweeps of the two direct-convolution figures, as synthetic layers (shapes only; random inputs).
+
+  * MODELS: the distinct convolution shapes of VGG-19, ResNet-18/34, SqueezeNet 1.0 and Inception-v3 (the
+    networks of the end-to-end experiment of Sec. 7.3), each with the number of times the network runs it,
+    written down from the architectures' published descriptions.  Layers that need a different padding per
+    axis (the 1x7 / 7x1 / 1x3 / 3x1 factorised kernels of Inception-v3) are not expressible with the single
+    `pad` argument of the library and are left out; the lists say so in `SKIPPED`.
+  * figure_sweep(): 3x3 kernels with C_in = 256 over input extents, output channels and strides (the sweep
+    of the first figure of Sec. 7.1);
+  * batch_sweep(): the same family at C_out = 256, stride 1, over batch sizes (the batched test of Sec. 7.1).
+
+    python -m paper_2012_15667_amd.layersets --model vgg19 --batch 64
+    python -m paper_2012_15667_amd.layersets --batch-sweep
+    python -m paper_2012_15667_amd.layersets --figure-sweep --batch 32
+
+Each line of output is one JSON record: the layer, the time and direct-equivalent TFLOP/s of every algorithm
+that applies (direct always; Winograd F(2x2), F(4x4) for 3x3 stride-1 pad-1 layers with C_out a multiple of
+32), and the fastest.  A final record sums a network: time per image batch with the best algorithm per layer
+and with direct convolution only.
+"""
+import argparse
+import json
+import sys
+from collections import namedtuple
+
+Conv = namedtuple("Conv", "name C H W K R S stride pad count")
+
+
+def _c(name, C, HW, K, R, stride, pad, count=1):
+    return Conv(name, C, HW, HW, K, R, R, stride, pad, count)
+
+
+MODELS = {
+    # 16 convolutions, all 3x3 / stride 1 / pad 1
+    "vgg19": [
+        _c("conv1_1", 3, 224, 64, 3, 1, 1), _c("conv1_2", 64, 224, 64, 3, 1, 1),
+        _c("conv2_1", 64, 112, 128, 3, 1, 1), _c("conv2_2", 128, 112, 128, 3, 1, 1),
+        _c("conv3_1", 128, 56, 256, 3, 1, 1), _c("conv3_x", 256, 56, 256, 3, 1, 1, 3),
+        _c("conv4_1", 256, 28, 512, 3, 1, 1), _c("conv4_x", 512, 28, 512, 3, 1, 1, 3),
+        _c("conv5_x", 512, 14, 512, 3, 1, 1, 4),
+    ],
+    # basic blocks [2, 2, 2, 2]; the 1x1 stride-2 layers are the projection shortcuts
+    "resnet18": [
+        _c("conv1", 3, 224, 64, 7, 2, 3),
+        _c("layer1", 64, 56, 64, 3, 1, 1, 4),
+        _c("layer2_down", 64, 56, 128, 3, 2, 1), _c("layer2_proj", 64, 56, 128, 1, 2, 0), _c("layer2", 128, 28, 128, 3, 1, 1, 3),
+        _c("layer3_down", 128, 28, 256, 3, 2, 1), _c("layer3_proj", 128, 28, 256, 1, 2, 0), _c("layer3", 256, 14, 256, 3, 1, 1, 3),
+        _c("layer4_down", 256, 14, 512, 3, 2, 1), _c("layer4_proj", 256, 14, 512, 1, 2, 0), _c("layer4", 512, 7, 512, 3, 1, 1, 3),
+    ],
+    # basic blocks [3, 4, 6, 3]: the same shapes, run more often
+    "resnet34": [
+        _c("conv1", 3, 224, 64, 7, 2, 3),
+        _c("layer1", 64, 56, 64, 3, 1, 1, 6),
+        _c("layer2_down", 64, 56, 128, 3, 2, 1), _c("layer2_proj", 64, 56, 128, 1, 2, 0), _c("layer2", 128, 28, 128, 3, 1, 1, 7),
+        _c("layer3_down", 128, 28, 256, 3, 2, 1), _c("layer3_proj", 128, 28, 256, 1, 2, 0), _c("layer3", 256, 14, 256, 3, 1, 1, 11),
+        _c("layer4_down", 256, 14, 512, 3, 2, 1), _c("layer4_proj", 256, 14, 512, 1, 2, 0), _c("layer4", 512, 7, 512, 3, 1, 1, 5),
+    ],
+    # fire module = squeeze 1x1, then expand 1x1 and expand 3x3 side by side
+    "squeezenet": [
+        _c("conv1", 3, 227, 96, 7, 2, 0),
+        _c("fire2_s", 96, 55, 16, 1, 1, 0), _c("fire2_e1", 16, 55, 64, 1, 1, 0, 2), _c("fire2_e3", 16, 55, 64, 3, 1, 1, 2),
+        _c("fire3_s", 128, 55, 16, 1, 1, 0), _c("fire4_s", 128, 55, 32, 1, 1, 0),
+        _c("fire4_e1", 32, 55, 128, 1, 1, 0), _c("fire4_e3", 32, 55, 128, 3, 1, 1),
+        _c("fire5_s", 256, 27, 32, 1, 1, 0), _c("fire5_e1", 32, 27, 128, 1, 1, 0), _c("fire5_e3", 32, 27, 128, 3, 1, 1),
+        _c("fire6_s", 256, 27, 48, 1, 1, 0), _c("fire6_e1", 48, 27, 192, 1, 1, 0, 2), _c("fire6_e3", 48, 27, 192, 3, 1, 1, 2),
+        _c("fire7_s", 384, 27, 48, 1, 1, 0), _c("fire8_s", 384, 27, 64, 1, 1, 0),
+        _c("fire8_e1", 64, 27, 256, 1, 1, 0), _c("fire8_e3", 64, 27, 256, 3, 1, 1),
+        _c("fire9_s", 512, 13, 64, 1, 1, 0), _c("fire9_e1", 64, 13, 256, 1, 1, 0), _c("fire9_e3", 64, 13, 256, 3, 1, 1),
+        _c("conv10", 512, 13, 1000, 1, 1, 0),
+    ],
+    # stem and the square-kernel layers of the first inception stage (35 x 35 grid)
+    "inception_v3": [
+        _c("stem_1", 3, 299, 32, 3, 2, 0), _c("stem_2", 32, 149, 32, 3, 1, 0), _c("stem_3", 32, 147, 64, 3, 1, 1),
+        _c("stem_4", 64, 73, 80, 1, 1, 0), _c("stem_5", 80, 73, 192, 3, 1, 0),
+        _c("mixed5b_1x1", 192, 35, 64, 1, 1, 0, 2), _c("mixed5b_1x1_48", 192, 35, 48, 1, 1, 0), _c("mixed5b_pool", 192, 35, 32, 1, 1, 0),
+        _c("mixed5_5x5", 48, 35, 64, 5, 1, 2, 3), _c("mixed5_3x3a", 64, 35, 96, 3, 1, 1, 3), _c("mixed5_3x3b", 96, 35, 96, 3, 1, 1, 3),
+        _c("mixed5c_1x1", 256, 35, 64, 1, 1, 0, 3), _c("mixed5c_1x1_48", 256, 35, 48, 1, 1, 0),
+        _c("mixed5d_1x1", 288, 35, 64, 1, 1, 0, 3), _c("mixed5d_1x1_48", 288, 35, 48, 1, 1, 0),
+        _c("mixed6a_3x3", 288, 35, 384, 3, 2, 0), _c("mixed6a_3x3b", 96, 35, 96, 3, 2, 0),
+    ],
+}
+SKIPPED = {"inception_v3": "layers with 1x7 / 7x1 / 1x3 / 3x1 kernels (per-axis padding) and the 17x17 / 8x8 stages"}
+
+
+def figure_sweep():
+    """3x3, C_in = 256: H_in = W_in in {14, 28, 56, 112}, C_out in {64, 128, 256, 512}, stride in {1, 2}."""
+    return [Conv("hw%d_k%d_s%d" % (hw, k, st), 256, hw, hw, k, 3, 3, st, 1, 1)
+            for hw in (14, 28, 56, 112) for k in (64, 128, 256, 512) for st in (1, 2)]
+
+
+def batch_sweep():
+    """(batch, layer) pairs: 3x3, C_in = C_out = 256, stride 1, batch 1...128 at four input extents."""
+    return [(n, Conv("hw%d_n%d" % (hw, n), 256, hw, hw, 256, 3, 3, 1, 1, 1))
+            for hw in (14, 28, 56, 112) for n in (1, 2, 4, 8, 16, 32, 64, 128)]
+
+
+def out_extents(L):
+    return (L.H + 2 * L.pad - L.R) // L.stride + 1, (L.W + 2 * L.pad - L.S) // L.stride + 1
+
+
+def flops(N, L):
+    P, Q = out_extents(L)
+    return 2.0 * N * L.K * P * Q * L.C * L.R * L.S
+
+
+def winograd_applies(L):
+    return L.R == 3 and L.S == 3 and L.stride == 1 and L.pad == 1 and L.K % 32 == 0
+
+
+def time_layer(N, L, reps=5, seed=0):
+    """Times every applicable algorithm on the GPU; returns {algo: ms}."""
+    import torch
+    from . import binding as B
+    from .sweep import time_call
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    x = torch.rand((N, L.C, L.H, L.W), generator=g, device="cuda", dtype=torch.float32)
+    w = torch.randn((L.K, L.C, L.R, L.S), generator=g, device="cuda", dtype=torch.float32) * (2.0 / (L.R * L.S * L.C)) ** 0.5
+    P, Q = out_extents(L)
+    y = torch.empty((N, L.K, P, Q), device="cuda", dtype=torch.float32)
+    out = {"direct": time_call(torch, lambda: B.conv_direct(x, w, L.stride, L.pad, y=y), reps)}
+    if winograd_applies(L):
+        for m in (2, 4):
+            out["wino%d" % m] = time_call(torch, lambda: B.conv_winograd(x, w, m, y=y), reps)
+    return out
+
+
+def run(pairs, reps=5, out=sys.stdout):
+    """pairs: iterable of (batch, Conv).  Prints one record per layer; returns the records."""
+    records = []
+    for N, L in pairs:
+        ms = time_layer(N, L, reps)
+        f = flops(N, L)
+        best = min(ms, key=ms.get)
+        rec = {"layer": L.name, "N": N, "C": L.C, "H": L.H, "W": L.W, "K": L.K, "R": L.R, "S": L.S,
+               "stride": L.stride, "pad": L.pad, "count": L.count, "gflop": round(f / 1e9, 3),
+               "ms": {a: round(t, 4) for a, t in ms.items()},
+               "tflops_direct_equiv": {a: round(f / t / 1e9, 2) for a, t in ms.items()}, "best": best}
+        records.append(rec)
+        print(json.dumps(rec), file=out, flush=True)
+    return records
+
+
+def summarise(name, records):
+    total_f = sum(r["gflop"] * r["count"] for r in records)
+    t_best = sum(min(r["ms"].values()) * r["count"] for r in records)
+    t_direct = sum(r["ms"]["direct"] * r["count"] for r in records)
+    return {"model": name, "conv_layers": sum(r["count"] for r in records), "gflop": round(total_f, 2),
+            "ms_best_per_layer": round(t_best, 3), "tflops_best": round(total_f / t_best, 2),
+            "ms_direct_only": round(t_direct, 3), "tflops_direct_only": round(total_f / t_direct, 2),
+            "skipped": SKIPPED.get(name, "")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--model", default="", help="one of %s, or 'all'" % ", ".join(sorted(MODELS)))
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--batch-sweep", action="store_true")
+    ap.add_argument("--figure-sweep", action="store_true")
+    ap.add_argument("--reps", type=int, default=5)
+    a = ap.parse_args()
+    if a.batch_sweep:
+        run(batch_sweep(), a.reps)
+    if a.figure_sweep:
+        run([(a.batch, L) for L in figure_sweep()], a.reps)
+    names = sorted(MODELS) if a.model == "all" else ([a.model] if a.model else [])
+    for name in names:
+        recs = run([(a.batch, L) for L in MODELS[name]], a.reps)
+        print(json.dumps(summarise(name, recs)), flush=True)
+
+
+if __name__ == "__main__":
+    sys.exit(main())

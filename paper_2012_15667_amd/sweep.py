@@ -27,12 +27,23 @@ def time_call(torch, fn, reps, warmup=2):
     return e0.elapsed_time(e1) / reps
 
 
+def parse_layer(text):
+    """A named layer of inputs.CONFIGS, or "N,C,H,W,K,R,S,stride,pad" for any other shape."""
+    from .inputs import CONFIGS, Layer
+    if text in CONFIGS:
+        return CONFIGS[text]
+    v = [int(t) for t in text.split(",")]
+    if len(v) != 9:
+        raise ValueError("layer must be a configured name or N,C,H,W,K,R,S,stride,pad")
+    return Layer(text, "direct", *v, "u01", "he", 4242)
+
+
 def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_box=False, lds_bytes=0):
     import torch
     from . import binding as B
-    from .inputs import CONFIGS, layer_inputs
+    from .inputs import layer_inputs
 
-    L = CONFIGS[layer_name]
+    L = parse_layer(layer_name)
     x, w = layer_inputs(L)
     xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
     hwc = algo == "direct_hwc"
@@ -91,7 +102,7 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--layer", default="cfg3")
+    ap.add_argument("--layer", default="cfg3", help="configured layer name, or N,C,H,W,K,R,S,stride,pad")
     ap.add_argument("--algo", default="direct")
     ap.add_argument("--max", type=int, default=0, help="time at most this many tiles (evenly spaced in tuner order)")
     ap.add_argument("--reps", type=int, default=5)

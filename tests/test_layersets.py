@@ -1,0 +1,46 @@
+"""The layer tables of paper_2012_15667_amd/layersets.py against figures known from the networks' published
+descriptions (multiply-accumulate counts of the convolution layers) and against the tuner.  CPU only."""
+import pytest
+
+from paper_2012_15667_amd import binding as B
+from paper_2012_15667_amd import layersets as LS
+
+
+def _macs(model):
+    return sum(LS.flops(1, L) / 2 * L.count for L in LS.MODELS[model])
+
+
+@pytest.mark.parametrize("model,gmacs,layers", [("vgg19", 19.51, 16), ("resnet18", 1.813, 20), ("resnet34", 3.66, 36)])
+def test_convolution_work_matches_the_published_totals(model, gmacs, layers):
+    assert _macs(model) / 1e9 == pytest.approx(gmacs, rel=0.01)
+    assert sum(L.count for L in LS.MODELS[model]) == layers
+
+
+def test_squeezenet_fire_modules_chain():
+    by = {L.name: L for L in LS.MODELS["squeezenet"]}
+    # expand outputs are concatenated: the next squeeze layer sees e1 + e3 channels
+    assert by["fire3_s"].C == by["fire2_e1"].K + by["fire2_e3"].K
+    assert by["fire5_s"].C == by["fire4_e1"].K + by["fire4_e3"].K
+    assert by["fire7_s"].C == by["fire6_e1"].K + by["fire6_e3"].K
+    assert by["fire9_s"].C == by["fire8_e1"].K + by["fire8_e3"].K
+    assert LS.out_extents(by["conv1"]) == (111, 111)
+    assert sum(L.count for L in LS.MODELS["squeezenet"]) == 26
+
+
+@pytest.mark.parametrize("model", sorted(LS.MODELS))
+def test_every_layer_has_a_tile(model):
+    for L in LS.MODELS[model]:
+        P, Q = LS.out_extents(L)
+        assert P >= 1 and Q >= 1
+        cfg = B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad))
+        assert cfg["x"] >= 1 and Q % cfg["x"] == 0 and P % cfg["y"] == 0 and L.K % cfg["z"] == 0
+        if LS.winograd_applies(L):
+            for m in (2, 4):
+                B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, algo=B.WINO_ALGO[m]))
+
+
+def test_sweeps_have_the_stated_shapes():
+    fig = LS.figure_sweep()
+    assert len(fig) == 4 * 4 * 2 and all(L.C == 256 and L.R == 3 for L in fig)
+    bs = LS.batch_sweep()
+    assert len(bs) == 32 and {n for n, _ in bs} == {1, 2, 4, 8, 16, 32, 64, 128}
