@@ -200,9 +200,10 @@ def bounds(shape, Sf):
 #   * the per-stage input tile x' * y' * alpha and the weight slab R S alpha z, double buffered,
 #     must fit lds_bytes (the LDS share of one workgroup; when 0, S_sm / 2, or S_sm if the tile's
 #     registers allow only one workgroup per compute unit anyway).
-# Among feasible tiles the rule minimises the read volume of the dataflow of Sec. 5.2 evaluated
-# exactly (true halo x' = stride (x-1) + S instead of x' ~ stride x), after making sure the grid
-# keeps the 256 compute units busy.
+# Among feasible matrix-core tiles the rule minimises a modelled run time (mfma_tile_cost) in which the
+# read volume of the dataflow of Sec. 5.2, evaluated exactly (true halo x' = stride (x-1) + S instead of
+# x' ~ stride x), is the memory term; ties go to the smaller read volume.  FMA-path tiles (layers without
+# a 32-channel block) keep the simpler order: grid fill, then read volume.
 
 N_CU = 256
 T_MAX = 1024
@@ -220,7 +221,6 @@ def _auto_lds_budget(T, acc):
 
 T_CHOICES = (64, 128, 256, 512, 1024)
 EFF_CAP = 80
-IDLE_OK_PCT = 5      # up to this share of idle pixel slots a ragged tile counts as a full one
 
 
 def divisors(n):
@@ -267,6 +267,43 @@ def _wave_grids(MB, NB, vgpr_budget):
                 continue
             out.append((wn * nbw - NB, T, mbw + nbw, wm, wn, 16 * mbw * nbw))
     return out
+
+
+def _cdiv(a, b):
+    return -(-a // b)
+
+
+def mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, q_read, q_write):
+    """Modelled run time (matrix-core clock cycles) of a direct-convolution tile on the matrix-core path:
+    the ranking function of the tile rule.  Per stage a wave keeps the matrix core of its SIMD busy for
+    steps * blocks * 64 cycles (one 32x32x2 MFMA per block and step, steps = alpha/2 * R*S); it also issues
+    its operand reads (32 cycles each) and its share of the stage's load instructions (300 cycles each).
+    Waves of the workgroup that share a SIMD hide that behind each other's matrix work; a barrier costs
+    100 cycles per wave; a workgroup pays 15000 cycles to start and 200 per accumulator register to store.
+    Workgroups run one per compute unit in rounds over the 256 compute units.  The result cannot beat the
+    time the reading and writing volumes need at 4000 / 1500 bytes per cycle.  The constants come from
+    tile sweeps on an MI355X; everything is integer arithmetic."""
+    RS = s["R"] * s["S"]
+    waves = T // 64
+    mbw = (z // 32) // wm
+    nbw = acc // 16 // mbw
+    xp, yp = (x - 1) * s["stride"] + s["S"], (y - 1) * s["stride"] + s["R"]
+    halo = b * xp * yp
+    chunks_per_wave = _cdiv(_cdiv(halo, 64), waves)
+    if chunks_per_wave <= 8:
+        loads_in = chunks_per_wave * alpha                              # 64-element chunks of the flat tile
+    else:
+        loads_in = _cdiv(b * yp * _cdiv(xp, 64), waves) * alpha         # one per tile row and 64 columns
+    loads_w = _cdiv(alpha * RS * (z // 4), 64 * waves)
+    steps = (alpha // 2) * RS
+    mfma = steps * mbw * nbw * 64
+    own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w)
+    sharing = _cdiv(waves, 4)
+    stage = (max(mfma * sharing, own) if sharing > 1 else own) + 100 * waves
+    workgroup = _cdiv(s["C"], alpha) * stage + 15000 + 200 * acc
+    compute = _cdiv(nblocks, N_CU) * workgroup
+    memory = (4 * q_read) // 4000 + (4 * q_write) // 1500
+    return max(compute, memory)
 
 
 def _pow2ceil(v):
@@ -319,12 +356,12 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                     nblocks = (N // b) * (Q // x) * (P // y) * (K // z)
                     qread = nblocks * C * (halo + R * S * z)
                     _, T, _, wm, wn, acc = min(grids)
-                    # share of the workgroup's matrix-core work spent on pixels past the tile (path 1 only)
-                    slots = (acc // 16 // (z // 32 // wm) * wn * 32) if path == PATH_MFMA else npix
-                    idle_pct = (100 * (slots - npix)) // slots
-                    key = (-_grid_efficiency_pct(nblocks), 0 if idle_pct <= IDLE_OK_PCT else idle_pct, qread,
-                           abs(npix * st * st - R * S * z),
-                           -npix * z, -x, z, b, y, T)
+                    if path == PATH_MFMA:
+                        cost = mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, qread, N * K * P * Q)
+                        key = (cost, qread, -npix * z, -x, z, b, y, T, 0, 0)
+                    else:
+                        key = (-_grid_efficiency_pct(nblocks), 0, qread, abs(npix * st * st - R * S * z),
+                               -npix * z, -x, z, b, y, T)
                     cands.append((key, dict(b=b, x=x, y=y, z=z, alpha=alpha, threads=T, waves_m=wm,
                                             waves_n=wn, path=path, wt_mode=0,
                                             lds_bytes_used=lds_mult * alpha * (halo + R * S * z),
@@ -385,8 +422,9 @@ def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True):
 
 
 def tune(shape, lds_bytes=0, vgpr_budget=128):
-    """The tile the library's iolb_tune must return, or None when nothing fits."""
-    c = candidates(shape, lds_bytes, vgpr_budget, True)
+    """The tile the library's iolb_tune must return, or None when nothing fits.  Direct convolution ranks
+    the whole domain by modelled time; Winograd looks inside the optimality box first."""
+    c = candidates(shape, lds_bytes, vgpr_budget, shape["algo"] != DIRECT)
     if not c:
         c = candidates(shape, lds_bytes, vgpr_budget, False)   # tiny layers: drop the box
     if not c:

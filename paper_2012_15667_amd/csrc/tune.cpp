@@ -20,7 +20,6 @@ namespace {
 constexpr int64_t kComputeUnits = 256;   // grid-fill rule: a launch should keep every CU busy
 constexpr int64_t kMaxThreads = 1024;    // largest workgroup: bounds the optimality box
 constexpr int64_t kEffCap = 80;          // grid efficiency above this percentage is "good enough"
-constexpr int64_t kIdleOkPct = 5;        // a ragged tile with up to this share of idle pixel slots counts as full
 constexpr int64_t kLdsPerCu = 160 * 1024 - 256;   // LDS of a compute unit, minus a small reserve for alignment
 constexpr int64_t kLdsHalf = 81920;      // "two blocks per multiprocessor" share (Sec. 6.2)
 
@@ -100,6 +99,37 @@ bool best_wave_grid(int MB, int NB, int vgpr_budget, bool exact_only, WaveGrid* 
     return found;
 }
 
+// Modelled run time, in matrix-core clock cycles, of a direct-convolution tile on the MFMA path.  The
+// structure follows the kernel: per stage a wave keeps its SIMD's matrix core busy for steps * blocks * 64
+// cycles and also issues its operand reads (32 cycles each) and its share of the stage's load instructions
+// (300 cycles each: a load rewrites the LDS base register and waits for the previous one); the waves of a
+// workgroup that share a SIMD overlap these with each other's matrix work; workgroups run one per compute
+// unit in rounds; the result cannot beat the time the reading and writing volumes need.  The constants were
+// fitted to tile sweeps on an MI355X.  Integers only, so that both implementations of the tuner agree bit
+// for bit.
+int64_t mfma_tile_cost(const iolb_shape& s, int b, int x, int y, int z, int alpha, const WaveGrid& g,
+                       int64_t nblocks, int64_t q_read, int64_t q_write) {
+    const int64_t RS = (int64_t)s.R * s.S;
+    const int64_t waves = g.threads / 64;
+    const int64_t mbw = (z / 32) / g.wm, nbw = g.acc / 16 / mbw;
+    const int64_t xh = (int64_t)(x - 1) * s.stride + s.S, yh = (int64_t)(y - 1) * s.stride + s.R;
+    const int64_t halo = b * xh * yh;
+    // load instructions a wave issues per stage: input tile (flat chunks of 64 elements when a wave owns at
+    // most 8 of them, else one per tile row and 64-column segment) per channel, plus its share of the weights
+    const int64_t chunks_per_wave = ceil_div(ceil_div(halo, 64), waves);
+    const int64_t loads_in = (chunks_per_wave <= 8 ? chunks_per_wave : ceil_div(b * yh * ceil_div(xh, 64), waves)) * alpha;
+    const int64_t loads_w = ceil_div((int64_t)alpha * RS * (z / 4), 64 * waves);
+    const int64_t steps = (alpha / 2) * RS;                      // MFMA steps of a stage (two channels each)
+    const int64_t mfma = steps * mbw * nbw * 64;                 // cycles one wave's stage keeps the matrix core busy
+    const int64_t own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w);
+    const int64_t sharing = ceil_div(waves, 4);                  // waves of the workgroup per SIMD
+    const int64_t stage = (sharing > 1 ? std::max(mfma * sharing, own) : own) + 100 * waves;   // + barrier
+    const int64_t workgroup = ceil_div(s.C, alpha) * stage + 15000 + 200 * (int64_t)g.acc;     // + start-up, stores
+    const int64_t compute = ceil_div(nblocks, kComputeUnits) * workgroup;
+    const int64_t memory = (4 * q_read) / 4000 + (4 * q_write) / 1500;    // bytes over bytes per cycle
+    return std::max(compute, memory);
+}
+
 int pow2_at_least(int v) {
     int p = 1;
     while (p < v) p *= 2;
@@ -161,10 +191,14 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                     c.cfg.q_read_elems = nblocks * s.C * per_stage;
                     c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
                     // share of the workgroup's matrix-core work spent on pixels past the tile (MFMA path only)
-                    const int64_t slots = path == IOLB_PATH_MFMA ? (int64_t)(g.acc / 16 / (z / 32 / g.wm)) * g.wn * 32 : npix;
-                    const int64_t idle_pct = (100 * (slots - npix)) / slots;
-                    c.key = {-grid_efficiency(nblocks), idle_pct <= kIdleOkPct ? 0 : idle_pct, c.cfg.q_read_elems,
-                             std::llabs(npix * st2 - RS * z), -npix * z, -(int64_t)x, z, b, y, g.threads};
+                    if (path == IOLB_PATH_MFMA) {
+                        const int64_t cost = mfma_tile_cost(s, b, x, y, z, alpha, g, nblocks, c.cfg.q_read_elems,
+                                                            c.cfg.q_write_elems);
+                        c.key = {cost, c.cfg.q_read_elems, -npix * z, -(int64_t)x, z, b, y, g.threads, 0, 0};
+                    } else {
+                        c.key = {-grid_efficiency(nblocks), 0, c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z),
+                                 -npix * z, -(int64_t)x, z, b, y, g.threads};
+                    }
                     out->push_back(c);
                 }
             }
@@ -252,7 +286,9 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
 
 int tune(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, iolb_tile_config* cfg) {
     std::vector<Candidate> c;
-    int rc = enumerate(s, lds_bytes, vgpr_budget, true, &c);
+    // Direct convolution: the modelled time ranks the whole domain (the optimality box stays available to
+    // iolb_enumerate as the pruning device of the measured search).  Winograd: box first.
+    int rc = enumerate(s, lds_bytes, vgpr_budget, s.algo != IOLB_DIRECT, &c);
     if (rc != IOLB_OK) return rc;
     if (c.empty()) {                       // tiny layers: nothing inside the box, search the whole domain
         rc = enumerate(s, lds_bytes, vgpr_budget, false, &c);

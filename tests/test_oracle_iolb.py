@@ -161,13 +161,46 @@ def test_tile_rule_returns_a_feasible_tile(s, lds, vg):
 
 
 @pytest.mark.parametrize("s", SHAPES[:8])
-def test_tile_rule_minimises_read_volume_within_its_grid_class(s):
-    """Among candidates that keep the chip equally busy, none reads less than the pick."""
+def test_tile_rule_minimises_its_key(s):
+    """The pick is the candidate with the smallest key; for matrix-core tiles the key starts with the
+    modelled time and breaks ties by the read volume."""
     cfg = o.tune(s)
-    cands = o.candidates(s, use_f3=True) or o.candidates(s, use_f3=False)
-    best_eff = min(k[:2] for k, _ in cands)
-    same = [c for k, c in cands if k[:2] == best_eff]
-    assert cfg["q_read_elems"] == min(c["q_read_elems"] for c in same)
+    cands = o.candidates(s, use_f3=s["algo"] != o.DIRECT) or o.candidates(s, use_f3=False)
+    key, best = min(cands, key=lambda kc: kc[0])
+    assert best == cfg
+    if s["algo"] == o.DIRECT and cfg["path"] == o.PATH_MFMA:
+        P, Q = o.out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
+        nblocks = (s["N"] // cfg["b"]) * (Q // cfg["x"]) * (P // cfg["y"]) * (s["K"] // cfg["z"])
+        assert key[0] == o.mfma_tile_cost(s, cfg["b"], cfg["x"], cfg["y"], cfg["z"], cfg["alpha"], cfg["threads"],
+                                          cfg["waves_m"], cfg["acc_regs_per_thread"], nblocks,
+                                          cfg["q_read_elems"], cfg["q_write_elems"])
+        assert key[1] == cfg["q_read_elems"]
+
+
+def test_modelled_time_worked_example():
+    """N=64, C=K=256, 56x56, 3x3; tile b=1, x=y=28, z=64, alpha=8, 8 waves as 2 x 4, 1 x 7 blocks per wave.
+    By hand: halo 30*30 = 900 -> 15 chunks, 2 per wave -> 16 tile loads + ceil(8*9*16/512) = 3 weight loads;
+    36 steps -> 36*7*64 = 16128 matrix-core cycles per wave and stage, own = 16128 + 36*8*32 + 300*19 = 31044;
+    two waves per SIMD -> stage = max(32256, 31044) + 800 = 33056; 32 stages -> 1057792 + 15000 + 200*112
+    = 1095192 per workgroup; 1024 workgroups = 4 rounds -> 4380768.  Memory: 1024*256*(900+576) elements
+    read -> 386924 cycles, 51380224 written -> 137013: far below, so the time is the compute figure."""
+    s = shape(64, 256, 56, 56, 256)
+    q_read = 1024 * 256 * (900 + 576)
+    assert o.mfma_tile_cost(s, 1, 28, 28, 64, 8, 512, 2, 112, 1024, q_read, 51380224) == 4380768
+    # a tile whose rows are one pixel wide needs a load instruction per 64 elements as well, but moves
+    # nine input elements per output: the memory term takes over
+    wide = o.mfma_tile_cost(s, 64, 1, 1, 64, 8, 64, 2, 32, 64 * 56 * 56 * 4 // 64, 3136 * 4 * 256 * (576 + 576), 51380224)
+    assert wide > 4380768
+
+
+def test_modelled_time_properties():
+    s = shape(64, 256, 56, 56, 256)
+    base = dict(b=1, x=28, y=28, z=64, alpha=8, T=512, wm=2, acc=112)
+    f = lambda nblocks, q: o.mfma_tile_cost(s, base["b"], base["x"], base["y"], base["z"], base["alpha"], base["T"],
+                                            base["wm"], base["acc"], nblocks, q, 51380224)
+    assert f(256, 10**6) == f(1, 10**6)                 # one round of the 256 compute units either way
+    assert f(257, 10**6) == 2 * f(256, 10**6)           # one workgroup more: a second round
+    assert f(256, 10**12) == (4 * 10**12) // 4000 + (4 * 51380224) // 1500     # memory-bound: the volume decides
 
 
 def test_optimality_box_prunes_but_keeps_the_pick():
