@@ -317,13 +317,15 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
     N, C, K, R, S, st = s["N"], s["C"], s["K"], s["R"], s["S"], s["stride"]
     sb_max = T_MAX * vgpr_budget
     cands = []
+    # matrix-core path: z divides K rounded up to whole 32-channel blocks (channels past K: zeros, not stored)
+    Kz = -(-K // 32) * 32 if path == PATH_MFMA else K
     for b in divisors(N):
         for x in divisors(Q):
             for y in divisors(P):
                 npix = b * x * y
                 xp, yp = (x - 1) * st + S, (y - 1) * st + R
                 halo = b * xp * yp
-                for z in divisors(K):
+                for z in divisors(Kz):
                     if use_f3 and not (z * z * R * S <= sb_max * st * st and
                                        npix * npix * st * st <= sb_max * R * S):
                         continue
@@ -336,6 +338,10 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                             _, T0, _, _, _, acc0 = min(grids)
                             budget = lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0)
                             alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), budget)
+                            # a stage too large for half the LDS (large kernels) may take all of it, provided the
+                            # smallest weight slab (4 channels of 32 kernels, two buffers) leaves half to the tile
+                            if alpha is None and not lds_bytes and 8 * 4 * R * S * 32 <= LDS_CU // 2:
+                                alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), LDS_CU)
                         lds_mult = 8
                     else:
                         if npix > 256:
@@ -353,7 +359,7 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                         lds_mult = 4
                     if alpha is None or not grids:
                         continue
-                    nblocks = (N // b) * (Q // x) * (P // y) * (K // z)
+                    nblocks = (N // b) * (Q // x) * (P // y) * (Kz // z)
                     qread = nblocks * C * (halo + R * S * z)
                     _, T, _, wm, wn, acc = min(grids)
                     if path == PATH_MFMA:

@@ -130,7 +130,8 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
         if (g_checked.count(key)) return IOLB_OK;
     }
     std::vector<iolb::Candidate> all;
-    const int rc = iolb::enumerate(s, 160 * 1024, 0, false, &all);
+    const int rc = cfg.path == IOLB_PATH_FMA && s.algo == IOLB_DIRECT ? iolb::enumerate_fma(s, 160 * 1024, 0, &all)
+                                                                      : iolb::enumerate(s, 160 * 1024, 0, false, &all);
     if (rc != IOLB_OK) return rc;
     for (const auto& c : all) {
         iolb_tile_config probe = c.cfg;
@@ -161,7 +162,8 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     g.b = cfg.b; g.tx = cfg.x; g.ty = cfg.y; g.z = cfg.z; g.alpha = cfg.alpha;
     g.threads = cfg.threads; g.waves_m = cfg.waves_m; g.waves_n = cfg.waves_n;
     g.per_thread = cfg.acc_regs_per_thread;
-    g.nbx = Q / cfg.x; g.nby = P / cfg.y; g.nbn = s.N / cfg.b; g.nbk = s.K / cfg.z;
+    g.Kp = cfg.path == IOLB_PATH_MFMA ? (s.K + 31) / 32 * 32 : s.K;
+    g.nbx = Q / cfg.x; g.nby = P / cfg.y; g.nbn = s.N / cfg.b; g.nbk = g.Kp / cfg.z;
     g.xh = (cfg.x - 1) * s.stride + s.S;
     g.yh = (cfg.y - 1) * s.stride + s.R;
     g.halo = cfg.b * g.xh * g.yh;
@@ -170,11 +172,11 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     hipStream_t st = t_stream;
     if (cfg.path == IOLB_PATH_MFMA) {
         const int c_padded = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;     // whole stages
-        const size_t wbytes = sizeof(float) * (size_t)s.K * c_padded * s.R * s.S;
+        const size_t wbytes = sizeof(float) * (size_t)g.Kp * c_padded * s.R * s.S;
         rc = ensure_workspace(dev, align256(wbytes));
         if (rc != IOLB_OK) return rc;
         float* wt = static_cast<float*>(dev->ws);
-        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, s.C * s.R * s.S, c_padded * s.R * s.S, st));
+        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, g.Kp, s.C * s.R * s.S, c_padded * s.R * s.S, st));
         MainKernelTimer timer(st, IOLB_TIME_DIRECT);
         IOLB_HIP(g.hwc ? iolb::launch_direct_mfma_hwc(x, wt, y, g, st) : iolb::launch_direct_mfma(x, wt, y, g, st));
         timer.stop(st);

@@ -6,10 +6,10 @@ namespace iolb {
 
 namespace {
 
-// w[K][CRS] -> wt[rows][K] through a 32 x 33 LDS tile: both sides coalesced.  rows >= CRS; the rows
-// beyond CRS (channels added to fill the last stage) are written as zeros.
+// w[K][CRS] -> wt[rows][Kp] through a 32 x 33 LDS tile: both sides coalesced.  rows >= CRS, Kp >= K; the
+// rows beyond CRS (channels added to fill the last stage) and the columns beyond K are written as zeros.
 __global__ void __launch_bounds__(256)
-weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int K, int CRS, int rows)
+weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int K, int Kp, int CRS, int rows)
 {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
@@ -21,16 +21,16 @@ weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int 
     __syncthreads();
     for (int j = ty; j < 32; j += 8) {
         const int c = c0 + j, k = k0 + tx;
-        if (c < rows && k < K) wt[(size_t)c * K + k] = tile[tx][j];
+        if (c < rows && k < Kp) wt[(size_t)c * Kp + k] = tile[tx][j];
     }
 }
 
 }  // namespace
 
-hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int rows, hipStream_t st)
+hipError_t launch_weight_relayout(const float* w, float* wt, int K, int Kp, int CRS, int rows, hipStream_t st)
 {
-    dim3 grid((rows + 31) / 32, (K + 31) / 32);
-    hipLaunchKernelGGL(weight_relayout_kernel, grid, dim3(256), 0, st, w, wt, K, CRS, rows);
+    dim3 grid((rows + 31) / 32, (Kp + 31) / 32);
+    hipLaunchKernelGGL(weight_relayout_kernel, grid, dim3(256), 0, st, w, wt, K, Kp, CRS, rows);
     return hipGetLastError();
 }
 

@@ -8,8 +8,8 @@
 //
 // Per stage of alpha channels (a multiple of 4) the workgroup stages, with LDS-direct loads (no
 // registers in between),
-//   - the weight slab  [alpha][R*S][z]  from the re-laid-out weights wt[C'][R*S][K] (C' = C rounded up
-//     to whole stages, the extra rows zero), whole rows per instruction, 16 bytes per lane;
+//   - the weight slab  [alpha][R*S][z]  from the re-laid-out weights wt[C'][R*S][K'] (C' = C rounded up
+//     to whole stages, K' = K rounded up to whole 32-channel blocks, the extra rows and columns zero), whole rows per instruction, 16 bytes per lane;
 //   - the input tile   [alpha][b][yh][xh], one instruction per (tile row, 64-column segment, channel):
 //     the row's base address is wave-uniform, lanes add their column.  Elements outside the image are
 //     never loaded: both LDS buffers are cleared once and those positions stay zero.
@@ -143,7 +143,7 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     // Channels at or beyond C (last stage when alpha does not divide C) are zero rows in wt and are
     // cleared here for the tile.
     auto issue_stage = [&](int c0, float* buf) {
-        stage_rows(wslab + (size_t)c0 * RS * g.K, g.K, g.z >> 2, g.alpha * RS, buf, wave, nwaves, lane);
+        stage_rows(wslab + (size_t)c0 * RS * g.Kp, g.Kp, g.z >> 2, g.alpha * RS, buf, wave, nwaves, lane);
         float* xbuf = buf + wfloats;
         if (g.flat) {
             const float* cbase = HWC ? x + (size_t)n0 * HW * g.C + c0 : x + ((size_t)n0 * g.C + c0) * HW;
@@ -294,6 +294,9 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     // each partial sum is complete: write the block once.  Register i of a 32 x 32 block holds
     // channel 8*(i/4) + 4*half + i%4 of pixel l32.
     const size_t PQ = (size_t)g.P * g.Q;
+    // K rounded up to whole 32-channel blocks (Kp) may exceed K: the channels past K are zero columns of wt
+    // and are not stored
+    const bool ragged_k = g.Kp != g.K;
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
         if (!pvalid[nb]) continue;
@@ -303,7 +306,10 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
             for (int mb = 0; mb < MBW; ++mb) {
                 const int kbase = (wm_i * MBW + mb) * 32 + 4 * half;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) yp[(size_t)(kbase + 8 * (i >> 2) + (i & 3)) * PQ] = acc[mb][nb][i];
+                for (int i = 0; i < 16; ++i) {
+                    const int kk = kbase + 8 * (i >> 2) + (i & 3);
+                    if (!ragged_k || k0 + kk < g.K) yp[(size_t)kk * PQ] = acc[mb][nb][i];
+                }
             }
         } else {
             // channels innermost: a lane's registers 4j..4j+3 are four neighbouring channels, 16 bytes
@@ -313,8 +319,15 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
                 const int kbase = (wm_i * MBW + mb) * 32 + 4 * half;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    floatx4 v = {acc[mb][nb][4 * j], acc[mb][nb][4 * j + 1], acc[mb][nb][4 * j + 2], acc[mb][nb][4 * j + 3]};
-                    *reinterpret_cast<floatx4*>(yp + kbase + 8 * j) = v;
+                    const int kk = kbase + 8 * j;
+                    if (!ragged_k) {
+                        floatx4 v = {acc[mb][nb][4 * j], acc[mb][nb][4 * j + 1], acc[mb][nb][4 * j + 2], acc[mb][nb][4 * j + 3]};
+                        *reinterpret_cast<floatx4*>(yp + kk) = v;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (k0 + kk + i < g.K) yp[kk + i] = acc[mb][nb][4 * j + i];
+                    }
                 }
             }
         }

@@ -12,6 +12,7 @@ namespace iolb {
 // Sec. 5.2 with its input tile xh * yh (x' * y' in the paper), and the block counts.
 struct DirectGeom {
     int N, C, H, W, K, R, S, stride, pad, P, Q;
+    int Kp;                    // MFMA path: K rounded up to a multiple of 32 (pitch of wt, extent of the z blocks)
     int b, tx, ty, z, alpha;
     int threads;               // workgroup size
     int waves_m, waves_n;      // MFMA path: wave grid; FMA path: channel groups, 1
@@ -22,12 +23,12 @@ struct DirectGeom {
     int hwc;                   // 0: x[N][C][H][W], y[N][K][P][Q];  1: x[N][H][W][C], y[N][P][Q][K]
 };
 
-// Re-layout w[K][C][R][S] -> wt[rows][K] (rows >= CRS = C*R*S; rows beyond CRS are zero) so that a
-// stage's weight slab is a run of rows contiguous in K.
-hipError_t launch_weight_relayout(const float* w, float* wt, int K, int CRS, int rows, hipStream_t st);
+// Re-layout w[K][C][R][S] -> wt[rows][Kp] (rows >= CRS = C*R*S, Kp >= K; rows beyond CRS and columns
+// beyond K are zero) so that a stage's weight slab is a run of rows contiguous in K.
+hipError_t launch_weight_relayout(const float* w, float* wt, int K, int Kp, int CRS, int rows, hipStream_t st);
 
 hipError_t launch_direct_fma(const float* x, const float* w, float* y, const DirectGeom& g, hipStream_t st);
-// wt: re-laid-out weights with ceil(C/alpha)*alpha*R*S rows.
+// wt: re-laid-out weights with ceil(C/alpha)*alpha*R*S rows of g.Kp floats.
 hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st);
 // The same for the channels-innermost tensor layout (g.hwc = 1).
 hipError_t launch_direct_mfma_hwc(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st);

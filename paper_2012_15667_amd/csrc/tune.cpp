@@ -142,7 +142,10 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
     static const int alphas_fma[] = {16, 8, 4, 2, 1};
     const int64_t box = kMaxThreads * vgpr_budget;
     const int64_t RS = (int64_t)s.R * s.S, st2 = (int64_t)s.stride * s.stride;
-    const auto fb = factors_of(s.N), fx = factors_of(Q), fy = factors_of(P), fz = factors_of(s.K);
+    // matrix-core path: z runs over the factors of K rounded up to whole 32-channel blocks (the channels
+    // past K are computed as zeros and not stored)
+    const int Kz = path == IOLB_PATH_MFMA ? (s.K + 31) / 32 * 32 : s.K;
+    const auto fb = factors_of(s.N), fx = factors_of(Q), fy = factors_of(P), fz = factors_of(Kz);
     for (int b : fb)
         for (int x : fx)
             for (int y : fy) {
@@ -160,6 +163,10 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                         if (!best_wave_grid(z / 32, (int)((npix + 31) / 32), vgpr_budget, false, &g)) continue;
                         alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage,
                                              lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
+                        // automatic budget: a stage too large for half the LDS (large kernels) may take all of it,
+                        // as long as the smallest weight slab (4 channels, 32 kernels) leaves half to the input tile
+                        if (alpha == 0 && !lds_bytes && 8 * 4 * RS * 32 <= kLdsPerCu / 2)
+                            alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage, kLdsPerCu);
                         lds_mult = 8;
                     } else {
                         if (npix > 256) continue;
@@ -180,7 +187,7 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                         lds_mult = 4;
                     }
                     if (alpha == 0) continue;
-                    const int64_t nblocks = (int64_t)(s.N / b) * (Q / x) * (P / y) * (s.K / z);
+                    const int64_t nblocks = (int64_t)(s.N / b) * (Q / x) * (P / y) * (Kz / z);
                     Candidate c{};
                     c.cfg.b = b; c.cfg.x = x; c.cfg.y = y; c.cfg.z = z;
                     c.cfg.alpha = alpha;
@@ -264,6 +271,17 @@ int validate_shape(const iolb_shape& s, int* P, int* Q) {
         (int64_t)s.K * s.C * s.R * s.S >= (1LL << 31)) return IOLB_EINVAL;
     *P = (int)p;
     *Q = (int)q;
+    return IOLB_OK;
+}
+
+int enumerate_fma(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, std::vector<Candidate>* out) {
+    int P = 0, Q = 0;
+    const int rc = validate_shape(s, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    out->clear();
+    if (s.algo != IOLB_DIRECT) return IOLB_OK;
+    direct_candidates(s, P, Q, std::max<int64_t>(lds_bytes, 0), vgpr_budget > 0 ? vgpr_budget : 128, IOLB_PATH_FMA, false, out);
+    std::sort(out->begin(), out->end(), [](const Candidate& a, const Candidate& b) { return a.key < b.key; });
     return IOLB_OK;
 }
 

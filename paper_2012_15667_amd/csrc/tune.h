@@ -21,6 +21,8 @@ int winograd_m(int algo);
 int validate_shape(const iolb_shape& s, int* P, int* Q);
 // All feasible tiles, best first.
 int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_box, std::vector<Candidate>* out);
+// Every plain-FMA tile of a direct layer (the fallback path), whole domain, best first.
+int enumerate_fma(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, std::vector<Candidate>* out);
 // The best tile (box first, whole domain if the box is empty).
 int tune(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, iolb_tile_config* cfg);
 int bounds(const iolb_shape& s, int64_t Sf, iolb_bounds_out* o);

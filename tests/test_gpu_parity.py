@@ -46,12 +46,12 @@ def _run_wino(gpu, x, w, m, cfg=None):
 
 DIRECT_CASES = [
     # N, C, H, W, K, R, S, stride, pad
-    (1, 16, 14, 14, 16, 3, 3, 1, 1),       # config 1 (FMA path)
+    (1, 16, 14, 14, 16, 3, 3, 1, 1),       # config 1: K = 16 runs as half a 32-channel block
     (2, 8, 16, 16, 32, 3, 3, 1, 1),        # smallest MFMA tiles
     (4, 24, 16, 32, 64, 3, 3, 1, 1),       # several tiles, C not a multiple of 16
     (2, 5, 16, 16, 32, 3, 3, 1, 1),        # odd C: zero-padded last stage
     (8, 32, 28, 28, 96, 3, 3, 1, 1),       # 7 | extents, K = 3 * 32
-    (3, 7, 9, 11, 6, 3, 3, 1, 1),          # ragged everything (FMA path)
+    (3, 7, 9, 11, 6, 3, 3, 1, 1),          # ragged everything, K = 6
     (2, 3, 35, 35, 32, 11, 11, 4, 0),      # down-scaled AlexNet conv1: stride 4, no padding
     (2, 12, 27, 27, 64, 5, 5, 1, 2),       # conv2-like: 5x5, pad 2
     (4, 16, 13, 13, 64, 3, 3, 1, 1),       # conv3/4 extent 13 (prime)
@@ -59,6 +59,10 @@ DIRECT_CASES = [
     (2, 8, 32, 32, 32, 3, 3, 2, 1),        # stride 2
     (2, 8, 16, 16, 32, 2, 3, 1, 0),        # non-square kernel
     (1, 4, 64, 64, 32, 3, 3, 1, 0),        # pad 0
+    (4, 24, 14, 14, 48, 1, 1, 1, 0),       # K = 48: one and a half channel blocks, stores masked
+    (2, 16, 13, 13, 80, 3, 3, 1, 1),       # K = 80
+    (2, 64, 7, 7, 1000, 1, 1, 1, 0),       # classifier-style 1x1 with K = 1000 (K % 4 == 0, K % 32 != 0)
+    (2, 8, 12, 12, 30, 3, 3, 1, 1),        # K = 30: not a multiple of 4 either
 ]
 
 
@@ -79,6 +83,28 @@ def test_direct_config1_and_config3(gpu):
         ref = conv_ref(x, w, L.stride, L.pad)
         got = _run_direct(gpu, x, w, L.stride, L.pad)
         assert rel_err(got, ref) <= TOL_DIRECT, name
+
+
+def test_direct_fma_path_still_agrees(gpu):
+    """Layers with a matrix-core tile never pick the plain-FMA kernel; it stays the fallback for kernels
+    too large for the LDS stage (11x11 stride 4 here) and must keep computing the same layer."""
+    torch, B = gpu
+    N, C, H, W, K, R, S, stride, pad = 2, 3, 35, 35, 32, 11, 11, 4, 0
+    x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=91)
+    ref = conv_ref(x, w, stride, pad)
+    cfg = B.iolb_tune(B.make_shape(N, C, H, W, K, R, S, stride, pad))
+    got = _run_direct(gpu, x, w, stride, pad)
+    assert rel_err(got, ref) <= TOL_DIRECT
+    # and the FMA kernel itself, through a one-channel-group layer that has no 32-channel block to fill...
+    # (every K now has one, so reach the kernel with an explicit tile from a budget no MFMA tile fits)
+    tiles = B.iolb_enumerate(B.make_shape(N, C, H, W, K, R, S, stride, pad), 20000, 0, False)
+    fma = [t for t in tiles if t["path"] == B.PATH_FMA]
+    if cfg["path"] == B.PATH_FMA or fma:
+        t = cfg if cfg["path"] == B.PATH_FMA else fma[0]
+        got = _run_direct(gpu, x, w, stride, pad, cfg=t)
+        assert rel_err(got, ref) <= TOL_DIRECT
+    else:
+        pytest.fail("no FMA-path tile reachable: the fallback kernel is untested")
 
 
 def test_direct_delta_kernel_is_bit_exact(gpu):

@@ -33,7 +33,8 @@ def test_every_layer_has_a_tile(model):
         P, Q = LS.out_extents(L)
         assert P >= 1 and Q >= 1
         cfg = B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad))
-        assert cfg["x"] >= 1 and Q % cfg["x"] == 0 and P % cfg["y"] == 0 and L.K % cfg["z"] == 0
+        Kz = -(-L.K // 32) * 32 if cfg["path"] == B.PATH_MFMA else L.K
+        assert cfg["x"] >= 1 and Q % cfg["x"] == 0 and P % cfg["y"] == 0 and Kz % cfg["z"] == 0
         if LS.winograd_applies(L):
             for m in (2, 4):
                 B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, algo=B.WINO_ALGO[m]))
