@@ -387,8 +387,9 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
     sb_max = T_MAX * vgpr_budget
     cands = []
     tb_top = -(-tiles // 32) * 32
+    Kz = -(-K // 32) * 32          # whole 32-channel blocks; the channels past K are zeros
     for tb in range(32, min(tb_top, 1024) + 1, 32):
-        for z in divisors(K):
+        for z in divisors(Kz):
             if z % 32:
                 continue
             if use_f3 and not (z * z <= sb_max and tb * tb <= sb_max):
@@ -400,7 +401,7 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
             alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0))
             if alpha is None:
                 continue
-            nblocks = n2 * (-(-tiles // tb)) * (K // z)
+            nblocks = n2 * (-(-tiles // tb)) * (Kz // z)
             qread = nblocks * C * (tb + z)
             _, T, _, wm, wn, acc = min(grids)
             key = (-_grid_efficiency_pct(nblocks), qread, abs(tb - z), -tb * z, z, T)

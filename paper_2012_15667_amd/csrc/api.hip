@@ -199,11 +199,12 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
     g->z = cfg.z;
     g->alpha = cfg.alpha;
     g->Cp = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;
+    g->Kp = (s.K + 31) / 32 * 32;
     g->waves_m = cfg.waves_m;
     g->waves_n = cfg.waves_n;
     const int64_t pitch = (tiles + g->tb - 1) / g->tb * g->tb;
     const int64_t n2 = (int64_t)(m + 2) * (m + 2);
-    if (n2 * g->Cp * pitch >= (1LL << 31) || n2 * s.K * pitch >= (1LL << 31)) return IOLB_EINVAL;
+    if (n2 * g->Cp * pitch >= (1LL << 31) || n2 * g->Kp * pitch >= (1LL << 31)) return IOLB_EINVAL;
     g->tiles = (int)tiles;
     g->tiles_pitch = (int)pitch;
     return IOLB_OK;
@@ -247,7 +248,7 @@ int run_winograd(const float* x, const float* w, float* y, const iolb_shape& s, 
     iolb::WinoGeom g{};
     rc = winograd_geom(s, cfg, &g);
     if (rc != IOLB_OK) return rc;
-    const WinoWorkspace l = winograd_layout(g.Cp, s.K, g.m, g.tiles_pitch);
+    const WinoWorkspace l = winograd_layout(g.Cp, g.Kp, g.m, g.tiles_pitch);
     if (!ws || ws_bytes < l.total || (reinterpret_cast<uintptr_t>(ws) & 255)) return IOLB_EWORKSPACE;
     char* base = static_cast<char*>(ws);
     float* U = reinterpret_cast<float*>(base + l.u_off);
@@ -321,7 +322,7 @@ size_t conv_winograd_workspace_bytes(int N, int C, int H, int W, int K, int m)
     if (make_wino_shape(N, C, H, W, K, m, &s) != IOLB_OK) return 0;
     // large enough for every tile the enumeration can produce: blocks hold at most 1024 sub-domains
     const int64_t tiles = (int64_t)N * ((H + m - 1) / m) * ((W + m - 1) / m);
-    return winograd_layout(C + 15, K, m, tiles + 1024).total;     // stages hold at most 16 channels
+    return winograd_layout(C + 15, (K + 31) / 32 * 32, m, tiles + 1024).total;     // stages hold at most 16 channels
 }
 
 int conv_winograd_ws(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m,

@@ -221,7 +221,8 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
     const int64_t tiles = (int64_t)s.N * ceil_div(P, m) * ceil_div(Q, m);
     const int64_t box = kMaxThreads * vgpr_budget;
     const int64_t top = std::min<int64_t>(ceil_div(tiles, 32) * 32, 1024);
-    const auto fz = factors_of(s.K);
+    const int Kz = (s.K + 31) / 32 * 32;        // whole 32-channel blocks; the channels past K are zeros
+    const auto fz = factors_of(Kz);
     for (int64_t tb = 32; tb <= top; tb += 32)
         for (int z : fz) {
             if (z % 32) continue;
@@ -231,7 +232,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z),
                                            lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
             if (alpha == 0) continue;
-            const int64_t nblocks = planes * ceil_div(tiles, tb) * (s.K / z);
+            const int64_t nblocks = planes * ceil_div(tiles, tb) * (Kz / z);
             Candidate c{};
             c.cfg.b = 1; c.cfg.x = (int32_t)(m * tb); c.cfg.y = m; c.cfg.z = z;
             c.cfg.alpha = alpha;

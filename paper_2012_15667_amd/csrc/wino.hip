@@ -1,6 +1,7 @@
 // Winograd F(m x m, 3 x 3) convolution, m in {2, 3, 4, 6}: the four steps of Sec. 4.3 as four kernels.
 //
-//   step 1b  U[xi][c][k]  = (L K_{k,c} L^T)[xi]                    kernel transform
+//   step 1b  U[xi][c][k]  = (L K_{k,c} L^T)[xi]                    kernel transform (k padded to whole
+//                                                                   32-channel blocks with zeros)
 //   step 1a  V[xi][c][t]  = (B I_{c,t} B^T)[xi]                    input transform, t = sub-domain index
 //   step 2+3 M[xi][k][t]  = sum_c U[xi][c][k] * V[xi][c][t]        element-wise product + channel sum,
 //                                                                   one GEMM per transformed plane xi,
@@ -83,25 +84,26 @@ __device__ __forceinline__ void right_mul_t(const float (&in)[ROWS][IN], float (
     });
 }
 
-// step 1b: one lane per (c, k); k runs fastest so the writes of a wave are contiguous
+// step 1b: one lane per (c, k); k runs fastest so the writes of a wave are contiguous.  U has Cp rows of Kp
+// columns per plane: rows [C, Cp) and columns [K, Kp) are zero.
 template <int M>
 __global__ void __launch_bounds__(256)
-kernel_transform(const float* __restrict__ w, float* __restrict__ U, int C, int Cp, int K)
+kernel_transform(const float* __restrict__ w, float* __restrict__ U, int C, int Cp, int K, int Kp)
 {
     constexpr int n = Mats<M>::n;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)Cp * K) return;
-    const int k = idx % K, c = idx / K;
+    if (idx >= (size_t)Cp * Kp) return;
+    const int k = idx % Kp, c = idx / Kp;
     float g[3][3];
     const float* wp = w + ((size_t)k * C + c) * 9;
 #pragma unroll
     for (int i = 0; i < 3; ++i)
 #pragma unroll
-        for (int j = 0; j < 3; ++j) g[i][j] = (c < C) ? wp[i * 3 + j] : 0.f;     // rows [C, Cp) are zero
+        for (int j = 0; j < 3; ++j) g[i][j] = (c < C && k < K) ? wp[i * 3 + j] : 0.f;
     float t[n][3], u[n][n];
     left_mul<M, UseL, n, 3, 3>(g, t);
     right_mul_t<M, UseL, n, 3, n>(t, u);
-    const size_t plane = (size_t)Cp * K;
+    const size_t plane = (size_t)Cp * Kp;
 #pragma unroll
     for (int i = 0; i < n; ++i)
 #pragma unroll
@@ -200,7 +202,7 @@ output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g
     const int k = blockIdx.y;
     if (t >= g.tiles) return;
     const int tj = t % g.tw, ti = (t / g.tw) % g.th, img = t / (g.tw * g.th);
-    const size_t plane = (size_t)g.K * g.tiles_pitch;
+    const size_t plane = (size_t)g.Kp * g.tiles_pitch;
     const float* mp = Mp + (size_t)k * g.tiles_pitch + t;
     float pi[n][n];
 #pragma unroll
@@ -244,7 +246,7 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
     const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    const int nbk = g.K / g.z, nbt = g.tiles_pitch / g.tb;
+    const int nbk = g.Kp / g.z, nbt = g.tiles_pitch / g.tb;
     int bid = blockIdx.x;
     const int nblk = gridDim.x;
     if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
@@ -252,7 +254,7 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
     const int tbk = bid % nbt;
     const int xi = bid / nbt;
     const int k0 = kb * g.z, t0 = tbk * g.tb;
-    const float* Up = U + (size_t)xi * g.Cp * g.K + k0;
+    const float* Up = U + (size_t)xi * g.Cp * g.Kp + k0;
     const float* Vp = V + (size_t)xi * g.Cp * g.tiles_pitch + t0;
 
     const int half_c = g.alpha >> 1;
@@ -273,7 +275,7 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
     const int nwaves = T >> 6;
     // rows [C, Cp) of U and V are zero, so every stage is alpha whole rows
     auto issue_stage = [&](int c0, float* buf) {
-        stage_rows(Up + (size_t)c0 * g.K, g.K, g.z >> 2, g.alpha, buf, wave, nwaves, lane);
+        stage_rows(Up + (size_t)c0 * g.Kp, g.Kp, g.z >> 2, g.alpha, buf, wave, nwaves, lane);
         stage_rows(Vp + (size_t)c0 * g.tiles_pitch, g.tiles_pitch, g.tb >> 2, g.alpha, buf + ufloats, wave, nwaves, lane);
     };
 
@@ -342,7 +344,7 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
         }
     }
 
-    float* mp = Mp + ((size_t)xi * g.K + k0) * g.tiles_pitch + t0;
+    float* mp = Mp + ((size_t)xi * g.Kp + k0) * g.tiles_pitch + t0;
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
         const int tcol = (wn_i * NBW + nb) * 32 + l32;
@@ -375,13 +377,13 @@ hipError_t launch_product_one(const float* U, const float* V, float* Mp, const W
 
 hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom& g, hipStream_t st)
 {
-    const size_t n = (size_t)g.Cp * g.K;
+    const size_t n = (size_t)g.Cp * g.Kp;
     const int grid = (int)((n + 255) / 256);
     switch (g.m) {
-    case 2: hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
-    case 3: hipLaunchKernelGGL(kernel_transform<3>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
-    case 4: hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
-    case 6: hipLaunchKernelGGL(kernel_transform<6>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K); break;
+    case 2: hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
+    case 3: hipLaunchKernelGGL(kernel_transform<3>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
+    case 4: hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
+    case 6: hipLaunchKernelGGL(kernel_transform<6>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -431,7 +433,7 @@ hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeo
 
 hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const WinoGeom& g, hipStream_t st)
 {
-    if (g.tb % 32 || g.z % 32 || (g.alpha & 3) || g.K % g.z || g.tiles_pitch % g.tb || g.Cp % g.alpha || g.Cp < g.C)
+    if (g.tb % 32 || g.z % 32 || (g.alpha & 3) || g.Kp % g.z || g.Kp < g.K || g.tiles_pitch % g.tb || g.Cp % g.alpha || g.Cp < g.C)
         return hipErrorInvalidValue;
     const int MB = g.z / 32, NB = g.tb / 32;
     if (MB % g.waves_m || NB % g.waves_n) return hipErrorInvalidValue;
@@ -441,7 +443,7 @@ hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const 
     const size_t shm = 2 * sizeof(float) * (size_t)g.alpha * (g.z + g.tb);
     if (shm > 160 * 1024) return hipErrorInvalidValue;
     const int n = g.m + 2;
-    const long long grid_ll = (long long)n * n * (g.K / g.z) * (g.tiles_pitch / g.tb);
+    const long long grid_ll = (long long)n * n * (g.Kp / g.z) * (g.tiles_pitch / g.tb);
     if (grid_ll > 0x7fffffffLL) return hipErrorInvalidValue;
     const int grid = (int)grid_ll;
 #define IOLB_CASE(M_, N_)                                                                                      \

@@ -15,9 +15,9 @@ shape sweeps of the two direct-convolution figures, as synthetic layers (shapes 
     python -m paper_2012_15667_amd.layersets --figure-sweep --batch 32
 
 Each line of output is one JSON record: the layer, the time and direct-equivalent TFLOP/s of every algorithm
-that applies (direct always; Winograd F(2x2), F(4x4) for 3x3 stride-1 pad-1 layers with C_out a multiple of
-32), and the fastest.  A final record sums a network: time per image batch with the best algorithm per layer
-and with direct convolution only.
+that applies (direct always; Winograd F(2x2), F(4x4) for 3x3 stride-1 pad-1 layers), and the fastest.  A final
+record sums a network: time per image batch with the best algorithm per layer and with direct convolution
+only.
 """
 import argparse
 import json
@@ -105,7 +105,7 @@ def flops(N, L):
 
 
 def winograd_applies(L):
-    return L.R == 3 and L.S == 3 and L.stride == 1 and L.pad == 1 and L.K % 32 == 0
+    return L.R == 3 and L.S == 3 and L.stride == 1 and L.pad == 1
 
 
 def time_layer(N, L, reps=5, seed=0):

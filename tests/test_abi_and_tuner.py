@@ -45,7 +45,8 @@ SHAPES = [
     _shape(2, 8, 16, 16, 32, 1, 1, 1, 0), _shape(3, 5, 9, 7, 6), _shape(4, 32, 32, 32, 64), _shape(4, 32, 32, 32, 64, algo=2),
     _shape(2, 6, 20, 12, 96, 3, 3, 2, 1), _shape(1, 1, 1, 1, 1, 1, 1, 1, 0), _shape(5, 7, 11, 13, 17, 2, 3, 1, 1),
     _shape(64, 256, 56, 56, 256, algo=4), _shape(64, 128, 112, 112, 128, algo=3), _shape(8, 64, 28, 28, 64, algo=3),
-    _shape(4, 20, 13, 17, 96, algo=4),
+    _shape(4, 20, 13, 17, 96, algo=4), _shape(1, 16, 14, 14, 16, algo=1), _shape(4, 20, 13, 17, 48, algo=2),
+    _shape(2, 16, 13, 13, 80), _shape(2, 64, 7, 7, 1000, 1, 1, 1, 0),
 ]
 BUDGETS = [(0, 0), (32768, 64), (163840, 128), (8192, 32)]
 

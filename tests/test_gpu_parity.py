@@ -265,6 +265,8 @@ WINO_CASES = [
     (6, 3, 10, 14, 14, 64),      # 14 = 2.33 sub-domains of 6
     (6, 2, 16, 13, 13, 96),
     (6, 1, 3, 5, 37, 32),        # smaller than one sub-domain in height; odd C
+    (2, 1, 16, 14, 14, 16),      # config 1's shape: K = 16 is half a 32-channel block
+    (4, 4, 20, 13, 17, 48),      # K = 48
 ]
 
 

@@ -117,7 +117,7 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
     P, Q = o.out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
     b, x, y, z, a, T = (cfg[k] for k in ("b", "x", "y", "z", "alpha", "threads"))
     # matrix-core tiles cut K rounded up to whole 32-channel blocks
-    Kz = -(-s["K"] // 32) * 32 if cfg["path"] == o.PATH_MFMA and s["algo"] == o.DIRECT else s["K"]
+    Kz = -(-s["K"] // 32) * 32 if cfg["path"] == o.PATH_MFMA else s["K"]
     assert Kz % z == 0 and T in (64, 128, 256, 512, 1024)
     assert cfg["lds_bytes_used"] <= (lds_bytes or o.LDS_CU) and cfg["acc_regs_per_thread"] <= vgpr_budget
     if s["algo"] == o.DIRECT:
@@ -149,7 +149,8 @@ SHAPES = [shape(1, 16, 14, 14, 16), shape(8, 64, 28, 28, 64, algo=o.WINO_F2), sh
           shape(64, 128, 112, 112, 128), shape(64, 512, 28, 28, 512), shape(16, 96, 27, 27, 256, 5, 5, 1, 2),
           shape(16, 3, 227, 227, 96, 11, 11, 4, 0), shape(4, 32, 32, 32, 64, algo=o.WINO_F4),
           shape(2, 8, 16, 16, 32, 1, 1, 1, 0), shape(3, 5, 9, 7, 6),
-          shape(64, 256, 56, 56, 256, algo=o.WINO_F6), shape(8, 64, 28, 28, 64, algo=o.WINO_F3)]
+          shape(64, 256, 56, 56, 256, algo=o.WINO_F6), shape(8, 64, 28, 28, 64, algo=o.WINO_F3),
+          shape(1, 16, 14, 14, 16, algo=o.WINO_F2), shape(4, 20, 13, 17, 48, algo=o.WINO_F4)]
 
 
 @pytest.mark.parametrize("s", SHAPES)
