@@ -42,7 +42,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 // chunks of 64 input-tile elements whose load offsets a wave keeps in registers (flat staging)
 constexpr int FLAT_CHUNKS = 8;
-template <int MBW, int NBW, int LB, int RR, int SS, bool HWC>
+template <int MBW, int NBW, int LB, int RR, int SS, bool HWC, bool EVEN>
 __global__ void __launch_bounds__(LB)
 direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y, DirectGeom g)
 {
@@ -70,20 +70,25 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
 
     const int wm_i = wave % g.waves_m, wn_i = wave / g.waves_m;
 
-    // per-lane read bases inside a stage buffer
-    // A tile whose pixel count is not a multiple of 32 (or does not fill the wave grid) leaves pixel slots
-    // idle: they read the tile's last pixel and store nothing.
+    // The tile's pixels form ceil(npix / 32) blocks, dealt to the waves_n wave columns as evenly as whole
+    // blocks allow: the first `extra` columns own NBW blocks, the others NBW - 1 (all NBW when the blocks
+    // divide evenly: the EVEN instantiations).  A wave that owns NBW - 1 blocks skips the MFMAs of the last one.  With waves w and
+    // w + 4 on one SIMD this keeps the SIMDs within one block of each other.  Pixel slots past the tile in
+    // the last block read the tile's last pixel and store nothing.
     int bbase[NBW], pimg[NBW], ppy[NBW], ppx[NBW];
-    bool pvalid[NBW];
     const int txy = g.tx * g.ty;
     const int npix = g.b * txy;
+    const int nblocks_pix = (npix + 31) >> 5;
+    const int col_base = nblocks_pix / g.waves_n, col_extra = nblocks_pix % g.waves_n;
+    const int my_blocks = col_base + (wn_i < col_extra ? 1 : 0);              // NBW or NBW - 1
+    const int first_block = wn_i * col_base + (wn_i < col_extra ? wn_i : col_extra);
+    const bool owns_last = EVEN || my_blocks == NBW;      // wave-uniform; EVEN: the blocks divide evenly, no test
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
-        const int slot = (wn_i * NBW + nb) * 32 + l32;
-        pvalid[nb] = slot < npix;
-        const int pix = pvalid[nb] ? slot : npix - 1;
-        pimg[nb] = pix / txy;
+        const int slot = (first_block + nb) * 32 + l32;
+        const int pix = slot < npix ? slot : npix - 1;
         const int rem = pix % txy;
+        pimg[nb] = pix / txy;
         ppy[nb] = rem / g.tx;
         ppx[nb] = rem % g.tx;
         bbase[nb] = wfloats + half * half_c * g.halo + pimg[nb] * g.yh * g.xh + ppy[nb] * g.stride * g.xh +
@@ -214,8 +219,13 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
 #pragma unroll
         for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
-            for (int nb = 0; nb < NBW; ++nb)
+            for (int nb = 0; nb < NBW - 1; ++nb)
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
+        if (owns_last) {
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb)
+                acc[mb][NBW - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[NBW - 1], acc[mb][NBW - 1], 0, 0, 0);
+        }
     };
 
     issue_stage(0, lds);
@@ -299,7 +309,7 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     const bool ragged_k = g.Kp != g.K;
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
-        if (!pvalid[nb]) continue;
+        if (nb >= my_blocks || (first_block + nb) * 32 + l32 >= npix) continue;
         if constexpr (!HWC) {
             float* yp = y + ((size_t)(n0 + pimg[nb]) * g.K + k0) * PQ + (size_t)(y0 + ppy[nb]) * g.Q + x0 + ppx[nb];
 #pragma unroll
@@ -334,11 +344,11 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     }
 }
 
-template <int MBW, int NBW, int LB, int RR, int SS, bool HWC>
+template <int MBW, int NBW, int LB, int RR, int SS, bool HWC, bool EVEN>
 hipError_t launch_one(const float* x, const float* wt, float* y, const DirectGeom& g,
                       size_t shm, hipStream_t st)
 {
-    auto kern = direct_mfma_kernel<MBW, NBW, LB, RR, SS, HWC>;
+    auto kern = direct_mfma_kernel<MBW, NBW, LB, RR, SS, HWC, EVEN>;
     static bool raised = false;               // dynamic LDS above 64 KB needs an opt-in, once per kernel
     if (shm > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -363,6 +373,7 @@ hipError_t launch_direct_mfma_layout(const float* x, const float* wt, float* y, 
     const int MB = g.z / 32, NB = (npix + 31) / 32;          // a ragged last block is masked in the kernel
     if (MB % g.waves_m || g.waves_n > NB) return hipErrorInvalidValue;
     const int mbw = MB / g.waves_m, nbw = (NB + g.waves_n - 1) / g.waves_n;
+    const bool even = NB % g.waves_n == 0;                   // every wave column owns nbw blocks
     const size_t stage = ((size_t)g.alpha * ((size_t)g.R * g.S * g.z + g.halo) + 3) & ~(size_t)3;
     const size_t shm = 2 * stage * sizeof(float);
     if (shm > 160 * 1024) return hipErrorInvalidValue;
@@ -372,13 +383,13 @@ hipError_t launch_direct_mfma_layout(const float* x, const float* wt, float* y, 
 #define IOLB_CASE(M_, N_)                                                                              \
     if (mbw == M_ && nbw == N_) {                                                                      \
         if (g.R == 3 && g.S == 3) {                                                                    \
-            if (g.threads <= 256) return launch_one<M_, N_, 256, 3, 3, HWC>(x, wt, y, g, shm, st);          \
-            if (g.threads <= 512) return launch_one<M_, N_, 512, 3, 3, HWC>(x, wt, y, g, shm, st);          \
-            if constexpr (M_ * N_ <= 4) return launch_one<M_, N_, 1024, 3, 3, HWC>(x, wt, y, g, shm, st);   \
+            if (g.threads <= 256) return even ? launch_one<M_, N_, 256, 3, 3, HWC, true>(x, wt, y, g, shm, st) : launch_one<M_, N_, 256, 3, 3, HWC, false>(x, wt, y, g, shm, st);          \
+            if (g.threads <= 512) return even ? launch_one<M_, N_, 512, 3, 3, HWC, true>(x, wt, y, g, shm, st) : launch_one<M_, N_, 512, 3, 3, HWC, false>(x, wt, y, g, shm, st);          \
+            if constexpr (M_ * N_ <= 4) return even ? launch_one<M_, N_, 1024, 3, 3, HWC, true>(x, wt, y, g, shm, st) : launch_one<M_, N_, 1024, 3, 3, HWC, false>(x, wt, y, g, shm, st);   \
         } else {                                                                                       \
-            if (g.threads <= 256) return launch_one<M_, N_, 256, 0, 0, HWC>(x, wt, y, g, shm, st);          \
-            if (g.threads <= 512) return launch_one<M_, N_, 512, 0, 0, HWC>(x, wt, y, g, shm, st);          \
-            if constexpr (M_ * N_ <= 4) return launch_one<M_, N_, 1024, 0, 0, HWC>(x, wt, y, g, shm, st);   \
+            if (g.threads <= 256) return even ? launch_one<M_, N_, 256, 0, 0, HWC, true>(x, wt, y, g, shm, st) : launch_one<M_, N_, 256, 0, 0, HWC, false>(x, wt, y, g, shm, st);          \
+            if (g.threads <= 512) return even ? launch_one<M_, N_, 512, 0, 0, HWC, true>(x, wt, y, g, shm, st) : launch_one<M_, N_, 512, 0, 0, HWC, false>(x, wt, y, g, shm, st);          \
+            if constexpr (M_ * N_ <= 4) return even ? launch_one<M_, N_, 1024, 0, 0, HWC, true>(x, wt, y, g, shm, st) : launch_one<M_, N_, 1024, 0, 0, HWC, false>(x, wt, y, g, shm, st);   \
         }                                                                                              \
     }
     IOLB_CASE(1, 1) IOLB_CASE(1, 2) IOLB_CASE(1, 3) IOLB_CASE(1, 4)
