@@ -134,3 +134,16 @@ def test_library_winograd_matrices_satisfy_the_defining_identity(m):
     with pytest.raises(B.IolbError) as e:
         B.iolb_winograd_matrices(5)
     assert e.value.code == -2
+
+
+def test_maximum_tensor_sizes():
+    """Tensors hold at most 2^31 - 1 elements: one element more is rejected before anything is tuned."""
+    ok = B.make_shape(32767, 64, 32, 32, 64)            # x: 2^31 - 65536 elements
+    cfg = B.iolb_tune(ok)
+    assert 32767 % cfg["b"] == 0 and cfg["q_write_elems"] == 32767 * 64 * 32 * 32
+    for bad in (B.make_shape(32768, 64, 32, 32, 64),    # x: exactly 2^31
+                B.make_shape(1, 1, 4, 4, 2 ** 27, 4, 4, 1, 0),   # w: 2^31
+                B.make_shape(32768, 1, 32, 32, 64)):    # y: 2^31
+        with pytest.raises(B.IolbError) as e:
+            B.iolb_tune(bad)
+        assert e.value.code == -1

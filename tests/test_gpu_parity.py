@@ -158,6 +158,28 @@ def test_direct_alexnet_rows_full_size_sampled(gpu, name):
     assert np.isfinite(got).all()
 
 
+def test_direct_large_tensor_sampled(gpu):
+    """A 2^30-element input (4 GiB) and a 2^29-element output: offsets beyond 32 bits of bytes."""
+    torch, B = gpu
+    N, C, H, W, K = 64, 64, 512, 512, 32
+    rng = np.random.default_rng(77)
+    x = rng.random((N, C, H, W), dtype=np.float32)
+    w = (rng.standard_normal((K, C, 3, 3)) * (2.0 / (9 * C)) ** 0.5).astype(np.float32)
+    y = B.conv_direct(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), 1, 1)
+    torch.cuda.synchronize()
+    idx = sample_output_indices(N, K, H, W, 2048, seed=5)
+    t = torch.from_numpy(idx.astype(np.int64)).cuda()
+    g = y[t[:, 0], t[:, 1], t[:, 2], t[:, 3]].cpu().numpy()
+    ref = conv_ref_points(x, w, idx, 1, 1)
+    assert rel_err(g, ref) <= TOL_DIRECT
+    # the last image's last row: the far end of both tensors
+    tail = y[N - 1, K - 1, H - 1, :].cpu().numpy()
+    tidx = np.array([[N - 1, K - 1, H - 1, q] for q in range(W)], dtype=np.int32)
+    assert rel_err(tail, conv_ref_points(x, w, tidx, 1, 1)) <= TOL_DIRECT
+    del y
+    torch.cuda.empty_cache()
+
+
 def test_direct_is_reproducible_bit_for_bit(gpu):
     """Each output block is owned by one workgroup and summed in a fixed order: no run-to-run noise."""
     x, w = make_inputs(8, 32, 28, 28, 64, 3, 3, "u01", "he", seed=5)
