@@ -78,6 +78,15 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
                          dtype=torch.uint8, device="cuda")
     flops = 2.0 * L.N * L.K * P * Q * L.C * L.R * L.S
     rows = []
+    # the first launches after an idle period run at lower clocks: keep the chip busy for a while on the
+    # tuner's pick before anything is timed, or whichever tile comes first looks 10 % slow
+    if algo == "direct":
+        warm = lambda: B.conv_direct(xd, wd, L.stride, L.pad, y=y, cfg=pick)
+    elif hwc:
+        warm = lambda: B.conv_direct_layout(xd, wd, L.stride, L.pad, B.LAYOUT_HWC, y=y, cfg=pick)
+    else:
+        warm = lambda: B.conv_winograd(xd, wd, int(algo[4:]), y=y, cfg=pick, workspace=ws)
+    time_call(torch, warm, 30, warmup=10)
     for t in tiles:
         if algo == "direct":
             fn = lambda: B.conv_direct(xd, wd, L.stride, L.pad, y=y, cfg=t)
