@@ -33,7 +33,8 @@ extern "C" {
 
 enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2, IOLB_WINO_F3 = 3, IOLB_WINO_F6 = 4 };
 enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1 };
-enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1 };   /* per image: channels outermost / innermost */
+enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1, IOLB_LAYOUT_CWH = 2 };   /* per image: channels outermost, channels
+                                                                           innermost, channels outermost with W before H */
 
 /* A convolution layer (Sec. 2.2).  Output extents are P = floor((H+2 pad-R)/stride)+1 and
  * Q = floor((W+2 pad-S)/stride)+1.  For the Winograd algos R = S = 3 and stride = 1. */
@@ -91,7 +92,9 @@ int conv_direct_cfg(const float* x, const float* w, float* y,
 
 /* Direct convolution with the tensor layout as a parameter (the layout entry of the searching
  * domain, Table 1 of Sec. 6.2).  IOLB_LAYOUT_CHW: as conv_direct.  IOLB_LAYOUT_HWC:
- * x: [N][H][W][C], y: [N][P][Q][K].  w is [K][C][R][S] for both.  cfg may be NULL (the tuned
+ * x: [N][H][W][C], y: [N][P][Q][K].  IOLB_LAYOUT_CWH: x: [N][C][W][H], y: [N][K][Q][P] (the
+ * transposed image: computed as the CHW convolution of the W x H image with the kernels
+ * transposed, so tiles are those of that transposed layer).  w is [K][C][R][S] for all.  cfg may be NULL (the tuned
  * tile is used; tiles do not depend on the layout).  Other layout values: IOLB_EUNSUPPORTED. */
 int conv_direct_layout(const float* x, const float* w, float* y,
                        int N, int C, int H, int W, int K, int R, int S, int stride, int pad,

@@ -89,3 +89,12 @@ def conv_ref_hwc(x_hwc, w, stride=1, pad=0):
     x = np.ascontiguousarray(np.transpose(np.asarray(x_hwc), (0, 3, 1, 2)))
     y = conv_ref(x, w, stride, pad)
     return np.ascontiguousarray(np.transpose(y, (0, 2, 3, 1)))
+
+
+def conv_ref_cwh(x_cwh, w, stride=1, pad=0):
+    """The same definition for images stored with the W axis before the H axis (the CWH layout of Table 1,
+    Sec. 6.2): x_cwh[n,c,w,h], result y[n,k,q,p]; w stays [k,c,r,s].  Only the index order differs, so the
+    tensors are permuted around conv_ref."""
+    x = np.ascontiguousarray(np.transpose(np.asarray(x_cwh), (0, 1, 3, 2)))
+    y = conv_ref(x, w, stride, pad)
+    return np.ascontiguousarray(np.transpose(y, (0, 1, 3, 2)))

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_PKG, "libiolbconv.so")
 DIRECT, WINO_F2, WINO_F4, WINO_F3, WINO_F6 = 0, 1, 2, 3, 4
 WINO_ALGO = {2: WINO_F2, 3: WINO_F3, 4: WINO_F4, 6: WINO_F6}     # algo id of F(m x m, 3 x 3)
 PATH_FMA, PATH_MFMA = 0, 1
-LAYOUT_CHW, LAYOUT_HWC = 0, 1
+LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 
 EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_workspace_bytes",
            "conv_winograd_ws", "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
@@ -189,10 +189,13 @@ def conv_direct(x, w, stride=1, pad=0, y=None, cfg=None):
 
 def conv_direct_layout(x, w, stride=1, pad=0, layout=LAYOUT_HWC, y=None, cfg=None):
     """Direct convolution with the tensor layout given: LAYOUT_CHW as conv_direct; LAYOUT_HWC takes
-    x [N][H][W][C] and returns y [N][P][Q][K].  w is [K][C][R][S] for both."""
+    x [N][H][W][C] and returns y [N][P][Q][K]; LAYOUT_CWH takes x [N][C][W][H] and returns y [N][K][Q][P].
+    w is [K][C][R][S] for all."""
     import torch
     if layout == LAYOUT_HWC:
         N, H, W, C = x.shape
+    elif layout == LAYOUT_CWH:
+        N, C, W, H = x.shape
     else:
         N, C, H, W = x.shape
     K, C2, R, S = w.shape
@@ -201,7 +204,7 @@ def conv_direct_layout(x, w, stride=1, pad=0, layout=LAYOUT_HWC, y=None, cfg=Non
     valid = stride >= 1 and pad >= 0 and H + 2 * pad >= R and W + 2 * pad >= S
     if valid:
         P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
-        shape = (N, P, Q, K) if layout == LAYOUT_HWC else (N, K, P, Q)
+        shape = (N, P, Q, K) if layout == LAYOUT_HWC else (N, K, Q, P) if layout == LAYOUT_CWH else (N, K, P, Q)
         if y is None:
             y = torch.empty(shape, dtype=torch.float32, device=x.device)
         elif tuple(y.shape) != shape:

@@ -150,6 +150,8 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
     return IOLB_EINVAL;
 }
 
+// layout CWH: s, P, Q describe the transposed layer (H and W, R and S exchanged) and the weights are read
+// transposed; the tensors are then plain CHW tensors of that layer.
 int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, int P, int Q, const iolb_tile_config& cfg,
                int layout = IOLB_LAYOUT_CHW)
 {
@@ -168,6 +170,7 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     g.yh = (cfg.y - 1) * s.stride + s.R;
     g.halo = cfg.b * g.xh * g.yh;
     g.hwc = layout == IOLB_LAYOUT_HWC;
+    g.w_transposed = layout == IOLB_LAYOUT_CWH;
     if ((int64_t)g.nbx * g.nby * g.nbn * g.nbk > 0x7fffffffLL) return IOLB_EINVAL;
     hipStream_t st = t_stream;
     if (cfg.path == IOLB_PATH_MFMA) {
@@ -176,7 +179,10 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
         rc = ensure_workspace(dev, align256(wbytes));
         if (rc != IOLB_OK) return rc;
         float* wt = static_cast<float*>(dev->ws);
-        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, g.Kp, s.C * s.R * s.S, c_padded * s.R * s.S, st));
+        if (g.w_transposed)
+            IOLB_HIP(iolb::launch_weight_relayout_transposed(w, wt, s.K, g.Kp, s.C, s.R, s.S, c_padded * s.R * s.S, st));
+        else
+            IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, g.Kp, s.C * s.R * s.S, c_padded * s.R * s.S, st));
         MainKernelTimer timer(st, IOLB_TIME_DIRECT);
         IOLB_HIP(g.hwc ? iolb::launch_direct_mfma_hwc(x, wt, y, g, st) : iolb::launch_direct_mfma(x, wt, y, g, st));
         timer.stop(st);
@@ -299,8 +305,10 @@ int conv_direct_layout(const float* x, const float* w, float* y, int N, int C, i
                        int stride, int pad, int layout, const iolb_tile_config* cfg)
 {
     if (!x || !w || !y) return IOLB_EINVAL;
-    if (layout != IOLB_LAYOUT_CHW && layout != IOLB_LAYOUT_HWC) return IOLB_EUNSUPPORTED;
-    const iolb_shape s{N, C, H, W, K, R, S, stride, pad, IOLB_DIRECT};
+    if (layout != IOLB_LAYOUT_CHW && layout != IOLB_LAYOUT_HWC && layout != IOLB_LAYOUT_CWH) return IOLB_EUNSUPPORTED;
+    // CWH: the W x H image convolved with the transposed kernels, as a CHW layer
+    const bool cwh = layout == IOLB_LAYOUT_CWH;
+    const iolb_shape s{N, C, cwh ? W : H, cwh ? H : W, K, cwh ? S : R, cwh ? R : S, stride, pad, IOLB_DIRECT};
     int P = 0, Q = 0;
     int rc = iolb::validate_shape(s, &P, &Q);
     if (rc != IOLB_OK) return rc;

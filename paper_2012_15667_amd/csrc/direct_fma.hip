@@ -58,7 +58,9 @@ direct_fma_kernel(const float* __restrict__ x, const float* __restrict__ w, floa
             const int kk = i / (g.alpha * RS), crs = i % (g.alpha * RS);       // crs fastest: contiguous reads
             const int c = crs / RS, rs = crs % RS;
             float v = 0.f;
-            if (c0 + c < g.C) v = w[((size_t)(k0 + kk) * g.C + c0 + c) * RS + rs];
+            // w_transposed: this launch's (r, s) is stored as w[k][c][s][r] (stored extents S x R)
+            const int src = g.w_transposed ? (rs % g.S) * g.R + rs / g.S : rs;
+            if (c0 + c < g.C) v = w[((size_t)(k0 + kk) * g.C + c0 + c) * RS + src];
             ws[crs * g.z + kk] = v;
         }
         __syncthreads();

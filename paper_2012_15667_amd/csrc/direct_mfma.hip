@@ -1,5 +1,5 @@
 // Direct convolution on the matrix cores, x[N][C][H][W] -> y[N][K][P][Q] instantiations, and the
-// weight re-layout pre-pass shared by both tensor layouts.
+// weight re-layout pre-passes shared by all tensor layouts.
 #include "direct_mfma_impl.h"
 
 namespace iolb {
@@ -25,7 +25,29 @@ weight_relayout_kernel(const float* __restrict__ w, float* __restrict__ wt, int 
     }
 }
 
+// The transposed-kernel variant: row (c, r, s) of wt comes from w[k][c][s][r] (stored extents S x R).  A few
+// hundred kilobytes at most: one lane per element of wt, writes coalesced along k.
+__global__ void __launch_bounds__(256)
+weight_relayout_transposed_kernel(const float* __restrict__ w, float* __restrict__ wt, int K, int Kp, int C, int R, int S,
+                                  int rows)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)rows * Kp) return;
+    const int k = idx % Kp, row = idx / Kp;
+    const int RS = R * S, c = row / RS, rs = row % RS, r = rs / S, s_ = rs % S;
+    wt[idx] = (k < K && c < C) ? w[((size_t)k * C + c) * RS + s_ * R + r] : 0.f;
+}
+
 }  // namespace
+
+hipError_t launch_weight_relayout_transposed(const float* w, float* wt, int K, int Kp, int C, int R, int S, int rows,
+                                             hipStream_t st)
+{
+    const size_t n = (size_t)rows * Kp;
+    hipLaunchKernelGGL(weight_relayout_transposed_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, wt, K, Kp,
+                       C, R, S, rows);
+    return hipGetLastError();
+}
 
 hipError_t launch_weight_relayout(const float* w, float* wt, int K, int Kp, int CRS, int rows, hipStream_t st)
 {

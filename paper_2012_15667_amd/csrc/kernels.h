@@ -20,12 +20,17 @@ struct DirectGeom {
     int nbx, nby, nbn, nbk;    // blocks along W_out, H_out, batch, C_out
     int xh, yh, halo;          // input tile extents and elements per channel (b * yh * xh)
     int flat;                  // MFMA path, set by the launcher: input tile staged in flat 64-element chunks
+    int w_transposed;          // weights are read with r and s exchanged: w[k][c][s'][r'] for this launch's (r', s')
     int hwc;                   // 0: x[N][C][H][W], y[N][K][P][Q];  1: x[N][H][W][C], y[N][P][Q][K]
 };
 
 // Re-layout w[K][C][R][S] -> wt[rows][Kp] (rows >= CRS = C*R*S, Kp >= K; rows beyond CRS and columns
 // beyond K are zero) so that a stage's weight slab is a run of rows contiguous in K.
 hipError_t launch_weight_relayout(const float* w, float* wt, int K, int Kp, int CRS, int rows, hipStream_t st);
+// The same for a launch whose kernel extents (R, S) are the transposes of the stored weights' (S, R): row
+// c*R*S + r*S + s of wt is taken from w[k][c][s][r].
+hipError_t launch_weight_relayout_transposed(const float* w, float* wt, int K, int Kp, int C, int R, int S, int rows,
+                                             hipStream_t st);
 
 hipError_t launch_direct_fma(const float* x, const float* w, float* y, const DirectGeom& g, hipStream_t st);
 // wt: re-laid-out weights with ceil(C/alpha)*alpha*R*S rows of g.Kp floats.

@@ -6,7 +6,7 @@ direct convolution 1e-4, Winograd 5e-3 (F(2x2), F(3x3), F(4x4) and F(6x6)).
 import numpy as np
 import pytest
 
-from oracle.conv_oracle import conv_ref, conv_ref_hwc, conv_ref_points
+from oracle.conv_oracle import conv_ref, conv_ref_cwh, conv_ref_hwc, conv_ref_points
 from paper_2012_15667_amd.inputs import CONFIGS, layer_inputs, make_inputs, sample_output_indices
 from tests.conftest import rel_err
 
@@ -254,6 +254,27 @@ def test_direct_hwc_enumerated_tiles_agree(gpu):
         assert rel_err(got, ref) <= TOL_DIRECT, cfg
 
 
+@pytest.mark.parametrize("case", [
+    (2, 8, 16, 24, 32, 3, 3, 1, 1),        # H != W
+    (2, 5, 12, 20, 48, 2, 3, 1, 0),        # non-square kernel: r and s must be exchanged too
+    (1, 3, 35, 27, 32, 11, 11, 4, 0),      # the plain-FMA path reads the weights transposed as well
+    (2, 16, 14, 28, 64, 1, 1, 2, 0),
+    (3, 7, 9, 11, 6, 3, 3, 1, 1),
+])
+def test_direct_cwh_matches_oracle(gpu, case):
+    """Images stored W-major (the CWH layout of Table 1): x [N][C][W][H] -> y [N][K][Q][P]."""
+    torch, B = gpu
+    N, C, H, W, K, R, S, stride, pad = case
+    x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=400 + C + H)
+    x_cwh = np.ascontiguousarray(np.transpose(x, (0, 1, 3, 2)))
+    ref = conv_ref_cwh(x_cwh, w, stride, pad)
+    y = B.conv_direct_layout(torch.from_numpy(x_cwh).cuda(), torch.from_numpy(w).cuda(), stride, pad, B.LAYOUT_CWH)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL_DIRECT
+
+
 @pytest.mark.parametrize("name", ["cfg3", "cfg5a", "cfg5c", "alex1", "alex2"])
 def test_direct_hwc_full_size_sampled(gpu, name):
     L = CONFIGS[name]
@@ -373,7 +394,7 @@ def test_layout_error_codes(gpu):
     L = B.lib()
     import ctypes
     args = [ctypes.c_void_p(t.data_ptr()) for t in (x, w, y)] + [1, 4, 8, 8, 32, 3, 3, 1, 1]
-    assert L.conv_direct_layout(*args, 2, None) == -2
+    assert L.conv_direct_layout(*args, 3, None) == -2
     assert L.conv_direct_layout(*args, -1, None) == -2
     assert L.conv_direct_layout(None, *args[1:], 1, None) == -1
     assert L.conv_direct_layout(*args, 1, None) == 0

@@ -6,7 +6,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from oracle.conv_oracle import conv_ref, conv_ref_hwc, conv_ref_points, out_extent
+from oracle.conv_oracle import conv_ref, conv_ref_cwh, conv_ref_hwc, conv_ref_points, out_extent
 from paper_2012_15667_amd.inputs import make_inputs, sample_output_indices
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "conv_hand_cases.txt")
@@ -113,6 +113,29 @@ def test_hwc_layout_brute_force_in_its_own_index_order(N, C, H, W, K, R, S, stri
                                 for c in range(C):
                                     acc += int(x[n, h, ww, c]) * int(w[k, c, r, s])
                     assert y[n, p, q, k] == acc
+
+
+def test_cwh_layout_brute_force_in_its_own_index_order():
+    """W before H: y[n,k,q,p] = sum x[n, c, q*stride+s-pad, p*stride+r-pad] w[k,c,r,s], summed on the CWH arrays."""
+    N, C, H, W, K, R, S, stride, pad = 2, 2, 5, 7, 3, 2, 3, 1, 1
+    rng = np.random.default_rng(12)
+    x = rng.integers(-4, 5, size=(N, C, W, H)).astype(np.float32)
+    w = rng.integers(-3, 4, size=(K, C, R, S)).astype(np.float32)
+    y = conv_ref_cwh(x, w, stride, pad)
+    P, Q = out_extent(H, W, R, S, stride, pad)
+    assert y.shape == (N, K, Q, P)
+    for n in range(N):
+        for k in range(K):
+            for q in range(Q):
+                for p in range(P):
+                    acc = 0
+                    for c in range(C):
+                        for r in range(R):
+                            for s in range(S):
+                                h, ww = p * stride + r - pad, q * stride + s - pad
+                                if 0 <= h < H and 0 <= ww < W:
+                                    acc += int(x[n, c, ww, h]) * int(w[k, c, r, s])
+                    assert y[n, k, q, p] == acc
 
 
 def test_delta_kernel_reproduces_input_bitwise():
