@@ -9,7 +9,9 @@
  *
  * Work is enqueued on the stream given to iolb_set_stream (the null stream by default) and
  * the calls return without waiting for it.  One stream per host thread; calls that use the
- * library's workspace and overlap on one GPU race.
+ * library's workspace and overlap on one GPU race.  A call that does not have to grow the
+ * workspace enqueues kernels only (no allocation, no memset, no synchronisation), so after one
+ * eager call for the same layer it can be recorded by a stream capture and replayed as a graph.
  *
  * Symbols (paper -> here): W_in,H_in,C_in -> W,H,C;  C_out -> K;  W_ker,H_ker -> S,R;
  * W_out,H_out -> Q,P;  mu -> stride;  e -> m.  A batch of N images shares the K kernels.

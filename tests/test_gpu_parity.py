@@ -386,6 +386,42 @@ def test_measured_autotuner_returns_a_valid_fast_tile(gpu):
 # error paths (nothing is launched)
 # ---------------------------------------------------------------------------------------------
 
+def test_calls_can_be_captured_in_a_hip_graph(gpu):
+    """After one eager call (which sizes the library's workspace and opts the kernels into large LDS), a call
+    enqueues kernels only -- no allocation, no memset, no host synchronisation -- so a stream capture records it.
+    Replayed three times on new inputs, with eager work in between, every replay must equal the eager result."""
+    torch, B = gpu
+    N, C, H, W, K = 4, 32, 28, 28, 64
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=61)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    yd = torch.empty((N, K, H, W), dtype=torch.float32, device="cuda")
+    yw = torch.empty_like(yd)
+    ws = torch.empty(B.winograd_workspace_bytes(N, C, H, W, K, 4), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up on the capture stream
+        B.conv_direct(xd, wd, 1, 1, y=yd)
+        B.conv_winograd(xd, wd, 4, y=yw, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.conv_direct(xd, wd, 1, 1, y=yd)
+        B.conv_winograd(xd, wd, 4, y=yw, workspace=ws)
+    for rep in range(3):
+        x2, _ = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=70 + rep)
+        xd.copy_(torch.from_numpy(x2).cuda())
+        yd.fill_(-1.0)
+        yw.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got_d, got_w = yd.cpu().numpy(), yw.cpu().numpy()
+        eager = B.conv_direct(xd, wd, 1, 1).cpu().numpy()             # eager work between the replays
+        assert np.array_equal(got_d, eager), rep
+        ref = conv_ref(x2, w, 1, 1)
+        assert rel_err(got_d, ref) <= TOL_DIRECT and rel_err(got_w, ref) <= TOL_WINO, rep
+
+
 def test_layout_error_codes(gpu):
     torch, B = gpu
     x = torch.zeros((1, 8, 8, 4), dtype=torch.float32, device="cuda")
