@@ -33,6 +33,8 @@
 #include "kernels.h"
 #include "lds_dma.h"
 
+#include <type_traits>
+
 namespace iolb {
 
 namespace {
@@ -72,7 +74,8 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
 
     // The tile's pixels form ceil(npix / 32) blocks, dealt to the waves_n wave columns as evenly as whole
     // blocks allow: the first `extra` columns own NBW blocks, the others NBW - 1 (all NBW when the blocks
-    // divide evenly: the EVEN instantiations).  A wave that owns NBW - 1 blocks skips the MFMAs of the last one.  With waves w and
+    // divide evenly: the EVEN instantiations).  A wave that owns NBW - 1 blocks runs a copy of the channel loop
+    // without the last block.  With waves w and
     // w + 4 on one SIMD this keeps the SIMDs within one block of each other.  Pixel slots past the tile in
     // the last block read the tile's last pixel and store nothing.
     int bbase[NBW], pimg[NBW], ppy[NBW], ppx[NBW];
@@ -82,7 +85,6 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     const int col_base = nblocks_pix / g.waves_n, col_extra = nblocks_pix % g.waves_n;
     const int my_blocks = col_base + (wn_i < col_extra ? 1 : 0);              // NBW or NBW - 1
     const int first_block = wn_i * col_base + (wn_i < col_extra ? wn_i : col_extra);
-    const bool owns_last = EVEN || my_blocks == NBW;      // wave-uniform; EVEN: the blocks divide evenly, no test
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
         const int slot = (first_block + nb) * 32 + l32;
@@ -200,106 +202,109 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     // wave of a SIMD is busy issuing loads the other keeps the matrix core fed.
     const int issue_group = (wave >> 2) & 1;
 
-    auto interleave_step = [&]() {
-        constexpr int MF = MBW * NBW, RD = MBW + NBW, PAIRS = (RD + 1) / 2;
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if constexpr (MF - 1 >= PAIRS) {
+    // The whole channel loop for a wave that owns NA pixel blocks (NA = NBW, or NBW - 1 for the wave columns
+    // that got one block less).  Both versions execute the same barriers.
+    auto run_stages = [&](auto na_c) {
+        constexpr int NA = decltype(na_c)::value;
+        auto interleave_step = [&]() {
+            constexpr int MF = MBW * NA, RD = MBW + NA, PAIRS = (RD + 1) / 2;
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if constexpr (MF - 1 >= PAIRS) {
 #pragma unroll
-            for (int i = 0; i < PAIRS; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                for (int i = 0; i < PAIRS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                if constexpr (MF - 1 - PAIRS > 0) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1 - PAIRS, 0);
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+                if constexpr (MF > 1) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1, 0);
             }
-            if constexpr (MF - 1 - PAIRS > 0) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1 - PAIRS, 0);
-        } else {
-            __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
-            if constexpr (MF > 1) __builtin_amdgcn_sched_group_barrier(0x008, MF - 1, 0);
-        }
-    };
-    auto multiply = [&](const float (&am)[MBW], const float (&bm)[NBW]) {
-#pragma unroll
-        for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-            for (int nb = 0; nb < NBW - 1; ++nb)
-                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
-        if (owns_last) {
+        };
+        auto multiply = [&](const float (&am)[MBW], const float (&bm)[NA]) {
 #pragma unroll
             for (int mb = 0; mb < MBW; ++mb)
-                acc[mb][NBW - 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[NBW - 1], acc[mb][NBW - 1], 0, 0, 0);
-        }
-    };
+#pragma unroll
+                for (int nb = 0; nb < NA; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(am[mb], bm[nb], acc[mb][nb], 0, 0, 0);
+        };
 
-    issue_stage(0, lds);
-    for (int s = 0; s < nstages; ++s) {
-        lds_dma_wait_all();
-        __syncthreads();                                    // stage s has landed; stage s-1 is consumed
-        float* cur = lds + (s & 1) * stage_floats;
-        float* nxt = lds + ((s + 1) & 1) * stage_floats;
-        const bool more = s + 1 < nstages;
-        const int c0_next = (s + 1) * g.alpha;
+        issue_stage(0, lds);
+        for (int s = 0; s < nstages; ++s) {
+            lds_dma_wait_all();
+            __syncthreads();                                    // stage s has landed; stage s-1 is consumed
+            float* cur = lds + (s & 1) * stage_floats;
+            float* nxt = lds + ((s + 1) & 1) * stage_floats;
+            const bool more = s + 1 < nstages;
+            const int c0_next = (s + 1) * g.alpha;
 
-        if constexpr (RR > 0) {
-            // Kernel extents known at compile time: the R*S steps of a channel pair are unrolled, so a
-            // step costs its LDS reads and a couple of address adds.  A body is two channel pairs (alpha
-            // is a multiple of 4), which keeps the two operand register sets in phase.
-            constexpr int RSc = RR * SS, BODY = 2 * RSc;
-            const int nbodies = half_c >> 1;
-            float fa[2][MBW], fb[2][NBW];
-            auto fetch = [&](int set, int bi, int t) {
-                const int cl = t / RSc, rs = t % RSc, r = rs / SS, sx = rs % SS;
-                const float* wp = cur + abase + ((2 * bi + cl) * RSc + rs) * g.z;
-                const int sc = (2 * bi + cl) * g.halo + r * g.xh;
+            if constexpr (RR > 0) {
+                // Kernel extents known at compile time: the R*S steps of a channel pair are unrolled, so a
+                // step costs its LDS reads and a couple of address adds.  A body is two channel pairs (alpha
+                // is a multiple of 4), which keeps the two operand register sets in phase.
+                constexpr int RSc = RR * SS, BODY = 2 * RSc;
+                const int nbodies = half_c >> 1;
+                float fa[2][MBW], fb[2][NA];
+                auto fetch = [&](int set, int bi, int t) {
+                    const int cl = t / RSc, rs = t % RSc, r = rs / SS, sx = rs % SS;
+                    const float* wp = cur + abase + ((2 * bi + cl) * RSc + rs) * g.z;
+                    const int sc = (2 * bi + cl) * g.halo + r * g.xh;
 #pragma unroll
-                for (int mb = 0; mb < MBW; ++mb) fa[set][mb] = wp[mb * 32];
+                    for (int mb = 0; mb < MBW; ++mb) fa[set][mb] = wp[mb * 32];
 #pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) fb[set][nb] = cur[bbase[nb] + sc + sx];
-            };
-            fetch(0, 0, 0);
-            for (int bi = 0; bi < nbodies; ++bi) {
-                const int bnext = (bi + 1 < nbodies) ? bi + 1 : 0;   // after the last body: wrap, read and drop
+                    for (int nb = 0; nb < NA; ++nb) fb[set][nb] = cur[bbase[nb] + sc + sx];
+                };
+                fetch(0, 0, 0);
+                for (int bi = 0; bi < nbodies; ++bi) {
+                    const int bnext = (bi + 1 < nbodies) ? bi + 1 : 0;   // after the last body: wrap, read and drop
 #pragma unroll
-                for (int t = 0; t < BODY; ++t) {
-                    if (t == 0 || t == RSc) {
-                        if (more && bi == 0 && issue_group == (t == 0 ? 0 : 1)) issue_stage(c0_next, nxt);
+                    for (int t = 0; t < BODY; ++t) {
+                        if (t == 0 || t == RSc) {
+                            if (more && bi == 0 && issue_group == (t == 0 ? 0 : 1)) issue_stage(c0_next, nxt);
+                        }
+                        if (t + 1 < BODY) fetch((t + 1) & 1, bi, t + 1);
+                        else              fetch(0, bnext, 0);
+                        multiply(fa[t & 1], fb[t & 1]);
+                        interleave_step();
                     }
-                    if (t + 1 < BODY) fetch((t + 1) & 1, bi, t + 1);
-                    else              fetch(0, bnext, 0);
-                    multiply(fa[t & 1], fb[t & 1]);
+                }
+            } else {
+                // General loop: steps j = (c2, r, s) flattened, two per iteration with two operand register
+                // sets (alpha is a multiple of 4, so the count is even).  After the last step the fetch wraps
+                // to step 0 (read and dropped).
+                const float* wrow = cur + abase;
+                int r = 0, sx = 0, xo = 0;              // position of the NEXT step to fetch
+                float a[MBW], bv[NA], a1[MBW], b1[NA];
+                auto fetch = [&](float (&an)[MBW], float (&bn)[NA], bool last) {
+#pragma unroll
+                    for (int mb = 0; mb < MBW; ++mb) an[mb] = wrow[mb * 32];
+#pragma unroll
+                    for (int nb = 0; nb < NA; ++nb) bn[nb] = cur[bbase[nb] + xo];
+                    // advance (r, s), the tile offset xo = c2*halo + r*xh + s and the weight row without branches
+                    const int wrap_s = (sx + 1 == g.S), wrap_r = wrap_s & (r + 1 == g.R);
+                    xo = last ? 0 : xo + (wrap_r ? step_c : (wrap_s ? step_r : 1));
+                    wrow = last ? cur + abase : wrow + g.z;
+                    sx = wrap_s ? 0 : sx + 1;
+                    r = wrap_r ? 0 : r + wrap_s;
+                };
+                const int issue_at = issue_group ? ((nsteps >> 1) & ~1) : 0;
+                fetch(a, bv, false);
+#pragma unroll 1
+                for (int j = 0; j < nsteps; j += 2) {
+                    if (more && j == issue_at) issue_stage(c0_next, nxt);
+                    fetch(a1, b1, false);
+                    multiply(a, bv);
+                    interleave_step();
+                    fetch(a, bv, j + 2 >= nsteps);
+                    multiply(a1, b1);
                     interleave_step();
                 }
             }
-        } else {
-            // General loop: steps j = (c2, r, s) flattened, two per iteration with two operand register
-            // sets (alpha is a multiple of 4, so the count is even).  After the last step the fetch wraps
-            // to step 0 (read and dropped).
-            const float* wrow = cur + abase;
-            int r = 0, sx = 0, xo = 0;              // position of the NEXT step to fetch
-            float a[MBW], bv[NBW], a1[MBW], b1[NBW];
-            auto fetch = [&](float (&an)[MBW], float (&bn)[NBW], bool last) {
-#pragma unroll
-                for (int mb = 0; mb < MBW; ++mb) an[mb] = wrow[mb * 32];
-#pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) bn[nb] = cur[bbase[nb] + xo];
-                // advance (r, s), the tile offset xo = c2*halo + r*xh + s and the weight row without branches
-                const int wrap_s = (sx + 1 == g.S), wrap_r = wrap_s & (r + 1 == g.R);
-                xo = last ? 0 : xo + (wrap_r ? step_c : (wrap_s ? step_r : 1));
-                wrow = last ? cur + abase : wrow + g.z;
-                sx = wrap_s ? 0 : sx + 1;
-                r = wrap_r ? 0 : r + wrap_s;
-            };
-            const int issue_at = issue_group ? ((nsteps >> 1) & ~1) : 0;
-            fetch(a, bv, false);
-#pragma unroll 1
-            for (int j = 0; j < nsteps; j += 2) {
-                if (more && j == issue_at) issue_stage(c0_next, nxt);
-                fetch(a1, b1, false);
-                multiply(a, bv);
-                interleave_step();
-                fetch(a, bv, j + 2 >= nsteps);
-                multiply(a1, b1);
-                interleave_step();
-            }
         }
-    }
+
+    };
+    if (EVEN || my_blocks == NBW) run_stages(std::integral_constant<int, NBW>{});
+    else if constexpr (!EVEN && NBW > 1) run_stages(std::integral_constant<int, NBW - 1>{});
 
     // each partial sum is complete: write the block once.  Register i of a 32 x 32 block holds
     // channel 8*(i/4) + 4*half + i%4 of pixel l32.
