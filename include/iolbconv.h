@@ -118,6 +118,19 @@ int conv_winograd_ws(const float* x, const float* w, float* y,
                      int N, int C, int H, int W, int K, int m,
                      void* workspace, size_t workspace_bytes, const iolb_tile_config* cfg);
 
+/* Kernels transformed once, used by many calls (inference: the weights do not change).
+ * conv_winograd_kernel_bytes: size of the transformed-kernel buffer for C x K kernels of
+ * F(m x m, 3 x 3) (0 on invalid arguments).  conv_winograd_transform_kernels: writes
+ * U = L g L^T (first step of Sec. 4.3) for w [K][C][3][3] into that caller-owned, 256-byte
+ * aligned device buffer, laid out [(m+2)^2][C rounded up to 16][K rounded up to 32] with zeros
+ * in the padding.  conv_winograd_pre: conv_winograd_ws with U in place of w; the workspace
+ * size is the one conv_winograd_workspace_bytes reports. */
+size_t conv_winograd_kernel_bytes(int C, int K, int m);
+int conv_winograd_transform_kernels(const float* w, float* U, int C, int K, int m);
+int conv_winograd_pre(const float* x, const float* U, float* y,
+                      int N, int C, int H, int W, int K, int m,
+                      void* workspace, size_t workspace_bytes, const iolb_tile_config* cfg);
+
 /* The analytical tuner (searching domain of Table 1, Sec. 6.2; objective: reading volume of
  * the dataflow of Sec. 5.2 / 5.3).  Host only; shape and out are host pointers.
  * lds_bytes: LDS available to one workgroup; 0 = automatic: 81920 (half a compute unit's LDS, the

@@ -15,7 +15,8 @@ PATH_FMA, PATH_MFMA = 0, 1
 LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 
 EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_workspace_bytes",
-           "conv_winograd_ws", "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
+           "conv_winograd_ws", "conv_winograd_kernel_bytes", "conv_winograd_transform_kernels", "conv_winograd_pre",
+           "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
            "iolb_timing_enable", "iolb_timing_read", "iolb_release_workspace", "iolb_strerror",
            "iolb_last_hip_error"]
 
@@ -77,6 +78,12 @@ def lib():
         L.conv_winograd_workspace_bytes.argtypes = [i] * 6
         L.conv_winograd_ws.restype = i
         L.conv_winograd_ws.argtypes = [vp, vp, vp] + [i] * 6 + [vp, sz, ctypes.POINTER(TileConfig)]
+        L.conv_winograd_kernel_bytes.restype = sz
+        L.conv_winograd_kernel_bytes.argtypes = [i] * 3
+        L.conv_winograd_transform_kernels.restype = i
+        L.conv_winograd_transform_kernels.argtypes = [vp, vp] + [i] * 3
+        L.conv_winograd_pre.restype = i
+        L.conv_winograd_pre.argtypes = [vp, vp, vp] + [i] * 6 + [vp, sz, ctypes.POINTER(TileConfig)]
         L.iolb_tune.restype = i
         L.iolb_tune.argtypes = [ctypes.POINTER(Shape), sz, i, ctypes.POINTER(TileConfig)]
         L.iolb_enumerate.restype = ctypes.c_int64
@@ -246,6 +253,45 @@ def conv_winograd(x, w, m, y=None, cfg=None, workspace=None):
         c = ctypes.byref(cfg if isinstance(cfg, TileConfig) else TileConfig.from_dict(cfg))
     _check(L.conv_winograd_ws(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, m,
                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), c))
+    return y
+
+
+def winograd_transform_kernels(w, m):
+    """U = L g L^T for w [K][C][3][3], in a new device buffer the Winograd calls can reuse (see
+    conv_winograd_pre); returns (U, C, K)."""
+    import torch
+    K, C, R, S = w.shape
+    if R != 3 or S != 3:
+        raise ValueError("Winograd path needs 3x3 kernels")
+    need = lib().conv_winograd_kernel_bytes(C, K, m)
+    if need == 0:
+        raise IolbError(-2, "unsupported Winograd kernel set")
+    U = torch.empty(need // 4, dtype=torch.float32, device=w.device)
+    _use_current_stream()
+    _check(lib().conv_winograd_transform_kernels(_dev_f32(w, "w"), ctypes.c_void_p(U.data_ptr()), C, K, m))
+    return U, C, K
+
+
+def conv_winograd_pre(x, U, K, m, y=None, cfg=None, workspace=None):
+    """conv_winograd with kernels transformed beforehand by winograd_transform_kernels."""
+    import torch
+    N, C, H, W = x.shape
+    if y is None:
+        y = torch.empty((N, K, H, W), dtype=torch.float32, device=x.device)
+    elif tuple(y.shape) != (N, K, H, W):
+        raise ValueError("y has the wrong shape")
+    L = lib()
+    need = L.conv_winograd_workspace_bytes(N, C, H, W, K, m)
+    if need == 0:
+        raise IolbError(-2, "unsupported Winograd layer")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    c = None
+    if cfg is not None:
+        c = ctypes.byref(cfg if isinstance(cfg, TileConfig) else TileConfig.from_dict(cfg))
+    _use_current_stream()
+    _check(L.conv_winograd_pre(_dev_f32(x, "x"), _dev_f32(U, "U"), _dev_f32(y, "y"), N, C, H, W, K, m,
+                               ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), c))
     return y
 
 

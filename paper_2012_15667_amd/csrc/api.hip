@@ -206,6 +206,7 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
     g->alpha = cfg.alpha;
     g->Cp = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;
     g->Kp = (s.K + 31) / 32 * 32;
+    g->CpU = g->Cp;
     g->waves_m = cfg.waves_m;
     g->waves_n = cfg.waves_n;
     const int64_t pitch = (tiles + g->tb - 1) / g->tb * g->tb;
@@ -245,8 +246,13 @@ int make_wino_shape(int N, int C, int H, int W, int K, int m, iolb_shape* s)
     return iolb::validate_shape(*s, &P, &Q);
 }
 
-int run_winograd(const float* x, const float* w, float* y, const iolb_shape& s, const iolb_tile_config& cfg,
-                 void* ws, size_t ws_bytes)
+// Channel rows per plane of a caller-held transformed-kernel buffer: every stage depth divides 16.
+int pretransformed_rows(int C) { return (C + 15) / 16 * 16; }
+
+// w != nullptr: transform the kernels into the workspace first.  w == nullptr: Upre holds them already
+// (written by conv_winograd_transform_kernels).
+int run_winograd(const float* x, const float* w, const float* Upre, float* y, const iolb_shape& s,
+                 const iolb_tile_config& cfg, void* ws, size_t ws_bytes)
 {
     DeviceState* dev = nullptr;
     int rc = device_state(&dev);
@@ -261,10 +267,16 @@ int run_winograd(const float* x, const float* w, float* y, const iolb_shape& s, 
     float* V = reinterpret_cast<float*>(base + l.v_off);
     float* M = reinterpret_cast<float*>(base + l.m_off);
     hipStream_t st = t_stream;
-    IOLB_HIP(iolb::launch_wino_kernel_transform(w, U, g, st));
+    const float* Uuse = U;
+    if (w) {
+        IOLB_HIP(iolb::launch_wino_kernel_transform(w, U, g, st));
+    } else {
+        g.CpU = pretransformed_rows(s.C);
+        Uuse = Upre;
+    }
     IOLB_HIP(iolb::launch_wino_input_transform(x, V, g, st));
     MainKernelTimer timer(st, IOLB_TIME_WINO_PRODUCT);
-    IOLB_HIP(iolb::launch_wino_product(U, V, M, g, st));
+    IOLB_HIP(iolb::launch_wino_product(Uuse, V, M, g, st));
     timer.stop(st);
     IOLB_HIP(iolb::launch_wino_output_transform(M, y, g, st));
     return IOLB_OK;
@@ -349,7 +361,46 @@ int conv_winograd_ws(const float* x, const float* w, float* y, int N, int C, int
         rc = tuned_tile(s, &tile);
         if (rc != IOLB_OK) return rc;
     }
-    return run_winograd(x, w, y, s, tile, workspace, workspace_bytes);
+    return run_winograd(x, w, nullptr, y, s, tile, workspace, workspace_bytes);
+}
+
+size_t conv_winograd_kernel_bytes(int C, int K, int m)
+{
+    if (C < 1 || K < 1 || (m != 2 && m != 3 && m != 4 && m != 6)) return 0;
+    return sizeof(float) * (size_t)(m + 2) * (m + 2) * pretransformed_rows(C) * ((K + 31) / 32 * 32);
+}
+
+int conv_winograd_transform_kernels(const float* w, float* U, int C, int K, int m)
+{
+    if (!w || !U || C < 1 || K < 1) return IOLB_EINVAL;
+    if (m != 2 && m != 3 && m != 4 && m != 6) return IOLB_EUNSUPPORTED;
+    if ((int64_t)K * C * 9 >= (1LL << 31) || conv_winograd_kernel_bytes(C, K, m) / sizeof(float) >= ((size_t)1 << 31))
+        return IOLB_EINVAL;
+    iolb::WinoGeom g{};
+    g.C = C; g.K = K; g.m = m;
+    g.Kp = (K + 31) / 32 * 32;
+    g.CpU = pretransformed_rows(C);
+    IOLB_HIP(iolb::launch_wino_kernel_transform(w, U, g, t_stream));
+    return IOLB_OK;
+}
+
+int conv_winograd_pre(const float* x, const float* U, float* y, int N, int C, int H, int W, int K, int m,
+                      void* workspace, size_t workspace_bytes, const iolb_tile_config* cfg)
+{
+    if (!x || !U || !y) return IOLB_EINVAL;
+    iolb_shape s;
+    int rc = make_wino_shape(N, C, H, W, K, m, &s);
+    if (rc != IOLB_OK) return rc;
+    iolb_tile_config tile;
+    if (cfg) {
+        rc = check_config(s, *cfg);
+        if (rc != IOLB_OK) return rc;
+        tile = *cfg;
+    } else {
+        rc = tuned_tile(s, &tile);
+        if (rc != IOLB_OK) return rc;
+    }
+    return run_winograd(x, nullptr, U, y, s, tile, workspace, workspace_bytes);
 }
 
 int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m)
@@ -367,7 +418,7 @@ int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H,
     if (rc != IOLB_OK) return rc;
     rc = ensure_workspace(dev, bytes);
     if (rc != IOLB_OK) return rc;
-    return run_winograd(x, w, y, s, tile, dev->ws, dev->ws_bytes);
+    return run_winograd(x, w, nullptr, y, s, tile, dev->ws, dev->ws_bytes);
 }
 
 int iolb_winograd_matrices(int m, float* A, float* L, float* B)

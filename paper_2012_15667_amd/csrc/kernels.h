@@ -44,6 +44,7 @@ struct WinoGeom {
     int N, C, H, W, K, m;      // P = H, Q = W (pad 1)
     int Cp;                    // C rounded up to whole stages: U and V carry zero rows for c in [C, Cp)
     int Kp;                    // K rounded up to a multiple of 32: U carries zero columns, M unused rows for k in [K, Kp)
+    int CpU;                   // channel rows per plane of U (>= Cp; a caller-held U is padded to a multiple of 16)
     int th, tw;                // sub-domains along H_out and W_out
     int tiles;                 // N * th * tw
     int tiles_pitch;           // tiles rounded up to a whole number of blocks

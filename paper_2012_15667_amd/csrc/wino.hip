@@ -254,7 +254,7 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
     const int tbk = bid % nbt;
     const int xi = bid / nbt;
     const int k0 = kb * g.z, t0 = tbk * g.tb;
-    const float* Up = U + (size_t)xi * g.Cp * g.Kp + k0;
+    const float* Up = U + (size_t)xi * g.CpU * g.Kp + k0;
     const float* Vp = V + (size_t)xi * g.Cp * g.tiles_pitch + t0;
 
     const int half_c = g.alpha >> 1;
@@ -377,13 +377,13 @@ hipError_t launch_product_one(const float* U, const float* V, float* Mp, const W
 
 hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom& g, hipStream_t st)
 {
-    const size_t n = (size_t)g.Cp * g.Kp;
+    const size_t n = (size_t)g.CpU * g.Kp;
     const int grid = (int)((n + 255) / 256);
     switch (g.m) {
-    case 2: hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
-    case 3: hipLaunchKernelGGL(kernel_transform<3>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
-    case 4: hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
-    case 6: hipLaunchKernelGGL(kernel_transform<6>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.Cp, g.K, g.Kp); break;
+    case 2: hipLaunchKernelGGL(kernel_transform<2>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.CpU, g.K, g.Kp); break;
+    case 3: hipLaunchKernelGGL(kernel_transform<3>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.CpU, g.K, g.Kp); break;
+    case 4: hipLaunchKernelGGL(kernel_transform<4>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.CpU, g.K, g.Kp); break;
+    case 6: hipLaunchKernelGGL(kernel_transform<6>, dim3(grid), dim3(256), 0, st, w, U, g.C, g.CpU, g.K, g.Kp); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -433,7 +433,7 @@ hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeo
 
 hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const WinoGeom& g, hipStream_t st)
 {
-    if (g.tb % 32 || g.z % 32 || (g.alpha & 3) || g.Kp % g.z || g.Kp < g.K || g.tiles_pitch % g.tb || g.Cp % g.alpha || g.Cp < g.C)
+    if (g.tb % 32 || g.z % 32 || (g.alpha & 3) || g.Kp % g.z || g.Kp < g.K || g.tiles_pitch % g.tb || g.Cp % g.alpha || g.Cp < g.C || g.CpU < g.Cp)
         return hipErrorInvalidValue;
     const int MB = g.z / 32, NB = g.tb / 32;
     if (MB % g.waves_m || NB % g.waves_n) return hipErrorInvalidValue;

@@ -357,6 +357,24 @@ def test_winograd_full_size_sampled(gpu, name, m):
     assert np.isfinite(got).all()
 
 
+@pytest.mark.parametrize("m,N,C,H,W,K", [(4, 4, 20, 14, 14, 64), (2, 2, 64, 28, 28, 48), (6, 2, 7, 13, 17, 32)])
+def test_winograd_with_pretransformed_kernels_is_bit_identical(gpu, m, N, C, H, W, K):
+    """Kernels transformed once and reused give the bits of the on-the-fly path (same transform kernel,
+    same product), for C that is not a multiple of 16 and K that is not a multiple of 32 too."""
+    torch, B = gpu
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=120 + m)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    U, C2, K2 = B.winograd_transform_kernels(wd, m)
+    assert (C2, K2) == (C, K) and U.numel() * 4 == B.lib().conv_winograd_kernel_bytes(C, K, m)
+    a = B.conv_winograd(xd, wd, m)
+    for _ in range(2):                                   # the buffer is read-only: reuse it
+        b = B.conv_winograd_pre(xd, U, K, m)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+    assert rel_err(b.cpu().numpy(), conv_ref(x, w, 1, 1)) <= TOL_WINO
+    assert B.lib().conv_winograd_kernel_bytes(C, K, 5) == 0
+
+
 def test_measured_autotuner_returns_a_valid_fast_tile(gpu):
     """The measured tuning loop on a small layer: the tile it returns is one of the domain, gives the
     right layer, and is not slower than the analytical pick by more than timing noise allows."""
