@@ -237,7 +237,7 @@ output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g
 // for the whole channel loop.  Per stage, alpha rows of U (z floats) and of V (tb floats) go to LDS with
 // 16-byte LDS-direct loads; two buffers alternate.  Lane halves feed the two k-slices of an MFMA with
 // channels c2 and c2 + alpha/2.
-template <int MBW, int NBW, int LB>
+template <int MBW, int NBW, int LB, bool DEEP>
 __global__ void __launch_bounds__(LB)
 wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, float* __restrict__ Mp, WinoGeom g)
 {
@@ -318,6 +318,30 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
         float* nxt = lds + ((s + 1) & 1) * stage_floats;
         const bool more = s + 1 < nstages;
         const int c0_next = (s + 1) * g.alpha;
+        if constexpr (DEEP) {
+            // alpha = 16, the usual stage depth, has instantiations of its own: the eight channel steps are
+            // unrolled into one straight-line block (no loop branch, no wrap-around selects), which lets
+            // the reads of step t+1 be placed between the MFMAs of step t over the whole stage
+            float fa[2][MBW], fb[2][NBW];
+            auto fetch = [&](int set, int t) {
+                const float* ap = cur + abase + t * g.z;
+                const float* bp = cur + bbase + t * g.tb;
+#pragma unroll
+                for (int mb = 0; mb < MBW; ++mb) fa[set][mb] = ap[mb * 32];
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb) fb[set][nb] = bp[nb * 32];
+            };
+            fetch(0, 0);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                if (t == 0 || t == 4) {
+                    if (more && issue_group == (t == 0 ? 0 : 1)) issue_stage(c0_next, nxt);
+                }
+                fetch((t + 1) & 1, t + 1 < 8 ? t + 1 : 0);        // after the last step: wrap, read and drop
+                multiply(fa[t & 1], fb[t & 1]);
+                interleave_step();
+            }
+        } else {
         // operands of channel step j+1 are fetched while the MFMAs of step j are issued (two register
         // sets, two steps per iteration); after the last step the fetch wraps to step 0 (read, dropped)
         const float* ap = cur + abase;
@@ -342,6 +366,7 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
             multiply(a1, b1);
             interleave_step();
         }
+        }
     }
 
     float* mp = Mp + ((size_t)xi * g.Kp + k0) * g.tiles_pitch + t0;
@@ -358,11 +383,11 @@ wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, fl
     }
 }
 
-template <int MBW, int NBW, int LB>
+template <int MBW, int NBW, int LB, bool DEEP>
 hipError_t launch_product_one(const float* U, const float* V, float* Mp, const WinoGeom& g,
                               int grid, int threads, size_t shm, hipStream_t st)
 {
-    auto kern = wino_product_kernel<MBW, NBW, LB>;
+    auto kern = wino_product_kernel<MBW, NBW, LB, DEEP>;
     static bool raised = false;
     if (shm > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -446,12 +471,13 @@ hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const 
     const long long grid_ll = (long long)n * n * (g.Kp / g.z) * (g.tiles_pitch / g.tb);
     if (grid_ll > 0x7fffffffLL) return hipErrorInvalidValue;
     const int grid = (int)grid_ll;
+    const bool deep = g.alpha == 16;                // eight channel steps per stage: the unrolled instantiations
 #define IOLB_CASE(M_, N_)                                                                                      \
     if (mbw == M_ && nbw == N_) {                                                                              \
-        if (threads <= 256) return launch_product_one<M_, N_, 256>(U, V, Mp, g, grid, threads, shm, st); \
-        if (threads <= 512) return launch_product_one<M_, N_, 512>(U, V, Mp, g, grid, threads, shm, st); \
+        if (threads <= 256) return deep ? launch_product_one<M_, N_, 256, true>(U, V, Mp, g, grid, threads, shm, st) : launch_product_one<M_, N_, 256, false>(U, V, Mp, g, grid, threads, shm, st); \
+        if (threads <= 512) return deep ? launch_product_one<M_, N_, 512, true>(U, V, Mp, g, grid, threads, shm, st) : launch_product_one<M_, N_, 512, false>(U, V, Mp, g, grid, threads, shm, st); \
         if constexpr (M_ * N_ <= 4)                                                                            \
-            return launch_product_one<M_, N_, 1024>(U, V, Mp, g, grid, threads, shm, st);               \
+            return deep ? launch_product_one<M_, N_, 1024, true>(U, V, Mp, g, grid, threads, shm, st) : launch_product_one<M_, N_, 1024, false>(U, V, Mp, g, grid, threads, shm, st);               \
     }
     IOLB_CASE(1, 1) IOLB_CASE(1, 2) IOLB_CASE(1, 3) IOLB_CASE(1, 4)
     IOLB_CASE(1, 5) IOLB_CASE(1, 6) IOLB_CASE(1, 7) IOLB_CASE(1, 8)
