@@ -201,6 +201,10 @@ def main():
             "modelled_read_MB": round(4 * tile["q_read_elems"] / 1e6, 2),
         })
 
+    # ---- measured ceilings of this GPU (outside the timed region) ------------------------------
+    from paper_2012_15667_amd.ceilings import measure as measure_ceilings
+    ceilings = measure_ceilings()
+
     ms_step = 1e3 * elapsed / args.steps
     value = flops_step / (elapsed / args.steps) / 1e12
     roofline = None
@@ -209,6 +213,7 @@ def main():
         roofline = {"bound": "mfma", "kernel": "direct_mfma_kernel (all instantiations in the step)",
                     "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
+                    "frac_of_measured_mfma_loop": round(achieved / ceilings["mfma_f32_TFLOPs"], 4),
                     "avg_launch_ms": round(ms_direct / n_direct, 4), "launches": n_direct,
                     "traffic": read_traffic_note()}
     wino_roofline = None
@@ -217,6 +222,7 @@ def main():
         wino_roofline = {"bound": "mfma", "kernel": "wino_product_kernel (all instantiations in the step)",
                          "achieved": round(achieved_w, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                          "frac": round(achieved_w / PEAK_FP32_MFMA_TFLOPS, 4),
+                         "frac_of_measured_mfma_loop": round(achieved_w / ceilings["mfma_f32_TFLOPs"], 4),
                          "avg_launch_ms": round(ms_wino / n_wino, 4), "launches": n_wino}
 
     out = {
@@ -228,6 +234,7 @@ def main():
                    "convs_per_step": len(jobs), "direct_equiv_gflop_per_step": round(flops_step / 1e9, 1)},
         "roofline": roofline,
         "roofline_winograd_product": wino_roofline,
+        "measured_ceilings": ceilings,
         "layers": layers,
     }
     if not args.no_cpu_baseline:

@@ -166,6 +166,19 @@ enum { IOLB_TIME_DIRECT = 0, IOLB_TIME_WINO_PRODUCT = 1 };
 int iolb_timing_enable(int on);
 int iolb_timing_read(int kind, int* launches, float* total_ms);
 
+/* Ceiling probes for roofline reports (the experimental set-up of Sec. 7 quotes peak rates; these measure
+ * what the device at hand delivers).  Both run `reps` launches on the set stream after one untimed launch,
+ * wait for them, and return the average duration of a launch in milliseconds.
+ *   iolb_probe_hbm_copy: a streaming copy of `bytes` (a multiple of 16) from src to dst, device buffers
+ *     that do not overlap; the traffic of a launch is 2 * bytes.
+ *   iolb_probe_mfma_f32: a loop of independent v_mfma_f32_32x32x2_f32 with operands in registers; `sink`
+ *     is a device buffer of at least iolb_probe_mfma_sink_bytes() bytes that receives the accumulators'
+ *     sums; *flop_per_launch gets the floating-point operations of one launch.
+ * IOLB_EINVAL for null pointers, bytes == 0 or not a multiple of 16, iters < 1, reps < 1. */
+int iolb_probe_hbm_copy(const void* src, void* dst, size_t bytes, int reps, float* ms_per_launch);
+size_t iolb_probe_mfma_sink_bytes(void);
+int iolb_probe_mfma_f32(void* sink, int iters, int reps, float* ms_per_launch, double* flop_per_launch);
+
 /* Frees the library's device workspace (it is otherwise kept until the process ends). */
 int iolb_release_workspace(void);
 

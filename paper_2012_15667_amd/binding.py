@@ -17,6 +17,7 @@ LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_workspace_bytes",
            "conv_winograd_ws", "conv_winograd_kernel_bytes", "conv_winograd_transform_kernels", "conv_winograd_pre",
            "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
+           "iolb_probe_hbm_copy", "iolb_probe_mfma_sink_bytes", "iolb_probe_mfma_f32",
            "iolb_timing_enable", "iolb_timing_read", "iolb_release_workspace", "iolb_strerror",
            "iolb_last_hip_error"]
 
@@ -98,6 +99,12 @@ def lib():
         L.iolb_timing_enable.argtypes = [i]
         L.iolb_timing_read.restype = i
         L.iolb_timing_read.argtypes = [i, ctypes.POINTER(i), ctypes.POINTER(ctypes.c_float)]
+        L.iolb_probe_hbm_copy.restype = i
+        L.iolb_probe_hbm_copy.argtypes = [vp, vp, sz, i, ctypes.POINTER(ctypes.c_float)]
+        L.iolb_probe_mfma_sink_bytes.restype = sz
+        L.iolb_probe_mfma_sink_bytes.argtypes = []
+        L.iolb_probe_mfma_f32.restype = i
+        L.iolb_probe_mfma_f32.argtypes = [vp, i, i, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
         L.iolb_release_workspace.restype = i
         L.iolb_release_workspace.argtypes = []
         L.iolb_strerror.restype = ctypes.c_char_p
@@ -312,6 +319,31 @@ def timing_read(kind):
     ms = ctypes.c_float(0)
     _check(lib().iolb_timing_read(kind, ctypes.byref(n), ctypes.byref(ms)))
     return n.value, ms.value
+
+
+def probe_hbm_copy(src, dst, reps=5):
+    """Average milliseconds of one streaming copy of src into dst (float32 GPU tensors of equal size)."""
+    if src.numel() != dst.numel():
+        raise ValueError("src and dst differ in size")
+    _use_current_stream()
+    ms = ctypes.c_float(0)
+    _check(lib().iolb_probe_hbm_copy(_dev_f32(src, "src"), _dev_f32(dst, "dst"), src.numel() * 4, reps, ctypes.byref(ms)))
+    return ms.value
+
+
+def probe_mfma_sink_bytes():
+    return lib().iolb_probe_mfma_sink_bytes()
+
+
+def probe_mfma_f32(sink, iters=20000, reps=3):
+    """(average milliseconds, flop) of one launch of the register-only fp32 MFMA loop."""
+    if sink.numel() * 4 < probe_mfma_sink_bytes():
+        raise ValueError("sink is too small")
+    _use_current_stream()
+    ms = ctypes.c_float(0)
+    flop = ctypes.c_double(0)
+    _check(lib().iolb_probe_mfma_f32(_dev_f32(sink, "sink"), iters, reps, ctypes.byref(ms), ctypes.byref(flop)))
+    return ms.value, flop.value
 
 
 def release_workspace():

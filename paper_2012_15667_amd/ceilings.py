@@ -1,0 +1,33 @@
+"""Measured ceilings of the GPU at hand: a streaming copy (HBM) and a register-only fp32 MFMA loop.
+
+    python -m paper_2012_15667_amd.ceilings
+
+prints one JSON line.  bench.py quotes its roofline fractions against the published peaks and, beside them,
+against these.
+"""
+import json
+import sys
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_F32_PEAK_TFLOPS = 157.3
+
+
+def measure(copy_bytes=1 << 30, copy_reps=5, mfma_iters=20000, mfma_reps=3):
+    import torch
+    from . import binding as B
+    src = torch.zeros(copy_bytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    ms_copy = B.probe_hbm_copy(src, dst, copy_reps)
+    del src, dst
+    sink = torch.empty(B.probe_mfma_sink_bytes() // 4, dtype=torch.float32, device="cuda")
+    ms_mfma, flop = B.probe_mfma_f32(sink, mfma_iters, mfma_reps)
+    copy_gbps = 2.0 * copy_bytes / ms_copy / 1e6
+    mfma_tflops = flop / ms_mfma / 1e9
+    return {"hbm_copy_GBps": round(copy_gbps, 1), "hbm_copy_frac_of_published": round(copy_gbps / HBM_PEAK_GBPS, 4),
+            "mfma_f32_TFLOPs": round(mfma_tflops, 2), "mfma_f32_frac_of_published": round(mfma_tflops / MFMA_F32_PEAK_TFLOPS, 4),
+            "copy_bytes": copy_bytes, "mfma_ms": round(ms_mfma, 3)}
+
+
+if __name__ == "__main__":
+    print(json.dumps(measure()))
+    sys.exit(0)

@@ -282,6 +282,27 @@ int run_winograd(const float* x, const float* w, const float* Upre, float* y, co
     return IOLB_OK;
 }
 
+// Runs `launch` once untimed and then `reps` times between two events on the set stream.
+template <typename Launch>
+int time_probe(int reps, float* ms_per_launch, Launch launch)
+{
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    IOLB_HIP(launch());                                   // untimed: clocks up, code loaded
+    IOLB_HIP(hipEventCreate(&e0));
+    hipError_t e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = hipEventRecord(e0, t_stream);
+    for (int r = 0; r < reps && e == hipSuccess; ++r) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(e1, t_stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return hip_fail(e);
+    *ms_per_launch = ms / reps;
+    return IOLB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -477,6 +498,25 @@ int iolb_timing_read(int kind, int* launches, float* total_ms)
     *launches = count;
     *total_ms = sum;
     return rc;
+}
+
+int iolb_probe_hbm_copy(const void* src, void* dst, size_t bytes, int reps, float* ms_per_launch)
+{
+    if (!src || !dst || !ms_per_launch || bytes == 0 || bytes % 16 || reps < 1) return IOLB_EINVAL;
+    return time_probe(reps, ms_per_launch, [&] { return iolb::launch_probe_copy(src, dst, bytes, t_stream); });
+}
+
+size_t iolb_probe_mfma_sink_bytes(void)
+{
+    return sizeof(float) * 256 * (size_t)iolb::PROBE_MFMA_BLOCKS;
+}
+
+int iolb_probe_mfma_f32(void* sink, int iters, int reps, float* ms_per_launch, double* flop_per_launch)
+{
+    if (!sink || !ms_per_launch || !flop_per_launch || iters < 1 || reps < 1) return IOLB_EINVAL;
+    *flop_per_launch = 4096.0 * iolb::PROBE_ACC * iters * 4.0 * iolb::PROBE_MFMA_BLOCKS;
+    return time_probe(reps, ms_per_launch,
+                      [&] { return iolb::launch_probe_mfma(static_cast<float*>(sink), iters, t_stream); });
 }
 
 int iolb_release_workspace(void)

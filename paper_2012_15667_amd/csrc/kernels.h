@@ -56,6 +56,15 @@ hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom&
 hipError_t launch_wino_product(const float* U, const float* V, float* M, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_output_transform(const float* M, float* y, const WinoGeom& g, hipStream_t st);
 
+// Ceiling probes (probe.hip).  The copy moves bytes / 16 16-byte pieces; the MFMA loop runs
+// PROBE_MFMA_BLOCKS workgroups of four waves, each wave PROBE_ACC MFMAs (4096 flop each) per iteration, and
+// writes PROBE_MFMA_BLOCKS * 256 floats to sink.
+constexpr int PROBE_COPY_BLOCKS = 8192;
+constexpr int PROBE_MFMA_BLOCKS = 1024;
+constexpr int PROBE_ACC = 8;
+hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+hipError_t launch_probe_mfma(float* sink, int iters, hipStream_t st);
+
 }  // namespace iolb
 
 #endif

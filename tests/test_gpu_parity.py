@@ -3,6 +3,7 @@
 Tolerances (max_i |g_i - r_i| / max(|r_i|, rms(r)), fp32 GPU result against the fp64 oracle):
 direct convolution 1e-4, Winograd 5e-3 (F(2x2), F(3x3), F(4x4) and F(6x6)).
 """
+import ctypes
 import numpy as np
 import pytest
 
@@ -477,3 +478,26 @@ def test_error_codes(gpu):
     assert e.value.code == -4
     torch.cuda.synchronize()
     assert float(y.min()) == 7.0 and float(y.max()) == 7.0      # failed calls wrote nothing
+
+
+def test_ceiling_probes(gpu):
+    """The copy probe copies; the MFMA probe leaves the sums its operands fix: A[i][k] = 1 + (i mod 8),
+    B = 1/2, two k-slices per instruction, so a partial sum in row i grows by 1 + (i mod 8) per MFMA; a lane
+    of the lower half holds rows with (i mod 8) in 0..3 four times each (sum 40), of the upper half 4..7
+    (sum 104), in each of the 8 accumulator blocks."""
+    torch, B = gpu
+    g = torch.Generator(device="cuda").manual_seed(5)
+    src = torch.rand(1 << 22, generator=g, device="cuda", dtype=torch.float32)
+    dst = torch.zeros_like(src)
+    ms = B.probe_hbm_copy(src, dst, reps=2)
+    assert ms > 0 and torch.equal(src, dst)
+    sink = torch.zeros(B.probe_mfma_sink_bytes() // 4, device="cuda", dtype=torch.float32)
+    iters = 100
+    ms, flop = B.probe_mfma_f32(sink, iters=iters, reps=1)
+    assert ms > 0 and flop == 4096.0 * 8 * iters * 4 * (sink.numel() // 256)
+    s = sink.view(-1, 64).cpu()
+    assert torch.all(s[:, :32] == 8 * iters * 40.0) and torch.all(s[:, 32:] == 8 * iters * 104.0)
+    L = B.lib()
+    f = ctypes.c_float(0)
+    assert L.iolb_probe_hbm_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), 24, 1, ctypes.byref(f)) == -1
+    assert L.iolb_probe_hbm_copy(None, ctypes.c_void_p(dst.data_ptr()), 16, 1, ctypes.byref(f)) == -1
