@@ -105,7 +105,10 @@ int conv_direct_layout(const float* x, const float* w, float* y,
 /* Winograd F(m x m, 3 x 3) convolution (Sec. 2.3; four steps of Sec. 4.3), R = S = 3,
  * stride 1, pad 1 (P = H, Q = W), m in {2, 3, 4, 6} (Sec. 2.3 names e = 2 and e = 3; larger m
  * trades more rounding error for fewer multiplications).  Same layouts as conv_direct.  The transformed
- * kernels, inputs and products live in the library's device workspace, grown on demand. */
+ * kernels, inputs and products live in the library's device workspace, grown on demand.
+ * Thin layers (C <= 4 and C * (m+2)^2 <= 128; the tuned tile then has path == IOLB_PATH_FMA) run the
+ * fused dataflow of Sec. 5.3 as one kernel: transformed inputs and channel sums stay in registers, the
+ * workspace holds the transformed kernels only. */
 int conv_winograd(const float* x, const float* w, float* y,
                   int N, int C, int H, int W, int K, int m);
 

@@ -388,6 +388,17 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
     cands = []
     tb_top = -(-tiles // 32) * 32
     Kz = -(-K // 32) * 32          # whole 32-channel blocks; the channels past K are zeros
+    # Thin layers: all (e+2)^2 transformed values of every channel of a sub-domain fit in one lane's
+    # registers, so the fused dataflow of Sec. 5.3 runs as one kernel (256 sub-domains per workgroup, every
+    # output channel, inputs and transformed kernels read once, no temporaries in memory).  It ranks before
+    # every unfused tile.
+    if C <= 4 and n2 * C <= vgpr_budget:
+        nblocks = -(-tiles // 256)
+        qread = nblocks * C * n2 * (256 + Kz)
+        cands.append(((-(1 << 62), qread, 0, 0, Kz, 256),
+                      dict(b=1, x=e * 256, y=e, z=Kz, alpha=C, threads=256, waves_m=1, waves_n=4,
+                           path=PATH_FMA, wt_mode=1, lds_bytes_used=0, acc_regs_per_thread=n2 * C,
+                           q_read_elems=qread, q_write_elems=N * K * P * Q)))
     for tb in range(32, min(tb_top, 1024) + 1, 32):
         for z in divisors(Kz):
             if z % 32:

@@ -211,7 +211,8 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
     g->waves_n = cfg.waves_n;
     const int64_t pitch = (tiles + g->tb - 1) / g->tb * g->tb;
     const int64_t n2 = (int64_t)(m + 2) * (m + 2);
-    if (n2 * g->Cp * pitch >= (1LL << 31) || n2 * g->Kp * pitch >= (1LL << 31)) return IOLB_EINVAL;
+    // V and M of the unfused path are indexed with 32-bit element counts
+    if (cfg.path != IOLB_PATH_FMA && (n2 * g->Cp * pitch >= (1LL << 31) || n2 * g->Kp * pitch >= (1LL << 31))) return IOLB_EINVAL;
     g->tiles = (int)tiles;
     g->tiles_pitch = (int)pitch;
     return IOLB_OK;
@@ -220,14 +221,16 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
 struct WinoWorkspace {
     size_t u_off, v_off, m_off, total;
 };
-WinoWorkspace winograd_layout(int C, int K, int m, int64_t tiles_pitch)
+// fused: the one-kernel path keeps the transformed inputs and the channel sums in registers; the workspace
+// holds U and, in V's place, U again as one row per output channel
+WinoWorkspace winograd_layout(int C, int K, int m, int64_t tiles_pitch, bool fused = false)
 {
     const size_t n2 = (size_t)(m + 2) * (m + 2);
     WinoWorkspace l;
     l.u_off = 0;
     l.v_off = l.u_off + align256(sizeof(float) * n2 * C * K);
-    l.m_off = l.v_off + align256(sizeof(float) * n2 * C * tiles_pitch);
-    l.total = l.m_off + align256(sizeof(float) * n2 * K * tiles_pitch);
+    l.m_off = l.v_off + align256(fused ? sizeof(float) * K * iolb::wino_fused_row(m, C) : sizeof(float) * n2 * C * tiles_pitch);
+    l.total = l.m_off + (fused ? 0 : align256(sizeof(float) * n2 * K * tiles_pitch));
     return l;
 }
 
@@ -260,7 +263,8 @@ int run_winograd(const float* x, const float* w, const float* Upre, float* y, co
     iolb::WinoGeom g{};
     rc = winograd_geom(s, cfg, &g);
     if (rc != IOLB_OK) return rc;
-    const WinoWorkspace l = winograd_layout(g.Cp, g.Kp, g.m, g.tiles_pitch);
+    const bool fused = cfg.path == IOLB_PATH_FMA;
+    const WinoWorkspace l = winograd_layout(g.Cp, g.Kp, g.m, g.tiles_pitch, fused);
     if (!ws || ws_bytes < l.total || (reinterpret_cast<uintptr_t>(ws) & 255)) return IOLB_EWORKSPACE;
     char* base = static_cast<char*>(ws);
     float* U = reinterpret_cast<float*>(base + l.u_off);
@@ -273,6 +277,11 @@ int run_winograd(const float* x, const float* w, const float* Upre, float* y, co
     } else {
         g.CpU = pretransformed_rows(s.C);
         Uuse = Upre;
+    }
+    if (fused) {
+        IOLB_HIP(iolb::launch_wino_fused_relayout(Uuse, V, g, st));
+        IOLB_HIP(iolb::launch_wino_fused(x, V, y, g, st));
+        return IOLB_OK;
     }
     IOLB_HIP(iolb::launch_wino_input_transform(x, V, g, st));
     MainKernelTimer timer(st, IOLB_TIME_WINO_PRODUCT);
@@ -433,7 +442,9 @@ int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H,
     iolb_tile_config tile;
     rc = tuned_tile(s, &tile);
     if (rc != IOLB_OK) return rc;
-    const size_t bytes = conv_winograd_workspace_bytes(N, C, H, W, K, m);
+    // the one-kernel path stores the transformed kernels only
+    const size_t bytes = tile.path == IOLB_PATH_FMA ? winograd_layout(C, (K + 31) / 32 * 32, m, 0, true).total
+                                                    : conv_winograd_workspace_bytes(N, C, H, W, K, m);
     DeviceState* dev = nullptr;
     rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;

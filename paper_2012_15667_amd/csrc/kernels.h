@@ -55,6 +55,12 @@ hipError_t launch_wino_kernel_transform(const float* w, float* U, const WinoGeom
 hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_product(const float* U, const float* V, float* M, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_output_transform(const float* M, float* y, const WinoGeom& g, hipStream_t st);
+// All four steps in one kernel, for C <= 4 with C * (m+2)^2 <= 128 (wino_fused.hip).  Its kernel-side
+// factors are K rows of wino_fused_row(m, C) floats, Uk[k][xi * C + c], which launch_wino_fused_relayout
+// makes from the plane-major U of launch_wino_kernel_transform.
+int wino_fused_row(int m, int C);
+hipError_t launch_wino_fused_relayout(const float* U, float* Uk, const WinoGeom& g, hipStream_t st);
+hipError_t launch_wino_fused(const float* x, const float* Uk, float* y, const WinoGeom& g, hipStream_t st);
 
 // Ceiling probes (probe.hip).  The copy moves bytes / 16 16-byte pieces; the MFMA loop runs
 // PROBE_MFMA_BLOCKS workgroups of four waves, each wave PROBE_ACC MFMAs (4096 flop each) per iteration, and

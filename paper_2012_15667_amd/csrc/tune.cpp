@@ -222,6 +222,25 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
     const int64_t box = kMaxThreads * vgpr_budget;
     const int64_t top = std::min<int64_t>(ceil_div(tiles, 32) * 32, 1024);
     const int Kz = (s.K + 31) / 32 * 32;        // whole 32-channel blocks; the channels past K are zeros
+    // Thin layers: the (m+2)^2 transformed values of all C channels of a sub-domain fit in one lane's
+    // registers, so the four steps run in one kernel (the fused dataflow of Sec. 5.3): a workgroup of 256
+    // lanes covers 256 sub-domains and every output channel, reads its input windows and the transformed
+    // kernels once and writes the outputs -- no temporaries in memory.  Ranked before every unfused tile:
+    // those move (m+2)^2 / m^2 times the output tensor to memory and back.
+    if (s.C <= 4 && planes * s.C <= vgpr_budget) {
+        const int64_t nblocks = ceil_div(tiles, 256);
+        Candidate c{};
+        c.cfg.b = 1; c.cfg.x = (int32_t)(m * 256); c.cfg.y = m; c.cfg.z = Kz;
+        c.cfg.alpha = s.C;
+        c.cfg.threads = 256; c.cfg.waves_m = 1; c.cfg.waves_n = 4;
+        c.cfg.path = IOLB_PATH_FMA; c.cfg.wt_mode = 1;
+        c.cfg.lds_bytes_used = 0;
+        c.cfg.acc_regs_per_thread = (int32_t)(planes * s.C);
+        c.cfg.q_read_elems = nblocks * s.C * planes * (256 + Kz);
+        c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+        c.key = {-(1LL << 62), 0, c.cfg.q_read_elems, 0, 0, Kz, 256, 0, 0, 0};
+        out->push_back(c);
+    }
     const auto fz = factors_of(Kz);
     for (int64_t tb = 32; tb <= top; tb += 32)
         for (int z : fz) {

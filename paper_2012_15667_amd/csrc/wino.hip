@@ -16,73 +16,13 @@
 #include "kernels.h"
 #include "lds_dma.h"
 #include "wino_mats.h"
-
-#include <type_traits>
-#include <utility>
+#include "wino_transform.h"
 
 namespace iolb {
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-// Compile-time loops: the body receives its index as an integral constant, so that a matrix coefficient
-// read with it is a constant expression (a plain unrolled loop leaves the coefficient a run-time value,
-// and every "is it zero / one" test becomes a branch).
-template <class F, int... Is>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-// which constant matrix of Mats<M> a product uses
-struct UseA { template <int M> static constexpr float at(int i, int k) { return Mats<M>::A[i][k]; } };
-struct UseB { template <int M> static constexpr float at(int i, int k) { return Mats<M>::B[i][k]; } };
-struct UseL { template <int M> static constexpr float at(int i, int k) { return Mats<M>::L[i][k]; } };
-
-// s += coef * v with the coefficient known at compile time: zeros vanish, +-1 are an add / subtract
-template <int M, class Sel, int I, int K>
-__device__ __forceinline__ void accumulate(float& s, bool& first, float v)
-{
-    constexpr float coef = Sel::template at<M>(I, K);
-    if constexpr (coef != 0.f) {
-        if (first) s = (coef == 1.f) ? v : (coef == -1.f) ? -v : coef * v;
-        else       s = (coef == 1.f) ? s + v : (coef == -1.f) ? s - v : __builtin_fmaf(coef, v, s);
-        first = false;
-    }
-}
-
-// out[ROWS][COLS] = Mx[ROWS][IN] * in[IN][COLS], Mx = Sel's matrix of Mats<M>
-template <int M, class Sel, int ROWS, int IN, int COLS>
-__device__ __forceinline__ void left_mul(const float (&in)[IN][COLS], float (&out)[ROWS][COLS])
-{
-    static_for<ROWS>([&](auto i) {
-        static_for<COLS>([&](auto j) {
-            float s = 0.f;
-            bool first = true;
-            static_for<IN>([&](auto k) { accumulate<M, Sel, decltype(i)::value, decltype(k)::value>(s, first, in[k][j]); });
-            out[i][j] = s;
-        });
-    });
-}
-// out[ROWS][COLS] = in[ROWS][IN] * Mx[COLS][IN]^T
-template <int M, class Sel, int ROWS, int IN, int COLS>
-__device__ __forceinline__ void right_mul_t(const float (&in)[ROWS][IN], float (&out)[ROWS][COLS])
-{
-    static_for<ROWS>([&](auto i) {
-        static_for<COLS>([&](auto j) {
-            float s = 0.f;
-            bool first = true;
-            static_for<IN>([&](auto k) { accumulate<M, Sel, decltype(j)::value, decltype(k)::value>(s, first, in[i][k]); });
-            out[i][j] = s;
-        });
-    });
-}
 
 // step 1b: one lane per (c, k); k runs fastest so the writes of a wave are contiguous.  U has Cp rows of Kp
 // columns per plane: rows [C, Cp) and columns [K, Kp) are zero.
@@ -125,7 +65,6 @@ input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
     if (t >= g.tiles) return;
     const int tj = t % g.tw, ti = (t / g.tw) % g.th, img = t / (g.tw * g.th);
     const int h0 = ti * M - 1, w0 = tj * M - 1;
-    const float* xp = x + ((size_t)img * g.C + c) * g.H * g.W;
     float d[n][n];
     if constexpr (VEC) {
         typedef float vec __attribute__((ext_vector_type(M)));
@@ -172,12 +111,22 @@ input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
             d[i][n - 1] = row ? right : 0.f;
         }
     } else {
+        // clamped addresses, zeroed afterwards: no branches, the loads of a window are in flight together
+        const float* xc = x + ((size_t)img * g.C + (c < g.C ? c : g.C - 1)) * g.H * g.W;
 #pragma unroll
         for (int i = 0; i < n; ++i)
 #pragma unroll
             for (int j = 0; j < n; ++j) {
                 const int h = h0 + i, ww = w0 + j;
-                d[i][j] = (c < g.C && h >= 0 && h < g.H && ww >= 0 && ww < g.W) ? xp[(size_t)h * g.W + ww] : 0.f;
+                const int hc = h < 0 ? 0 : (h >= g.H ? g.H - 1 : h), wc = ww < 0 ? 0 : (ww >= g.W ? g.W - 1 : ww);
+                d[i][j] = xc[(size_t)hc * g.W + wc];
+            }
+#pragma unroll
+        for (int i = 0; i < n; ++i)
+#pragma unroll
+            for (int j = 0; j < n; ++j) {
+                const int h = h0 + i, ww = w0 + j;
+                if (!(c < g.C && h >= 0 && h < g.H && ww >= 0 && ww < g.W)) d[i][j] = 0.f;
             }
     }
     float tmp[n][n], v[n][n];

@@ -47,6 +47,9 @@ SHAPES = [
     _shape(64, 256, 56, 56, 256, algo=4), _shape(64, 128, 112, 112, 128, algo=3), _shape(8, 64, 28, 28, 64, algo=3),
     _shape(4, 20, 13, 17, 96, algo=4), _shape(1, 16, 14, 14, 16, algo=1), _shape(4, 20, 13, 17, 48, algo=2),
     _shape(2, 16, 13, 13, 80), _shape(2, 64, 7, 7, 1000, 1, 1, 1, 0),
+    # thin Winograd layers: fused one-kernel candidate when C <= 4 and C (m+2)^2 fits the register budget
+    _shape(64, 3, 224, 224, 64, algo=2), _shape(2, 4, 37, 41, 33, algo=1), _shape(2, 4, 14, 14, 32, algo=2),
+    _shape(2, 2, 14, 14, 32, algo=4), _shape(2, 3, 14, 14, 32, algo=4), _shape(1, 1, 9, 9, 5, algo=3),
 ]
 BUDGETS = [(0, 0), (32768, 64), (163840, 128), (8192, 32)]
 

@@ -345,7 +345,43 @@ def test_winograd_caller_workspace_and_tiles(gpu):
         assert rel_err(got, ref) <= TOL_WINO, cfg
 
 
-@pytest.mark.parametrize("name,m", [("cfg5a", 2), ("cfg5b", 4), ("cfg5c", 4), ("cfg5d", 2), ("alex3", 4), ("alex4", 2),
+FUSED_CASES = [
+    # m, N, C, H, W, K: thin layers that run as one fused kernel (C <= 4, C (m+2)^2 <= 128)
+    (2, 2, 1, 8, 8, 5), (2, 2, 3, 37, 41, 33), (2, 1, 4, 7, 9, 64), (2, 3, 2, 16, 16, 7),
+    (3, 2, 1, 9, 9, 5), (3, 2, 4, 37, 41, 33), (3, 1, 3, 14, 14, 6),
+    (4, 2, 1, 8, 8, 5), (4, 2, 3, 37, 41, 33), (4, 1, 2, 13, 13, 7), (4, 2, 3, 16, 16, 64),
+    (6, 2, 1, 12, 12, 5), (6, 2, 2, 37, 41, 33),
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CASES)
+def test_winograd_fused_thin_layers_match_direct_oracle(gpu, case):
+    torch, B = gpu
+    m, N, C, H, W, K = case
+    algo = {2: B.WINO_F2, 3: B.WINO_F3, 4: B.WINO_F4, 6: B.WINO_F6}[m]
+    assert B.iolb_tune(B.make_shape(N, C, H, W, K, algo=algo))["path"] == B.PATH_FMA
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u11", "he", seed=300 + 10 * m + C)
+    ref = conv_ref(x, w, 1, 1)
+    got = _run_wino(gpu, x, w, m)
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL_WINO
+
+
+def test_winograd_thin_layer_unfused_tiles_still_agree(gpu):
+    """A caller may still ask for a matrix-core tile on a thin layer (every other entry of the enumeration)."""
+    torch, B = gpu
+    m, N, C, H, W, K = 4, 2, 3, 20, 24, 40
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=33)
+    ref = conv_ref(x, w, 1, 1)
+    tiles = B.iolb_enumerate(B.make_shape(N, C, H, W, K, algo=B.WINO_F4), 0, 0, False)
+    assert tiles[0]["path"] == B.PATH_FMA and all(t["path"] == B.PATH_MFMA for t in tiles[1:])
+    step = max(1, len(tiles) // 5)
+    for cfg in tiles[::step]:
+        got = _run_wino(gpu, x, w, m, cfg=cfg)
+        assert rel_err(got, ref) <= TOL_WINO, cfg
+
+
+@pytest.mark.parametrize("name,m", [("cfg5a", 4), ("cfg5a", 2), ("cfg5b", 4), ("cfg5c", 4), ("cfg5d", 2), ("alex3", 4), ("alex4", 2),
                                     ("cfg5c", 6), ("cfg5d", 3), ("cfg4", 6), ("alex4", 3)])
 def test_winograd_full_size_sampled(gpu, name, m):
     L = CONFIGS[name]
@@ -358,7 +394,8 @@ def test_winograd_full_size_sampled(gpu, name, m):
     assert np.isfinite(got).all()
 
 
-@pytest.mark.parametrize("m,N,C,H,W,K", [(4, 4, 20, 14, 14, 64), (2, 2, 64, 28, 28, 48), (6, 2, 7, 13, 17, 32)])
+@pytest.mark.parametrize("m,N,C,H,W,K", [(4, 4, 20, 14, 14, 64), (2, 2, 64, 28, 28, 48), (6, 2, 7, 13, 17, 32),
+                                         (4, 2, 3, 14, 18, 40), (2, 2, 4, 9, 9, 33)])     # the last two: fused kernel
 def test_winograd_with_pretransformed_kernels_is_bit_identical(gpu, m, N, C, H, W, K):
     """Kernels transformed once and reused give the bits of the on-the-fly path (same transform kernel,
     same product), for C that is not a multiple of 16 and K that is not a multiple of 32 too."""

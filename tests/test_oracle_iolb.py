@@ -249,3 +249,28 @@ def test_bounds_report():
     assert r["compulsory_elems"] == 32 * 64 * 3136 + 64 * 64 * 9 + 32 * 64 * 3136
     assert r["vertices"] == (2 * 9 * 64 - 1) * 56 * 56 * 64 * 32
     assert isclose(r["q_lower_lead"], 9 * 64 * 3136 * 64 * 32 / (4 * sqrt(2 * 9 * 20480)), rel_tol=1e-12)
+
+
+def test_thin_winograd_layers_get_the_fused_candidate_first():
+    """C <= 4 and C (e+2)^2 <= register budget: the one-kernel dataflow of Sec. 5.3 is a candidate, ranks
+    first, covers every output channel with 256 sub-domains per workgroup and uses no LDS; otherwise every
+    candidate is an unfused matrix-core tile."""
+    for algo, e in o.WINO_E.items():
+        n2 = (e + 2) ** 2
+        for C in range(1, 7):
+            for budget in (128, 64):
+                s = dict(N=2, C=C, H=20, W=24, K=40, R=3, S=3, stride=1, pad=1, algo=algo)
+                cands = o.candidates(s, 0, budget, use_f3=False)
+                fused = [c for _, c in cands if c["path"] == o.PATH_FMA]
+                if C <= 4 and n2 * C <= budget:
+                    assert len(fused) == 1
+                    f = fused[0]
+                    assert o.tune(s, 0, budget) == f
+                    tiles = 2 * -(-20 // e) * -(-24 // e)
+                    assert (f["x"], f["y"], f["z"], f["alpha"], f["threads"]) == (256 * e, e, 64, C, 256)
+                    assert f["lds_bytes_used"] == 0 and f["acc_regs_per_thread"] == n2 * C
+                    assert f["q_read_elems"] == -(-tiles // 256) * C * n2 * (256 + 64)
+                    assert f["q_write_elems"] == 2 * 40 * 20 * 24
+                else:
+                    assert not fused
+                    assert o.tune(s, 0, budget)["path"] == o.PATH_MFMA
