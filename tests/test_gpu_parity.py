@@ -367,6 +367,29 @@ def test_winograd_fused_thin_layers_match_direct_oracle(gpu, case):
     assert rel_err(got, ref) <= TOL_WINO
 
 
+def test_winograd_fused_large_tensor_sampled(gpu):
+    """A 2^29-element output (2 GiB) from the fused kernel: offsets beyond 32 bits of bytes, 2 million
+    sub-domains, output channels split over three groups."""
+    torch, B = gpu
+    N, C, H, W, K = 32, 3, 512, 512, 64
+    rng = np.random.default_rng(78)
+    x = rng.random((N, C, H, W), dtype=np.float32)
+    w = (rng.standard_normal((K, C, 3, 3)) * (2.0 / (9 * C)) ** 0.5).astype(np.float32)
+    for m in (2, 4):
+        y = B.conv_winograd(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), m)
+        torch.cuda.synchronize()
+        idx = sample_output_indices(N, K, H, W, 2048, seed=6)
+        t = torch.from_numpy(idx.astype(np.int64)).cuda()
+        g = y[t[:, 0], t[:, 1], t[:, 2], t[:, 3]].cpu().numpy()
+        assert rel_err(g, conv_ref_points(x, w, idx, 1, 1)) <= TOL_WINO, m
+        tail = y[N - 1, K - 1, H - 1, :].cpu().numpy()
+        tidx = np.array([[N - 1, K - 1, H - 1, q] for q in range(W)], dtype=np.int32)
+        assert rel_err(tail, conv_ref_points(x, w, tidx, 1, 1)) <= TOL_WINO, m
+        assert bool(torch.isfinite(y).all())
+        del y
+    torch.cuda.empty_cache()
+
+
 def test_winograd_thin_layer_unfused_tiles_still_agree(gpu):
     """A caller may still ask for a matrix-core tile on a thin layer (every other entry of the enumeration)."""
     torch, B = gpu
