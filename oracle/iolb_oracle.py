@@ -232,11 +232,12 @@ def _grid_efficiency_pct(nblocks):
     return min((100 * nblocks) // (rounds * N_CU), EFF_CAP)
 
 
-def _pick_alpha(C, choices, per_alpha_bytes, lds_bytes):
-    """Channels per stage: least channel padding first, then the deepest stage that fits."""
+def _pick_alpha(C, choices, per_alpha_bytes, lds_bytes, buffers=1):
+    """Channels per stage: least channel padding first, then the deepest stage that fits.  per_alpha_bytes
+    covers `buffers` stage buffers; a stage that holds all C channels is the only one and needs one."""
     best = None
     for a in choices:
-        if per_alpha_bytes * a > lds_bytes:
+        if per_alpha_bytes * a // (buffers if a >= C else 1) > lds_bytes:
             continue
         padded = -(-C // a) * a
         key = (padded, -a)
@@ -337,12 +338,12 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                         if grids:
                             _, T0, _, _, _, acc0 = min(grids)
                             budget = lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0)
-                            alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), budget)
+                            alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), budget, 2)
                             # a stage too large for half the LDS (large kernels) may take all of it, provided the
                             # smallest weight slab (4 channels of 32 kernels, two buffers) leaves half to the tile
                             if alpha is None and not lds_bytes and 8 * 4 * R * S * 32 <= LDS_CU // 2:
-                                alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), LDS_CU)
-                        lds_mult = 8
+                                alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), LDS_CU, 2)
+                        lds_mult = 4 if alpha is not None and alpha >= C else 8      # one stage only: one buffer
                     else:
                         if npix > 256:
                             continue
@@ -409,7 +410,7 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
             if not grids:
                 continue
             _, T0, _, _, _, acc0 = min(grids)
-            alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0))
+            alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0), 2)
             if alpha is None:
                 continue
             nblocks = n2 * (-(-tiles // tb)) * (Kz // z)
@@ -418,7 +419,7 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
             key = (-_grid_efficiency_pct(nblocks), qread, abs(tb - z), -tb * z, z, T)
             cands.append((key, dict(b=1, x=e * tb, y=e, z=z, alpha=alpha, threads=T, waves_m=wm,
                                     waves_n=wn, path=PATH_MFMA, wt_mode=1,
-                                    lds_bytes_used=8 * alpha * (tb + z), acc_regs_per_thread=acc,
+                                    lds_bytes_used=(4 if alpha >= C else 8) * alpha * (tb + z), acc_regs_per_thread=acc,
                                     q_read_elems=qread, q_write_elems=N * K * P * Q)))
     return cands
 
@@ -432,8 +433,13 @@ def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True):
         return []
     if s["algo"] == DIRECT:
         c = _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_MFMA, use_f3)
-        if not c:
-            c = _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
+        # the FMA path: when no matrix-core tile fits, and when the best of them is modelled more than four
+        # times slower than a quarter of the vector FMA rate (8192 flop per cycle) plus the model's start-up
+        # constant -- very large kernels whose weight slab leaves the LDS room for a few pixels only.  FMA
+        # tiles carry no modelled time: their keys start below zero and sort first.
+        flop = 2 * s["N"] * s["K"] * P * Q * s["C"] * s["R"] * s["S"]
+        if not c or min(k[0] for k, _ in c) > 4 * (15000 + flop // 8192):
+            c = c + _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
         return c
     e = WINO_E[s["algo"]]
     return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3)

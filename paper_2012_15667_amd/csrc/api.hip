@@ -139,7 +139,9 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
         if (cfg.alpha >= 1 && cfg.alpha <= c.cfg.alpha && (cfg.path == IOLB_PATH_FMA || cfg.alpha % 4 == 0) &&
             c.cfg.alpha % cfg.alpha == 0) {
             probe.alpha = cfg.alpha;
-            probe.lds_bytes_used = (int32_t)((int64_t)c.cfg.lds_bytes_used / c.cfg.alpha * cfg.alpha);
+            // a single-stage tile counts one buffer, a shallower (multi-stage) depth two
+            const int64_t buffers = cfg.path == IOLB_PATH_MFMA && c.cfg.alpha >= s.C && cfg.alpha < s.C ? 2 : 1;
+            probe.lds_bytes_used = (int32_t)((int64_t)c.cfg.lds_bytes_used / c.cfg.alpha * cfg.alpha * buffers);
         }
         if (same_config(probe, cfg)) {
             std::lock_guard<std::mutex> lock(g_mutex);

@@ -45,7 +45,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // chunks of 64 input-tile elements whose load offsets a wave keeps in registers (flat staging)
 constexpr int FLAT_CHUNKS = 8;
 template <int MBW, int NBW, int LB, int RR, int SS, bool HWC, bool EVEN>
-__global__ void __launch_bounds__(LB)
+__global__ void __launch_bounds__(LB, LB <= 256 ? 2 : 1)
 direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y, DirectGeom g)
 {
     extern __shared__ float lds[];
@@ -380,7 +380,7 @@ hipError_t launch_direct_mfma_layout(const float* x, const float* wt, float* y, 
     const int mbw = MB / g.waves_m, nbw = (NB + g.waves_n - 1) / g.waves_n;
     const bool even = NB % g.waves_n == 0;                   // every wave column owns nbw blocks
     const size_t stage = ((size_t)g.alpha * ((size_t)g.R * g.S * g.z + g.halo) + 3) & ~(size_t)3;
-    const size_t shm = 2 * stage * sizeof(float);
+    const size_t shm = (g.C <= g.alpha ? 1 : 2) * stage * sizeof(float);      // a single stage needs one buffer
     if (shm > 160 * 1024) return hipErrorInvalidValue;
     // the register file of a compute unit holds 131072 lane-registers: a workgroup of T threads gets
     // 131072 / T per lane, of which 16 * mbw * nbw are partial sums

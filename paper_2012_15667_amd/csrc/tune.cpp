@@ -50,12 +50,14 @@ int64_t grid_efficiency(int64_t nblocks) {
 }
 
 // Channels per stage: least zero-padding of C first, then the deepest stage that fits the LDS.
-int choose_alpha(int C, const int* choices, int nchoices, int64_t bytes_per_channel, int64_t lds_bytes) {
+// bytes_per_channel covers `buffers` stage buffers; a stage that holds all C channels is the only one and
+// needs a single buffer.
+int choose_alpha(int C, const int* choices, int nchoices, int64_t bytes_per_channel, int64_t lds_bytes, int buffers = 1) {
     int best = 0;
     int64_t best_padded = 0;
     for (int i = 0; i < nchoices; ++i) {
         const int a = choices[i];
-        if (bytes_per_channel * a > lds_bytes) continue;
+        if (bytes_per_channel * a / (a >= C ? buffers : 1) > lds_bytes) continue;
         const int64_t padded = ceil_div(C, a) * a;
         if (best == 0 || padded < best_padded || (padded == best_padded && a > best)) {
             best = a;
@@ -162,12 +164,12 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                         if (z % 32) continue;
                         if (!best_wave_grid(z / 32, (int)((npix + 31) / 32), vgpr_budget, false, &g)) continue;
                         alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage,
-                                             lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
+                                             lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc), 2);
                         // automatic budget: a stage too large for half the LDS (large kernels) may take all of it,
                         // as long as the smallest weight slab (4 channels, 32 kernels) leaves half to the input tile
                         if (alpha == 0 && !lds_bytes && 8 * 4 * RS * 32 <= kLdsPerCu / 2)
-                            alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage, kLdsPerCu);
-                        lds_mult = 8;
+                            alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage, kLdsPerCu, 2);
+                        lds_mult = alpha >= s.C ? 4 : 8;            // one stage only: one buffer
                     } else {
                         if (npix > 256) continue;
                         const int lanes = std::max(pow2_at_least((int)npix), 16);
@@ -249,7 +251,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             WaveGrid g{};
             if (!best_wave_grid(z / 32, (int)(tb / 32), vgpr_budget, true, &g)) continue;    // tb is free: no idle blocks
             const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z),
-                                           lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc));
+                                           lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc), 2);
             if (alpha == 0) continue;
             const int64_t nblocks = planes * ceil_div(tiles, tb) * (Kz / z);
             Candidate c{};
@@ -257,7 +259,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             c.cfg.alpha = alpha;
             c.cfg.threads = g.threads; c.cfg.waves_m = g.wm; c.cfg.waves_n = g.wn;
             c.cfg.path = IOLB_PATH_MFMA; c.cfg.wt_mode = 1;
-            c.cfg.lds_bytes_used = (int32_t)(8 * alpha * (tb + z));
+            c.cfg.lds_bytes_used = (int32_t)((alpha >= s.C ? 4 : 8) * alpha * (tb + z));     // one stage only: one buffer
             c.cfg.acc_regs_per_thread = g.acc;
             c.cfg.q_read_elems = nblocks * s.C * (tb + z);
             c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
@@ -314,7 +316,20 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
     out->clear();
     if (s.algo == IOLB_DIRECT) {
         direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_MFMA, use_box, out);
-        if (out->empty()) direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_FMA, use_box, out);
+        // The plain-FMA path serves when no matrix-core tile fits, and also when the best one is modelled
+        // more than four times slower than a quarter of the vector FMA rate (8192 flop per cycle, plus the
+        // start-up constant of the model) would be: very large kernels, whose weight slab leaves the LDS
+        // room for a few pixels only (an 11 x 11, stride-4 first layer measures 0.59 ms on its best
+        // matrix-core tile and 0.27 ms on the FMA path; no other measured layer comes near the threshold).
+        // FMA tiles carry no modelled time; their keys start below zero and sort first.
+        bool fma = out->empty();
+        if (!fma) {
+            int64_t best = out->front().key[0];
+            for (const auto& c : *out) best = std::min(best, c.key[0]);
+            const int64_t flop = 2LL * s.N * s.K * P * Q * s.C * s.R * s.S;
+            fma = best > 4 * (15000 + flop / 8192);
+        }
+        if (fma) direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_FMA, use_box, out);
     } else {
         winograd_candidates(s, P, Q, winograd_m(s.algo), lds_bytes, vgpr_budget, use_box, out);
     }

@@ -187,7 +187,7 @@ output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g
 // 16-byte LDS-direct loads; two buffers alternate.  Lane halves feed the two k-slices of an MFMA with
 // channels c2 and c2 + alpha/2.
 template <int MBW, int NBW, int LB, bool DEEP>
-__global__ void __launch_bounds__(LB)
+__global__ void __launch_bounds__(LB, LB <= 256 ? 2 : 1)
 wino_product_kernel(const float* __restrict__ U, const float* __restrict__ V, float* __restrict__ Mp, WinoGeom g)
 {
     extern __shared__ float lds[];
@@ -414,7 +414,7 @@ hipError_t launch_wino_product(const float* U, const float* V, float* Mp, const 
     const int mbw = MB / g.waves_m, nbw = NB / g.waves_n;
     const int threads = 64 * g.waves_m * g.waves_n;
     if (threads > 1024 || 16 * mbw * nbw + 64 > 131072 / threads) return hipErrorInvalidValue;
-    const size_t shm = 2 * sizeof(float) * (size_t)g.alpha * (g.z + g.tb);
+    const size_t shm = (g.C <= g.alpha ? 1 : 2) * sizeof(float) * (size_t)g.alpha * (g.z + g.tb);   // a single stage needs one buffer
     if (shm > 160 * 1024) return hipErrorInvalidValue;
     const int n = g.m + 2;
     const long long grid_ll = (long long)n * n * (g.Kp / g.z) * (g.tiles_pitch / g.tb);

@@ -54,6 +54,7 @@ DIRECT_CASES = [
     (8, 32, 28, 28, 96, 3, 3, 1, 1),       # 7 | extents, K = 3 * 32
     (3, 7, 9, 11, 6, 3, 3, 1, 1),          # ragged everything, K = 6
     (2, 3, 35, 35, 32, 11, 11, 4, 0),      # down-scaled AlexNet conv1: stride 4, no padding
+    (4, 3, 112, 112, 64, 7, 7, 2, 3),      # ResNet-style first layer: C <= alpha, one stage in a single LDS buffer
     (2, 12, 27, 27, 64, 5, 5, 1, 2),       # conv2-like: 5x5, pad 2
     (4, 16, 13, 13, 64, 3, 3, 1, 1),       # conv3/4 extent 13 (prime)
     (4, 16, 32, 32, 64, 1, 1, 1, 0),       # 1x1: a plain GEMM

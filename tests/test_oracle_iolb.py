@@ -128,7 +128,8 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
         assert cfg["q_read_elems"] == blocks * s["C"] * per_stage
         if cfg["path"] == o.PATH_MFMA:
             assert z % 32 == 0 and a % 4 == 0
-            assert cfg["lds_bytes_used"] == 2 * 4 * a * per_stage
+            buffers = 1 if a >= s["C"] else 2                             # one stage only: one buffer
+            assert cfg["lds_bytes_used"] == buffers * 4 * a * per_stage
             padded = -(-(b * x * y) // 32) * 32
             assert padded * z <= cfg["acc_regs_per_thread"] * T           # every output has a register
             assert cfg["acc_regs_per_thread"] * T < (padded + 32 * 8 * cfg["waves_n"]) * z
@@ -140,7 +141,7 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
         assert b == 1 and y == e and x % (32 * e) == 0 and z % 32 == 0
         tb = x // e
         assert tb * z == cfg["acc_regs_per_thread"] * T
-        assert cfg["lds_bytes_used"] == 8 * a * (tb + z)
+        assert cfg["lds_bytes_used"] == (4 if a >= s["C"] else 8) * a * (tb + z)     # one stage only: one buffer
     assert cfg["q_write_elems"] == s["N"] * s["K"] * P * Q
 
 
@@ -274,3 +275,22 @@ def test_thin_winograd_layers_get_the_fused_candidate_first():
                 else:
                     assert not fused
                     assert o.tune(s, 0, budget)["path"] == o.PATH_MFMA
+
+
+def test_single_stage_tiles_count_one_buffer_and_large_kernels_fall_back_to_fma():
+    """A layer whose channels fit one stage (C <= alpha) keeps a single LDS buffer, which admits tiles twice
+    as large (7x7 stride-2 first layer: more than 80 KB in one buffer, eight waves).  An 11x11 stride-4 first
+    layer, whose weight slab leaves room for 25 pixels only, is handed to the FMA path."""
+    s = shape(64, 3, 224, 224, 64, 7, 7, 2, 3)
+    t = o.tune(s)
+    halo = t["b"] * ((t["x"] - 1) * 2 + 7) * ((t["y"] - 1) * 2 + 7)
+    assert t["path"] == o.PATH_MFMA and t["alpha"] == 4 and t["threads"] == 512
+    assert t["lds_bytes_used"] == 4 * 4 * (halo + 49 * t["z"]) and 81920 < t["lds_bytes_used"] <= o.LDS_CU
+    a = o.tune(shape(16, 3, 227, 227, 96, 11, 11, 4, 0))
+    assert a["path"] == o.PATH_FMA
+    # with more channels than a stage holds the same 7x7 layer needs both buffers again
+    t2 = o.tune(shape(64, 8, 224, 224, 64, 7, 7, 2, 3))
+    halo2 = t2["b"] * ((t2["x"] - 1) * 2 + 7) * ((t2["y"] - 1) * 2 + 7)
+    assert t2["alpha"] < 8 or t2["lds_bytes_used"] == 4 * t2["alpha"] * (halo2 + 49 * t2["z"])
+    if t2["alpha"] < 8:
+        assert t2["lds_bytes_used"] == 8 * t2["alpha"] * (halo2 + 49 * t2["z"])
