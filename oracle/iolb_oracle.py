@@ -233,11 +233,14 @@ def _grid_efficiency_pct(nblocks):
 
 
 def _pick_alpha(C, choices, per_alpha_bytes, lds_bytes, buffers=1):
-    """Channels per stage: least channel padding first, then the deepest stage that fits.  per_alpha_bytes
+    """Channels per stage: least channel padding first, then the deepest stage that fits (stages of 32 or 64
+    channels, which help 1x1 kernels whose stages are short, only where at least four stages remain).  per_alpha_bytes
     covers `buffers` stage buffers; a stage that holds all C channels is the only one and needs one."""
     best = None
     for a in choices:
         if per_alpha_bytes * a // (buffers if a >= C else 1) > lds_bytes:
+            continue
+        if a > 16 and -(-C // a) < 4:          # deep stages only where four or more remain to pipeline
             continue
         padded = -(-C // a) * a
         key = (padded, -a)
@@ -281,8 +284,10 @@ def mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, q_read, q_write):
     its operand reads (32 cycles each) and its share of the stage's load instructions (300 cycles each).
     Waves of the workgroup that share a SIMD hide that behind each other's matrix work; a barrier costs
     100 cycles per wave; a workgroup pays 15000 cycles to start and 200 per accumulator register to store.
-    Workgroups run one per compute unit in rounds over the 256 compute units.  The result cannot beat the
-    time the reading and writing volumes need at 4000 / 1500 bytes per cycle.  The constants come from
+    Workgroups run one per compute unit (several, if they have at most four waves) in rounds over the 256
+    compute units.  The result cannot beat the
+    time the reading and writing volumes need at 4000 / 1500 bytes per cycle (a tile row counts at least one
+    128-byte request).  The constants come from
     tile sweeps on an MI355X; everything is integer arithmetic."""
     RS = s["R"] * s["S"]
     waves = T // 64
@@ -299,11 +304,24 @@ def mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, q_read, q_write):
     steps = (alpha // 2) * RS
     mfma = steps * mbw * nbw * 64
     own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w)
-    sharing = _cdiv(waves, 4)
-    stage = (max(mfma * sharing, own) if sharing > 1 else own) + 100 * waves
+    # Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as
+    # many as the LDS holds (a single stage needs one buffer) and the registers hold (512 per SIMD lane,
+    # acc + 64 per wave), at most 8 (2 for four-wave workgroups), and no more than the layer has per compute
+    # unit.  Waves of different workgroups overlap a little less well than those of one (+10 % on the shared
+    # matrix-core time).  Larger workgroups are modelled one per compute unit.
+    resident = 1
+    if waves <= 4:
+        lds_used = (4 if alpha >= s["C"] else 8) * alpha * (halo + RS * z)
+        resident = max(1, min(LDS_CU // lds_used, 4 * (512 // (acc + 64)) // waves, 2 if waves == 4 else 8,
+                              _cdiv(nblocks, N_CU)))
+    sharing = _cdiv(resident * waves, 4)                    # waves per SIMD
+    shared = mfma * sharing * 11 // 10 if resident > 1 else mfma * sharing
+    stage = (max(shared, own) if sharing > 1 else own) + 100 * waves
     workgroup = _cdiv(s["C"], alpha) * stage + 15000 + 200 * acc
-    compute = _cdiv(nblocks, N_CU) * workgroup
-    memory = (4 * q_read) // 4000 + (4 * q_write) // 1500
+    compute = _cdiv(nblocks, N_CU * resident) * workgroup
+    in_bytes = nblocks * s["C"] * b * yp * max(4 * xp, 128)     # a short tile row still costs a 128-byte request
+    w_bytes = 4 * (q_read - nblocks * s["C"] * halo)
+    memory = (in_bytes + w_bytes) // 4000 + (4 * q_write) // 1500
     return max(compute, memory)
 
 
@@ -338,11 +356,11 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                         if grids:
                             _, T0, _, _, _, acc0 = min(grids)
                             budget = lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0)
-                            alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), budget, 2)
+                            alpha = _pick_alpha(C, (64, 32, 16, 8, 4), 8 * (halo + R * S * z), budget, 2)
                             # a stage too large for half the LDS (large kernels) may take all of it, provided the
                             # smallest weight slab (4 channels of 32 kernels, two buffers) leaves half to the tile
                             if alpha is None and not lds_bytes and 8 * 4 * R * S * 32 <= LDS_CU // 2:
-                                alpha = _pick_alpha(C, (16, 8, 4), 8 * (halo + R * S * z), LDS_CU, 2)
+                                alpha = _pick_alpha(C, (64, 32, 16, 8, 4), 8 * (halo + R * S * z), LDS_CU, 2)
                         lds_mult = 4 if alpha is not None and alpha >= C else 8      # one stage only: one buffer
                     else:
                         if npix > 256:
@@ -433,12 +451,10 @@ def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True):
         return []
     if s["algo"] == DIRECT:
         c = _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_MFMA, use_f3)
-        # the FMA path: when no matrix-core tile fits, and when the best of them is modelled more than four
-        # times slower than a quarter of the vector FMA rate (8192 flop per cycle) plus the model's start-up
-        # constant -- very large kernels whose weight slab leaves the LDS room for a few pixels only.  FMA
-        # tiles carry no modelled time: their keys start below zero and sort first.
-        flop = 2 * s["N"] * s["K"] * P * Q * s["C"] * s["R"] * s["S"]
-        if not c or min(k[0] for k, _ in c) > 4 * (15000 + flop // 8192):
+        # the FMA path: when no matrix-core tile fits, and when none of them covers two blocks of 32 pixels --
+        # very large kernels whose weight slab leaves the LDS room for a few pixels only.  FMA tiles carry no
+        # modelled time: their keys start below zero and sort first.
+        if max([t["b"] * t["x"] * t["y"] for _, t in c], default=0) < 64:
             c = c + _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
         return c
     e = WINO_E[s["algo"]]

@@ -58,6 +58,7 @@ int choose_alpha(int C, const int* choices, int nchoices, int64_t bytes_per_chan
     for (int i = 0; i < nchoices; ++i) {
         const int a = choices[i];
         if (bytes_per_channel * a / (a >= C ? buffers : 1) > lds_bytes) continue;
+        if (a > 16 && ceil_div(C, a) < 4) continue;      // deep stages only where four or more remain to pipeline
         const int64_t padded = ceil_div(C, a) * a;
         if (best == 0 || padded < best_padded || (padded == best_padded && a > best)) {
             best = a;
@@ -106,7 +107,7 @@ bool best_wave_grid(int MB, int NB, int vgpr_budget, bool exact_only, WaveGrid* 
 // cycles and also issues its operand reads (32 cycles each) and its share of the stage's load instructions
 // (300 cycles each: a load rewrites the LDS base register and waits for the previous one); the waves of a
 // workgroup that share a SIMD overlap these with each other's matrix work; workgroups run one per compute
-// unit in rounds; the result cannot beat the time the reading and writing volumes need.  The constants were
+// unit (several, if they have at most four waves) in rounds; the result cannot beat the time the reading and writing volumes need.  The constants were
 // fitted to tile sweeps on an MI355X.  Integers only, so that both implementations of the tuner agree bit
 // for bit.
 int64_t mfma_tile_cost(const iolb_shape& s, int b, int x, int y, int z, int alpha, const WaveGrid& g,
@@ -124,11 +125,26 @@ int64_t mfma_tile_cost(const iolb_shape& s, int b, int x, int y, int z, int alph
     const int64_t steps = (alpha / 2) * RS;                      // MFMA steps of a stage (two channels each)
     const int64_t mfma = steps * mbw * nbw * 64;                 // cycles one wave's stage keeps the matrix core busy
     const int64_t own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w);
-    const int64_t sharing = ceil_div(waves, 4);                  // waves of the workgroup per SIMD
-    const int64_t stage = (sharing > 1 ? std::max(mfma * sharing, own) : own) + 100 * waves;   // + barrier
+    // Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as many
+    // as the LDS holds (a single stage needs one buffer) and the registers hold (512 per SIMD lane, acc + 64 per
+    // wave), at most 8 (2 for four-wave workgroups), and no more than the layer has per compute unit.  Waves of
+    // different workgroups overlap a little less well than those of one (+10 % on the shared matrix-core time).
+    // Larger workgroups are modelled one per compute unit.
+    int64_t resident = 1;
+    if (waves <= 4) {
+        const int64_t lds_used = (alpha >= s.C ? 4 : 8) * alpha * (halo + RS * z);
+        resident = std::max<int64_t>(1, std::min({kLdsPerCu / lds_used, 4 * (512 / ((int64_t)g.acc + 64)) / waves,
+                                                  (int64_t)(waves == 4 ? 2 : 8), ceil_div(nblocks, kComputeUnits)}));
+    }
+    const int64_t sharing = ceil_div(resident * waves, 4);       // waves per SIMD
+    const int64_t shared = resident > 1 ? mfma * sharing * 11 / 10 : mfma * sharing;
+    const int64_t stage = (sharing > 1 ? std::max(shared, own) : own) + 100 * waves;           // + barrier
     const int64_t workgroup = ceil_div(s.C, alpha) * stage + 15000 + 200 * (int64_t)g.acc;     // + start-up, stores
-    const int64_t compute = ceil_div(nblocks, kComputeUnits) * workgroup;
-    const int64_t memory = (4 * q_read) / 4000 + (4 * q_write) / 1500;    // bytes over bytes per cycle
+    const int64_t compute = ceil_div(nblocks, kComputeUnits * resident) * workgroup;
+    // bytes over bytes per cycle; a tile row shorter than 128 bytes still costs a whole 128-byte request
+    const int64_t in_bytes = nblocks * s.C * b * yh * std::max<int64_t>(4 * xh, 128);
+    const int64_t w_bytes = 4 * (q_read - nblocks * s.C * halo);
+    const int64_t memory = (in_bytes + w_bytes) / 4000 + (4 * q_write) / 1500;
     return std::max(compute, memory);
 }
 
@@ -140,7 +156,7 @@ int pow2_at_least(int v) {
 
 void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int vgpr_budget, int path,
                        bool use_box, std::vector<Candidate>* out) {
-    static const int alphas_mfma[] = {16, 8, 4};       // whole channel quads: two per lane half
+    static const int alphas_mfma[] = {64, 32, 16, 8, 4};       // whole channel quads: two per lane half
     static const int alphas_fma[] = {16, 8, 4, 2, 1};
     const int64_t box = kMaxThreads * vgpr_budget;
     const int64_t RS = (int64_t)s.R * s.S, st2 = (int64_t)s.stride * s.stride;
@@ -163,12 +179,12 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                     if (path == IOLB_PATH_MFMA) {
                         if (z % 32) continue;
                         if (!best_wave_grid(z / 32, (int)((npix + 31) / 32), vgpr_budget, false, &g)) continue;
-                        alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage,
+                        alpha = choose_alpha(s.C, alphas_mfma, 5, 8 * per_stage,
                                              lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc), 2);
                         // automatic budget: a stage too large for half the LDS (large kernels) may take all of it,
                         // as long as the smallest weight slab (4 channels, 32 kernels) leaves half to the input tile
                         if (alpha == 0 && !lds_bytes && 8 * 4 * RS * 32 <= kLdsPerCu / 2)
-                            alpha = choose_alpha(s.C, alphas_mfma, 3, 8 * per_stage, kLdsPerCu, 2);
+                            alpha = choose_alpha(s.C, alphas_mfma, 5, 8 * per_stage, kLdsPerCu, 2);
                         lds_mult = alpha >= s.C ? 4 : 8;            // one stage only: one buffer
                     } else {
                         if (npix > 256) continue;
@@ -316,19 +332,14 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
     out->clear();
     if (s.algo == IOLB_DIRECT) {
         direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_MFMA, use_box, out);
-        // The plain-FMA path serves when no matrix-core tile fits, and also when the best one is modelled
-        // more than four times slower than a quarter of the vector FMA rate (8192 flop per cycle, plus the
-        // start-up constant of the model) would be: very large kernels, whose weight slab leaves the LDS
-        // room for a few pixels only (an 11 x 11, stride-4 first layer measures 0.59 ms on its best
-        // matrix-core tile and 0.27 ms on the FMA path; no other measured layer comes near the threshold).
-        // FMA tiles carry no modelled time; their keys start below zero and sort first.
-        bool fma = out->empty();
-        if (!fma) {
-            int64_t best = out->front().key[0];
-            for (const auto& c : *out) best = std::min(best, c.key[0]);
-            const int64_t flop = 2LL * s.N * s.K * P * Q * s.C * s.R * s.S;
-            fma = best > 4 * (15000 + flop / 8192);
-        }
+        // The plain-FMA path serves when no matrix-core tile fits, and also when none of them covers two
+        // blocks of 32 pixels: very large kernels, whose weight slab leaves the LDS room for a few pixels only
+        // (an 11 x 11, stride-4 first layer: at most 25 pixels per tile; 0.59 ms on the best matrix-core tile,
+        // 0.27 ms on the FMA path).  FMA tiles carry no modelled time; their keys start below zero and sort
+        // first.
+        int64_t most_pixels = 0;
+        for (const auto& c : *out) most_pixels = std::max<int64_t>(most_pixels, (int64_t)c.cfg.b * c.cfg.x * c.cfg.y);
+        const bool fma = most_pixels < 64;
         if (fma) direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_FMA, use_box, out);
     } else {
         winograd_candidates(s, P, Q, winograd_m(s.algo), lds_bytes, vgpr_budget, use_box, out);
