@@ -32,16 +32,24 @@ def features(cfg):
                                                             float(cfg.get("layout", 0))]
 
 
-def with_stage_depths(tiles, min_alpha=4):
-    """Each tile also with every shallower stage depth alpha/2, alpha/4, ... >= min_alpha."""
+def stage_depth_variant(t, a, C=None):
+    """Tile t with the shallower stage depth a.  On the matrix-core path a tile whose single stage holds all
+    C channels counts one LDS buffer; with a < C there are several stages and two buffers."""
+    v = dict(t)
+    buffers = 2 if C is not None and t["path"] == 1 and t["alpha"] >= C > a else 1
+    v["lds_bytes_used"] = t["lds_bytes_used"] // t["alpha"] * a * buffers
+    v["alpha"] = a
+    return v
+
+
+def with_stage_depths(tiles, min_alpha=4, C=None):
+    """Each tile also with every shallower stage depth alpha/2, alpha/4, ... >= min_alpha (C: the layer's
+    input channels, needed for the LDS figure of single-stage tiles)."""
     out = []
     for t in tiles:
         a = t["alpha"]
         while a >= min_alpha:
-            v = dict(t)
-            v["lds_bytes_used"] = t["lds_bytes_used"] // t["alpha"] * a
-            v["alpha"] = a
-            out.append(v)
+            out.append(stage_depth_variant(t, a, C))
             a //= 2
     return out
 
@@ -197,17 +205,17 @@ def autotune(dom, measure, n_s=8, patience=4, max_iterations=40, seed=0, seeds=(
 def gpu_domain_and_measure(layer_name, algo, use_box=True, reps=3, layouts=False):
     import torch
     from . import binding as B
-    from .inputs import CONFIGS, layer_inputs
-    from .sweep import time_call
+    from .inputs import layer_inputs
+    from .sweep import parse_layer, time_call
 
-    L = CONFIGS[layer_name]
+    L = parse_layer(layer_name)          # a configured name or N,C,H,W,K,R,S,stride,pad
     x, w = layer_inputs(L)
     xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
     algo_id = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino3": B.WINO_F3, "wino4": B.WINO_F4, "wino6": B.WINO_F6}[algo]
     shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
     pick = B.iolb_tune(shape)
     tiles = B.iolb_enumerate(shape, 163840, 0, use_box)
-    dom = with_stage_depths(tiles, 4 if tiles and tiles[0]["path"] == B.PATH_MFMA else 1)
+    dom = with_stage_depths(tiles, 4 if tiles and tiles[0]["path"] == B.PATH_MFMA else 1, L.C)
     P = (L.H + 2 * L.pad - L.R) // L.stride + 1
     Q = (L.W + 2 * L.pad - L.S) // L.stride + 1
     y = torch.empty((L.N, L.K, P, Q), dtype=torch.float32, device="cuda")
@@ -248,7 +256,7 @@ def main():
     a = ap.parse_args()
     from . import binding as B
     shape, pick, dom, measure = gpu_domain_and_measure(a.layer, a.algo, not a.no_box, layouts=a.layouts)
-    full = with_stage_depths(B.iolb_enumerate(shape, 163840, 0, False), 4 if dom and dom[0]["path"] == 1 else 1)
+    full = with_stage_depths(B.iolb_enumerate(shape, 163840, 0, False), 4 if dom and dom[0]["path"] == 1 else 1, shape.C)
     seeds = [c for c in dom if all(c[k] == pick[k] for k in ("b", "x", "y", "z", "alpha"))]
     best, best_ms, history = autotune(dom, measure, a.n_s, a.patience, seed=a.seed, seeds=seeds)
     pick_ms = measure(pick) if not seeds else measure(seeds[0])

@@ -59,14 +59,12 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
     if pick not in tiles:
         tiles.insert(0, pick)
     if vary_alpha:
+        from .autotune import stage_depth_variant
         extra = []
         for t in tiles:
             a = t["alpha"] // 2
             while a >= 4:
-                v = dict(t)
-                v["lds_bytes_used"] = t["lds_bytes_used"] // t["alpha"] * a
-                v["alpha"] = a
-                extra.append(v)
+                extra.append(stage_depth_variant(t, a, L.C))
                 a //= 2
         tiles = tiles + extra
     P = (L.H + 2 * L.pad - L.R) // L.stride + 1

@@ -198,12 +198,20 @@ def test_direct_shallower_stages_agree(gpu):
     ref = conv_ref(x, w, 1, 1)
     tile = B.iolb_enumerate(B.make_shape(N, C, H, W, K), 163840, 0, False)[0]
     assert tile["path"] == B.PATH_MFMA
+    from paper_2012_15667_amd.autotune import stage_depth_variant
     a = tile["alpha"]
     while a >= 4:
-        cfg = dict(tile, alpha=a, lds_bytes_used=tile["lds_bytes_used"] // tile["alpha"] * a)
-        got = _run_direct(gpu, x, w, 1, 1, cfg=cfg)
+        got = _run_direct(gpu, x, w, 1, 1, cfg=stage_depth_variant(tile, a, C))
         assert rel_err(got, ref) <= TOL_DIRECT, a
         a //= 2
+    # C = 16 fits one stage of 16 channels (a single LDS buffer); stages of 8 and 4 need both buffers
+    x, w = make_inputs(N, 16, H, W, K, 3, 3, "u01", "he", seed=7)
+    ref = conv_ref(x, w, 1, 1)
+    tile = B.iolb_enumerate(B.make_shape(N, 16, H, W, K), 163840, 0, False)[0]
+    assert tile["alpha"] == 16
+    for a in (16, 8, 4):
+        got = _run_direct(gpu, x, w, 1, 1, cfg=stage_depth_variant(tile, a, 16))
+        assert rel_err(got, ref) <= TOL_DIRECT, a
 
 
 # ---------------------------------------------------------------------------------------------
