@@ -306,13 +306,13 @@ def mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, q_read, q_write):
     own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w)
     # Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as
     # many as the LDS holds (a single stage needs one buffer) and the registers hold (512 per SIMD lane,
-    # acc + 64 per wave), at most 8 (2 for four-wave workgroups), and no more than the layer has per compute
+    # acc + 64 per wave), at most 4 one-wave or 2 larger workgroups, and no more than the layer has per compute
     # unit.  Waves of different workgroups overlap a little less well than those of one (+10 % on the shared
     # matrix-core time).  Larger workgroups are modelled one per compute unit.
     resident = 1
     if waves <= 4:
         lds_used = (4 if alpha >= s["C"] else 8) * alpha * (halo + RS * z)
-        resident = max(1, min(LDS_CU // lds_used, 4 * (512 // (acc + 64)) // waves, 2 if waves == 4 else 8,
+        resident = max(1, min(LDS_CU // lds_used, 4 * (512 // (acc + 64)) // waves, 4 if waves == 1 else 2,
                               _cdiv(nblocks, N_CU)))
     sharing = _cdiv(resident * waves, 4)                    # waves per SIMD
     shared = mfma * sharing * 11 // 10 if resident > 1 else mfma * sharing
@@ -332,6 +332,16 @@ def _pow2ceil(v):
     return p
 
 
+def tile_extents(n, path):
+    """Tile extents along an output axis of n pixels: the factors of n (Table 1) and, on the matrix-core path,
+    the balanced cuts ceil(n / k) into k = 1..8 tiles, whose last tile hangs over the edge (its pixels past
+    the image are computed on zeros and not stored) -- extents like 35, 55 or 73 have too few factors."""
+    ext = set(divisors(n))
+    if path == PATH_MFMA:
+        ext |= {-(-n // k) for k in range(1, 9)}
+    return sorted(ext)
+
+
 def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
     N, C, K, R, S, st = s["N"], s["C"], s["K"], s["R"], s["S"], s["stride"]
     sb_max = T_MAX * vgpr_budget
@@ -339,8 +349,8 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
     # matrix-core path: z divides K rounded up to whole 32-channel blocks (channels past K: zeros, not stored)
     Kz = -(-K // 32) * 32 if path == PATH_MFMA else K
     for b in divisors(N):
-        for x in divisors(Q):
-            for y in divisors(P):
+        for x in tile_extents(Q, path):
+            for y in tile_extents(P, path):
                 npix = b * x * y
                 xp, yp = (x - 1) * st + S, (y - 1) * st + R
                 halo = b * xp * yp
@@ -378,7 +388,7 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                         lds_mult = 4
                     if alpha is None or not grids:
                         continue
-                    nblocks = (N // b) * (Q // x) * (P // y) * (Kz // z)
+                    nblocks = (N // b) * (-(-Q // x)) * (-(-P // y)) * (Kz // z)
                     qread = nblocks * C * (halo + R * S * z)
                     _, T, _, wm, wn, acc = min(grids)
                     if path == PATH_MFMA:

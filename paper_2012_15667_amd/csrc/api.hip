@@ -167,7 +167,7 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     g.threads = cfg.threads; g.waves_m = cfg.waves_m; g.waves_n = cfg.waves_n;
     g.per_thread = cfg.acc_regs_per_thread;
     g.Kp = cfg.path == IOLB_PATH_MFMA ? (s.K + 31) / 32 * 32 : s.K;
-    g.nbx = Q / cfg.x; g.nby = P / cfg.y; g.nbn = s.N / cfg.b; g.nbk = g.Kp / cfg.z;
+    g.nbx = (Q + cfg.x - 1) / cfg.x; g.nby = (P + cfg.y - 1) / cfg.y; g.nbn = s.N / cfg.b; g.nbk = g.Kp / cfg.z;   // edge tiles may hang over
     g.xh = (cfg.x - 1) * s.stride + s.S;
     g.yh = (cfg.y - 1) * s.stride + s.R;
     g.halo = cfg.b * g.xh * g.yh;

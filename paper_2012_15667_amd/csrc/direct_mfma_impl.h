@@ -315,6 +315,7 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
         if (nb >= my_blocks || (first_block + nb) * 32 + l32 >= npix) continue;
+        if (y0 + ppy[nb] >= g.P || x0 + ppx[nb] >= g.Q) continue;     // an edge tile's pixels past the image
         if constexpr (!HWC) {
             float* yp = y + ((size_t)(n0 + pimg[nb]) * g.K + k0) * PQ + (size_t)(y0 + ppy[nb]) * g.Q + x0 + ppx[nb];
 #pragma unroll

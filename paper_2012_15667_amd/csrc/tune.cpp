@@ -39,6 +39,19 @@ std::vector<int> factors_of(int n) {
     return f;
 }
 
+// Tile extents along an output axis of n pixels: the factors of n (Table 1) and, on the matrix-core path, the
+// balanced cuts ceil(n / k) into k = 1..8 tiles, whose last tile hangs over the edge (its pixels past the
+// image are computed on zeros and not stored) -- extents like 35, 55 or 73 have too few factors.
+std::vector<int> tile_extents(int n, bool ragged) {
+    std::vector<int> e = factors_of(n);
+    if (ragged) {
+        for (int k = 1; k <= 8; ++k) e.push_back((n + k - 1) / k);
+        std::sort(e.begin(), e.end());
+        e.erase(std::unique(e.begin(), e.end()), e.end());
+    }
+    return e;
+}
+
 bool allowed_threads(int64_t t) { return t == 64 || t == 128 || t == 256 || t == 512 || t == 1024; }
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -127,14 +140,14 @@ int64_t mfma_tile_cost(const iolb_shape& s, int b, int x, int y, int z, int alph
     const int64_t own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w);
     // Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as many
     // as the LDS holds (a single stage needs one buffer) and the registers hold (512 per SIMD lane, acc + 64 per
-    // wave), at most 8 (2 for four-wave workgroups), and no more than the layer has per compute unit.  Waves of
+    // wave), at most 4 one-wave or 2 larger workgroups, and no more than the layer has per compute unit.  Waves of
     // different workgroups overlap a little less well than those of one (+10 % on the shared matrix-core time).
     // Larger workgroups are modelled one per compute unit.
     int64_t resident = 1;
     if (waves <= 4) {
         const int64_t lds_used = (alpha >= s.C ? 4 : 8) * alpha * (halo + RS * z);
         resident = std::max<int64_t>(1, std::min({kLdsPerCu / lds_used, 4 * (512 / ((int64_t)g.acc + 64)) / waves,
-                                                  (int64_t)(waves == 4 ? 2 : 8), ceil_div(nblocks, kComputeUnits)}));
+                                                  (int64_t)(waves == 1 ? 4 : 2), ceil_div(nblocks, kComputeUnits)}));
     }
     const int64_t sharing = ceil_div(resident * waves, 4);       // waves per SIMD
     const int64_t shared = resident > 1 ? mfma * sharing * 11 / 10 : mfma * sharing;
@@ -163,7 +176,8 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
     // matrix-core path: z runs over the factors of K rounded up to whole 32-channel blocks (the channels
     // past K are computed as zeros and not stored)
     const int Kz = path == IOLB_PATH_MFMA ? (s.K + 31) / 32 * 32 : s.K;
-    const auto fb = factors_of(s.N), fx = factors_of(Q), fy = factors_of(P), fz = factors_of(Kz);
+    const auto fb = factors_of(s.N), fz = factors_of(Kz);
+    const auto fx = tile_extents(Q, path == IOLB_PATH_MFMA), fy = tile_extents(P, path == IOLB_PATH_MFMA);
     for (int b : fb)
         for (int x : fx)
             for (int y : fy) {
@@ -205,7 +219,7 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                         lds_mult = 4;
                     }
                     if (alpha == 0) continue;
-                    const int64_t nblocks = (int64_t)(s.N / b) * (Q / x) * (P / y) * (Kz / z);
+                    const int64_t nblocks = (int64_t)(s.N / b) * ceil_div(Q, x) * ceil_div(P, y) * (Kz / z);
                     Candidate c{};
                     c.cfg.b = b; c.cfg.x = x; c.cfg.y = y; c.cfg.z = z;
                     c.cfg.alpha = alpha;

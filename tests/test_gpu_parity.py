@@ -132,6 +132,36 @@ def test_direct_every_enumerated_path_agrees(gpu):
         assert rel_err(got, ref) <= TOL_DIRECT, cfg
 
 
+@pytest.mark.parametrize("shape", [(2, 8, 35, 35, 32, 3, 3, 1, 1), (2, 12, 13, 17, 64, 3, 3, 1, 1),
+                                   (2, 8, 37, 41, 32, 3, 3, 2, 1), (2, 8, 35, 35, 64, 5, 5, 1, 2)])
+def test_direct_tiles_that_hang_over_the_edge(gpu, shape):
+    """Tile extents that do not divide the output (balanced cuts ceil(extent / k)): the last tile of a row or
+    column computes pixels past the image on zeros and must store only the ones inside -- every such tile of
+    the enumeration's sample, in both tensor layouts, against the oracle; the bytes after the output tensor
+    stay untouched."""
+    torch, B = gpu
+    N, C, H, W, K, R, S, stride, pad = shape
+    x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=90 + H)
+    ref = conv_ref(x, w, stride, pad)
+    P, Q = ref.shape[2], ref.shape[3]
+    tiles = [t for t in B.iolb_enumerate(B.make_shape(N, C, H, W, K, R, S, stride, pad), 0, 0, False)
+             if Q % t["x"] or P % t["y"]]
+    assert len(tiles) > 10
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    x_hwc = torch.from_numpy(_to_hwc(x)).cuda()
+    step = max(1, len(tiles) // 10)
+    for cfg in tiles[::step]:
+        buf = torch.full((N * K * P * Q + 4096,), 7.0, device="cuda", dtype=torch.float32)
+        y = buf[:N * K * P * Q].view(N, K, P, Q)
+        B.conv_direct(xd, wd, stride, pad, y=y, cfg=cfg)
+        torch.cuda.synchronize()
+        assert rel_err(y.cpu().numpy(), ref) <= TOL_DIRECT, cfg
+        assert bool((buf[N * K * P * Q:] == 7.0).all()), cfg
+        got = B.conv_direct_layout(x_hwc, wd, stride, pad, B.LAYOUT_HWC, cfg=cfg)
+        torch.cuda.synchronize()
+        assert rel_err(got.cpu().numpy(), _to_hwc(ref)) <= TOL_DIRECT, cfg
+
+
 @pytest.mark.parametrize("name", ["cfg5a", "cfg5b", "cfg5c", "cfg5d"])
 def test_direct_full_size_sampled(gpu, name):
     """Full-size VGG-style layers in the launch configuration the benchmark times; 4096 sampled

@@ -34,7 +34,9 @@ def test_every_layer_has_a_tile(model):
         assert P >= 1 and Q >= 1
         cfg = B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad))
         Kz = -(-L.K // 32) * 32 if cfg["path"] == B.PATH_MFMA else L.K
-        assert cfg["x"] >= 1 and Q % cfg["x"] == 0 and P % cfg["y"] == 0 and Kz % cfg["z"] == 0
+        # tile extents: factors of the output extent or a balanced cut into up to 8 tiles
+        fits = lambda n, t: n % t == 0 or any(t == -(-n // k) for k in range(1, 9))
+        assert cfg["x"] >= 1 and fits(Q, cfg["x"]) and fits(P, cfg["y"]) and Kz % cfg["z"] == 0
         if LS.winograd_applies(L):
             for m in (2, 4):
                 B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, algo=B.WINO_ALGO[m]))

@@ -121,10 +121,14 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
     assert Kz % z == 0 and T in (64, 128, 256, 512, 1024)
     assert cfg["lds_bytes_used"] <= (lds_bytes or o.LDS_CU) and cfg["acc_regs_per_thread"] <= vgpr_budget
     if s["algo"] == o.DIRECT:
-        assert s["N"] % b == 0 and Q % x == 0 and P % y == 0
+        # tile extents: factors of the output extent, or (matrix-core path) a balanced cut into up to 8 tiles
+        ragged = cfg["path"] == o.PATH_MFMA
+        assert s["N"] % b == 0
+        assert Q % x == 0 or (ragged and any(x == -(-Q // k) for k in range(1, 9)))
+        assert P % y == 0 or (ragged and any(y == -(-P // k) for k in range(1, 9)))
         halo = b * ((x - 1) * s["stride"] + s["S"]) * ((y - 1) * s["stride"] + s["R"])
         per_stage = halo + s["R"] * s["S"] * z
-        blocks = (s["N"] // b) * (Q // x) * (P // y) * (Kz // z)
+        blocks = (s["N"] // b) * -(-Q // x) * -(-P // y) * (Kz // z)
         assert cfg["q_read_elems"] == blocks * s["C"] * per_stage
         if cfg["path"] == o.PATH_MFMA:
             assert z % 32 == 0 and a % 4 == 0
@@ -174,7 +178,7 @@ def test_tile_rule_minimises_its_key(s):
     assert best == cfg
     if s["algo"] == o.DIRECT and cfg["path"] == o.PATH_MFMA:
         P, Q = o.out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
-        nblocks = (s["N"] // cfg["b"]) * (Q // cfg["x"]) * (P // cfg["y"]) * (-(-s["K"] // 32) * 32 // cfg["z"])
+        nblocks = (s["N"] // cfg["b"]) * -(-Q // cfg["x"]) * -(-P // cfg["y"]) * (-(-s["K"] // 32) * 32 // cfg["z"])
         assert key[0] == o.mfma_tile_cost(s, cfg["b"], cfg["x"], cfg["y"], cfg["z"], cfg["alpha"], cfg["threads"],
                                           cfg["waves_m"], cfg["acc_regs_per_thread"], nblocks,
                                           cfg["q_read_elems"], cfg["q_write_elems"])
