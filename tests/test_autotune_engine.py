@@ -76,3 +76,16 @@ def test_layout_is_a_parameter_of_the_domain():
     best, best_ms, _ = A.autotune(dom, measure, n_s=8, patience=4, seed=3)
     assert best["layout"] == 1
     assert best_ms <= min(measure(c) for c in dom) * 1.03
+
+
+def test_shallower_stage_of_a_single_stage_tile_counts_two_buffers():
+    """lds_bytes_used of a matrix-core tile whose one stage holds all C channels is one buffer; the same tile
+    with fewer channels per stage has several stages and two buffers -- the figure the library checks."""
+    from paper_2012_15667_amd.autotune import stage_depth_variant, with_stage_depths
+    t = dict(path=1, alpha=16, lds_bytes_used=4 * 16 * 100)
+    assert stage_depth_variant(t, 16, 16)["lds_bytes_used"] == 6400
+    assert stage_depth_variant(t, 8, 16)["lds_bytes_used"] == 2 * 4 * 8 * 100
+    assert stage_depth_variant(t, 8, 64)["lds_bytes_used"] == 3200      # C = 64: several stages to begin with, the figure just scales
+    assert [v["alpha"] for v in with_stage_depths([t], 4, 16)] == [16, 8, 4]
+    f = dict(path=0, alpha=4, lds_bytes_used=400)
+    assert stage_depth_variant(f, 2, 3)["lds_bytes_used"] == 200                    # FMA path: single-buffered throughout
