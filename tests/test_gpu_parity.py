@@ -555,6 +555,42 @@ def test_layout_error_codes(gpu):
     torch.cuda.synchronize()
 
 
+def test_random_shapes_and_tiles_match_oracle(gpu):
+    """Seeded random layers (kernel 1..7, stride 1..3, pad 0..3, odd extents and channel counts), each with the
+    tuned tile and two random tiles of the enumeration, in both tensor layouts; the 3x3 / stride 1 / pad 1 ones
+    also through every Winograd variant with the tuned and a random tile."""
+    import random
+    torch, B = gpu
+    rnd = random.Random(11)
+    for it in range(24):
+        R = rnd.choice([1, 3, 3, 5, 7]); S = rnd.choice([R, R, 3, 1])
+        st = rnd.choice([1, 1, 2, 3]); pad = rnd.choice([0, 1, 2, 3])
+        if it % 4 == 0:
+            R = S = 3; st = pad = 1
+        N = rnd.choice([1, 2, 3, 4, 6]); C = rnd.choice([1, 2, 3, 4, 5, 8, 12, 16, 20, 33, 64])
+        K = rnd.choice([1, 5, 16, 32, 40, 64, 96])
+        H = rnd.randint(max(R - 2 * pad, 1), 40); W = rnd.randint(max(S - 2 * pad, 1), 40)
+        x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=2000 + it)
+        ref = conv_ref(x, w, st, pad)
+        xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        xh = torch.from_numpy(_to_hwc(x)).cuda()
+        tiles = B.iolb_enumerate(B.make_shape(N, C, H, W, K, R, S, st, pad), 0, 0, False)
+        case = (N, C, H, W, K, R, S, st, pad)
+        for cfg in (None, rnd.choice(tiles), rnd.choice(tiles)):
+            y = B.conv_direct(xd, wd, st, pad, cfg=cfg)
+            yh = B.conv_direct_layout(xh, wd, st, pad, B.LAYOUT_HWC, cfg=cfg)
+            torch.cuda.synchronize()
+            assert rel_err(y.cpu().numpy(), ref) <= TOL_DIRECT, (case, cfg)
+            assert rel_err(yh.cpu().numpy(), _to_hwc(ref)) <= TOL_DIRECT, (case, cfg)
+        if (R, S, st, pad) == (3, 3, 1, 1):
+            for m in (2, 3, 4, 6):
+                wt = B.iolb_enumerate(B.make_shape(N, C, H, W, K, algo=B.WINO_ALGO[m]), 0, 0, False)
+                for cfg in (None, rnd.choice(wt)):
+                    y = B.conv_winograd(xd, wd, m, cfg=cfg)
+                    torch.cuda.synchronize()
+                    assert rel_err(y.cpu().numpy(), ref) <= TOL_WINO, (case, m, cfg)
+
+
 def test_error_codes(gpu):
     torch, B = gpu
     x = torch.zeros((1, 4, 8, 8), device="cuda")
