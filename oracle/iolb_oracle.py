@@ -335,9 +335,10 @@ def _pow2ceil(v):
 def tile_extents(n, path):
     """Tile extents along an output axis of n pixels: the factors of n (Table 1) and, on the matrix-core path,
     the balanced cuts ceil(n / k) into k = 1..8 tiles, whose last tile hangs over the edge (its pixels past
-    the image are computed on zeros and not stored) -- extents like 35, 55 or 73 have too few factors."""
+    the image are computed on zeros and not stored) -- for extents with at most six factors (13, 28, 35, 55,
+    73, 147 ...), which leave too little choice; 56, 112 or 224 have enough."""
     ext = set(divisors(n))
-    if path == PATH_MFMA:
+    if path == PATH_MFMA and len(ext) <= 6:
         ext |= {-(-n // k) for k in range(1, 9)}
     return sorted(ext)
 

@@ -41,10 +41,11 @@ std::vector<int> factors_of(int n) {
 
 // Tile extents along an output axis of n pixels: the factors of n (Table 1) and, on the matrix-core path, the
 // balanced cuts ceil(n / k) into k = 1..8 tiles, whose last tile hangs over the edge (its pixels past the
-// image are computed on zeros and not stored) -- extents like 35, 55 or 73 have too few factors.
+// image are computed on zeros and not stored) -- for extents with at most six factors (13, 28, 35, 55, 73,
+// 147 ...), which leave too little choice; 56, 112 or 224 have enough.
 std::vector<int> tile_extents(int n, bool ragged) {
     std::vector<int> e = factors_of(n);
-    if (ragged) {
+    if (ragged && e.size() <= 6) {
         for (int k = 1; k <= 8; ++k) e.push_back((n + k - 1) / k);
         std::sort(e.begin(), e.end());
         e.erase(std::unique(e.begin(), e.end()), e.end());

@@ -306,7 +306,8 @@ def test_single_stage_tiles_count_one_buffer_and_large_kernels_fall_back_to_fma(
 def test_tile_extents_are_factors_plus_balanced_cuts():
     assert o.tile_extents(35, o.PATH_MFMA) == [1, 5, 6, 7, 9, 12, 18, 35]       # factors 1, 5, 7, 35; ceil(35/k), k <= 8
     assert o.tile_extents(35, o.PATH_FMA) == [1, 5, 7, 35]
-    assert o.tile_extents(56, o.PATH_MFMA) == [1, 2, 4, 7, 8, 10, 12, 14, 19, 28, 56]
+    assert o.tile_extents(56, o.PATH_MFMA) == [1, 2, 4, 7, 8, 14, 28, 56]          # eight factors: no cuts needed
+    assert o.tile_extents(28, o.PATH_MFMA) == [1, 2, 4, 5, 6, 7, 10, 14, 28]        # six factors: cuts admitted
     # a cut into k tiles covers the extent with the last tile hanging over by less than k pixels
     for n in (13, 27, 55, 73, 147, 149):
         for x in o.tile_extents(n, o.PATH_MFMA):
