@@ -112,6 +112,12 @@ int conv_direct_layout(const float* x, const float* w, float* y,
 int conv_winograd(const float* x, const float* w, float* y,
                   int N, int C, int H, int W, int K, int m);
 
+/* conv_winograd with `pad` zeros on every side instead of one (pad >= 0, H + 2 pad >= 3, W + 2 pad >= 3):
+ * y is [N][K][H + 2 pad - 2][W + 2 pad - 2].  Sub-domain (i, j) reads the (m+2) x (m+2) window whose corner is
+ * (i m - pad, j m - pad).  Library workspace, tuned tile. */
+int conv_winograd_pad(const float* x, const float* w, float* y,
+                      int N, int C, int H, int W, int K, int m, int pad);
+
 /* Bytes of workspace conv_winograd_ws needs for this layer (0 on invalid arguments). */
 size_t conv_winograd_workspace_bytes(int N, int C, int H, int W, int K, int m);
 

@@ -14,7 +14,7 @@ WINO_ALGO = {2: WINO_F2, 3: WINO_F3, 4: WINO_F4, 6: WINO_F6}     # algo id of F(
 PATH_FMA, PATH_MFMA = 0, 1
 LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 
-EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_workspace_bytes",
+EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_pad", "conv_winograd_workspace_bytes",
            "conv_winograd_ws", "conv_winograd_kernel_bytes", "conv_winograd_transform_kernels", "conv_winograd_pre",
            "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
            "iolb_probe_hbm_copy", "iolb_probe_mfma_sink_bytes", "iolb_probe_mfma_f32",
@@ -75,6 +75,8 @@ def lib():
         L.conv_direct_layout.argtypes = [vp, vp, vp] + [i] * 10 + [ctypes.POINTER(TileConfig)]
         L.conv_winograd.restype = i
         L.conv_winograd.argtypes = [vp, vp, vp] + [i] * 6
+        L.conv_winograd_pad.restype = i
+        L.conv_winograd_pad.argtypes = [vp, vp, vp] + [i] * 7
         L.conv_winograd_workspace_bytes.restype = sz
         L.conv_winograd_workspace_bytes.argtypes = [i] * 6
         L.conv_winograd_ws.restype = i
@@ -234,13 +236,27 @@ def conv_direct_layout(x, w, stride=1, pad=0, layout=LAYOUT_HWC, y=None, cfg=Non
     return y
 
 
-def conv_winograd(x, w, m, y=None, cfg=None, workspace=None):
-    """y = Winograd F(m x m, 3 x 3) convolution (stride 1, pad 1) on the current stream."""
+def conv_winograd(x, w, m, y=None, cfg=None, workspace=None, pad=1):
+    """y = Winograd F(m x m, 3 x 3) convolution (stride 1, pad 1 unless `pad` says otherwise) on the current
+    stream.  Another padding runs with the tuned tile and the library's workspace only."""
     import torch
     N, C, H, W = x.shape
     K, C2, R, S = w.shape
     if C2 != C or R != 3 or S != 3:
         raise ValueError("Winograd path needs 3x3 kernels with matching channels")
+    if pad != 1:
+        if cfg is not None or workspace is not None:
+            raise ValueError("cfg and workspace are available for pad = 1 only")
+        if pad < 0 or H + 2 * pad < 3 or W + 2 * pad < 3:
+            raise IolbError(-1, "invalid argument")
+        shape = (N, K, H + 2 * pad - 2, W + 2 * pad - 2)
+        if y is None:
+            y = torch.empty(shape, dtype=torch.float32, device=x.device)
+        elif tuple(y.shape) != shape:
+            raise ValueError("y has the wrong shape")
+        _use_current_stream()
+        _check(lib().conv_winograd_pad(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, m, pad))
+        return y
     if y is None:
         y = torch.empty((N, K, H, W), dtype=torch.float32, device=x.device)
     elif tuple(y.shape) != (N, K, H, W):

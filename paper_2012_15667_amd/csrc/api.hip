@@ -200,8 +200,11 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
 {
     const int m = iolb::winograd_m(s.algo);
     g->N = s.N; g->C = s.C; g->H = s.H; g->W = s.W; g->K = s.K; g->m = m;
-    g->th = (s.H + m - 1) / m;
-    g->tw = (s.W + m - 1) / m;
+    g->pad = s.pad;
+    g->P = s.H + 2 * s.pad - 2;
+    g->Q = s.W + 2 * s.pad - 2;
+    g->th = (g->P + m - 1) / m;
+    g->tw = (g->Q + m - 1) / m;
     const int64_t tiles = (int64_t)s.N * g->th * g->tw;
     g->tb = cfg.x / m;
     g->z = cfg.z;
@@ -236,7 +239,7 @@ WinoWorkspace winograd_layout(int C, int K, int m, int64_t tiles_pitch, bool fus
     return l;
 }
 
-int make_wino_shape(int N, int C, int H, int W, int K, int m, iolb_shape* s)
+int make_wino_shape(int N, int C, int H, int W, int K, int m, iolb_shape* s, int pad = 1)
 {
     int algo = 0;
     switch (m) {
@@ -246,7 +249,7 @@ int make_wino_shape(int N, int C, int H, int W, int K, int m, iolb_shape* s)
     case 6: algo = IOLB_WINO_F6; break;
     default: return IOLB_EUNSUPPORTED;
     }
-    *s = iolb_shape{N, C, H, W, K, 3, 3, 1, 1, algo};
+    *s = iolb_shape{N, C, H, W, K, 3, 3, 1, pad, algo};
     int P = 0, Q = 0;
     return iolb::validate_shape(*s, &P, &Q);
 }
@@ -447,6 +450,28 @@ int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H,
     // the one-kernel path stores the transformed kernels only
     const size_t bytes = tile.path == IOLB_PATH_FMA ? winograd_layout(C, (K + 31) / 32 * 32, m, 0, true).total
                                                     : conv_winograd_workspace_bytes(N, C, H, W, K, m);
+    DeviceState* dev = nullptr;
+    rc = device_state(&dev);
+    if (rc != IOLB_OK) return rc;
+    rc = ensure_workspace(dev, bytes);
+    if (rc != IOLB_OK) return rc;
+    return run_winograd(x, w, nullptr, y, s, tile, dev->ws, dev->ws_bytes);
+}
+
+int conv_winograd_pad(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m, int pad)
+{
+    if (!x || !w || !y) return IOLB_EINVAL;
+    iolb_shape s;
+    int rc = make_wino_shape(N, C, H, W, K, m, &s, pad);
+    if (rc != IOLB_OK) return rc;
+    iolb_tile_config tile;
+    rc = tuned_tile(s, &tile);
+    if (rc != IOLB_OK) return rc;
+    // workspace for the output extents of this padding
+    const int P = H + 2 * pad - 2, Q = W + 2 * pad - 2;
+    const int64_t tiles = (int64_t)N * ((P + m - 1) / m) * ((Q + m - 1) / m);
+    const size_t bytes = tile.path == IOLB_PATH_FMA ? winograd_layout(C, (K + 31) / 32 * 32, m, 0, true).total
+                                                    : winograd_layout(C + 15, (K + 31) / 32 * 32, m, tiles + 1024).total;
     DeviceState* dev = nullptr;
     rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;

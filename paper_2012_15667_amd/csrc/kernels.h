@@ -41,7 +41,8 @@ hipError_t launch_direct_mfma_hwc(const float* x, const float* wt, float* y, con
 // Winograd F(m x m, 3 x 3), unfused: kernel transform, input transform, batched product over the
 // (m+2)^2 planes, output transform (steps 1-4 of Sec. 4.3).
 struct WinoGeom {
-    int N, C, H, W, K, m;      // P = H, Q = W (pad 1)
+    int N, C, H, W, K, m;
+    int pad, P, Q;             // zero padding on every side; output extents P = H + 2 pad - 2, Q = W + 2 pad - 2
     int Cp;                    // C rounded up to whole stages: U and V carry zero rows for c in [C, Cp)
     int Kp;                    // K rounded up to a multiple of 32: U carries zero columns, M unused rows for k in [K, Kp)
     int CpU;                   // channel rows per plane of U (>= Cp; a caller-held U is padded to a multiple of 16)

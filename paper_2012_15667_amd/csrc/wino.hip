@@ -10,7 +10,7 @@
 //
 // xi runs over the n*n = (m+2)^2 positions of a transformed tile.  Sub-domain t = (image, tile row,
 // tile column) in that order; tile (ti, tj) reads the n x n input window whose top-left corner is
-// (ti*m - 1, tj*m - 1), zero outside the image.
+// (ti*m - pad, tj*m - pad), zero outside the image (pad = 1 keeps the extents: P = H, Q = W).
 //
 // The transform matrices (wino_mats.h) are compile-time constants: zeros and +-1 cost nothing.
 #include "kernels.h"
@@ -64,9 +64,9 @@ input_transform(const float* __restrict__ x, float* __restrict__ V, WinoGeom g)
     const int c = blockIdx.y;
     if (t >= g.tiles) return;
     const int tj = t % g.tw, ti = (t / g.tw) % g.th, img = t / (g.tw * g.th);
-    const int h0 = ti * M - 1, w0 = tj * M - 1;
+    const int h0 = ti * M - g.pad, w0 = tj * M - g.pad;
     float d[n][n];
-    if constexpr (VEC) {
+    if constexpr (VEC) {                                  // pad = 1 only: the own columns start at a multiple of m
         typedef float vec __attribute__((ext_vector_type(M)));
         const int lane = threadIdx.x & 63;
         const bool own_left = tj > 0 && lane == 0, own_right = tj + 1 < g.tw && lane == 63;
@@ -161,7 +161,7 @@ output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g
     float tmp[M][n], o[M][M];
     left_mul<M, UseA, M, n, n>(pi, tmp);
     right_mul_t<M, UseA, M, n, M>(tmp, o);
-    float* yp = y + ((size_t)img * g.K + k) * g.H * g.W;
+    float* yp = y + ((size_t)img * g.K + k) * g.P * g.Q;
 #pragma unroll
     for (int i = 0; i < M; ++i) {
         const int h = ti * M + i;
@@ -170,12 +170,12 @@ output_transform(const float* __restrict__ Mp, float* __restrict__ y, WinoGeom g
             vec v;
 #pragma unroll
             for (int j = 0; j < M; ++j) v[j] = o[i][j];
-            if (h < g.H) *reinterpret_cast<vec*>(yp + (size_t)h * g.W + tj * M) = v;
+            if (h < g.P) *reinterpret_cast<vec*>(yp + (size_t)h * g.Q + tj * M) = v;
         } else {
 #pragma unroll
             for (int j = 0; j < M; ++j) {
                 const int ww = tj * M + j;
-                if (h < g.H && ww < g.W) yp[(size_t)h * g.W + ww] = o[i][j];
+                if (h < g.P && ww < g.Q) yp[(size_t)h * g.Q + ww] = o[i][j];
             }
         }
     }
@@ -367,7 +367,7 @@ hipError_t launch_wino_input_transform(const float* x, float* V, const WinoGeom&
 {
     if (g.Cp > 65535) return hipErrorInvalidValue;
     dim3 grid((g.tiles + 255) / 256, g.Cp);
-    const bool vec = g.W % g.m == 0 && (reinterpret_cast<uintptr_t>(x) & (4 * g.m - 1)) == 0;
+    const bool vec = g.pad == 1 && g.W % g.m == 0 && (reinterpret_cast<uintptr_t>(x) & (4 * g.m - 1)) == 0;
     switch (g.m) {
     case 2:
         if (vec) hipLaunchKernelGGL((input_transform<2, true>), grid, dim3(256), 0, st, x, V, g);
@@ -388,7 +388,7 @@ hipError_t launch_wino_output_transform(const float* Mp, float* y, const WinoGeo
 {
     if (g.K > 65535) return hipErrorInvalidValue;
     dim3 grid((g.tiles + 255) / 256, g.K);
-    const bool vec = g.W % g.m == 0 && (reinterpret_cast<uintptr_t>(y) & (4 * g.m - 1)) == 0;
+    const bool vec = g.Q % g.m == 0 && (reinterpret_cast<uintptr_t>(y) & (4 * g.m - 1)) == 0;
     switch (g.m) {
     case 2:
         if (vec) hipLaunchKernelGGL((output_transform<2, true>), grid, dim3(256), 0, st, Mp, y, g);

@@ -36,7 +36,7 @@ wino_fused_kernel(const float* __restrict__ x, const float* __restrict__ Uk, flo
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= g.tiles) return;                                   // no barriers below
     const int tj = t % g.tw, ti = (t / g.tw) % g.th, img = t / (g.tw * g.th);
-    const int h0 = ti * M - 1, w0 = tj * M - 1;
+    const int h0 = ti * M - g.pad, w0 = tj * M - g.pad;
 
     float v[CC][n][n];
     static_for<CC>([&](auto c) {
@@ -63,8 +63,8 @@ wino_fused_kernel(const float* __restrict__ x, const float* __restrict__ Uk, flo
         right_mul_t<M, UseB, n, n, n>(tmp, v[c]);
     });
 
-    const size_t yplane = (size_t)g.H * g.W;
-    float* yp = y + (size_t)img * g.K * yplane + (size_t)(ti * M) * g.W + tj * M;
+    const size_t yplane = (size_t)g.P * g.Q;
+    float* yp = y + (size_t)img * g.K * yplane + (size_t)(ti * M) * g.Q + tj * M;
     // blockIdx.y selects kc output channels: their factor rows stay in the scalar cache while the
     // workgroups of the same channel group, which are dispatched together, walk over them
     const int k_begin = blockIdx.y * kc, k_end = k_begin + kc < g.K ? k_begin + kc : g.K;
@@ -96,11 +96,11 @@ wino_fused_kernel(const float* __restrict__ x, const float* __restrict__ Uk, flo
                 vec q;
 #pragma unroll
                 for (int j = 0; j < M; ++j) q[j] = o[i][j];
-                if (h < g.H) *reinterpret_cast<vec*>(yk + (size_t)i * g.W) = q;
+                if (h < g.P) *reinterpret_cast<vec*>(yk + (size_t)i * g.Q) = q;
             } else {
 #pragma unroll
                 for (int j = 0; j < M; ++j)
-                    if (h < g.H && tj * M + j < g.W) yk[(size_t)i * g.W + j] = o[i][j];
+                    if (h < g.P && tj * M + j < g.Q) yk[(size_t)i * g.Q + j] = o[i][j];
             }
         }
     }
@@ -126,7 +126,7 @@ hipError_t launch_fused_mc(const float* x, const float* U, float* y, const WinoG
     const dim3 grid((g.tiles + 255) / 256, (g.K + kc - 1) / kc);
     if (grid.y > 65535) return hipErrorInvalidValue;
     constexpr bool can_vec = M == 2 || M == 4;
-    const bool vec = can_vec && g.W % M == 0 && (reinterpret_cast<uintptr_t>(y) & (4 * M - 1)) == 0;
+    const bool vec = can_vec && g.Q % M == 0 && (reinterpret_cast<uintptr_t>(y) & (4 * M - 1)) == 0;
     if constexpr (can_vec) {
         if (vec) {
             hipLaunchKernelGGL((wino_fused_kernel<M, CC, true>), grid, dim3(256), 0, st, x, U, y, g, kc);

@@ -15,7 +15,7 @@ shape sweeps of the two direct-convolution figures, as synthetic layers (shapes 
     python -m paper_2012_15667_amd.layersets --figure-sweep --batch 32
 
 Each line of output is one JSON record: the layer, the time and direct-equivalent TFLOP/s of every algorithm
-that applies (direct always; Winograd F(2x2), F(4x4) for 3x3 stride-1 pad-1 layers), and the fastest.  A final
+that applies (direct always; Winograd F(2x2), F(4x4) for 3x3 stride-1 layers), and the fastest.  A final
 record sums a network: time per image batch with the best algorithm per layer and with direct convolution
 only.
 """
@@ -105,7 +105,7 @@ def flops(N, L):
 
 
 def winograd_applies(L):
-    return L.R == 3 and L.S == 3 and L.stride == 1 and L.pad == 1
+    return L.R == 3 and L.S == 3 and L.stride == 1
 
 
 def time_layer(N, L, reps=5, seed=0):
@@ -121,7 +121,7 @@ def time_layer(N, L, reps=5, seed=0):
     out = {"direct": time_call(torch, lambda: B.conv_direct(x, w, L.stride, L.pad, y=y), reps)}
     if winograd_applies(L):
         for m in (2, 4):
-            out["wino%d" % m] = time_call(torch, lambda: B.conv_winograd(x, w, m, y=y), reps)
+            out["wino%d" % m] = time_call(torch, lambda: B.conv_winograd(x, w, m, y=y, pad=L.pad), reps)
     return out
 
 

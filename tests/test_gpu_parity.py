@@ -363,6 +363,27 @@ def test_winograd_matches_direct_oracle(gpu, case):
     assert rel_err(got, ref) <= TOL_WINO
 
 
+WINO_PAD_CASES = [
+    # m, N, C, H, W, K, pad: other paddings than 1 (output extents H + 2 pad - 2, W + 2 pad - 2)
+    (2, 2, 8, 10, 12, 32, 0), (2, 1, 6, 9, 9, 40, 2), (2, 2, 3, 18, 22, 33, 0),        # the last: fused kernel
+    (4, 2, 16, 18, 18, 32, 0), (4, 1, 10, 13, 15, 64, 2), (4, 2, 3, 18, 22, 33, 0), (4, 2, 3, 9, 9, 8, 2),
+    (3, 2, 8, 11, 14, 32, 0), (6, 2, 8, 14, 26, 32, 0), (6, 1, 5, 7, 7, 32, 3),
+    (4, 1, 8, 3, 3, 32, 0),                                                               # one output pixel
+]
+
+
+@pytest.mark.parametrize("case", WINO_PAD_CASES)
+def test_winograd_other_paddings_match_direct_oracle(gpu, case):
+    torch, B = gpu
+    m, N, C, H, W, K, pad = case
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u11", "he", seed=400 + m + C + pad)
+    ref = conv_ref(x, w, 1, pad)
+    y = B.conv_winograd(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), m, pad=pad)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == ref.shape == (N, K, H + 2 * pad - 2, W + 2 * pad - 2)
+    assert rel_err(y.cpu().numpy(), ref) <= TOL_WINO
+
+
 def test_winograd_config2_and_config4(gpu):
     for name, m in (("cfg2", 2), ("cfg4", 4)):
         L = CONFIGS[name]

@@ -39,7 +39,7 @@ def test_every_layer_has_a_tile(model):
         assert cfg["x"] >= 1 and fits(Q, cfg["x"]) and fits(P, cfg["y"]) and Kz % cfg["z"] == 0
         if LS.winograd_applies(L):
             for m in (2, 4):
-                B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, algo=B.WINO_ALGO[m]))
+                B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, 3, 3, 1, L.pad, algo=B.WINO_ALGO[m]))
 
 
 def test_sweeps_have_the_stated_shapes():
