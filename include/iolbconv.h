@@ -102,6 +102,12 @@ int conv_direct_layout(const float* x, const float* w, float* y,
                        int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                        int layout, const iolb_tile_config* cfg);
 
+/* conv_direct with its own padding per axis: pad_h rows of zeros above and below, pad_w columns left and
+ * right (the 1 x 7 / 7 x 1 factorised kernels of Inception-v3 pad one axis only); P and Q follow from
+ * pad_h and pad_w.  NCHW tensors, tuned tile. */
+int conv_direct_pad2(const float* x, const float* w, float* y,
+                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad_h, int pad_w);
+
 /* Winograd F(m x m, 3 x 3) convolution (Sec. 2.3; four steps of Sec. 4.3), R = S = 3,
  * stride 1, pad 1 (P = H, Q = W), m in {2, 3, 4, 6} (Sec. 2.3 names e = 2 and e = 3; larger m
  * trades more rounding error for fewer multiplications).  Same layouts as conv_direct.  The transformed

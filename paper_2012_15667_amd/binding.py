@@ -14,7 +14,7 @@ WINO_ALGO = {2: WINO_F2, 3: WINO_F3, 4: WINO_F4, 6: WINO_F6}     # algo id of F(
 PATH_FMA, PATH_MFMA = 0, 1
 LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 
-EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_winograd", "conv_winograd_pad", "conv_winograd_workspace_bytes",
+EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_direct_pad2", "conv_winograd", "conv_winograd_pad", "conv_winograd_workspace_bytes",
            "conv_winograd_ws", "conv_winograd_kernel_bytes", "conv_winograd_transform_kernels", "conv_winograd_pre",
            "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
            "iolb_probe_hbm_copy", "iolb_probe_mfma_sink_bytes", "iolb_probe_mfma_f32",
@@ -71,6 +71,8 @@ def lib():
         L.conv_direct.argtypes = [vp, vp, vp] + [i] * 9
         L.conv_direct_cfg.restype = i
         L.conv_direct_cfg.argtypes = [vp, vp, vp] + [i] * 9 + [ctypes.POINTER(TileConfig)]
+        L.conv_direct_pad2.restype = i
+        L.conv_direct_pad2.argtypes = [vp, vp, vp] + [i] * 10
         L.conv_direct_layout.restype = i
         L.conv_direct_layout.argtypes = [vp, vp, vp] + [i] * 10 + [ctypes.POINTER(TileConfig)]
         L.conv_winograd.restype = i
@@ -178,12 +180,28 @@ def _dev_f32(t, name):
 
 
 def conv_direct(x, w, stride=1, pad=0, y=None, cfg=None):
-    """y = direct convolution of x [N][C][H][W] with w [K][C][R][S] on the current stream."""
+    """y = direct convolution of x [N][C][H][W] with w [K][C][R][S] on the current stream.  pad: zeros per
+    side, or (pad_h, pad_w) for a padding of its own per axis (tuned tile only)."""
     import torch
     N, C, H, W = x.shape
     K, C2, R, S = w.shape
     if C2 != C:
         raise ValueError("channel mismatch")
+    if isinstance(pad, (tuple, list)):
+        ph, pw = pad
+        if cfg is not None:
+            raise ValueError("cfg is available with one padding for both axes only")
+        if stride < 1 or ph < 0 or pw < 0 or H + 2 * ph < R or W + 2 * pw < S:
+            raise IolbError(-1, "invalid argument")
+        shape = (N, K, (H + 2 * ph - R) // stride + 1, (W + 2 * pw - S) // stride + 1)
+        if y is None:
+            y = torch.empty(shape, dtype=torch.float32, device=x.device)
+        elif tuple(y.shape) != shape:
+            raise ValueError("y has the wrong shape")
+        _use_current_stream()
+        _check(lib().conv_direct_pad2(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, R, S,
+                                      stride, ph, pw))
+        return y
     valid = stride >= 1 and pad >= 0 and H + 2 * pad >= R and W + 2 * pad >= S
     if valid:
         shape = (N, K, (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1)

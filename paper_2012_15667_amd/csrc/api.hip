@@ -155,13 +155,14 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
 // layout CWH: s, P, Q describe the transposed layer (H and W, R and S exchanged) and the weights are read
 // transposed; the tensors are then plain CHW tensors of that layer.
 int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, int P, int Q, const iolb_tile_config& cfg,
-               int layout = IOLB_LAYOUT_CHW)
+               int layout = IOLB_LAYOUT_CHW, int pad_w = -1)
 {
     DeviceState* dev = nullptr;
     int rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;
     iolb::DirectGeom g{};
     g.N = s.N; g.C = s.C; g.H = s.H; g.W = s.W; g.K = s.K; g.R = s.R; g.S = s.S; g.stride = s.stride; g.pad = s.pad;
+    g.pad_w = pad_w < 0 ? s.pad : pad_w;
     g.P = P; g.Q = Q;
     g.b = cfg.b; g.tx = cfg.x; g.ty = cfg.y; g.z = cfg.z; g.alpha = cfg.alpha;
     g.threads = cfg.threads; g.waves_m = cfg.waves_m; g.waves_n = cfg.waves_n;
@@ -346,6 +347,26 @@ int conv_direct(const float* x, const float* w, float* y, int N, int C, int H, i
     rc = tuned_tile(s, &cfg);
     if (rc != IOLB_OK) return rc;
     return run_direct(x, w, y, s, P, Q, cfg);
+}
+
+int conv_direct_pad2(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                     int stride, int pad_h, int pad_w)
+{
+    if (!x || !w || !y) return IOLB_EINVAL;
+    if (pad_h < 0 || pad_w < 0) return IOLB_EINVAL;
+    // The tile depends on the layer through its output extents only: tune the layer whose image already
+    // contains the zero borders (H + 2 pad_h by W + 2 pad_w, no padding), run the real one.
+    if ((int64_t)H + 2LL * pad_h > 0x7fffffffLL || (int64_t)W + 2LL * pad_w > 0x7fffffffLL) return IOLB_EINVAL;
+    const iolb_shape bordered{N, C, H + 2 * pad_h, W + 2 * pad_w, K, R, S, stride, 0, IOLB_DIRECT};
+    int P = 0, Q = 0;
+    int rc = iolb::validate_shape(bordered, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    if (H < 1 || W < 1) return IOLB_EINVAL;
+    iolb_tile_config cfg;
+    rc = tuned_tile(bordered, &cfg);
+    if (rc != IOLB_OK) return rc;
+    const iolb_shape s{N, C, H, W, K, R, S, stride, pad_h, IOLB_DIRECT};
+    return run_direct(x, w, y, s, P, Q, cfg, IOLB_LAYOUT_CHW, pad_w);
 }
 
 int conv_direct_layout(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,

@@ -41,7 +41,7 @@ direct_fma_kernel(const float* __restrict__ x, const float* __restrict__ w, floa
 #pragma unroll
     for (int j = 0; j < ZT; ++j) acc[j] = 0.f;
 
-    const int gy0 = y0 * g.stride - g.pad, gx0 = x0 * g.stride - g.pad;
+    const int gy0 = y0 * g.stride - g.pad, gx0 = x0 * g.stride - g.pad_w;
     for (int c0 = 0; c0 < g.C; c0 += g.alpha) {
         __syncthreads();
         for (int i = tid; i < g.alpha * g.halo; i += T) {

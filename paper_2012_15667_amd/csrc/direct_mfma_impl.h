@@ -106,7 +106,7 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[mb][nb][i] = 0.f;
 
-    const int gy0 = y0 * g.stride - g.pad, gx0 = x0 * g.stride - g.pad;
+    const int gy0 = y0 * g.stride - g.pad, gx0 = x0 * g.stride - g.pad_w;
     const int nwaves = T >> 6;
     const int tile_rows = g.b * g.yh;                       // rows of the input tile per channel
     const int nseg = (g.xh + 63) >> 6;                      // 64-lane segments per tile row

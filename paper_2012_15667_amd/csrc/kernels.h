@@ -11,7 +11,8 @@ namespace iolb {
 // Geometry of one direct-convolution launch: the layer, the output sub-block b * tx * ty * z of
 // Sec. 5.2 with its input tile xh * yh (x' * y' in the paper), and the block counts.
 struct DirectGeom {
-    int N, C, H, W, K, R, S, stride, pad, P, Q;
+    int N, C, H, W, K, R, S, stride, pad, P, Q;   // pad: rows of zeros above and below
+    int pad_w;                 // columns of zeros left and right (= pad except for conv_direct_pad2)
     int Kp;                    // MFMA path: K rounded up to a multiple of 32 (pitch of wt, extent of the z blocks)
     int b, tx, ty, z, alpha;
     int threads;               // workgroup size

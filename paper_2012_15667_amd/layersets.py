@@ -3,9 +3,9 @@ shape sweeps of the two direct-convolution figures, as synthetic layers (shapes 
 
   * MODELS: the distinct convolution shapes of VGG-19, ResNet-18/34, SqueezeNet 1.0 and Inception-v3 (the
     networks of the end-to-end experiment of Sec. 7.3), each with the number of times the network runs it,
-    written down from the architectures' published descriptions.  Layers that need a different padding per
-    axis (the 1x7 / 7x1 / 1x3 / 3x1 factorised kernels of Inception-v3) are not expressible with the single
-    `pad` argument of the library and are left out; the lists say so in `SKIPPED`.
+    written down from the architectures' published descriptions.  Layers that pad one axis only (the
+    1x7 / 7x1 / 1x3 / 3x1 factorised kernels of Inception-v3) carry a (pad_h, pad_w) pair and run through
+    conv_direct_pad2.
   * figure_sweep(): 3x3 kernels with C_in = 256 over input extents, output channels and strides (the sweep
     of the first figure of Sec. 7.1);
   * batch_sweep(): the same family at C_out = 256, stride 1, over batch sizes (the batched test of Sec. 7.1).
@@ -29,6 +29,18 @@ Conv = namedtuple("Conv", "name C H W K R S stride pad count")
 
 def _c(name, C, HW, K, R, stride, pad, count=1):
     return Conv(name, C, HW, HW, K, R, R, stride, pad, count)
+
+
+def _r(name, C, HW, K, R, S, count=1):
+    """R x S kernel, stride 1, padded to keep the extents: pad = ((R-1)/2, (S-1)/2), one axis only for 1 x n."""
+    return Conv(name, C, HW, HW, K, R, S, 1, ((R - 1) // 2, (S - 1) // 2), count)
+
+
+def _inception_17(c, tag, times=1):
+    """One InceptionC module at 17 x 17 with c channels in its 7-tap branches."""
+    return [_c("mixed6%s_1x1_c" % tag, 768, 17, c, 1, 1, 0, 2 * times),
+            _r("mixed6%s_1x7" % tag, c, 17, c, 1, 7, 2 * times), _r("mixed6%s_7x1" % tag, c, 17, c, 7, 1, 2 * times),
+            _r("mixed6%s_7x1_out" % tag, c, 17, 192, 7, 1, times), _r("mixed6%s_1x7_out" % tag, c, 17, 192, 1, 7, times)]
 
 
 MODELS = {
@@ -69,7 +81,7 @@ MODELS = {
         _c("fire9_s", 512, 13, 64, 1, 1, 0), _c("fire9_e1", 64, 13, 256, 1, 1, 0), _c("fire9_e3", 64, 13, 256, 3, 1, 1),
         _c("conv10", 512, 13, 1000, 1, 1, 0),
     ],
-    # stem and the square-kernel layers of the first inception stage (35 x 35 grid)
+    # stem, the 35 x 35 stage, the 17 x 17 stage with its factorised 7-tap kernels, the 8 x 8 stage
     "inception_v3": [
         _c("stem_1", 3, 299, 32, 3, 2, 0), _c("stem_2", 32, 149, 32, 3, 1, 0), _c("stem_3", 32, 147, 64, 3, 1, 1),
         _c("stem_4", 64, 73, 80, 1, 1, 0), _c("stem_5", 80, 73, 192, 3, 1, 0),
@@ -78,9 +90,22 @@ MODELS = {
         _c("mixed5c_1x1", 256, 35, 64, 1, 1, 0, 3), _c("mixed5c_1x1_48", 256, 35, 48, 1, 1, 0),
         _c("mixed5d_1x1", 288, 35, 64, 1, 1, 0, 3), _c("mixed5d_1x1_48", 288, 35, 48, 1, 1, 0),
         _c("mixed6a_3x3", 288, 35, 384, 3, 2, 0), _c("mixed6a_3x3b", 96, 35, 96, 3, 2, 0),
+        _c("mixed6a_1x1", 288, 35, 64, 1, 1, 0), _c("mixed6a_3x3a", 64, 35, 96, 3, 1, 1),
+        # 17 x 17: four modules (7-tap branches of 128, 160, 160, 192 channels); 1x1 to 192: twice per module
+        _c("mixed6_1x1_192", 768, 17, 192, 1, 1, 0, 8),
+    ] + _inception_17(128, "b") + _inception_17(160, "cd", 2) + _inception_17(192, "e") + [
+        # reduction to 8 x 8
+        _c("mixed7a_1x1", 768, 17, 192, 1, 1, 0, 2), _c("mixed7a_3x3", 192, 17, 320, 3, 2, 0),
+        _r("mixed7a_1x7", 192, 17, 192, 1, 7), _r("mixed7a_7x1", 192, 17, 192, 7, 1), _c("mixed7a_3x3b", 192, 17, 192, 3, 2, 0),
+        # 8 x 8: two modules, 1280 and 2048 input channels
+        _c("mixed7b_1x1_320", 1280, 8, 320, 1, 1, 0), _c("mixed7b_1x1_384", 1280, 8, 384, 1, 1, 0),
+        _c("mixed7b_1x1_448", 1280, 8, 448, 1, 1, 0), _c("mixed7b_1x1_192", 1280, 8, 192, 1, 1, 0),
+        _c("mixed7c_1x1_320", 2048, 8, 320, 1, 1, 0), _c("mixed7c_1x1_384", 2048, 8, 384, 1, 1, 0),
+        _c("mixed7c_1x1_448", 2048, 8, 448, 1, 1, 0), _c("mixed7c_1x1_192", 2048, 8, 192, 1, 1, 0),
+        _r("mixed7_1x3", 384, 8, 384, 1, 3, 4), _r("mixed7_3x1", 384, 8, 384, 3, 1, 4), _c("mixed7_3x3", 448, 8, 384, 3, 1, 1, 2),
     ],
 }
-SKIPPED = {"inception_v3": "layers with 1x7 / 7x1 / 1x3 / 3x1 kernels (per-axis padding) and the 17x17 / 8x8 stages"}
+SKIPPED = {}
 
 
 def figure_sweep():
@@ -95,8 +120,14 @@ def batch_sweep():
             for hw in (14, 28, 56, 112) for n in (1, 2, 4, 8, 16, 32, 64, 128)]
 
 
+def pads(L):
+    """(pad_h, pad_w) of a layer: its pad is one number for both axes or a pair."""
+    return tuple(L.pad) if isinstance(L.pad, (tuple, list)) else (L.pad, L.pad)
+
+
 def out_extents(L):
-    return (L.H + 2 * L.pad - L.R) // L.stride + 1, (L.W + 2 * L.pad - L.S) // L.stride + 1
+    ph, pw = pads(L)
+    return (L.H + 2 * ph - L.R) // L.stride + 1, (L.W + 2 * pw - L.S) // L.stride + 1
 
 
 def flops(N, L):
@@ -105,7 +136,7 @@ def flops(N, L):
 
 
 def winograd_applies(L):
-    return L.R == 3 and L.S == 3 and L.stride == 1
+    return L.R == 3 and L.S == 3 and L.stride == 1 and not isinstance(L.pad, (tuple, list))
 
 
 def time_layer(N, L, reps=5, seed=0):
@@ -133,7 +164,7 @@ def run(pairs, reps=5, out=sys.stdout):
         f = flops(N, L)
         best = min(ms, key=ms.get)
         rec = {"layer": L.name, "N": N, "C": L.C, "H": L.H, "W": L.W, "K": L.K, "R": L.R, "S": L.S,
-               "stride": L.stride, "pad": L.pad, "count": L.count, "gflop": round(f / 1e9, 3),
+               "stride": L.stride, "pad": list(pads(L)) if isinstance(L.pad, (tuple, list)) else L.pad, "count": L.count, "gflop": round(f / 1e9, 3),
                "ms": {a: round(t, 4) for a, t in ms.items()},
                "tflops_direct_equiv": {a: round(f / t / 1e9, 2) for a, t in ms.items()}, "best": best}
         records.append(rec)

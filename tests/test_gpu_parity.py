@@ -162,6 +162,23 @@ def test_direct_tiles_that_hang_over_the_edge(gpu, shape):
         assert rel_err(got.cpu().numpy(), _to_hwc(ref)) <= TOL_DIRECT, cfg
 
 
+@pytest.mark.parametrize("shape", [(2, 8, 17, 17, 32, 1, 7, 1, 0, 3), (2, 8, 17, 17, 32, 7, 1, 1, 3, 0),
+                                   (2, 16, 8, 8, 64, 1, 3, 1, 0, 1), (2, 16, 8, 8, 64, 3, 1, 1, 1, 0),
+                                   (3, 5, 20, 13, 16, 3, 5, 2, 0, 2), (1, 3, 35, 35, 32, 11, 11, 4, 2, 0),
+                                   (2, 6, 9, 9, 32, 3, 3, 1, 2, 1)])
+def test_direct_with_its_own_padding_per_axis(gpu, shape):
+    """pad_h rows and pad_w columns of zeros: against the oracle run on the explicitly bordered image."""
+    torch, B = gpu
+    N, C, H, W, K, R, S, stride, ph, pw = shape
+    x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=500 + H + R)
+    bordered = np.pad(x, ((0, 0), (0, 0), (ph, ph), (pw, pw)))
+    ref = conv_ref(bordered, w, stride, 0)
+    y = B.conv_direct(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), stride, (ph, pw))
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == ref.shape
+    assert rel_err(y.cpu().numpy(), ref) <= TOL_DIRECT
+
+
 @pytest.mark.parametrize("name", ["cfg5a", "cfg5b", "cfg5c", "cfg5d"])
 def test_direct_full_size_sampled(gpu, name):
     """Full-size VGG-style layers in the launch configuration the benchmark times; 4096 sampled

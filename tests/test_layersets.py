@@ -10,7 +10,8 @@ def _macs(model):
     return sum(LS.flops(1, L) / 2 * L.count for L in LS.MODELS[model])
 
 
-@pytest.mark.parametrize("model,gmacs,layers", [("vgg19", 19.51, 16), ("resnet18", 1.813, 20), ("resnet34", 3.66, 36)])
+@pytest.mark.parametrize("model,gmacs,layers", [("vgg19", 19.51, 16), ("resnet18", 1.813, 20), ("resnet34", 3.66, 36),
+                                                 ("inception_v3", 5.71, 94)])
 def test_convolution_work_matches_the_published_totals(model, gmacs, layers):
     assert _macs(model) / 1e9 == pytest.approx(gmacs, rel=0.01)
     assert sum(L.count for L in LS.MODELS[model]) == layers
@@ -32,7 +33,11 @@ def test_every_layer_has_a_tile(model):
     for L in LS.MODELS[model]:
         P, Q = LS.out_extents(L)
         assert P >= 1 and Q >= 1
-        cfg = B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad))
+        ph, pw = LS.pads(L)
+        if ph == pw:
+            cfg = B.iolb_tune(B.make_shape(8, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, ph))
+        else:       # per-axis padding: the library tunes the layer whose image already holds the zero borders
+            cfg = B.iolb_tune(B.make_shape(8, L.C, L.H + 2 * ph, L.W + 2 * pw, L.K, L.R, L.S, L.stride, 0))
         Kz = -(-L.K // 32) * 32 if cfg["path"] == B.PATH_MFMA else L.K
         # tile extents: factors of the output extent or a balanced cut into up to 8 tiles
         fits = lambda n, t: n % t == 0 or any(t == -(-n // k) for k in range(1, 9))
@@ -47,3 +52,17 @@ def test_sweeps_have_the_stated_shapes():
     assert len(fig) == 4 * 4 * 2 and all(L.C == 256 and L.R == 3 for L in fig)
     bs = LS.batch_sweep()
     assert len(bs) == 32 and {n for n, _ in bs} == {1, 2, 4, 8, 16, 32, 64, 128}
+
+
+def test_inception_modules_chain_and_keep_their_extents():
+    """The factorised kernels pad one axis only and keep 17 x 17 / 8 x 8; the concatenated branch outputs give
+    the next stage's input channels (64 + 64 + 96 + 32 = 256, ..., 4 x 192 = 768, 320 + 192 + 768 = 1280)."""
+    by = {L.name: L for L in LS.MODELS["inception_v3"]}
+    for name, L in by.items():
+        if L.R != L.S:
+            assert LS.out_extents(L) == (L.H, L.W), name
+            assert sorted(LS.pads(L)) == [0, (max(L.R, L.S) - 1) // 2], name
+    assert by["mixed5c_1x1"].C == 64 + 64 + 96 + 32 and by["mixed5d_1x1"].C == 64 + 64 + 96 + 64
+    assert by["mixed6_1x1_192"].C == 384 + 96 + 288 == 4 * 192
+    assert by["mixed7b_1x1_320"].C == 320 + 192 + 768 and by["mixed7c_1x1_320"].C == 320 + 2 * 384 + 2 * 384 + 192
+    assert LS.out_extents(by["mixed7a_3x3"]) == (8, 8) and LS.out_extents(by["mixed6a_3x3"]) == (17, 17)
