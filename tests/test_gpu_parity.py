@@ -649,6 +649,13 @@ def test_error_codes(gpu):
     with pytest.raises(B.IolbError) as e:
         B.conv_winograd(x, w, 4, y=y, workspace=ws)
     assert e.value.code == -4
+    L = B.lib()
+    p = [ctypes.c_void_p(t.data_ptr()) for t in (x, w, y)]
+    assert L.conv_direct_pad2(*p, 1, 4, 8, 8, 32, 3, 3, 1, -1, 1) == -1          # negative padding
+    assert L.conv_direct_pad2(None, p[1], p[2], 1, 4, 8, 8, 32, 3, 3, 1, 1, 1) == -1
+    assert L.conv_winograd_pad(*p, 1, 4, 8, 8, 32, 5, 1) == -2                   # m = 5
+    assert L.conv_winograd_pad(*p, 1, 4, 8, 8, 32, 4, -1) == -1
+    assert L.conv_winograd_pad(p[0], None, p[2], 1, 4, 8, 8, 32, 4, 1) == -1
     torch.cuda.synchronize()
     assert float(y.min()) == 7.0 and float(y.max()) == 7.0      # failed calls wrote nothing
 
