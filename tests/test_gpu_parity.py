@@ -578,6 +578,52 @@ def test_calls_can_be_captured_in_a_hip_graph(gpu):
         assert rel_err(got_d, ref) <= TOL_DIRECT and rel_err(got_w, ref) <= TOL_WINO, rep
 
 
+def test_padded_and_fused_calls_can_be_captured_too(gpu):
+    """The fused thin-layer Winograd kernel, conv_winograd_pad and conv_direct_pad2 use the library's workspace:
+    after an eager call of each shape a capture records kernels only.  Two replays on new inputs, eager work in
+    between, each equal to the eager result bit for bit."""
+    torch, B = gpu
+    N, H, W = 2, 20, 22
+    xa, wa = make_inputs(N, 3, H, W, 16, 3, 3, "u01", "he", seed=81)        # thin layer: fused F(2x2)
+    xb, wb = make_inputs(N, 8, H, W, 32, 3, 3, "u01", "he", seed=82)        # F(4x4), pad 0
+    xc, wc = make_inputs(N, 8, H, W, 32, 1, 7, "u01", "he", seed=83)        # 1x7, pad (0, 3)
+    dev = [torch.from_numpy(a).cuda() for a in (xa, wa, xb, wb, xc, wc)]
+    ya = torch.empty((N, 16, H, W), device="cuda")
+    yb = torch.empty((N, 32, H - 2, W - 2), device="cuda")
+    yc = torch.empty((N, 32, H, W), device="cuda")
+
+    def calls():
+        B.conv_winograd(dev[0], dev[1], 2, y=ya)
+        B.conv_winograd(dev[2], dev[3], 4, y=yb, pad=0)
+        B.conv_direct(dev[4], dev[5], 1, (0, 3), y=yc)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        calls()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        calls()
+    for rep in range(2):
+        for t, (n, c) in zip((dev[0], dev[2], dev[4]), ((N, 3), (N, 8), (N, 8))):
+            t.copy_(torch.rand((n, c, H, W), device="cuda"))
+        for y in (ya, yb, yc):
+            y.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [y.clone() for y in (ya, yb, yc)]
+        calls()                                                     # eager, same inputs
+        torch.cuda.synchronize()
+        for g, y in zip(got, (ya, yb, yc)):
+            assert torch.equal(g, y), rep
+        ref = conv_ref(np.pad(dev[4].cpu().numpy(), ((0, 0), (0, 0), (0, 0), (3, 3))), wc, 1, 0)
+        assert rel_err(got[2].cpu().numpy(), ref) <= TOL_DIRECT
+        assert rel_err(got[1].cpu().numpy(), conv_ref(dev[2].cpu().numpy(), wb, 1, 0)) <= TOL_WINO
+        assert rel_err(got[0].cpu().numpy(), conv_ref(dev[0].cpu().numpy(), wa, 1, 1)) <= TOL_WINO
+
+
 def test_layout_error_codes(gpu):
     torch, B = gpu
     x = torch.zeros((1, 8, 8, 4), dtype=torch.float32, device="cuda")
