@@ -117,6 +117,18 @@ def test_invalid_arguments_are_rejected_without_a_gpu():
     assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 5) == 0
     assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 3) > 0
     assert B.winograd_workspace_bytes(1, 8, 8, 8, 32, 4) > 0
+    # the padded entry points check their arguments before any GPU call (the pointers are never followed)
+    import ctypes
+    L = B.lib()
+    fake = [ctypes.c_void_p(4096)] * 3
+    assert L.conv_direct_pad2(None, None, None, 1, 4, 8, 8, 32, 3, 3, 1, 1, 1) == -1
+    assert L.conv_direct_pad2(*fake, 1, 4, 8, 8, 32, 3, 3, 1, -1, 0) == -1
+    assert L.conv_direct_pad2(*fake, 1, 4, 8, 4, 32, 1, 7, 1, 0, 1) == -1          # W + 2 pad_w < S
+    assert L.conv_direct_pad2(*fake, 1, 4, 8, 8, 32, 3, 3, 0, 1, 1) == -1          # stride 0
+    assert L.conv_winograd_pad(None, None, None, 1, 4, 8, 8, 32, 4, 1) == -1
+    assert L.conv_winograd_pad(*fake, 1, 4, 8, 8, 32, 5, 1) == -2                   # m = 5
+    assert L.conv_winograd_pad(*fake, 1, 4, 8, 8, 32, 4, -1) == -1
+    assert L.conv_winograd_pad(*fake, 1, 4, 2, 2, 32, 4, 0) == -1                   # H + 2 pad < 3
 
 
 @pytest.mark.parametrize("m", [2, 3, 4, 6])
