@@ -34,7 +34,8 @@ extern "C" {
 #define IOLB_EHIP         -5   /* a HIP runtime call or launch failed; see iolb_last_hip_error */
 
 enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2, IOLB_WINO_F3 = 3, IOLB_WINO_F6 = 4 };
-enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1 };
+enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1, IOLB_PATH_FUSED = 2 };   /* FUSED: Winograd only, all four steps in
+                                                                           one matrix-core kernel (Sec. 5.3) */
 enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1, IOLB_LAYOUT_CWH = 2 };   /* per image: channels outermost, channels
                                                                            innermost, channels outermost with W before H */
 
@@ -173,11 +174,12 @@ int iolb_winograd_matrices(int m, float* A, float* L, float* B);
 int iolb_set_stream(void* hip_stream);
 
 /* Timing hook for benchmarks: when enabled, the main kernel of each conv call is bracketed by
- * HIP events on the call's stream.  Kinds: the direct-convolution kernel (IOLB_TIME_DIRECT) and
- * the Winograd batched product (IOLB_TIME_WINO_PRODUCT).  iolb_timing_read waits for the recorded
+ * HIP events on the call's stream.  Kinds: the direct-convolution kernel (IOLB_TIME_DIRECT), the
+ * Winograd batched product (IOLB_TIME_WINO_PRODUCT) and the fused Winograd matrix-core kernel
+ * (IOLB_TIME_WINO_FUSED).  iolb_timing_read waits for the recorded
  * events of one kind, returns how many launches were timed since the last read of that kind and
  * their total duration in milliseconds, and forgets them. */
-enum { IOLB_TIME_DIRECT = 0, IOLB_TIME_WINO_PRODUCT = 1 };
+enum { IOLB_TIME_DIRECT = 0, IOLB_TIME_WINO_PRODUCT = 1, IOLB_TIME_WINO_FUSED = 2 };
 int iolb_timing_enable(int on);
 int iolb_timing_read(int kind, int* launches, float* total_ms);
 

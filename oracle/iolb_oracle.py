@@ -16,7 +16,7 @@ from math import isqrt, sqrt
 
 DIRECT, WINO_F2, WINO_F4, WINO_F3, WINO_F6 = 0, 1, 2, 3, 4
 WINO_E = {WINO_F2: 2, WINO_F3: 3, WINO_F4: 4, WINO_F6: 6}     # output tile extent e of each Winograd algo id
-PATH_FMA, PATH_MFMA = 0, 1
+PATH_FMA, PATH_MFMA, PATH_FUSED = 0, 1, 2
 
 # ------------------------------------------------------------------------------------------
 # shapes
@@ -406,7 +406,16 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
     return cands
 
 
-def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
+# Fused matrix-core blocks (every plane of a tb x z block resident in accumulator registers, Sec. 5.3), one per
+# kernel instantiation of the library: (e, tb, z, alpha, threads, waves_m, waves_n, lds_bytes, acc)
+FUSED_BLOCKS = (
+    (2, 64, 64, 8, 256, 2, 2, 131072, 256),
+    (2, 64, 64, 8, 512, 4, 2, 131072, 128),
+    (4, 32, 64, 4, 256, 4, 1, 131072, 288),
+)
+
+
+def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs=True):
     """Winograd: the resident block is one transformed plane of `tb` sub-domains by z output
     channels (the channel-summation temporaries of step 3); per channel it reads tb transformed
     inputs and z transformed weights, for each of the (e+r-1)^2 planes.  Reported as a strip of
@@ -428,6 +437,17 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
         cands.append(((-(1 << 62), qread, 0, 0, Kz, 256),
                       dict(b=1, x=e * 256, y=e, z=Kz, alpha=C, threads=256, waves_m=1, waves_n=4,
                            path=PATH_FMA, wt_mode=1, lds_bytes_used=0, acc_regs_per_thread=n2 * C,
+                           q_read_elems=qread, q_write_elems=N * K * P * Q)))
+    # Fused blocks, any channel count: per channel a block reads the input windows of its tb sub-domains (a strip
+    # of e tb + 2 by e + 2 pixels) and (e+2)^2 z transformed weights.  Ranked after the unfused tiles.
+    for fe, ftb, fz, falpha, fT, fwm, fwn, flds, facc in FUSED_BLOCKS:
+        if fe != e or (lds_bytes and flds > lds_bytes) or (not auto_regs and facc > vgpr_budget):
+            continue
+        nblocks = (-(-tiles // ftb)) * (-(-K // fz))
+        qread = nblocks * C * ((e * ftb + 2) * (e + 2) + n2 * fz)
+        cands.append(((1, qread, 0, 0, fz, fT),
+                      dict(b=1, x=e * ftb, y=e, z=fz, alpha=falpha, threads=fT, waves_m=fwm, waves_n=fwn,
+                           path=PATH_FUSED, wt_mode=1, lds_bytes_used=flds, acc_regs_per_thread=facc,
                            q_read_elems=qread, q_write_elems=N * K * P * Q)))
     for tb in range(32, min(tb_top, 1024) + 1, 32):
         for z in divisors(Kz):
@@ -453,7 +473,7 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3):
     return cands
 
 
-def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True):
+def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True, auto_regs=True):
     """Every feasible tile with its ordering key (smaller is better); the MFMA path is preferred
     whenever it has a feasible tile.  Also what the exhaustive sweep enumerates (use_f3=False)."""
     s = shape
@@ -469,15 +489,15 @@ def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True):
             c = c + _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
         return c
     e = WINO_E[s["algo"]]
-    return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3)
+    return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs)
 
 
-def tune(shape, lds_bytes=0, vgpr_budget=128):
+def tune(shape, lds_bytes=0, vgpr_budget=128, auto_regs=True):
     """The tile the library's iolb_tune must return, or None when nothing fits.  Direct convolution ranks
     the whole domain by modelled time; Winograd looks inside the optimality box first."""
-    c = candidates(shape, lds_bytes, vgpr_budget, shape["algo"] != DIRECT)
-    if not c:
-        c = candidates(shape, lds_bytes, vgpr_budget, False)   # tiny layers: drop the box
+    c = candidates(shape, lds_bytes, vgpr_budget, shape["algo"] != DIRECT, auto_regs)
+    if not c or min(k for k, _ in c)[0] > 0:
+        c = candidates(shape, lds_bytes, vgpr_budget, False, auto_regs)   # tiny layers: drop the box
     if not c:
         return None
     return min(c, key=lambda kv: kv[0])[1]

@@ -66,7 +66,7 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // ---- timing hook --------------------------------------------------------------------------
 bool g_timing = false;
-std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events[2];
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_events[3];
 
 struct MainKernelTimer {
     hipEvent_t a = nullptr, b = nullptr;
@@ -211,14 +211,16 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
     g->z = cfg.z;
     g->alpha = cfg.alpha;
     g->Cp = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;
-    g->Kp = (s.K + 31) / 32 * 32;
+    // the fused matrix-core kernel covers K with whole z-channel blocks, the other paths with 32-channel blocks
+    g->Kp = cfg.path == IOLB_PATH_FUSED ? (s.K + cfg.z - 1) / cfg.z * cfg.z : (s.K + 31) / 32 * 32;
     g->CpU = g->Cp;
     g->waves_m = cfg.waves_m;
     g->waves_n = cfg.waves_n;
     const int64_t pitch = (tiles + g->tb - 1) / g->tb * g->tb;
     const int64_t n2 = (int64_t)(m + 2) * (m + 2);
     // V and M of the unfused path are indexed with 32-bit element counts
-    if (cfg.path != IOLB_PATH_FMA && (n2 * g->Cp * pitch >= (1LL << 31) || n2 * g->Kp * pitch >= (1LL << 31))) return IOLB_EINVAL;
+    if (cfg.path == IOLB_PATH_MFMA && (n2 * g->Cp * pitch >= (1LL << 31) || n2 * g->Kp * pitch >= (1LL << 31))) return IOLB_EINVAL;
+    if (n2 * g->Cp * g->Kp >= (1LL << 31)) return IOLB_EINVAL;
     g->tiles = (int)tiles;
     g->tiles_pitch = (int)pitch;
     return IOLB_OK;
@@ -227,17 +229,37 @@ int winograd_geom(const iolb_shape& s, const iolb_tile_config& cfg, iolb::WinoGe
 struct WinoWorkspace {
     size_t u_off, v_off, m_off, total;
 };
-// fused: the one-kernel path keeps the transformed inputs and the channel sums in registers; the workspace
-// holds U and, in V's place, U again as one row per output channel
-WinoWorkspace winograd_layout(int C, int K, int m, int64_t tiles_pitch, bool fused = false)
+// path: the tile's path.  IOLB_PATH_MFMA (unfused): U, V, M.  IOLB_PATH_FMA (thin layers, one kernel with the
+// transformed inputs and the channel sums in registers): U and, in V's place, U again as one row per output
+// channel.  IOLB_PATH_FUSED (one matrix-core kernel): U in the channel-pair layout and, in V's place, room
+// for a second copy (used when the caller brings plane-major transformed kernels).
+WinoWorkspace winograd_layout(int C, int K, int m, int64_t tiles_pitch, int path = IOLB_PATH_MFMA)
 {
     const size_t n2 = (size_t)(m + 2) * (m + 2);
+    const size_t ubytes = align256(sizeof(float) * n2 * C * K);
     WinoWorkspace l;
     l.u_off = 0;
-    l.v_off = l.u_off + align256(sizeof(float) * n2 * C * K);
-    l.m_off = l.v_off + align256(fused ? sizeof(float) * K * iolb::wino_fused_row(m, C) : sizeof(float) * n2 * C * tiles_pitch);
-    l.total = l.m_off + (fused ? 0 : align256(sizeof(float) * n2 * K * tiles_pitch));
+    l.v_off = l.u_off + ubytes;
+    if (path == IOLB_PATH_FMA) {
+        l.m_off = l.v_off + align256(sizeof(float) * K * iolb::wino_fused_row(m, C));
+        l.total = l.m_off;
+    } else if (path == IOLB_PATH_FUSED) {
+        l.m_off = l.v_off + ubytes;
+        l.total = l.m_off;
+    } else {
+        l.m_off = l.v_off + align256(sizeof(float) * n2 * C * tiles_pitch);
+        l.total = l.m_off + align256(sizeof(float) * n2 * K * tiles_pitch);
+    }
     return l;
+}
+
+// Largest workspace any tile of the enumeration can ask for: unfused blocks hold at most 1024 sub-domains and
+// stages at most 16 channels; the fused matrix-core blocks cover K with blocks of up to 64 channels.
+size_t winograd_workspace_max(int C, int K, int m, int64_t tiles)
+{
+    const size_t unfused = winograd_layout(C + 15, (K + 31) / 32 * 32, m, tiles + 1024).total;
+    const size_t fused = winograd_layout(C + 15, (K + 63) / 64 * 64, m, 0, IOLB_PATH_FUSED).total;
+    return unfused > fused ? unfused : fused;
 }
 
 int make_wino_shape(int N, int C, int H, int W, int K, int m, iolb_shape* s, int pad = 1)
@@ -270,7 +292,7 @@ int run_winograd(const float* x, const float* w, const float* Upre, float* y, co
     rc = winograd_geom(s, cfg, &g);
     if (rc != IOLB_OK) return rc;
     const bool fused = cfg.path == IOLB_PATH_FMA;
-    const WinoWorkspace l = winograd_layout(g.Cp, g.Kp, g.m, g.tiles_pitch, fused);
+    const WinoWorkspace l = winograd_layout(g.Cp, g.Kp, g.m, g.tiles_pitch, cfg.path);
     if (!ws || ws_bytes < l.total || (reinterpret_cast<uintptr_t>(ws) & 255)) return IOLB_EWORKSPACE;
     char* base = static_cast<char*>(ws);
     float* U = reinterpret_cast<float*>(base + l.u_off);
@@ -278,6 +300,19 @@ int run_winograd(const float* x, const float* w, const float* Upre, float* y, co
     float* M = reinterpret_cast<float*>(base + l.m_off);
     hipStream_t st = t_stream;
     const float* Uuse = U;
+    if (cfg.path == IOLB_PATH_FUSED) {
+        // the transformed kernels in the channel-pair layout: made from w, or re-laid out from the caller's
+        if (w) {
+            IOLB_HIP(iolb::launch_wino_kernel_transform_paired(w, U, g, st));
+        } else {
+            IOLB_HIP(iolb::launch_wino_pair_relayout(Upre, pretransformed_rows(s.C), (s.K + 31) / 32 * 32, V, g, st));
+            Uuse = V;
+        }
+        MainKernelTimer timer(st, IOLB_TIME_WINO_FUSED);
+        IOLB_HIP(iolb::launch_wino_fused_mfma(x, Uuse, y, g, st));
+        timer.stop(st);
+        return IOLB_OK;
+    }
     if (w) {
         IOLB_HIP(iolb::launch_wino_kernel_transform(w, U, g, st));
     } else {
@@ -396,9 +431,9 @@ size_t conv_winograd_workspace_bytes(int N, int C, int H, int W, int K, int m)
 {
     iolb_shape s;
     if (make_wino_shape(N, C, H, W, K, m, &s) != IOLB_OK) return 0;
-    // large enough for every tile the enumeration can produce: blocks hold at most 1024 sub-domains
+    // large enough for every tile the enumeration can produce
     const int64_t tiles = (int64_t)N * ((H + m - 1) / m) * ((W + m - 1) / m);
-    return winograd_layout(C + 15, (K + 31) / 32 * 32, m, tiles + 1024).total;     // stages hold at most 16 channels
+    return winograd_workspace_max(C, K, m, tiles);
 }
 
 int conv_winograd_ws(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m,
@@ -468,8 +503,8 @@ int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H,
     iolb_tile_config tile;
     rc = tuned_tile(s, &tile);
     if (rc != IOLB_OK) return rc;
-    // the one-kernel path stores the transformed kernels only
-    const size_t bytes = tile.path == IOLB_PATH_FMA ? winograd_layout(C, (K + 31) / 32 * 32, m, 0, true).total
+    // the one-kernel paths store the transformed kernels only
+    const size_t bytes = tile.path == IOLB_PATH_FMA ? winograd_layout(C, (K + 31) / 32 * 32, m, 0, IOLB_PATH_FMA).total
                                                     : conv_winograd_workspace_bytes(N, C, H, W, K, m);
     DeviceState* dev = nullptr;
     rc = device_state(&dev);
@@ -491,8 +526,8 @@ int conv_winograd_pad(const float* x, const float* w, float* y, int N, int C, in
     // workspace for the output extents of this padding
     const int P = H + 2 * pad - 2, Q = W + 2 * pad - 2;
     const int64_t tiles = (int64_t)N * ((P + m - 1) / m) * ((Q + m - 1) / m);
-    const size_t bytes = tile.path == IOLB_PATH_FMA ? winograd_layout(C, (K + 31) / 32 * 32, m, 0, true).total
-                                                    : winograd_layout(C + 15, (K + 31) / 32 * 32, m, tiles + 1024).total;
+    const size_t bytes = tile.path == IOLB_PATH_FMA ? winograd_layout(C, (K + 31) / 32 * 32, m, 0, IOLB_PATH_FMA).total
+                                                    : winograd_workspace_max(C, K, m, tiles);
     DeviceState* dev = nullptr;
     rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;
@@ -539,7 +574,7 @@ int iolb_timing_enable(int on)
 
 int iolb_timing_read(int kind, int* launches, float* total_ms)
 {
-    if (!launches || !total_ms || kind < 0 || kind > 1) return IOLB_EINVAL;
+    if (!launches || !total_ms || kind < 0 || kind > 2) return IOLB_EINVAL;
     std::lock_guard<std::mutex> lock(g_mutex);
     float sum = 0.f;
     int count = 0;

@@ -64,6 +64,14 @@ int wino_fused_row(int m, int C);
 hipError_t launch_wino_fused_relayout(const float* U, float* Uk, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_fused(const float* x, const float* Uk, float* y, const WinoGeom& g, hipStream_t st);
 
+// All four steps in one matrix-core kernel for any channel count, m in {2, 4} (wino_fused_mfma.hip).  Its
+// transformed kernels are U2[c / 2][xi][k][c % 2] with g.Cp rows (a multiple of g.alpha) and g.Kp columns (a
+// multiple of g.z), written from w by launch_wino_kernel_transform_paired or re-laid out from a plane-major
+// U[xi][rows][cols] by launch_wino_pair_relayout.  g.tb, g.z, g.alpha, g.waves_m, g.waves_n select the block.
+hipError_t launch_wino_kernel_transform_paired(const float* w, float* U2, const WinoGeom& g, hipStream_t st);
+hipError_t launch_wino_pair_relayout(const float* U, int rows, int cols, float* U2, const WinoGeom& g, hipStream_t st);
+hipError_t launch_wino_fused_mfma(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st);
+
 // Ceiling probes (probe.hip).  The copy moves bytes / 16 16-byte pieces; the MFMA loop runs
 // PROBE_MFMA_BLOCKS workgroups of four waves, each wave PROBE_ACC MFMAs (4096 flop each) per iteration, and
 // writes PROBE_MFMA_BLOCKS * 256 floats to sink.

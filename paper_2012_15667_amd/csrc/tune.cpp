@@ -247,7 +247,16 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
 // Winograd: the resident block is tb sub-domains by z output channels of ONE transformed plane
 // (the channel-summation temporaries of step 3); per channel it reads tb transformed inputs and
 // z transformed weights, for each of the (m+2)^2 planes.
-void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_bytes, int vgpr_budget,
+// The fused matrix-core blocks of wino_fused_mfma.hip: every plane of a tb x z block resident in accumulator
+// registers (Sec. 5.3).  Each entry is one kernel instantiation.
+struct FusedBlock { int m, tb, z, alpha, threads, waves_m, waves_n, lds_bytes, acc; };
+constexpr FusedBlock kFusedBlocks[] = {
+    {2, 64, 64, 8, 256, 2, 2, 131072, 256},     // one wave per block, all 16 planes
+    {2, 64, 64, 8, 512, 4, 2, 131072, 128},     // two waves per block, 8 planes each
+    {4, 32, 64, 4, 256, 4, 1, 131072, 288},     // two waves per block, 18 planes each
+};
+
+void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_bytes, int vgpr_budget, bool auto_regs,
                          bool use_box, std::vector<Candidate>* out) {
     static const int alphas[] = {16, 8, 4};
     const int64_t planes = (int64_t)(m + 2) * (m + 2);
@@ -272,6 +281,27 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
         c.cfg.q_read_elems = nblocks * s.C * planes * (256 + Kz);
         c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
         c.key = {-(1LL << 62), 0, c.cfg.q_read_elems, 0, 0, Kz, 256, 0, 0, 0};
+        out->push_back(c);
+    }
+    // Fused blocks for any channel count: per channel a block reads the input windows of its tb sub-domains
+    // (a strip of m tb + 2 by m + 2 pixels) and (m+2)^2 z transformed weights, and nothing else.  They rank
+    // after the unfused tiles of the same layer until a caller asks for one (key[0] = 1).
+    for (const FusedBlock& f : kFusedBlocks) {
+        if (f.m != m) continue;
+        if (lds_bytes && f.lds_bytes > lds_bytes) continue;
+        if (!auto_regs && f.acc > vgpr_budget) continue;
+        const int64_t Kf = ceil_div(s.K, f.z) * f.z;
+        const int64_t nblocks = ceil_div(tiles, f.tb) * (Kf / f.z);
+        Candidate c{};
+        c.cfg.b = 1; c.cfg.x = m * f.tb; c.cfg.y = m; c.cfg.z = f.z;
+        c.cfg.alpha = f.alpha;
+        c.cfg.threads = f.threads; c.cfg.waves_m = f.waves_m; c.cfg.waves_n = f.waves_n;
+        c.cfg.path = IOLB_PATH_FUSED; c.cfg.wt_mode = 1;
+        c.cfg.lds_bytes_used = f.lds_bytes;
+        c.cfg.acc_regs_per_thread = f.acc;
+        c.cfg.q_read_elems = nblocks * s.C * ((int64_t)(m * f.tb + 2) * (m + 2) + planes * f.z);
+        c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+        c.key = {1, 0, c.cfg.q_read_elems, 0, 0, f.z, f.threads, 0, 0, 0};
         out->push_back(c);
     }
     const auto fz = factors_of(Kz);
@@ -343,6 +373,7 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
     const int rc = validate_shape(s, &P, &Q);
     if (rc != IOLB_OK) return rc;
     if (lds_bytes < 0) lds_bytes = 0;       // 0: per-tile automatic budget
+    const bool auto_regs = vgpr_budget <= 0;
     if (vgpr_budget <= 0) vgpr_budget = 128;
     out->clear();
     if (s.algo == IOLB_DIRECT) {
@@ -357,7 +388,7 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
         const bool fma = most_pixels < 64;
         if (fma) direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_FMA, use_box, out);
     } else {
-        winograd_candidates(s, P, Q, winograd_m(s.algo), lds_bytes, vgpr_budget, use_box, out);
+        winograd_candidates(s, P, Q, winograd_m(s.algo), lds_bytes, vgpr_budget, auto_regs, use_box, out);
     }
     std::sort(out->begin(), out->end(), [](const Candidate& a, const Candidate& b) { return a.key < b.key; });
     return IOLB_OK;
@@ -369,7 +400,7 @@ int tune(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, iolb_tile_conf
     // iolb_enumerate as the pruning device of the measured search).  Winograd: box first.
     int rc = enumerate(s, lds_bytes, vgpr_budget, s.algo != IOLB_DIRECT, &c);
     if (rc != IOLB_OK) return rc;
-    if (c.empty()) {                       // tiny layers: nothing inside the box, search the whole domain
+    if (c.empty() || c.front().key[0] > 0) {   // tiny layers: no unfused tile inside the box, search the whole domain
         rc = enumerate(s, lds_bytes, vgpr_budget, false, &c);
         if (rc != IOLB_OK) return rc;
     }

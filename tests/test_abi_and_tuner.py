@@ -57,7 +57,7 @@ BUDGETS = [(0, 0), (32768, 64), (163840, 128), (8192, 32)]
 @pytest.mark.parametrize("s", SHAPES)
 @pytest.mark.parametrize("lds,vg", BUDGETS)
 def test_tuner_bit_exact_against_oracle(s, lds, vg):
-    want = o.tune(s, lds, vg or 128)
+    want = o.tune(s, lds, vg or 128, auto_regs=(vg == 0))
     sh = B.make_shape(**s)
     if want is None:
         with pytest.raises(B.IolbError) as e:

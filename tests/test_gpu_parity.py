@@ -422,6 +422,32 @@ def test_winograd_caller_workspace_and_tiles(gpu):
         assert rel_err(got, ref) <= TOL_WINO, cfg
 
 
+def _fused_blocks(B, N, C, H, W, K, m):
+    algo = {2: B.WINO_F2, 4: B.WINO_F4}[m]
+    tiles = B.iolb_enumerate(B.make_shape(N, C, H, W, K, algo=algo), 0, 0, False)
+    return [t for t in tiles if t["path"] == B.PATH_FUSED]
+
+
+@pytest.mark.parametrize("case", [c for c in WINO_CASES if c[0] in (2, 4)] + [
+    (2, 3, 24, 30, 34, 96),      # several blocks of 64 sub-domains and a ragged last one; K = 1.5 blocks of 64
+    (4, 2, 40, 22, 26, 160),     # several stages of 4 channels; K = 2.5 blocks of 64
+    (2, 5, 9, 3, 3, 40),         # fewer sub-domains per image than a block holds: a block spans several images
+    (4, 70, 5, 2, 2, 32),        # one sub-domain per image
+])
+def test_winograd_fused_matrix_core_blocks_match_direct_oracle(gpu, case):
+    """The fused matrix-core kernel (every plane of a block resident in registers) on each of its block shapes."""
+    torch, B = gpu
+    m, N, C, H, W, K = case
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u11", "he", seed=500 + m + C)
+    ref = conv_ref(x, w, 1, 1)
+    blocks = _fused_blocks(B, N, C, H, W, K, m)
+    assert blocks
+    for cfg in blocks:
+        got = _run_wino(gpu, x, w, m, cfg=cfg)
+        assert got.shape == ref.shape
+        assert rel_err(got, ref) <= TOL_WINO, cfg
+
+
 FUSED_CASES = [
     # m, N, C, H, W, K: thin layers that run as one fused kernel (C <= 4, C (m+2)^2 <= 128)
     (2, 2, 1, 8, 8, 5), (2, 2, 3, 37, 41, 33), (2, 1, 4, 7, 9, 64), (2, 3, 2, 16, 16, 7),
