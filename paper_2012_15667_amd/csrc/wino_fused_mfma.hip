@@ -102,7 +102,12 @@ __device__ __forceinline__ void output_rows(const float (&pi)[NR][M + 2], float 
 // M: output tile edge.  RG: row groups (waves per 32 x 32 block).  WT x WK: blocks of the workgroup along
 // sub-domains and channels (tb = 32 WT, z = 32 WK).  ALPHA: channels per stage.  CPT: channels per
 // transform task (2: a lane transforms a channel pair and writes 8-byte pairs; 1: one channel, 4-byte writes).
-template <int M, int RG, int WT, int WK, int ALPHA, int CPT>
+// VEC (pad = 1, W a multiple of M, x aligned to 4 M bytes): a lane loads the M columns under its own
+// sub-domain as one aligned vector per window row and takes the two border columns from its neighbour lanes
+// (the sub-domains left and right of it; a border column outside the image is zero anyway), which replaces
+// (M+2)^2 four-byte loads per window by M+2 wide ones; the first and the last lane of a block, whose
+// neighbours belong to other workgroups, load their outer border column themselves.
+template <int M, int RG, int WT, int WK, int ALPHA, int CPT, bool VEC>
 __global__ void __launch_bounds__(64 * RG * WT * WK, 1)
 wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2, float* __restrict__ y, WinoGeom g)
 {
@@ -135,8 +140,12 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
     const int tpi = g.th * g.tw;                                   // sub-domains per image
     const int img0 = t0 / tpi;
     const int HW = g.H * g.W;
-    unsigned voff[n][n];                                           // byte offsets of the window from the channel base
+    typedef float vecm __attribute__((ext_vector_type(M)));
+    unsigned voff[VEC ? 1 : n][VEC ? 1 : n];                       // scalar path: byte offsets of the window elements
+    unsigned vrow[VEC ? n : 1];                                    // vector path: byte offsets of the own columns per row
     bool rv[n], cv[n];
+    bool edge_lane = false;
+    int edge_delta = 0;
     {
         int t = t0 + lane;
         const bool tv = task && t < g.tiles;
@@ -152,14 +161,25 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
             ro[i] = (unsigned)((img - img0) * g.C * HW + (h < 0 ? 0 : (h >= g.H ? g.H - 1 : h)) * g.W);
             co[i] = (unsigned)(ww < 0 ? 0 : (ww >= g.W ? g.W - 1 : ww));
         }
+        if constexpr (VEC) {
 #pragma unroll
-        for (int i = 0; i < n; ++i)
+            for (int i = 0; i < n; ++i) vrow[i] = 4u * (ro[i] + (unsigned)(tj * M));
+            // the block's first lane has no left neighbour in the wave, its last lane no right one
+            const bool first = lane == 0 && tj > 0, last = lane == TB - 1 && tj + 1 < g.tw;
+            edge_lane = tv && (first || last);
+            edge_delta = first ? -4 : 4 * M;
+        } else {
 #pragma unroll
-            for (int j = 0; j < n; ++j) voff[i][j] = 4u * (ro[i] + co[j]);
+            for (int i = 0; i < n; ++i)
+#pragma unroll
+                for (int j = 0; j < n; ++j) voff[i][j] = 4u * (ro[i] + co[j]);
+        }
     }
     const float* xblk = x + (size_t)img0 * g.C * HW;
 
-    float win[CPT][n][n];
+    float win[VEC ? 1 : CPT][VEC ? 1 : n][VEC ? 1 : n];
+    vecm mid[VEC ? CPT : 1][VEC ? n : 1];
+    float edge[VEC ? CPT : 1][VEC ? n : 1];
     // channels at or beyond C (the last stage of a C that is not a multiple of ALPHA) read channel C - 1 and
     // are zeroed in the transform
     auto load_windows = [&](int c0) {
@@ -167,12 +187,27 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
 #pragma unroll
         for (int e = 0; e < CPT; ++e) {
             const int c = c0 + wave * CPT + e;
-            const float* xc = xblk + (size_t)(c < g.C ? c : g.C - 1) * HW;
+            const char* xc = reinterpret_cast<const char*>(xblk + (size_t)(c < g.C ? c : g.C - 1) * HW);
+            if constexpr (VEC) {
 #pragma unroll
-            for (int i = 0; i < n; ++i)
+                for (int i = 0; i < n; ++i) mid[e][i] = *reinterpret_cast<const vecm*>(xc + vrow[i]);
+            } else {
 #pragma unroll
-                for (int j = 0; j < n; ++j)
-                    win[e][i][j] = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(xc) + voff[i][j]);
+                for (int i = 0; i < n; ++i)
+#pragma unroll
+                    for (int j = 0; j < n; ++j) win[e][i][j] = *reinterpret_cast<const float*>(xc + voff[i][j]);
+            }
+        }
+        if constexpr (VEC) {
+            if (edge_lane) {
+#pragma unroll
+                for (int e = 0; e < CPT; ++e) {
+                    const int c = c0 + wave * CPT + e;
+                    const char* xc = reinterpret_cast<const char*>(xblk + (size_t)(c < g.C ? c : g.C - 1) * HW);
+#pragma unroll
+                    for (int i = 0; i < n; ++i) edge[e][i] = *reinterpret_cast<const float*>(xc + vrow[i] + edge_delta);
+                }
+            }
         }
     };
     auto transform_windows = [&](int c0, float* vbuf) {
@@ -182,10 +217,29 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
         for (int e = 0; e < CPT; ++e) {
             const bool cvalid = c0 + wave * CPT + e < g.C;
             float d[n][n], tmp[n][n];
+            if constexpr (VEC) {
 #pragma unroll
-            for (int i = 0; i < n; ++i)
+                for (int i = 0; i < n; ++i) {
+                    // the value of the lane below / above (ds_bpermute: a lane reads the lane whose byte index it
+                    // gives).  The components are copied to scalars first: a bit cast applied directly to a vector
+                    // element reads element 0.
+                    const float own_last = mid[e][i][M - 1], own_first = mid[e][i][0];
+                    float left = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane - 1), __float_as_int(own_last)));
+                    float right = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane + 1), __float_as_int(own_first)));
+                    if (lane == 0) left = edge[e][i];
+                    if (lane == TB - 1) right = edge[e][i];
+                    const bool row = cvalid && rv[i];
+                    d[i][0] = (row && cv[0]) ? left : 0.f;
 #pragma unroll
-                for (int j = 0; j < n; ++j) d[i][j] = (cvalid && rv[i] && cv[j]) ? win[e][i][j] : 0.f;
+                    for (int j = 0; j < M; ++j) d[i][j + 1] = row ? mid[e][i][j] : 0.f;
+                    d[i][n - 1] = (row && cv[n - 1]) ? right : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < n; ++i)
+#pragma unroll
+                    for (int j = 0; j < n; ++j) d[i][j] = (cvalid && rv[i] && cv[j]) ? win[e][i][j] : 0.f;
+            }
             left_mul<M, UseB, n, n, n>(d, tmp);
             right_mul_t<M, UseB, n, n, n>(tmp, v[e]);
         }
@@ -233,22 +287,45 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
         const float* cur = lds + (s & 1) * STAGE;
         float* nxt = lds + ((s + 1) & 1) * STAGE;
         if (s + 1 < nstages) {
+#ifndef EXP_NO_U
             issue_kernels((s + 1) * ALPHA, nxt);
+#endif
+#ifndef EXP_NO_TRANSFORM
             transform_windows((s + 1) * ALPHA, nxt + UFLOATS);
+#endif
         }
+#ifndef EXP_NO_WINLOAD
         if (s + 2 < nstages) load_windows((s + 2) * ALPHA);
+#endif
+#ifndef EXP_NO_MFMA
+        // Operands of a group of GP planes are fetched while the previous group multiplies (two register sets).
         const float* ap = cur + aoff;
         const float* bp = cur + boff;
+        constexpr int GP = NPW % 4 == 0 ? 4 : 3, NGRP = (ALPHA / 4) * (NPW / GP);
+        static_assert(NPW % GP == 0, "planes per wave must split into operand groups");
+        floatx2 fa[2][GP], fb[2][GP];
+        auto fetch = [&](int set, int grpi) {
+            const int j = grpi / (NPW / GP), p0 = (grpi % (NPW / GP)) * GP;
 #pragma unroll
-        for (int j = 0; j < ALPHA / 4; ++j) {
-#pragma unroll
-            for (int p = 0; p < NPW; ++p) {
-                const floatx2 a = *reinterpret_cast<const floatx2*>(ap + ((2 * j) * NP + p) * Z * 2);
-                const floatx2 b = *reinterpret_cast<const floatx2*>(bp + ((2 * j) * NP + p) * TB * 2);
-                acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc[p], 0, 0, 0);
-                acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc[p], 0, 0, 0);
+            for (int q = 0; q < GP; ++q) {
+                fa[set][q] = *reinterpret_cast<const floatx2*>(ap + ((2 * j) * NP + p0 + q) * Z * 2);
+                fb[set][q] = *reinterpret_cast<const floatx2*>(bp + ((2 * j) * NP + p0 + q) * TB * 2);
             }
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int gi = 0; gi < NGRP; ++gi) {
+            if (gi + 1 < NGRP) fetch((gi + 1) & 1, gi + 1);
+            const int p0 = (gi % (NPW / GP)) * GP;
+#pragma unroll
+            for (int q = 0; q < GP; ++q)
+                acc[p0 + q] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[gi & 1][q][0], fb[gi & 1][q][0], acc[p0 + q], 0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < GP; ++q)
+                acc[p0 + q] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[gi & 1][q][1], fb[gi & 1][q][1], acc[p0 + q], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+#endif
     }
 
     // ---- output transform and store -------------------------------------------------------------------------
@@ -332,8 +409,8 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
     }
 }
 
-template <int M, int RG, int WT, int WK, int ALPHA, int CPT>
-hipError_t launch_fused_one(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st)
+template <int M, int RG, int WT, int WK, int ALPHA, int CPT, bool VEC>
+hipError_t launch_fused_vec(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st)
 {
     constexpr int n = M + 2, TB = 32 * WT, Z = 32 * WK, T = 64 * RG * WT * WK;
     constexpr size_t stage = sizeof(float) * (size_t)(ALPHA / 2) * n * n * (Z + TB) * 2;
@@ -346,7 +423,7 @@ hipError_t launch_fused_one(const float* x, const float* U2, float* y, const Win
     const long long tpi = (long long)g.th * g.tw;
     const long long span = ((TB + tpi - 1) / tpi + 2) * (long long)g.C * g.H * g.W * 4;
     if (span >= (1LL << 32)) return hipErrorInvalidValue;
-    auto kern = wino_fused_mfma_kernel<M, RG, WT, WK, ALPHA, CPT>;
+    auto kern = wino_fused_mfma_kernel<M, RG, WT, WK, ALPHA, CPT, VEC>;
     static std::once_flag raised;
     static hipError_t raise_rc = hipSuccess;
     std::call_once(raised, [&] {
@@ -358,6 +435,14 @@ hipError_t launch_fused_one(const float* x, const float* U2, float* y, const Win
     if (grid_ll > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid_ll), dim3(T), shm, st, x, U2, y, g);
     return hipGetLastError();
+}
+
+template <int M, int RG, int WT, int WK, int ALPHA, int CPT>
+hipError_t launch_fused_one(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st)
+{
+    const bool vec = g.pad == 1 && g.W % M == 0 && (reinterpret_cast<uintptr_t>(x) & (4 * M - 1)) == 0;
+    return vec ? launch_fused_vec<M, RG, WT, WK, ALPHA, CPT, true>(x, U2, y, g, st)
+               : launch_fused_vec<M, RG, WT, WK, ALPHA, CPT, false>(x, U2, y, g, st);
 }
 
 }  // namespace
