@@ -411,7 +411,10 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
 FUSED_BLOCKS = (
     (2, 64, 64, 8, 256, 2, 2, 131072, 256),
     (2, 64, 64, 8, 512, 4, 2, 131072, 128),
+    (2, 64, 64, 8, 1024, 8, 2, 131072, 64),
     (4, 32, 64, 4, 256, 4, 1, 131072, 288),
+    (2, 64, 64, 4, 1024, 8, 2, 131072, 64),
+    (4, 32, 64, 4, 768, 12, 1, 148480, 96),
 )
 
 
@@ -445,7 +448,7 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs=True)
             continue
         nblocks = (-(-tiles // ftb)) * (-(-K // fz))
         qread = nblocks * C * ((e * ftb + 2) * (e + 2) + n2 * fz)
-        cands.append(((1, qread, 0, 0, fz, fT),
+        cands.append(((1, qread, 0, 0, fz, fT, falpha),
                       dict(b=1, x=e * ftb, y=e, z=fz, alpha=falpha, threads=fT, waves_m=fwm, waves_n=fwn,
                            path=PATH_FUSED, wt_mode=1, lds_bytes_used=flds, acc_regs_per_thread=facc,
                            q_read_elems=qread, q_write_elems=N * K * P * Q)))

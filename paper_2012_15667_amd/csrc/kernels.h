@@ -71,6 +71,8 @@ hipError_t launch_wino_fused(const float* x, const float* Uk, float* y, const Wi
 hipError_t launch_wino_kernel_transform_paired(const float* w, float* U2, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_pair_relayout(const float* U, int rows, int cols, float* U2, const WinoGeom& g, hipStream_t st);
 hipError_t launch_wino_fused_mfma(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st);
+// The same with one wave per plane row and the input transform shared out over all threads (wino_fused_rows.hip).
+hipError_t launch_wino_fused_rows(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st);
 
 // Ceiling probes (probe.hip).  The copy moves bytes / 16 16-byte pieces; the MFMA loop runs
 // PROBE_MFMA_BLOCKS workgroups of four waves, each wave PROBE_ACC MFMAs (4096 flop each) per iteration, and

@@ -253,7 +253,10 @@ struct FusedBlock { int m, tb, z, alpha, threads, waves_m, waves_n, lds_bytes, a
 constexpr FusedBlock kFusedBlocks[] = {
     {2, 64, 64, 8, 256, 2, 2, 131072, 256},     // one wave per block, all 16 planes
     {2, 64, 64, 8, 512, 4, 2, 131072, 128},     // two waves per block, 8 planes each
+    {2, 64, 64, 8, 1024, 8, 2, 131072, 64},     // four waves per block, one row of 4 planes each
     {4, 32, 64, 4, 256, 4, 1, 131072, 288},     // two waves per block, 18 planes each
+    {2, 64, 64, 4, 1024, 8, 2, 131072, 64},     // the same with the input transform shared out over all threads
+    {4, 32, 64, 4, 768, 12, 1, 148480, 96},     // six waves per block, one row of 6 planes each, shared-out transform
 };
 
 void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_bytes, int vgpr_budget, bool auto_regs,
@@ -301,7 +304,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
         c.cfg.acc_regs_per_thread = f.acc;
         c.cfg.q_read_elems = nblocks * s.C * ((int64_t)(m * f.tb + 2) * (m + 2) + planes * f.z);
         c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
-        c.key = {1, 0, c.cfg.q_read_elems, 0, 0, f.z, f.threads, 0, 0, 0};
+        c.key = {1, 0, c.cfg.q_read_elems, 0, 0, f.z, f.threads, f.alpha, 0, 0};
         out->push_back(c);
     }
     const auto fz = factors_of(Kz);

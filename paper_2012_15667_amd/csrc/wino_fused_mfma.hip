@@ -79,6 +79,18 @@ pair_relayout_kernel(const float* __restrict__ U, int rows, int cols, float* __r
     U2[idx] = (c < rows && k < cols) ? U[((size_t)xi * rows + c) * cols + k] : 0.f;
 }
 
+// out[ROWS] = Mx[ROWS][IN] * in[IN], Mx = Sel's matrix of Mats<M>, coefficients folded at compile time.
+template <int M, class Sel, int ROWS, int IN>
+__device__ __forceinline__ void mat_vec(const float (&in)[IN], float (&out)[ROWS])
+{
+    static_for<ROWS>([&](auto i) {
+        float s = 0.f;
+        bool first = true;
+        static_for<IN>([&](auto k) { accumulate<M, Sel, decltype(i)::value, decltype(k)::value>(s, first, in[k]); });
+        out[decltype(i)::value] = s;
+    });
+}
+
 // Partial output transform over the rows [R0, R0 + NR) of the planes: yp[a][b] = sum_{i in rows} A[a][i] *
 // (sum_j pi[i - R0][j] * A[b][j]), coefficients folded at compile time.
 template <int M, int R0, int NR>
@@ -212,6 +224,51 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
     };
     auto transform_windows = [&](int c0, float* vbuf) {
         if (!task) return;
+        if constexpr (CPT == 1) {
+            // One channel per lane, written for few live registers (the accumulators leave little room when
+            // many waves share a SIMD): first B d column by column, then (B d) B^T row by row, each row stored
+            // as soon as it is complete.
+            const bool cvalid = c0 + wave < g.C;
+            float tmp[n][n];
+            static_for<n>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                float col[n], out[n];
+#pragma unroll
+                for (int i = 0; i < n; ++i) {
+                    float vin;
+                    if constexpr (VEC) {
+                        if constexpr (j == 0) {
+                            const float own_last = mid[0][i][M - 1];
+                            vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane - 1), __float_as_int(own_last)));
+                            if (lane == 0) vin = edge[0][i];
+                        } else if constexpr (j == n - 1) {
+                            const float own_first = mid[0][i][0];
+                            vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane + 1), __float_as_int(own_first)));
+                            if (lane == TB - 1) vin = edge[0][i];
+                        } else {
+                            vin = mid[0][i][j - 1];
+                        }
+                    } else {
+                        vin = win[0][i][j];
+                    }
+                    col[i] = (cvalid && rv[i] && cv[j]) ? vin : 0.f;
+                }
+                mat_vec<M, UseB, n, n>(col, out);
+#pragma unroll
+                for (int i = 0; i < n; ++i) tmp[i][j] = out[i];
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            float* vp = vbuf + ((size_t)(wave >> 1) * NP * TB + lane) * 2 + (wave & 1);
+            static_for<n>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                float out[n];
+                mat_vec<M, UseB, n, n>(tmp[i], out);
+#pragma unroll
+                for (int j = 0; j < n; ++j) vp[(i * n + j) * TB * 2] = out[j];
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            return;
+        }
         float v[CPT][n][n];
 #pragma unroll
         for (int e = 0; e < CPT; ++e) {
@@ -365,7 +422,7 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
 #pragma unroll
             for (int c = 0; c < n; ++c) pi[r][c] = acc[r * n + c][i];
         if (grp == 0) output_rows<M, 0, RPG>(pi, o);
-        else if constexpr (RG > 1) output_rows<M, RPG, RPG>(pi, o);
+        else if constexpr (RG == 2) output_rows<M, RPG, RPG>(pi, o);
     };
     if constexpr (RG == 1) {
         static_for<16>([&](auto ic) {
@@ -374,8 +431,7 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
             partial(ic, o);
             store_tile(kbase + 8 * (i >> 2) + (i & 3), o);
         });
-    } else {
-        static_assert(RG <= 2, "more than two row groups need a reduction tree");
+    } else if constexpr (RG == 2) {
         // The two waves of a block each hold the sum over their plane rows.  Group 0 finishes registers 0..7,
         // group 1 registers 8..15: each writes the partial sums of the other's registers to LDS (the staging
         // buffers are free by now), then adds what the other wrote to its own.
@@ -406,6 +462,41 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
             const int i = grp == 0 ? j : 8 + j;
             store_tile(kbase + 8 * (i >> 2) + (i & 3), o);
         });
+    } else {
+        // One wave per plane row (RG = m + 2).  The output transform is done in two halves around an exchange:
+        // wave i applies A^T from the right to its row, T[i][b] = sum_j Pi[i][j] A[b][j], and writes the m values
+        // per (register, lane) to LDS; then the 16 registers are dealt to the waves of the block, and the wave
+        // that finishes register r reads the (m+2) x m values T[.][.] of its lanes, applies A from the left and
+        // stores.  The exchange runs in ROUNDS rounds of 16 / ROUNDS registers so that it fits the LDS.
+        static_assert(RG == n, "row groups: 1, 2 or one per plane row");
+        constexpr int NBLK = WT * WK;
+        constexpr int ROUNDS = (NBLK * n * 16 * M * 64 * 4 > 160 * 1024) ? 2 : 1, RPR = 16 / ROUNDS;
+        float* xch = lds + (size_t)blk * n * RPR * M * 64;           // [block][row][register of the round][b][lane]
+        static_for<ROUNDS>([&](auto rc) {
+            constexpr int r0 = decltype(rc)::value * RPR;
+            __syncthreads();                                        // the staging buffers / the previous round are free
+            static_for<RPR>([&](auto jc) {
+                constexpr int r = r0 + decltype(jc)::value;
+                float pi[1][n], tr[1][M];
+#pragma unroll
+                for (int c = 0; c < n; ++c) pi[0][c] = acc[c][r];
+                right_mul_t<M, UseA, 1, n, M>(pi, tr);
+                float* dst = xch + ((size_t)grp * RPR + decltype(jc)::value) * M * 64 + lane;
+#pragma unroll
+                for (int b = 0; b < M; ++b) dst[b * 64] = tr[0][b];
+            });
+            __syncthreads();
+            for (int jr = grp; jr < RPR; jr += n) {
+                float tin[n][M], o[M][M];
+#pragma unroll
+                for (int i = 0; i < n; ++i)
+#pragma unroll
+                    for (int b = 0; b < M; ++b) tin[i][b] = xch[((size_t)i * RPR + jr) * M * 64 + b * 64 + lane];
+                left_mul<M, UseA, M, n, M>(tin, o);
+                const int r = r0 + jr;
+                store_tile(kbase + 8 * (r >> 2) + (r & 3), o);
+            }
+        });
     }
 }
 
@@ -414,7 +505,9 @@ hipError_t launch_fused_vec(const float* x, const float* U2, float* y, const Win
 {
     constexpr int n = M + 2, TB = 32 * WT, Z = 32 * WK, T = 64 * RG * WT * WK;
     constexpr size_t stage = sizeof(float) * (size_t)(ALPHA / 2) * n * n * (Z + TB) * 2;
-    constexpr size_t xch = RG > 1 ? sizeof(float) * (size_t)WT * WK * 2 * 8 * M * M * 64 : 0;
+    constexpr size_t xch_all = sizeof(float) * (size_t)WT * WK * n * 16 * M * 64;       // one wave per plane row
+    constexpr size_t xch = RG == 1 ? 0 : RG == 2 ? sizeof(float) * (size_t)WT * WK * 2 * 8 * M * M * 64
+                                                 : (xch_all > 160 * 1024 ? xch_all / 2 : xch_all);
     constexpr size_t shm = 2 * stage > xch ? 2 * stage : xch;
     static_assert(shm <= 160 * 1024, "block does not fit the LDS");
     if (g.tb != TB || g.z != Z || g.alpha != ALPHA || g.Kp % Z || g.Cp % ALPHA || g.Cp < g.C) return hipErrorInvalidValue;
@@ -478,9 +571,13 @@ hipError_t launch_wino_fused_mfma(const float* x, const float* U2, float* y, con
     if (g.m == 2 && g.tb == 64 && g.z == 64 && g.alpha == 8) {
         if (g.waves_m == 2) return launch_fused_one<2, 1, 2, 2, 8, 2>(x, U2, y, g, st);
         if (g.waves_m == 4) return launch_fused_one<2, 2, 2, 2, 8, 2>(x, U2, y, g, st);
+        if (g.waves_m == 8) return launch_fused_one<2, 4, 2, 2, 8, 1>(x, U2, y, g, st);
     }
-    if (g.m == 4 && g.tb == 32 && g.z == 64 && g.alpha == 4 && g.waves_m == 4)
-        return launch_fused_one<4, 2, 1, 2, 4, 1>(x, U2, y, g, st);
+    if (g.m == 4 && g.tb == 32 && g.z == 64 && g.alpha == 4) {
+        if (g.waves_m == 4) return launch_fused_one<4, 2, 1, 2, 4, 1>(x, U2, y, g, st);
+        if (g.waves_m == 12) return launch_wino_fused_rows(x, U2, y, g, st);
+    }
+    if (g.m == 2 && g.tb == 64 && g.z == 64 && g.alpha == 4 && g.waves_m == 8) return launch_wino_fused_rows(x, U2, y, g, st);
     return hipErrorInvalidValue;
 }
 
