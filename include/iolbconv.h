@@ -147,13 +147,23 @@ int conv_winograd_pre(const float* x, const float* U, float* y,
                       int N, int C, int H, int W, int K, int m,
                       void* workspace, size_t workspace_bytes, const iolb_tile_config* cfg);
 
-/* The analytical tuner (searching domain of Table 1, Sec. 6.2; objective: reading volume of
- * the dataflow of Sec. 5.2 / 5.3).  Host only; shape and out are host pointers.
+/* The analytical tuner.  Searching domain: Table 1 of Sec. 6.2 read for this machine (tile extents from the
+ * factors of the output extents, blocks that fit the accumulator registers and the LDS).  Order: a modelled
+ * run time -- THIS LIBRARY'S HEURISTIC, fitted to tile sweeps on an MI355X -- whose memory term and tie-break
+ * are the reading volume of the dataflow of Sec. 5.2 / 5.3.  Host only; shape and out are host pointers.
  * lds_bytes: LDS available to one workgroup; 0 = automatic: 81920 (half a compute unit's LDS, the
  * "two blocks per multiprocessor" rule of Sec. 6.2), or the whole LDS for tiles whose registers
  * allow only one workgroup per compute unit anyway.  vgpr_budget: accumulator registers per
- * lane (0 = default 128).  IOLB_ENOTILE when nothing fits. */
+ * lane (0 = default 128; the fused Winograd blocks, which hold up to 96, are exempt from the default).
+ * IOLB_ENOTILE when nothing fits. */
 int iolb_tune(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, iolb_tile_config* out);
+
+/* The bound-only pick: the same domain restricted to the optimality box of Table 1 (z <= sqrt(S_b/rho),
+ * x y <= sqrt(S_b rho); the whole domain if the box is empty), ordered by the paper's objective alone -- the
+ * reading volume Q_read of Sec. 5.2 / 5.3 evaluated exactly for the tile, ties by |b x y mu^2 - W_ker H_ker z|
+ * (distance from the optimality condition x y = R z), then the fuller block.  For the Winograd algos the fused
+ * dataflow of Sec. 5.3 comes before the unfused tiles.  Same arguments and errors as iolb_tune. */
+int iolb_tune_bound(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, iolb_tile_config* out);
 
 /* Every feasible tile for the shape, best first (the domain the exhaustive sweep times).
  * use_box != 0 applies the optimality-condition box z <= sqrt(S_b/rho), xy <= sqrt(S_b rho).

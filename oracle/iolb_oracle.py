@@ -187,6 +187,63 @@ def bounds(shape, Sf):
 
 
 # ------------------------------------------------------------------------------------------
+# the paper's tile rule: searching domain of Table 1 (Sec. 6.2), objective of Sec. 5.2
+# ------------------------------------------------------------------------------------------
+#
+# Everything in this section follows the paper alone (with the batch reading: a block covers b images).  The
+# library's bound-only pick (iolb_tune_bound) applies the same order to the tiles its kernels can run.
+
+def input_tile(x, y, R, S, stride):
+    """Extents x', y' of the input tile under an x by y output block: the paper approximates x' ~ mu x
+    (Sec. 5.2); exactly, x' = mu (x - 1) + W_ker."""
+    return (x - 1) * stride + S, (y - 1) * stride + R
+
+
+def Qread_exact(N, C, P, Q, K, R, S, stride, b, x, y, z):
+    """Reading volume of the dataflow of Sec. 5.2 for an output block of b images, x by y pixels and z
+    channels: every block loads, per input channel, its b x' y' input tile and the W_ker H_ker z weights of its
+    z kernels, once.  Blocks that hang over an edge count whole."""
+    xp, yp = input_tile(x, y, R, S, stride)
+    nblocks = (N // b) * (-(-Q // x)) * (-(-P // y)) * (-(-K // z))
+    return nblocks * C * (b * xp * yp + R * S * z)
+
+
+def in_optimality_box(b, x, y, z, R, S, stride, Sb):
+    """Table 1: z <= sqrt(S_b / rho) and x y <= sqrt(S_b rho), rho = W_ker H_ker / mu^2, in integers."""
+    return z * z * R * S <= Sb * stride * stride and (b * x * y) ** 2 * stride * stride <= Sb * R * S
+
+
+def paper_domain(N, P, Q, K, R, S, stride, Sb, z_step=1):
+    """Table 1: tile extents are factors of the output extents (b | N for the batch), the block fits the fast
+    memory of a processor, b x y z <= S_b, and lies inside the optimality box.  z_step: granularity of z the
+    hardware asks for (1: none)."""
+    out = []
+    for b in divisors(N):
+        for x in divisors(Q):
+            for y in divisors(P):
+                for z in divisors(K):
+                    if z % z_step == 0 and b * x * y * z <= Sb and in_optimality_box(b, x, y, z, R, S, stride, Sb):
+                        out.append((b, x, y, z))
+    return out
+
+
+def volume_order(N, C, P, Q, K, R, S, stride, b, x, y, z):
+    """The order of the bound-only rule: reading volume; then the distance from the optimality condition
+    b x y = rho z (Sec. 5.2, in integers: |b x y mu^2 - W_ker H_ker z|); then the fuller block (the dataflow
+    wants x y z ~ S / N_p); then the longer rows, fewer channels, fewer images."""
+    return (Qread_exact(N, C, P, Q, K, R, S, stride, b, x, y, z),
+            abs(b * x * y * stride * stride - R * S * z), -b * x * y * z, -x, z, b, y)
+
+
+def tune_by_volume(N, C, P, Q, K, R, S, stride, Sb, z_step=1):
+    """(b, x, y, z) of least reading volume in the paper's domain, or None when the domain is empty."""
+    dom = paper_domain(N, P, Q, K, R, S, stride, Sb, z_step)
+    if not dom:
+        return None
+    return min(dom, key=lambda t: volume_order(N, C, P, Q, K, R, S, stride, *t))
+
+
+# ------------------------------------------------------------------------------------------
 # tile selection (the analytical tuner)
 # ------------------------------------------------------------------------------------------
 #
@@ -200,10 +257,31 @@ def bounds(shape, Sf):
 #   * the per-stage input tile x' * y' * alpha and the weight slab R S alpha z, double buffered,
 #     must fit lds_bytes (the LDS share of one workgroup; when 0, S_sm / 2, or S_sm if the tile's
 #     registers allow only one workgroup per compute unit anyway).
-# Among feasible matrix-core tiles the rule minimises a modelled run time (mfma_tile_cost) in which the
-# read volume of the dataflow of Sec. 5.2, evaluated exactly (true halo x' = stride (x-1) + S instead of
-# x' ~ stride x), is the memory term; ties go to the smaller read volume.  FMA-path tiles (layers without
-# a 32-channel block) keep the simpler order: grid fill, then read volume.
+# Two orders over the same tiles:
+#   * bound_pick: the paper's order (volume_order above) -- what the library's iolb_tune_bound returns;
+#   * tune: THIS BUILD'S HEURISTIC, not the paper's: among feasible matrix-core tiles it minimises a modelled run
+#     time (mfma_tile_cost) in which the read volume is the memory term and the tie-break; FMA-path tiles keep
+#     a simpler order (grid fill, then read volume); a fused Winograd block comes first where fused_faster says
+#     so.  The constants of the model are listed in MODEL_CONSTANTS with the measurement each came from; they
+#     are mirrored from the library, so the bit-for-bit comparison of `tune` with iolb_tune checks that two
+#     implementations agree, not that the heuristic is right ("parity unpinned" for tune, candidates,
+#     mfma_tile_cost, _wave_grids, _pick_alpha, _auto_lds_budget, fused_faster).
+
+MODEL_CONSTANTS = {
+    # name: (value, unit, where it came from)
+    "operand_read": (32, "cycles per LDS operand read of a wave", "fit to 300-tile sweeps on 21 layers, one MI355X"),
+    "load_issue": (300, "cycles per LDS-direct load instruction", "s_memtime around the issue of back-to-back loads"),
+    "barrier": (100, "cycles per wave and stage", "fit to the same sweeps"),
+    "startup": (15000, "cycles per workgroup", "fit to the same sweeps"),
+    "store": (200, "cycles per accumulator register", "fit to the same sweeps"),
+    "read_rate": (4000, "bytes per cycle, whole chip", "fit; the streaming-copy probe reads 2000-2700"),
+    "write_rate": (1500, "bytes per cycle, whole chip", "fit; the streaming-copy probe writes 1900-2300"),
+    "resident_penalty": (11, "tenths: matrix time of several resident workgroups", "150-tile sweeps on 19 layers"),
+    "unfused_flop_rate": (105000, "flop per ns, Winograd product kernel", "bench step, eight layers"),
+    "transform_rate": (5200, "bytes per ns, Winograd transform kernels", "cfg5c transforms, rocprofv3 durations"),
+    "launch": (3000, "ns per kernel launch", "cfg2, back-to-back launches"),
+    "fused_rate": ({2: 328, 4: 242}, "flop per ns and compute unit, fused Winograd kernels", "cfg5b-d, 84 / 62 Tflop/s"),
+}
 
 N_CU = 256
 T_MAX = 1024
@@ -409,13 +487,25 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
 # Fused matrix-core blocks (every plane of a tb x z block resident in accumulator registers, Sec. 5.3), one per
 # kernel instantiation of the library: (e, tb, z, alpha, threads, waves_m, waves_n, lds_bytes, acc)
 FUSED_BLOCKS = (
-    (2, 64, 64, 8, 256, 2, 2, 131072, 256),
-    (2, 64, 64, 8, 512, 4, 2, 131072, 128),
     (2, 64, 64, 8, 1024, 8, 2, 131072, 64),
-    (4, 32, 64, 4, 256, 4, 1, 131072, 288),
-    (2, 64, 64, 4, 1024, 8, 2, 131072, 64),
     (4, 32, 64, 4, 768, 12, 1, 148480, 96),
 )
+
+
+def fused_faster(s, P, Q, e, ftb, fz, falpha):
+    """Heuristic of this build (integers, nanoseconds): does the fused block beat the unfused path?
+    unfused: product flop at 105 Tflop/s + (x + V + M + y) bytes at 5.2 TB/s + 4 launches of 3 us;
+    fused: rounds of 256 workgroups, each its own flop at one compute unit's rate, + 2 launches."""
+    N, C, K = s["N"], s["C"], s["K"]
+    n2 = (e + 2) * (e + 2)
+    tiles = N * (-(-P // e)) * (-(-Q // e))
+    Kz, Cp16, tiles_p = -(-K // 32) * 32, -(-C // 16) * 16, -(-tiles // 32) * 32
+    t_unfused = (2 * n2 * tiles_p * Cp16 * Kz) // 105000 + \
+                (4 * (N * C * s["H"] * s["W"] + n2 * tiles_p * (Cp16 + Kz) + N * K * P * Q)) // 5200 + 4 * 3000
+    Cf = -(-C // falpha) * falpha
+    nblocks = (-(-tiles // ftb)) * (-(-K // fz))
+    t_fused = (-(-nblocks // N_CU)) * ((2 * n2 * ftb * fz * Cf) // (328 if e == 2 else 242)) + 2 * 3000
+    return t_fused < t_unfused
 
 
 def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs=True):
@@ -442,13 +532,14 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs=True)
                            path=PATH_FMA, wt_mode=1, lds_bytes_used=0, acc_regs_per_thread=n2 * C,
                            q_read_elems=qread, q_write_elems=N * K * P * Q)))
     # Fused blocks, any channel count: per channel a block reads the input windows of its tb sub-domains (a strip
-    # of e tb + 2 by e + 2 pixels) and (e+2)^2 z transformed weights.  Ranked after the unfused tiles.
+    # of e tb + 2 by e + 2 pixels) and (e+2)^2 z transformed weights.  First where the time model prefers them.
     for fe, ftb, fz, falpha, fT, fwm, fwn, flds, facc in FUSED_BLOCKS:
         if fe != e or (lds_bytes and flds > lds_bytes) or (not auto_regs and facc > vgpr_budget):
             continue
         nblocks = (-(-tiles // ftb)) * (-(-K // fz))
         qread = nblocks * C * ((e * ftb + 2) * (e + 2) + n2 * fz)
-        cands.append(((1, qread, 0, 0, fz, fT, falpha),
+        first = fused_faster(s, P, Q, e, ftb, fz, falpha)
+        cands.append(((-(1 << 61) if first else 1, qread, 0, 0, fz, fT, falpha),
                       dict(b=1, x=e * ftb, y=e, z=fz, alpha=falpha, threads=fT, waves_m=fwm, waves_n=fwn,
                            path=PATH_FUSED, wt_mode=1, lds_bytes_used=flds, acc_regs_per_thread=facc,
                            q_read_elems=qread, q_write_elems=N * K * P * Q)))
@@ -499,8 +590,35 @@ def tune(shape, lds_bytes=0, vgpr_budget=128, auto_regs=True):
     """The tile the library's iolb_tune must return, or None when nothing fits.  Direct convolution ranks
     the whole domain by modelled time; Winograd looks inside the optimality box first."""
     c = candidates(shape, lds_bytes, vgpr_budget, shape["algo"] != DIRECT, auto_regs)
-    if not c or min(k for k, _ in c)[0] > 0:
+    if all(t["path"] == PATH_FUSED for _, t in c):
         c = candidates(shape, lds_bytes, vgpr_budget, False, auto_regs)   # tiny layers: drop the box
     if not c:
         return None
     return min(c, key=lambda kv: kv[0])[1]
+
+
+def _volume_key(shape, t):
+    """volume_order for a library tile (the thread count, then the matrix-core path, break the last ties); Winograd: the fused dataflow of
+    Sec. 5.3 before the unfused tiles, whose temporaries make a round trip through memory that q_read does not
+    count; unfused tiles by read volume, then |tb - z| (the optimality condition x y = r^2 z for sub-domain
+    strips), then the fuller block."""
+    if shape["algo"] == DIRECT:
+        P, Q = out_extent(shape["H"], shape["W"], shape["R"], shape["S"], shape["stride"], shape["pad"])
+        return volume_order(shape["N"], shape["C"], P, Q, -(-shape["K"] // 32) * 32 if t["path"] == PATH_MFMA else shape["K"],
+                            shape["R"], shape["S"], shape["stride"], t["b"], t["x"], t["y"], t["z"]) + (t["threads"], -t["path"])
+    e = WINO_E[shape["algo"]]
+    tb = t["x"] // e
+    if t["path"] == PATH_FMA:
+        return (-(1 << 62), 0, 0, 0, t["z"], 256, 0, 0)
+    if t["path"] == PATH_FUSED:
+        return (-(1 << 61), t["q_read_elems"], 0, 0, t["z"], t["threads"], 0, 0)
+    return (0, t["q_read_elems"], abs(tb - t["z"]), -tb * t["z"], t["z"], t["threads"], 0, 0)
+
+
+def bound_pick(shape, lds_bytes=0, vgpr_budget=128, auto_regs=True):
+    """The tile the library's iolb_tune_bound must return: least reading volume (the paper's objective) among
+    the tiles the kernels can run, inside the optimality box; the whole domain when the box is empty."""
+    c = candidates(shape, lds_bytes, vgpr_budget, True, auto_regs) or candidates(shape, lds_bytes, vgpr_budget, False, auto_regs)
+    if not c:
+        return None
+    return min((t for _, t in c), key=lambda t: _volume_key(shape, t))

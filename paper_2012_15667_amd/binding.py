@@ -16,7 +16,7 @@ LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 
 EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_direct_pad2", "conv_winograd", "conv_winograd_pad", "conv_winograd_workspace_bytes",
            "conv_winograd_ws", "conv_winograd_kernel_bytes", "conv_winograd_transform_kernels", "conv_winograd_pre",
-           "iolb_tune", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
+           "iolb_tune", "iolb_tune_bound", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
            "iolb_probe_hbm_copy", "iolb_probe_mfma_sink_bytes", "iolb_probe_mfma_f32",
            "iolb_timing_enable", "iolb_timing_read", "iolb_release_workspace", "iolb_strerror",
            "iolb_last_hip_error"]
@@ -91,6 +91,8 @@ def lib():
         L.conv_winograd_pre.argtypes = [vp, vp, vp] + [i] * 6 + [vp, sz, ctypes.POINTER(TileConfig)]
         L.iolb_tune.restype = i
         L.iolb_tune.argtypes = [ctypes.POINTER(Shape), sz, i, ctypes.POINTER(TileConfig)]
+        L.iolb_tune_bound.restype = i
+        L.iolb_tune_bound.argtypes = [ctypes.POINTER(Shape), sz, i, ctypes.POINTER(TileConfig)]
         L.iolb_enumerate.restype = ctypes.c_int64
         L.iolb_enumerate.argtypes = [ctypes.POINTER(Shape), sz, i, i, ctypes.POINTER(TileConfig), ctypes.c_int64]
         L.iolb_bounds.restype = i
@@ -137,6 +139,13 @@ def iolb_tune(shape, lds_bytes=0, vgpr_budget=0):
     """Tile the analytical tuner picks for `shape` (a Shape); returns a dict."""
     out = TileConfig()
     _check(lib().iolb_tune(ctypes.byref(shape), lds_bytes, vgpr_budget, ctypes.byref(out)))
+    return out.as_dict()
+
+
+def iolb_tune_bound(shape, lds_bytes=0, vgpr_budget=0):
+    """Tile of least reading volume inside the optimality box (the paper's objective alone); returns a dict."""
+    out = TileConfig()
+    _check(lib().iolb_tune_bound(ctypes.byref(shape), lds_bytes, vgpr_budget, ctypes.byref(out)))
     return out.as_dict()
 
 

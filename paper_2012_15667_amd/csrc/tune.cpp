@@ -1,8 +1,13 @@
 // Host-side analytical tuner and lower-bound figures (no GPU code in this file).
 //
-// The searching domain is Table 1 of Sec. 6.2 read for a wave64 machine whose partial sums
-// live in registers and whose staging buffers live in LDS; the objective is the reading volume
-// of the dataflow of Sec. 5.2 (direct) / Sec. 5.3 (Winograd) evaluated exactly for each tile.
+// The searching domain is Table 1 of Sec. 6.2 read for a wave64 machine whose partial sums live in registers
+// and whose staging buffers live in LDS.  Every tile carries two orders:
+//   - `volume`: the paper's objective -- the reading volume of the dataflow of Sec. 5.2 (direct) / Sec. 5.3
+//     (Winograd) evaluated exactly for the tile, ties by the distance from the optimality condition x y = R z.
+//     iolb_tune_bound returns its minimum inside the optimality box.
+//   - `key`: this build's own order, a modelled run time whose constants were fitted to tile sweeps on an
+//     MI355X (a heuristic, not taken from the paper), with the reading volume as its memory term and
+//     tie-break.  iolb_tune returns its minimum.
 // All decisions are taken in 64-bit integers.
 #include "iolbconv.h"
 #include "tune.h"
@@ -230,7 +235,7 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                     c.cfg.acc_regs_per_thread = g.acc;
                     c.cfg.q_read_elems = nblocks * s.C * per_stage;
                     c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
-                    // share of the workgroup's matrix-core work spent on pixels past the tile (MFMA path only)
+                    c.volume = {c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z), -npix * z, -(int64_t)x, z, b, y, g.threads, -path, 0};
                     if (path == IOLB_PATH_MFMA) {
                         const int64_t cost = mfma_tile_cost(s, b, x, y, z, alpha, g, nblocks, c.cfg.q_read_elems,
                                                             c.cfg.q_write_elems);
@@ -251,12 +256,8 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
 // registers (Sec. 5.3).  Each entry is one kernel instantiation.
 struct FusedBlock { int m, tb, z, alpha, threads, waves_m, waves_n, lds_bytes, acc; };
 constexpr FusedBlock kFusedBlocks[] = {
-    {2, 64, 64, 8, 256, 2, 2, 131072, 256},     // one wave per block, all 16 planes
-    {2, 64, 64, 8, 512, 4, 2, 131072, 128},     // two waves per block, 8 planes each
-    {2, 64, 64, 8, 1024, 8, 2, 131072, 64},     // four waves per block, one row of 4 planes each
-    {4, 32, 64, 4, 256, 4, 1, 131072, 288},     // two waves per block, 18 planes each
-    {2, 64, 64, 4, 1024, 8, 2, 131072, 64},     // the same with the input transform shared out over all threads
-    {4, 32, 64, 4, 768, 12, 1, 148480, 96},     // six waves per block, one row of 6 planes each, shared-out transform
+    {2, 64, 64, 8, 1024, 8, 2, 131072, 64},     // F(2x2): 2 x 2 blocks of 32 x 32, four row waves each
+    {4, 32, 64, 4, 768, 12, 1, 148480, 96},     // F(4x4): 1 x 2 blocks, six row waves each
 };
 
 void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_bytes, int vgpr_budget, bool auto_regs,
@@ -284,28 +285,44 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
         c.cfg.q_read_elems = nblocks * s.C * planes * (256 + Kz);
         c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
         c.key = {-(1LL << 62), 0, c.cfg.q_read_elems, 0, 0, Kz, 256, 0, 0, 0};
+        c.volume = {-(1LL << 62), 0, 0, 0, Kz, 256, 0, 0, 0, 0};
         out->push_back(c);
     }
-    // Fused blocks for any channel count: per channel a block reads the input windows of its tb sub-domains
-    // (a strip of m tb + 2 by m + 2 pixels) and (m+2)^2 z transformed weights, and nothing else.  They rank
-    // after the unfused tiles of the same layer until a caller asks for one (key[0] = 1).
-    for (const FusedBlock& f : kFusedBlocks) {
-        if (f.m != m) continue;
-        if (lds_bytes && f.lds_bytes > lds_bytes) continue;
-        if (!auto_regs && f.acc > vgpr_budget) continue;
-        const int64_t Kf = ceil_div(s.K, f.z) * f.z;
-        const int64_t nblocks = ceil_div(tiles, f.tb) * (Kf / f.z);
-        Candidate c{};
-        c.cfg.b = 1; c.cfg.x = m * f.tb; c.cfg.y = m; c.cfg.z = f.z;
-        c.cfg.alpha = f.alpha;
-        c.cfg.threads = f.threads; c.cfg.waves_m = f.waves_m; c.cfg.waves_n = f.waves_n;
-        c.cfg.path = IOLB_PATH_FUSED; c.cfg.wt_mode = 1;
-        c.cfg.lds_bytes_used = f.lds_bytes;
-        c.cfg.acc_regs_per_thread = f.acc;
-        c.cfg.q_read_elems = nblocks * s.C * ((int64_t)(m * f.tb + 2) * (m + 2) + planes * f.z);
-        c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
-        c.key = {1, 0, c.cfg.q_read_elems, 0, 0, f.z, f.threads, f.alpha, 0, 0};
-        out->push_back(c);
+    // Fused matrix-core blocks, for any channel count: per channel a block reads the input windows of its tb
+    // sub-domains (a strip of m tb + 2 by m + 2 pixels) and (m+2)^2 z transformed weights, and nothing else: this
+    // is the dataflow of Sec. 5.3, so in the paper's order (`volume`) they come before the unfused tiles, whose
+    // transformed inputs and products make a round trip through memory that q_read does not show.  In this
+    // build's order a fused block comes first only where a time model says it beats the unfused path (heuristic;
+    // constants measured on an MI355X, in nanoseconds):
+    //   unfused: product flop at 105 Tflop/s + (x + V + M + y) bytes at 5.2 TB/s + 4 launches of 3 us;
+    //   fused:   rounds of 256 workgroups, each its own flop at the rate of one compute unit (328 flop/ns for
+    //            F(2x2), 242 for F(4x4)) + 2 launches.
+    {
+        const int64_t Cp16 = ceil_div(s.C, 16) * 16;
+        const int64_t tiles_p = ceil_div(tiles, 32) * 32;
+        const int64_t flop_unfused = 2 * planes * tiles_p * Cp16 * Kz;
+        const int64_t bytes_unfused = 4 * ((int64_t)s.N * s.C * s.H * s.W + planes * tiles_p * (Cp16 + Kz) + (int64_t)s.N * s.K * P * Q);
+        const int64_t t_unfused = flop_unfused / 105000 + bytes_unfused / 5200 + 4 * 3000;
+        for (const FusedBlock& f : kFusedBlocks) {
+            if (f.m != m) continue;
+            if (lds_bytes && f.lds_bytes > lds_bytes) continue;
+            if (!auto_regs && f.acc > vgpr_budget) continue;
+            const int64_t Kf = ceil_div(s.K, f.z) * f.z, Cf = ceil_div(s.C, f.alpha) * f.alpha;
+            const int64_t nblocks = ceil_div(tiles, f.tb) * (Kf / f.z);
+            const int64_t t_fused = ceil_div(nblocks, kComputeUnits) * (2 * planes * f.tb * f.z * Cf / (m == 2 ? 328 : 242)) + 2 * 3000;
+            Candidate c{};
+            c.cfg.b = 1; c.cfg.x = m * f.tb; c.cfg.y = m; c.cfg.z = f.z;
+            c.cfg.alpha = f.alpha;
+            c.cfg.threads = f.threads; c.cfg.waves_m = f.waves_m; c.cfg.waves_n = f.waves_n;
+            c.cfg.path = IOLB_PATH_FUSED; c.cfg.wt_mode = 1;
+            c.cfg.lds_bytes_used = f.lds_bytes;
+            c.cfg.acc_regs_per_thread = f.acc;
+            c.cfg.q_read_elems = nblocks * s.C * ((int64_t)(m * f.tb + 2) * (m + 2) + planes * f.z);
+            c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+            c.key = {t_fused < t_unfused ? -(1LL << 61) : 1, 0, c.cfg.q_read_elems, 0, 0, f.z, f.threads, f.alpha, 0, 0};
+            c.volume = {-(1LL << 61), c.cfg.q_read_elems, 0, 0, f.z, f.threads, 0, 0, 0, 0};
+            out->push_back(c);
+        }
     }
     const auto fz = factors_of(Kz);
     for (int64_t tb = 32; tb <= top; tb += 32)
@@ -328,6 +345,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             c.cfg.q_read_elems = nblocks * s.C * (tb + z);
             c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
             c.key = {-grid_efficiency(nblocks), 0, c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0};
+            c.volume = {0, c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0, 0};
             out->push_back(c);
         }
 }
@@ -403,12 +421,30 @@ int tune(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, iolb_tile_conf
     // iolb_enumerate as the pruning device of the measured search).  Winograd: box first.
     int rc = enumerate(s, lds_bytes, vgpr_budget, s.algo != IOLB_DIRECT, &c);
     if (rc != IOLB_OK) return rc;
-    if (c.empty() || c.front().key[0] > 0) {   // tiny layers: no unfused tile inside the box, search the whole domain
+    bool any_unfused = false;
+    for (const auto& cand : c) any_unfused = any_unfused || cand.cfg.path != IOLB_PATH_FUSED;
+    if (!any_unfused) {                    // tiny layers: no unfused tile inside the box, search the whole domain
         rc = enumerate(s, lds_bytes, vgpr_budget, false, &c);
         if (rc != IOLB_OK) return rc;
     }
     if (c.empty()) return IOLB_ENOTILE;
     *cfg = c.front().cfg;
+    return IOLB_OK;
+}
+
+int tune_by_volume(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, iolb_tile_config* cfg) {
+    std::vector<Candidate> c;
+    int rc = enumerate(s, lds_bytes, vgpr_budget, true, &c);
+    if (rc != IOLB_OK) return rc;
+    if (c.empty()) {                       // tiny layers: nothing inside the box, search the whole domain
+        rc = enumerate(s, lds_bytes, vgpr_budget, false, &c);
+        if (rc != IOLB_OK) return rc;
+    }
+    if (c.empty()) return IOLB_ENOTILE;
+    const Candidate* best = &c.front();
+    for (const auto& cand : c)
+        if (cand.volume < best->volume) best = &cand;
+    *cfg = best->cfg;
     return IOLB_OK;
 }
 
@@ -458,6 +494,11 @@ int bounds(const iolb_shape& s, int64_t Sf, iolb_bounds_out* o) {
 extern "C" int iolb_tune(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, iolb_tile_config* out) {
     if (!shape || !out || vgpr_budget < 0) return IOLB_EINVAL;
     return iolb::tune(*shape, (int64_t)lds_bytes, vgpr_budget, out);
+}
+
+extern "C" int iolb_tune_bound(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, iolb_tile_config* out) {
+    if (!shape || !out || vgpr_budget < 0) return IOLB_EINVAL;
+    return iolb::tune_by_volume(*shape, (int64_t)lds_bytes, vgpr_budget, out);
 }
 
 extern "C" int64_t iolb_enumerate(const iolb_shape* shape, size_t lds_bytes, int vgpr_budget, int use_box,

@@ -1,28 +1,27 @@
-// Winograd F(m x m, 3 x 3), m in {2, 4}, for layers with many channels: the fused dataflow of Sec. 5.3 on the
-// fp32 matrix cores.  One workgroup owns a block of tb sub-domains by z output channels and keeps ALL
-// (m+2)^2 planes of its channel-summation temporaries (the Pi of step 3, Sec. 4.3) in accumulator registers
-// for the whole channel loop; the transformed inputs (step 1) are made inside the workgroup, per stage of
-// ALPHA channels, straight into the LDS buffer the products read, and the output transform (step 4) is
-// applied to the accumulators in registers.  Neither the transformed inputs nor the temporaries ever reach
-// memory: the layer reads x and the transformed kernels and writes y.
+// Winograd F(m x m, 3 x 3) for layers with many channels: the fused dataflow of Sec. 5.3 on the fp32 matrix
+// cores.  One workgroup owns a block of tb sub-domains by z output channels and keeps ALL (m+2)^2 planes of its
+// channel-summation temporaries (the Pi of step 3, Sec. 4.3) in accumulator registers for the whole channel
+// loop; the transformed inputs (step 1) are made inside the workgroup, per stage of ALPHA channels, straight
+// into the LDS buffer the products read, and the output transform (step 4) is applied to the accumulators.
+// Neither the transformed inputs nor the temporaries ever reach memory: the layer reads x and the transformed
+// kernels and writes y.
 //
 // Wave layout.  A 32 x 32 block (32 sub-domains by 32 channels) of one plane is one v_mfma_f32_32x32x2_f32
-// accumulator of 16 registers.  The (m+2) rows of planes are dealt to RG "row groups"; a wave owns the
-// (m+2)^2 / RG planes of its row group for one 32 x 32 block, so that, for a given (sub-domain, channel),
-// every plane of the group sits in the same lane and register index of the wave's accumulators, and the
-// output transform  Y = A Pi A^T = sum over rows i of  A[:, i] (Pi[i, :] A^T)  needs no data from other
-// lanes.  With RG = 1 a wave finishes its outputs alone; with RG = 2 the two waves of a block each hold the
-// partial sum over their rows, exchange half of it through LDS and add.
+// accumulator of 16 registers.  A wave owns one ROW of m+2 planes of one 32 x 32 block, so a compute unit
+// runs (m+2) * blocks light waves (16 for F(2x2) with 2 x 2 blocks) that fill each other's gaps.
 //
-// Per stage the workgroup
-//   - loads the (m+2) x (m+2) input windows of its sub-domains for the stage's channels from global memory
-//     into registers (issued one stage ahead), transforms them (B d B^T) and writes them to LDS as
-//     V[channel pair][plane][sub-domain][2];
-//   - copies the stage's slab of the transformed kernels, U2[channel pair][plane][k][2], to LDS with
-//     LDS-direct loads (issued one stage ahead);
-//   - multiplies: per plane and group of four channels one 8-byte LDS read per operand feeds two MFMAs
-//     (lane halves take channel pairs 2j and 2j + 1, so both halves use the same offsets).
-// Two LDS buffers alternate; one barrier per stage.
+// This file holds the variant in which a LANE transforms a whole window (used for m = 2, whose 4 x 4 windows
+// are small; wino_fused_rows.hip shares the transform out differently for m = 4).  Per stage the workgroup
+//   - loads the (m+2) x (m+2) input windows of its sub-domains from global memory into registers (issued one
+//     stage ahead; one lane per (sub-domain, channel), the waves 0 .. ALPHA-1 take one channel each), transforms
+//     them (B d B^T) and writes them to LDS as V[channel pair][plane][sub-domain][2];
+//   - copies the stage's slab of the transformed kernels, U2[channel pair][plane][k][2], to LDS with LDS-direct
+//     loads (issued one stage ahead);
+//   - multiplies: per plane and group of four channels one 8-byte LDS read per operand feeds two MFMAs (lane
+//     halves take channel pairs 2j and 2j + 1, so both halves use the same offsets).
+// Two LDS buffers alternate; one barrier per stage.  The output transform  Y = A Pi A^T  is split around an
+// exchange through LDS: wave i applies A^T from the right to its row, T[i][b] = sum_j Pi[i][j] A[b][j]; the wave
+// that finishes register r then reads the (m+2) x m values of its lanes, applies A from the left and stores.
 #include <mutex>
 
 #include "kernels.h"
@@ -91,53 +90,29 @@ __device__ __forceinline__ void mat_vec(const float (&in)[IN], float (&out)[ROWS
     });
 }
 
-// Partial output transform over the rows [R0, R0 + NR) of the planes: yp[a][b] = sum_{i in rows} A[a][i] *
-// (sum_j pi[i - R0][j] * A[b][j]), coefficients folded at compile time.
-template <int M, int R0, int NR>
-__device__ __forceinline__ void output_rows(const float (&pi)[NR][M + 2], float (&yp)[M][M])
-{
-    constexpr int n = M + 2;
-    float t[NR][M];
-    right_mul_t<M, UseA, NR, n, M>(pi, t);
-    static_for<M>([&](auto a) {
-        static_for<M>([&](auto b) {
-            float s = 0.f;
-            bool first = true;
-            static_for<NR>([&](auto i) {
-                accumulate<M, UseA, decltype(a)::value, R0 + decltype(i)::value>(s, first, t[decltype(i)::value][decltype(b)::value]);
-            });
-            yp[decltype(a)::value][decltype(b)::value] = s;
-        });
-    });
-}
-
-// M: output tile edge.  RG: row groups (waves per 32 x 32 block).  WT x WK: blocks of the workgroup along
-// sub-domains and channels (tb = 32 WT, z = 32 WK).  ALPHA: channels per stage.  CPT: channels per
-// transform task (2: a lane transforms a channel pair and writes 8-byte pairs; 1: one channel, 4-byte writes).
+// M: output tile edge.  WT x WK: 32 x 32 blocks of the workgroup along sub-domains and channels (tb = 32 WT,
+// z = 32 WK).  ALPHA: channels per stage, one transform wave each.
 // VEC (pad = 1, W a multiple of M, x aligned to 4 M bytes): a lane loads the M columns under its own
 // sub-domain as one aligned vector per window row and takes the two border columns from its neighbour lanes
 // (the sub-domains left and right of it; a border column outside the image is zero anyway), which replaces
 // (M+2)^2 four-byte loads per window by M+2 wide ones; the first and the last lane of a block, whose
 // neighbours belong to other workgroups, load their outer border column themselves.
-template <int M, int RG, int WT, int WK, int ALPHA, int CPT, bool VEC>
-__global__ void __launch_bounds__(64 * RG * WT * WK, 1)
+template <int M, int WT, int WK, int ALPHA, bool VEC>
+__global__ void __launch_bounds__(64 * (M + 2) * WT * WK, 1)
 wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2, float* __restrict__ y, WinoGeom g)
 {
     constexpr int n = M + 2, NP = n * n;
-    constexpr int RPG = n / RG;                    // plane rows per wave
-    constexpr int NPW = RPG * n;                   // planes per wave
-    constexpr int TB = 32 * WT, Z = 32 * WK;
-    constexpr int NWAVES = RG * WT * WK;
+    constexpr int TB = 32 * WT, Z = 32 * WK, NBLK = WT * WK;
+    constexpr int NWAVES = n * NBLK;
     constexpr int NCP = ALPHA / 2;                 // channel pairs per stage
-    constexpr int NCG = ALPHA / CPT;               // transform task groups per stage (one wave each)
     constexpr int UFLOATS = NCP * NP * Z * 2, VFLOATS = NCP * NP * TB * 2, STAGE = UFLOATS + VFLOATS;
-    static_assert(n % RG == 0 && ALPHA % 4 == 0 && NCG <= NWAVES && TB <= 64, "unsupported block");
+    static_assert(ALPHA % 4 == 0 && ALPHA <= NWAVES && TB <= 64, "unsupported block");
 
     extern __shared__ float lds[];
     const int tid = threadIdx.x;
     const int lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = wave % RG, blk = wave / RG, wt = blk % WT, wk = blk / WT;
+    const int row = wave % n, blk = wave / n, wt = blk % WT, wk = blk / WT;
 
     // blocks that share their sub-domains (the channel blocks of one strip) are neighbours on one XCD
     int bid = blockIdx.x;
@@ -147,8 +122,8 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
     const int kb = bid % nbk, tbk = bid / nbk;
     const int k0 = kb * Z, t0 = tbk * TB;
 
-    // ---- this lane's transform task: sub-domain t0 + lane, channel group `wave` of every stage -------------
-    const bool task = wave < NCG && lane < TB;
+    // ---- this lane's transform task: sub-domain t0 + lane, channel `wave` of every stage ---------------------
+    const bool task = wave < ALPHA && lane < TB;
     const int tpi = g.th * g.tw;                                   // sub-domains per image
     const int img0 = t0 / tpi;
     const int HW = g.H * g.W;
@@ -189,131 +164,75 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
     }
     const float* xblk = x + (size_t)img0 * g.C * HW;
 
-    float win[VEC ? 1 : CPT][VEC ? 1 : n][VEC ? 1 : n];
-    vecm mid[VEC ? CPT : 1][VEC ? n : 1];
-    float edge[VEC ? CPT : 1][VEC ? n : 1];
+    float win[VEC ? 1 : n][VEC ? 1 : n];
+    vecm mid[VEC ? n : 1];
+    float edge[VEC ? n : 1];
     // channels at or beyond C (the last stage of a C that is not a multiple of ALPHA) read channel C - 1 and
     // are zeroed in the transform
     auto load_windows = [&](int c0) {
         if (!task) return;
-#pragma unroll
-        for (int e = 0; e < CPT; ++e) {
-            const int c = c0 + wave * CPT + e;
-            const char* xc = reinterpret_cast<const char*>(xblk + (size_t)(c < g.C ? c : g.C - 1) * HW);
-            if constexpr (VEC) {
-#pragma unroll
-                for (int i = 0; i < n; ++i) mid[e][i] = *reinterpret_cast<const vecm*>(xc + vrow[i]);
-            } else {
-#pragma unroll
-                for (int i = 0; i < n; ++i)
-#pragma unroll
-                    for (int j = 0; j < n; ++j) win[e][i][j] = *reinterpret_cast<const float*>(xc + voff[i][j]);
-            }
-        }
+        const int c = c0 + wave;
+        const char* xc = reinterpret_cast<const char*>(xblk + (size_t)(c < g.C ? c : g.C - 1) * HW);
         if constexpr (VEC) {
+#pragma unroll
+            for (int i = 0; i < n; ++i) mid[i] = *reinterpret_cast<const vecm*>(xc + vrow[i]);
             if (edge_lane) {
 #pragma unroll
-                for (int e = 0; e < CPT; ++e) {
-                    const int c = c0 + wave * CPT + e;
-                    const char* xc = reinterpret_cast<const char*>(xblk + (size_t)(c < g.C ? c : g.C - 1) * HW);
-#pragma unroll
-                    for (int i = 0; i < n; ++i) edge[e][i] = *reinterpret_cast<const float*>(xc + vrow[i] + edge_delta);
-                }
+                for (int i = 0; i < n; ++i) edge[i] = *reinterpret_cast<const float*>(xc + vrow[i] + edge_delta);
             }
+        } else {
+#pragma unroll
+            for (int i = 0; i < n; ++i)
+#pragma unroll
+                for (int j = 0; j < n; ++j) win[i][j] = *reinterpret_cast<const float*>(xc + voff[i][j]);
         }
     };
+    // Written for few live registers (the accumulators leave little room when four waves share a SIMD): first
+    // B d column by column, then (B d) B^T row by row, each row stored as soon as it is complete.
     auto transform_windows = [&](int c0, float* vbuf) {
         if (!task) return;
-        if constexpr (CPT == 1) {
-            // One channel per lane, written for few live registers (the accumulators leave little room when
-            // many waves share a SIMD): first B d column by column, then (B d) B^T row by row, each row stored
-            // as soon as it is complete.
-            const bool cvalid = c0 + wave < g.C;
-            float tmp[n][n];
-            static_for<n>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                float col[n], out[n];
+        const bool cvalid = c0 + wave < g.C;
+        float tmp[n][n];
+        static_for<n>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            float col[n], out[n];
 #pragma unroll
-                for (int i = 0; i < n; ++i) {
-                    float vin;
-                    if constexpr (VEC) {
-                        if constexpr (j == 0) {
-                            const float own_last = mid[0][i][M - 1];
-                            vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane - 1), __float_as_int(own_last)));
-                            if (lane == 0) vin = edge[0][i];
-                        } else if constexpr (j == n - 1) {
-                            const float own_first = mid[0][i][0];
-                            vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane + 1), __float_as_int(own_first)));
-                            if (lane == TB - 1) vin = edge[0][i];
-                        } else {
-                            vin = mid[0][i][j - 1];
-                        }
+            for (int i = 0; i < n; ++i) {
+                float vin;
+                if constexpr (VEC) {
+                    // border columns: the value of the lane below / above (ds_bpermute: a lane reads the lane
+                    // whose byte index it gives).  The component is copied to a scalar first: a bit cast
+                    // applied directly to a vector element reads element 0.
+                    if constexpr (j == 0) {
+                        const float own_last = mid[i][M - 1];
+                        vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane - 1), __float_as_int(own_last)));
+                        if (lane == 0) vin = edge[i];
+                    } else if constexpr (j == n - 1) {
+                        const float own_first = mid[i][0];
+                        vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane + 1), __float_as_int(own_first)));
+                        if (lane == TB - 1) vin = edge[i];
                     } else {
-                        vin = win[0][i][j];
+                        vin = mid[i][j - 1];
                     }
-                    col[i] = (cvalid && rv[i] && cv[j]) ? vin : 0.f;
+                } else {
+                    vin = win[i][j];
                 }
-                mat_vec<M, UseB, n, n>(col, out);
-#pragma unroll
-                for (int i = 0; i < n; ++i) tmp[i][j] = out[i];
-                __builtin_amdgcn_sched_barrier(0);
-            });
-            float* vp = vbuf + ((size_t)(wave >> 1) * NP * TB + lane) * 2 + (wave & 1);
-            static_for<n>([&](auto ic) {
-                constexpr int i = decltype(ic)::value;
-                float out[n];
-                mat_vec<M, UseB, n, n>(tmp[i], out);
-#pragma unroll
-                for (int j = 0; j < n; ++j) vp[(i * n + j) * TB * 2] = out[j];
-                __builtin_amdgcn_sched_barrier(0);
-            });
-            return;
-        }
-        float v[CPT][n][n];
-#pragma unroll
-        for (int e = 0; e < CPT; ++e) {
-            const bool cvalid = c0 + wave * CPT + e < g.C;
-            float d[n][n], tmp[n][n];
-            if constexpr (VEC) {
-#pragma unroll
-                for (int i = 0; i < n; ++i) {
-                    // the value of the lane below / above (ds_bpermute: a lane reads the lane whose byte index it
-                    // gives).  The components are copied to scalars first: a bit cast applied directly to a vector
-                    // element reads element 0.
-                    const float own_last = mid[e][i][M - 1], own_first = mid[e][i][0];
-                    float left = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane - 1), __float_as_int(own_last)));
-                    float right = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane + 1), __float_as_int(own_first)));
-                    if (lane == 0) left = edge[e][i];
-                    if (lane == TB - 1) right = edge[e][i];
-                    const bool row = cvalid && rv[i];
-                    d[i][0] = (row && cv[0]) ? left : 0.f;
-#pragma unroll
-                    for (int j = 0; j < M; ++j) d[i][j + 1] = row ? mid[e][i][j] : 0.f;
-                    d[i][n - 1] = (row && cv[n - 1]) ? right : 0.f;
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < n; ++i)
-#pragma unroll
-                    for (int j = 0; j < n; ++j) d[i][j] = (cvalid && rv[i] && cv[j]) ? win[e][i][j] : 0.f;
+                col[i] = (cvalid && rv[i] && cv[j]) ? vin : 0.f;
             }
-            left_mul<M, UseB, n, n, n>(d, tmp);
-            right_mul_t<M, UseB, n, n, n>(tmp, v[e]);
-        }
-        if constexpr (CPT == 2) {
-            float* vp = vbuf + ((size_t)wave * NP * TB + lane) * 2;
+            mat_vec<M, UseB, n, n>(col, out);
 #pragma unroll
-            for (int i = 0; i < n; ++i)
+            for (int i = 0; i < n; ++i) tmp[i][j] = out[i];
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        float* vp = vbuf + ((size_t)(wave >> 1) * NP * TB + lane) * 2 + (wave & 1);
+        static_for<n>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            float out[n];
+            mat_vec<M, UseB, n, n>(tmp[i], out);
 #pragma unroll
-                for (int j = 0; j < n; ++j)
-                    *reinterpret_cast<floatx2*>(vp + (i * n + j) * TB * 2) = floatx2{v[0][i][j], v[1][i][j]};
-        } else {
-            float* vp = vbuf + ((size_t)(wave >> 1) * NP * TB + lane) * 2 + (wave & 1);
-#pragma unroll
-            for (int i = 0; i < n; ++i)
-#pragma unroll
-                for (int j = 0; j < n; ++j) vp[(i * n + j) * TB * 2] = v[0][i][j];
-        }
+            for (int j = 0; j < n; ++j) vp[(i * n + j) * TB * 2] = out[j];
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
     // the stage's slab of U2: NCP * NP rows of 2 Z floats, pitch 2 Kp
     const float* Ublk = U2 + (size_t)k0 * 2;
@@ -321,16 +240,15 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
         stage_rows(Ublk + (size_t)(c0 >> 1) * NP * g.Kp * 2, g.Kp * 2, Z / 2, NCP * NP, ubuf, wave, NWAVES, lane);
     };
 
-    floatx16 acc[NPW];
+    floatx16 acc[n];
 #pragma unroll
-    for (int p = 0; p < NPW; ++p)
+    for (int p = 0; p < n; ++p)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[p][i] = 0.f;
 
-    // operands of plane p (row grp * RPG + p / n): lane half h reads channel pair 2 j + h
-    const int plane0 = grp * NPW;
-    const int aoff = (half * NP + plane0) * Z * 2 + (wk * 32 + l32) * 2;
-    const int boff = UFLOATS + (half * NP + plane0) * TB * 2 + (wt * 32 + l32) * 2;
+    // operands of plane (row, p): lane half h reads channel pair 2 j + h
+    const int aoff = (half * NP + row * n) * Z * 2 + (wk * 32 + l32) * 2;
+    const int boff = UFLOATS + (half * NP + row * n) * TB * 2 + (wt * 32 + l32) * 2;
 
     const int nstages = (g.C + ALPHA - 1) / ALPHA;
     load_windows(0);
@@ -344,49 +262,39 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
         const float* cur = lds + (s & 1) * STAGE;
         float* nxt = lds + ((s + 1) & 1) * STAGE;
         if (s + 1 < nstages) {
-#ifndef EXP_NO_U
             issue_kernels((s + 1) * ALPHA, nxt);
-#endif
-#ifndef EXP_NO_TRANSFORM
             transform_windows((s + 1) * ALPHA, nxt + UFLOATS);
-#endif
         }
-#ifndef EXP_NO_WINLOAD
         if (s + 2 < nstages) load_windows((s + 2) * ALPHA);
-#endif
-#ifndef EXP_NO_MFMA
-        // Operands of a group of GP planes are fetched while the previous group multiplies (two register sets).
+        // the n planes of this wave's row, per group of four channels: operands of the next group are fetched
+        // while this one multiplies (two register sets)
         const float* ap = cur + aoff;
         const float* bp = cur + boff;
-        constexpr int GP = NPW % 4 == 0 ? 4 : 3, NGRP = (ALPHA / 4) * (NPW / GP);
-        static_assert(NPW % GP == 0, "planes per wave must split into operand groups");
-        floatx2 fa[2][GP], fb[2][GP];
-        auto fetch = [&](int set, int grpi) {
-            const int j = grpi / (NPW / GP), p0 = (grpi % (NPW / GP)) * GP;
+        constexpr int NGRP = ALPHA / 4;
+        floatx2 fa[2][n], fb[2][n];
+        auto fetch = [&](int set, int j) {
 #pragma unroll
-            for (int q = 0; q < GP; ++q) {
-                fa[set][q] = *reinterpret_cast<const floatx2*>(ap + ((2 * j) * NP + p0 + q) * Z * 2);
-                fb[set][q] = *reinterpret_cast<const floatx2*>(bp + ((2 * j) * NP + p0 + q) * TB * 2);
+            for (int p = 0; p < n; ++p) {
+                fa[set][p] = *reinterpret_cast<const floatx2*>(ap + ((2 * j) * NP + p) * Z * 2);
+                fb[set][p] = *reinterpret_cast<const floatx2*>(bp + ((2 * j) * NP + p) * TB * 2);
             }
         };
         fetch(0, 0);
 #pragma unroll
-        for (int gi = 0; gi < NGRP; ++gi) {
-            if (gi + 1 < NGRP) fetch((gi + 1) & 1, gi + 1);
-            const int p0 = (gi % (NPW / GP)) * GP;
+        for (int j = 0; j < NGRP; ++j) {
+            if (j + 1 < NGRP) fetch((j + 1) & 1, j + 1);
 #pragma unroll
-            for (int q = 0; q < GP; ++q)
-                acc[p0 + q] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[gi & 1][q][0], fb[gi & 1][q][0], acc[p0 + q], 0, 0, 0);
+            for (int p = 0; p < n; ++p)
+                acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j & 1][p][0], fb[j & 1][p][0], acc[p], 0, 0, 0);
 #pragma unroll
-            for (int q = 0; q < GP; ++q)
-                acc[p0 + q] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[gi & 1][q][1], fb[gi & 1][q][1], acc[p0 + q], 0, 0, 0);
+            for (int p = 0; p < n; ++p)
+                acc[p] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[j & 1][p][1], fb[j & 1][p][1], acc[p], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-#endif
     }
 
     // ---- output transform and store -------------------------------------------------------------------------
-    // register i of an accumulator: channel 8 (i / 4) + 4 half + i % 4 of sub-domain l32 of the wave's block
+    // register r of an accumulator: channel 8 (r / 4) + 4 half + r % 4 of sub-domain l32 of the wave's block
     const int t = t0 + wt * 32 + l32;
     const bool tvalid = t < g.tiles;
     const int tt = tvalid ? t : t0;
@@ -402,7 +310,6 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
         for (int a = 0; a < M; ++a) {
             if (ti * M + a >= g.P) continue;
             if (vec) {
-                typedef float vecm __attribute__((ext_vector_type(M)));
                 vecm q;
 #pragma unroll
                 for (int b = 0; b < M; ++b) q[b] = o[a][b];
@@ -414,100 +321,43 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
             }
         }
     };
-    auto partial = [&](auto ic, float (&o)[M][M]) {
-        constexpr int i = decltype(ic)::value;
-        float pi[RPG][n];
+    // The exchange runs in ROUNDS rounds of 16 / ROUNDS registers so that it fits the LDS.
+    constexpr int ROUNDS = (NBLK * n * 16 * M * 64 * 4 > 160 * 1024) ? 2 : 1, RPR = 16 / ROUNDS;
+    float* xch = lds + (size_t)blk * n * RPR * M * 64;               // [block][row][register of the round][b][lane]
+    static_for<ROUNDS>([&](auto rc) {
+        constexpr int r0 = decltype(rc)::value * RPR;
+        __syncthreads();                                            // the staging buffers / the previous round are free
+        static_for<RPR>([&](auto jc) {
+            constexpr int r = r0 + decltype(jc)::value;
+            float pi[n], tr[M];
 #pragma unroll
-        for (int r = 0; r < RPG; ++r)
+            for (int c = 0; c < n; ++c) pi[c] = acc[c][r];
+            mat_vec<M, UseA, M, n>(pi, tr);
+            float* dst = xch + ((size_t)row * RPR + decltype(jc)::value) * M * 64 + lane;
 #pragma unroll
-            for (int c = 0; c < n; ++c) pi[r][c] = acc[r * n + c][i];
-        if (grp == 0) output_rows<M, 0, RPG>(pi, o);
-        else if constexpr (RG == 2) output_rows<M, RPG, RPG>(pi, o);
-    };
-    if constexpr (RG == 1) {
-        static_for<16>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            float o[M][M];
-            partial(ic, o);
-            store_tile(kbase + 8 * (i >> 2) + (i & 3), o);
-        });
-    } else if constexpr (RG == 2) {
-        // The two waves of a block each hold the sum over their plane rows.  Group 0 finishes registers 0..7,
-        // group 1 registers 8..15: each writes the partial sums of the other's registers to LDS (the staging
-        // buffers are free by now), then adds what the other wrote to its own.
-        __syncthreads();                                            // every wave is done with the staging buffers
-        float* xch = lds + (size_t)blk * 2 * 8 * M * M * 64;         // [group that reads][8][M*M][64]
-        static_for<8>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            float o[M][M];
-            if (grp == 0) partial(std::integral_constant<int, 8 + j>{}, o);
-            else          partial(std::integral_constant<int, j>{}, o);
-            float* dst = xch + ((size_t)(1 - grp) * 8 + j) * M * M * 64 + lane;
-#pragma unroll
-            for (int a = 0; a < M; ++a)
-#pragma unroll
-                for (int b = 0; b < M; ++b) dst[(a * M + b) * 64] = o[a][b];
+            for (int b = 0; b < M; ++b) dst[b * 64] = tr[b];
         });
         __syncthreads();
-        static_for<8>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            float o[M][M];
-            if (grp == 0) partial(std::integral_constant<int, j>{}, o);
-            else          partial(std::integral_constant<int, 8 + j>{}, o);
-            const float* src = xch + ((size_t)grp * 8 + j) * M * M * 64 + lane;
+        for (int jr = row; jr < RPR; jr += n) {
+            float tin[n][M], o[M][M];
 #pragma unroll
-            for (int a = 0; a < M; ++a)
+            for (int i = 0; i < n; ++i)
 #pragma unroll
-                for (int b = 0; b < M; ++b) o[a][b] += src[(a * M + b) * 64];
-            const int i = grp == 0 ? j : 8 + j;
-            store_tile(kbase + 8 * (i >> 2) + (i & 3), o);
-        });
-    } else {
-        // One wave per plane row (RG = m + 2).  The output transform is done in two halves around an exchange:
-        // wave i applies A^T from the right to its row, T[i][b] = sum_j Pi[i][j] A[b][j], and writes the m values
-        // per (register, lane) to LDS; then the 16 registers are dealt to the waves of the block, and the wave
-        // that finishes register r reads the (m+2) x m values T[.][.] of its lanes, applies A from the left and
-        // stores.  The exchange runs in ROUNDS rounds of 16 / ROUNDS registers so that it fits the LDS.
-        static_assert(RG == n, "row groups: 1, 2 or one per plane row");
-        constexpr int NBLK = WT * WK;
-        constexpr int ROUNDS = (NBLK * n * 16 * M * 64 * 4 > 160 * 1024) ? 2 : 1, RPR = 16 / ROUNDS;
-        float* xch = lds + (size_t)blk * n * RPR * M * 64;           // [block][row][register of the round][b][lane]
-        static_for<ROUNDS>([&](auto rc) {
-            constexpr int r0 = decltype(rc)::value * RPR;
-            __syncthreads();                                        // the staging buffers / the previous round are free
-            static_for<RPR>([&](auto jc) {
-                constexpr int r = r0 + decltype(jc)::value;
-                float pi[1][n], tr[1][M];
-#pragma unroll
-                for (int c = 0; c < n; ++c) pi[0][c] = acc[c][r];
-                right_mul_t<M, UseA, 1, n, M>(pi, tr);
-                float* dst = xch + ((size_t)grp * RPR + decltype(jc)::value) * M * 64 + lane;
-#pragma unroll
-                for (int b = 0; b < M; ++b) dst[b * 64] = tr[0][b];
-            });
-            __syncthreads();
-            for (int jr = grp; jr < RPR; jr += n) {
-                float tin[n][M], o[M][M];
-#pragma unroll
-                for (int i = 0; i < n; ++i)
-#pragma unroll
-                    for (int b = 0; b < M; ++b) tin[i][b] = xch[((size_t)i * RPR + jr) * M * 64 + b * 64 + lane];
-                left_mul<M, UseA, M, n, M>(tin, o);
-                const int r = r0 + jr;
-                store_tile(kbase + 8 * (r >> 2) + (r & 3), o);
-            }
-        });
-    }
+                for (int b = 0; b < M; ++b) tin[i][b] = xch[((size_t)i * RPR + jr) * M * 64 + b * 64 + lane];
+            left_mul<M, UseA, M, n, M>(tin, o);
+            const int r = r0 + jr;
+            store_tile(kbase + 8 * (r >> 2) + (r & 3), o);
+        }
+    });
 }
 
-template <int M, int RG, int WT, int WK, int ALPHA, int CPT, bool VEC>
+template <int M, int WT, int WK, int ALPHA, bool VEC>
 hipError_t launch_fused_vec(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st)
 {
-    constexpr int n = M + 2, TB = 32 * WT, Z = 32 * WK, T = 64 * RG * WT * WK;
+    constexpr int n = M + 2, TB = 32 * WT, Z = 32 * WK, T = 64 * n * WT * WK;
     constexpr size_t stage = sizeof(float) * (size_t)(ALPHA / 2) * n * n * (Z + TB) * 2;
-    constexpr size_t xch_all = sizeof(float) * (size_t)WT * WK * n * 16 * M * 64;       // one wave per plane row
-    constexpr size_t xch = RG == 1 ? 0 : RG == 2 ? sizeof(float) * (size_t)WT * WK * 2 * 8 * M * M * 64
-                                                 : (xch_all > 160 * 1024 ? xch_all / 2 : xch_all);
+    constexpr size_t xch_all = sizeof(float) * (size_t)WT * WK * n * 16 * M * 64;
+    constexpr size_t xch = xch_all > 160 * 1024 ? xch_all / 2 : xch_all;
     constexpr size_t shm = 2 * stage > xch ? 2 * stage : xch;
     static_assert(shm <= 160 * 1024, "block does not fit the LDS");
     if (g.tb != TB || g.z != Z || g.alpha != ALPHA || g.Kp % Z || g.Cp % ALPHA || g.Cp < g.C) return hipErrorInvalidValue;
@@ -516,7 +366,7 @@ hipError_t launch_fused_vec(const float* x, const float* U2, float* y, const Win
     const long long tpi = (long long)g.th * g.tw;
     const long long span = ((TB + tpi - 1) / tpi + 2) * (long long)g.C * g.H * g.W * 4;
     if (span >= (1LL << 32)) return hipErrorInvalidValue;
-    auto kern = wino_fused_mfma_kernel<M, RG, WT, WK, ALPHA, CPT, VEC>;
+    auto kern = wino_fused_mfma_kernel<M, WT, WK, ALPHA, VEC>;
     static std::once_flag raised;
     static hipError_t raise_rc = hipSuccess;
     std::call_once(raised, [&] {
@@ -530,12 +380,12 @@ hipError_t launch_fused_vec(const float* x, const float* U2, float* y, const Win
     return hipGetLastError();
 }
 
-template <int M, int RG, int WT, int WK, int ALPHA, int CPT>
+template <int M, int WT, int WK, int ALPHA>
 hipError_t launch_fused_one(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st)
 {
     const bool vec = g.pad == 1 && g.W % M == 0 && (reinterpret_cast<uintptr_t>(x) & (4 * M - 1)) == 0;
-    return vec ? launch_fused_vec<M, RG, WT, WK, ALPHA, CPT, true>(x, U2, y, g, st)
-               : launch_fused_vec<M, RG, WT, WK, ALPHA, CPT, false>(x, U2, y, g, st);
+    return vec ? launch_fused_vec<M, WT, WK, ALPHA, true>(x, U2, y, g, st)
+               : launch_fused_vec<M, WT, WK, ALPHA, false>(x, U2, y, g, st);
 }
 
 }  // namespace
@@ -563,21 +413,14 @@ hipError_t launch_wino_pair_relayout(const float* U, int rows, int cols, float* 
     return hipGetLastError();
 }
 
-// U2: the transformed kernels in the layout of launch_wino_kernel_transform_paired, g.Cp / 2 channel pairs.
-// g.waves_m = RG * WK and g.waves_n = WT select the instantiation together with g.tb, g.z and g.alpha.
+// U2: the transformed kernels in the layout of launch_wino_kernel_transform_paired, g.Cp / 2 channel pairs of g.Kp
+// columns.  g.m, g.tb, g.z and g.alpha select the block: F(2x2) runs the kernel of this file, F(4x4) the one of
+// wino_fused_rows.hip.
 hipError_t launch_wino_fused_mfma(const float* x, const float* U2, float* y, const WinoGeom& g, hipStream_t st)
 {
     if (g.tiles < 1 || (reinterpret_cast<uintptr_t>(U2) & 15)) return hipErrorInvalidValue;
-    if (g.m == 2 && g.tb == 64 && g.z == 64 && g.alpha == 8) {
-        if (g.waves_m == 2) return launch_fused_one<2, 1, 2, 2, 8, 2>(x, U2, y, g, st);
-        if (g.waves_m == 4) return launch_fused_one<2, 2, 2, 2, 8, 2>(x, U2, y, g, st);
-        if (g.waves_m == 8) return launch_fused_one<2, 4, 2, 2, 8, 1>(x, U2, y, g, st);
-    }
-    if (g.m == 4 && g.tb == 32 && g.z == 64 && g.alpha == 4) {
-        if (g.waves_m == 4) return launch_fused_one<4, 2, 1, 2, 4, 1>(x, U2, y, g, st);
-        if (g.waves_m == 12) return launch_wino_fused_rows(x, U2, y, g, st);
-    }
-    if (g.m == 2 && g.tb == 64 && g.z == 64 && g.alpha == 4 && g.waves_m == 8) return launch_wino_fused_rows(x, U2, y, g, st);
+    if (g.m == 2 && g.tb == 64 && g.z == 64 && g.alpha == 8) return launch_fused_one<2, 2, 2, 8>(x, U2, y, g, st);
+    if (g.m == 4) return launch_wino_fused_rows(x, U2, y, g, st);
     return hipErrorInvalidValue;
 }
 

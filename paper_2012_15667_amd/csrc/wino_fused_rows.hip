@@ -198,22 +198,12 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
     auto prepare = [&](int k) {
         if (k >= 1 && k < nstages) {
             float* buf = lds + (k & 1) * STAGE;
-#ifndef EXP_NO_U
             store_kernels(buf);
-#endif
-#ifndef EXP_NO_P2
             pass2(scratch0 + (k & 1) * SCRATCH, buf + UFLOATS);
-#endif
         }
-#ifndef EXP_NO_U
         if (k >= 1 && k + 1 < nstages) load_kernels((k + 1) * ALPHA);
-#endif
-#ifndef EXP_NO_P1
         if (k >= 1 && k + 1 < nstages) pass1((k + 1) * ALPHA, scratch0 + ((k + 1) & 1) * SCRATCH);
-#endif
-#ifndef EXP_NO_LOADS
         if (k >= 1 && k + 2 < nstages) load_columns((k + 2) * ALPHA);
-#endif
     };
     // the n planes of this wave's row, per group of four channels: operands of the next group are fetched while
     // this one multiplies
@@ -259,9 +249,7 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
         if (!late) __syncthreads();
         prepare(late ? s : s + 1);
         if (late) __syncthreads();
-#ifndef EXP_NO_MFMA
         multiply(lds + (s & 1) * STAGE);
-#endif
     }
 
     // ---- output transform and store -------------------------------------------------------------------------
@@ -362,7 +350,6 @@ hipError_t launch_wino_fused_rows(const float* x, const float* U2, float* y, con
 {
     if (g.tiles < 1 || (reinterpret_cast<uintptr_t>(U2) & 15)) return hipErrorInvalidValue;
     if (g.m == 4 && g.tb == 32 && g.z == 64 && g.alpha == 4) return launch_rows_one<4, 1, 2, 4>(x, U2, y, g, st);
-    if (g.m == 2 && g.tb == 64 && g.z == 64 && g.alpha == 4) return launch_rows_one<2, 2, 2, 4>(x, U2, y, g, st);
     return hipErrorInvalidValue;
 }
 

@@ -67,6 +67,34 @@ def test_tuner_bit_exact_against_oracle(s, lds, vg):
         assert B.iolb_tune(sh, lds, vg) == want
 
 
+@pytest.mark.parametrize("s", SHAPES)
+@pytest.mark.parametrize("lds,vg", BUDGETS)
+def test_bound_only_pick_bit_exact_against_oracle(s, lds, vg):
+    """iolb_tune_bound (least reading volume inside the optimality box) against the oracle's bound_pick."""
+    want = o.bound_pick(s, lds, vg or 128, auto_regs=(vg == 0))
+    sh = B.make_shape(**s)
+    if want is None:
+        with pytest.raises(B.IolbError) as e:
+            B.iolb_tune_bound(sh, lds, vg)
+        assert e.value.code == -3
+    else:
+        assert B.iolb_tune_bound(sh, lds, vg) == want
+
+
+def test_bound_only_pick_minimises_the_reading_volume_of_the_enumerated_box():
+    """Against the library's own enumeration: no direct-convolution tile inside the box reads less."""
+    for s in SHAPES:
+        if s["algo"] != 0:
+            continue
+        sh = B.make_shape(**s)
+        inside = B.iolb_enumerate(sh, 0, 0, True) or B.iolb_enumerate(sh, 0, 0, False)
+        if not inside:
+            continue
+        pick = B.iolb_tune_bound(sh)
+        assert pick in inside
+        assert pick["q_read_elems"] == min(t["q_read_elems"] for t in inside)
+
+
 @pytest.mark.parametrize("s", SHAPES[:9] + SHAPES[12:14] + SHAPES[18:])
 @pytest.mark.parametrize("box", [True, False])
 def test_enumeration_bit_exact_and_in_order(s, box):
@@ -91,6 +119,7 @@ def test_random_small_shapes_bit_exact():
                 B.iolb_tune(sh)
         else:
             assert B.iolb_tune(sh) == want, s
+            assert B.iolb_tune_bound(sh) == o.bound_pick(s), s
 
 
 @pytest.mark.parametrize("s", SHAPES[:12] + SHAPES[24:])

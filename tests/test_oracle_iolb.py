@@ -168,23 +168,6 @@ def test_tile_rule_returns_a_feasible_tile(s, lds, vg):
     _check_feasible(s, cfg, lds, vg)
 
 
-@pytest.mark.parametrize("s", SHAPES[:8])
-def test_tile_rule_minimises_its_key(s):
-    """The pick is the candidate with the smallest key; for matrix-core tiles the key starts with the
-    modelled time and breaks ties by the read volume."""
-    cfg = o.tune(s)
-    cands = o.candidates(s, use_f3=s["algo"] != o.DIRECT) or o.candidates(s, use_f3=False)
-    key, best = min(cands, key=lambda kc: kc[0])
-    assert best == cfg
-    if s["algo"] == o.DIRECT and cfg["path"] == o.PATH_MFMA:
-        P, Q = o.out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
-        nblocks = (s["N"] // cfg["b"]) * -(-Q // cfg["x"]) * -(-P // cfg["y"]) * (-(-s["K"] // 32) * 32 // cfg["z"])
-        assert key[0] == o.mfma_tile_cost(s, cfg["b"], cfg["x"], cfg["y"], cfg["z"], cfg["alpha"], cfg["threads"],
-                                          cfg["waves_m"], cfg["acc_regs_per_thread"], nblocks,
-                                          cfg["q_read_elems"], cfg["q_write_elems"])
-        assert key[1] == cfg["q_read_elems"]
-
-
 def test_modelled_time_worked_example():
     """N=64, C=K=256, 56x56, 3x3; tile b=1, x=y=28, z=64, alpha=8, 8 waves as 2 x 4, 1 x 7 blocks per wave.
     By hand: halo 30*30 = 900 -> 15 chunks, 2 per wave -> 16 tile loads + ceil(8*9*16/512) = 3 weight loads;
@@ -213,14 +196,125 @@ def test_modelled_time_properties():
     assert f(256, 10**12) == (rows * 128 + 4 * (10**12 - halo)) // 4000 + (4 * 51380224) // 1500
 
 
-def test_optimality_box_prunes_but_keeps_the_pick():
-    s = shape(64, 256, 56, 56, 256)
-    inside = o.candidates(s, use_f3=True)
-    everything = o.candidates(s, use_f3=False)
-    assert 0 < len(inside) < len(everything)
+def test_optimality_box_prunes_and_holds_the_bound_pick():
+    """Table 1: the box z <= sqrt(S_b/rho), b x y <= sqrt(S_b rho) prunes the domain, and the bound-only pick
+    (least reading volume) lies inside it.  This build's heuristic pick need not: it ranks the whole domain."""
     sb = o.T_MAX * 128
-    for _, c in inside:
-        assert c["z"] ** 2 * 9 <= sb and (c["b"] * c["x"] * c["y"]) ** 2 <= sb * 9      # z<=sqrt(Sb/rho), xy<=sqrt(Sb rho)
+    for s in (shape(64, 256, 56, 56, 256), shape(32, 64, 56, 56, 64), shape(64, 128, 112, 112, 128), shape(16, 96, 27, 27, 256, 5, 5, 1, 2)):
+        inside = o.candidates(s, use_f3=True)
+        everything = o.candidates(s, use_f3=False)
+        assert 0 < len(inside) < len(everything)
+        RS, st2 = s["R"] * s["S"], s["stride"] ** 2
+        for _, c in inside:
+            assert c["z"] ** 2 * RS <= sb * st2 and (c["b"] * c["x"] * c["y"]) ** 2 * st2 <= sb * RS
+        pick = o.bound_pick(s)
+        assert pick in [c for _, c in inside]
+        assert pick["q_read_elems"] == min(c["q_read_elems"] for _, c in inside)
+
+
+# ---------------------------------------------------------------------------------------------
+# the paper's rule (Table 1 domain, reading volume of Sec. 5.2): pins that do not come from the oracle itself
+# ---------------------------------------------------------------------------------------------
+
+def _count_reads_by_walking_the_blocks(N, C, P, Q, K, R, S, stride, b, x, y, z):
+    """The dataflow of Sec. 5.2 walked block by block: per block and input channel, the pixels of the input
+    tile under the block (counted one by one from the first and last window of each axis) and the weights of
+    the block's kernels."""
+    total = 0
+    for n0 in range(0, N, b):
+        for q0 in range(0, Q, x):
+            for p0 in range(0, P, y):
+                for k0 in range(0, K, z):
+                    cols = len(range(q0 * stride, (q0 + x - 1) * stride + S))     # first pixel of the first window .. last of the last
+                    rows = len(range(p0 * stride, (p0 + y - 1) * stride + R))
+                    total += C * (b * rows * cols + R * S * z)
+    return total
+
+
+def test_reading_volume_equals_a_walk_over_the_blocks():
+    import random
+    rnd = random.Random(11)
+    for _ in range(60):
+        N, C, P, Q, K = rnd.choice([1, 2, 4]), rnd.randint(1, 5), rnd.choice([4, 6, 8, 12]), rnd.choice([4, 6, 9, 12]), rnd.choice([4, 8, 12])
+        R, S, st = rnd.choice([1, 2, 3]), rnd.choice([1, 3, 5]), rnd.choice([1, 2])
+        b, x, y, z = (rnd.choice(o.divisors(v)) for v in (N, Q, P, K))
+        assert o.Qread_exact(N, C, P, Q, K, R, S, st, b, x, y, z) == \
+               _count_reads_by_walking_the_blocks(N, C, P, Q, K, R, S, st, b, x, y, z)
+
+
+def test_reading_volume_approaches_the_papers_expression():
+    """With x' ~ mu x, as Sec. 5.2 takes it, the exact volume becomes (H W C_out / xyz) W_ker H_ker C_in (z + xy/rho)
+    for stride = kernel extent (no overlap between windows: the approximation is then exact)."""
+    C, P, Q, K = 3, 12, 12, 8
+    for x, y, z in ((2, 3, 4), (6, 4, 8), (12, 12, 1)):
+        assert o.Qread_exact(1, C, P, Q, K, 2, 2, 2, 1, x, y, z) == o.Qread_DC_paper(C, P, Q, K, 2, 2, 2, x, y, z)
+
+
+def test_bound_rule_worked_example():
+    """S_b = 2304, rho = 9, 24 x 24 outputs, 32 kernels: the box is z <= 16, x y <= 144, and x y = rho z is met
+    by x y = 144, z = 16 -- reached by (12, 12), (6, 24), (24, 6).  With the true input tile, (x + 2)(y + 2), the
+    square block reads least: 8 blocks of (14 * 14 + 9 * 16) elements per channel."""
+    N, C, P, Q, K = 1, 5, 24, 24, 32
+    dom = o.paper_domain(N, P, Q, K, 3, 3, 1, 2304)
+    assert max(z for _, _, _, z in dom) == 16 and max(b * x * y for b, x, y, _ in dom) == 144
+    assert {(1, 12, 12, 16), (1, 6, 24, 16), (1, 24, 6, 16)} <= set(dom)
+    pick = o.tune_by_volume(N, C, P, Q, K, 3, 3, 1, 2304)
+    assert pick == (1, 12, 12, 16)
+    assert o.Qread_exact(N, C, P, Q, K, 3, 3, 1, *pick) == 8 * C * (196 + 144)
+    # the three tiles on the optimality curve tie in the paper's approximate expression
+    vols = {o.Qread_DC_paper(C, P, Q, K, 3, 3, 1, x, y, 16) for x, y in ((12, 12), (6, 24), (24, 6))}
+    assert len(vols) == 1
+
+
+def test_bound_rule_is_the_argmin_over_an_independent_enumeration():
+    """Brute force on small layers: no tile of the Table 1 domain, listed here with itertools and its volume
+    counted by walking the blocks, reads less than the rule's pick; ties are broken towards x y = rho z."""
+    import itertools
+    import random
+    rnd = random.Random(3)
+    checked = 0
+    for _ in range(200):
+        N, C = rnd.choice([1, 2, 4]), rnd.randint(1, 4)
+        P, Q, K = rnd.choice([4, 6, 8, 12]), rnd.choice([4, 6, 8, 12]), rnd.choice([4, 8, 16])
+        R = S = rnd.choice([1, 3])
+        st = rnd.choice([1, 2])
+        Sb = rnd.choice([64, 256, 576])
+        pick = o.tune_by_volume(N, C, P, Q, K, R, S, st, Sb)
+        listed = [(b, x, y, z) for b, x, y, z in itertools.product(range(1, N + 1), range(1, Q + 1), range(1, P + 1), range(1, K + 1))
+                  if N % b == 0 and Q % x == 0 and P % y == 0 and K % z == 0 and b * x * y * z <= Sb
+                  and (z * z * R * S) <= Sb * st * st and (b * x * y * st) ** 2 <= Sb * R * S]
+        if not listed:
+            assert pick is None
+            continue
+        vol = {t: _count_reads_by_walking_the_blocks(N, C, P, Q, K, R, S, st, *t) for t in listed}
+        least = min(vol.values())
+        assert vol[pick] == least
+        ties = [t for t in listed if vol[t] == least]
+        dist = lambda t: abs(t[0] * t[1] * t[2] * st * st - R * S * t[3])
+        assert dist(pick) == min(dist(t) for t in ties)
+        checked += 1
+    assert checked > 150
+
+
+def test_more_fast_memory_never_reads_more():
+    """The domain only grows with S_b (and with the LDS budget): the least reading volume cannot rise."""
+    vols = [o.Qread_exact(4, 16, 28, 28, 64, 3, 3, 1, *o.tune_by_volume(4, 16, 28, 28, 64, 3, 3, 1, Sb))
+            for Sb in (64, 256, 1024, 4096, 16384)]
+    assert vols == sorted(vols, reverse=True) and vols[0] > vols[-1]
+    s = shape(64, 256, 56, 56, 256)
+    reads = [o.bound_pick(s, lds, 128)["q_read_elems"] for lds in (24576, 40960, 81920, 163840)]
+    assert reads == sorted(reads, reverse=True) and reads[0] > reads[-1]
+
+
+def test_bound_pick_runs_the_papers_winograd_dataflow():
+    """Sec. 5.3 keeps every temporary on chip: where a fused block exists the bound-only pick is one; without one
+    (F(3x3), F(6x6)) it is the unfused tile of least reading volume."""
+    assert o.bound_pick(shape(64, 128, 112, 112, 128, algo=o.WINO_F4))["path"] == o.PATH_FUSED
+    assert o.bound_pick(shape(64, 3, 224, 224, 64, algo=o.WINO_F2))["path"] == o.PATH_FMA          # thin: one-kernel FMA path
+    s = shape(8, 64, 28, 28, 64, algo=o.WINO_F3)
+    pick = o.bound_pick(s)
+    assert pick["path"] == o.PATH_MFMA
+    assert pick["q_read_elems"] == min(c["q_read_elems"] for _, c in o.candidates(s, use_f3=True))
 
 
 def test_continuous_optimum_is_on_the_optimality_curve():
@@ -241,7 +335,8 @@ def test_continuous_optimum_is_on_the_optimality_curve():
 
 
 def test_more_lds_never_costs_more():
-    """A larger LDS budget only adds feasible tiles and deeper stages: the modelled time of the pick cannot rise."""
+    """Heuristic order: a larger LDS budget only adds feasible tiles and deeper stages, so the modelled time of the
+    pick cannot rise (a property of this build's model, no pin of the paper's rule)."""
     s = shape(64, 256, 56, 56, 256)
     costs = [min(k[0] for k, _ in o.candidates(s, lds, 128, use_f3=False)) for lds in (24576, 40960, 81920, 163840)]
     assert costs == sorted(costs, reverse=True) and costs[0] > costs[-1]
@@ -262,7 +357,7 @@ def test_bounds_report():
 def test_thin_winograd_layers_get_the_fused_candidate_first():
     """C <= 4 and C (e+2)^2 <= register budget: the one-kernel dataflow of Sec. 5.3 is a candidate, ranks
     first, covers every output channel with 256 sub-domains per workgroup and uses no LDS; otherwise every
-    candidate is an unfused matrix-core tile."""
+    candidate is a matrix-core tile (unfused, or a fused block)."""
     for algo, e in o.WINO_E.items():
         n2 = (e + 2) ** 2
         for C in range(1, 7):
@@ -281,7 +376,7 @@ def test_thin_winograd_layers_get_the_fused_candidate_first():
                     assert f["q_write_elems"] == 2 * 40 * 20 * 24
                 else:
                     assert not fused
-                    assert o.tune(s, 0, budget)["path"] == o.PATH_MFMA
+                    assert o.tune(s, 0, budget)["path"] in (o.PATH_MFMA, o.PATH_FUSED)
 
 
 def test_single_stage_tiles_count_one_buffer_and_large_kernels_fall_back_to_fma():
