@@ -103,6 +103,19 @@ int conv_direct_layout(const float* x, const float* w, float* y,
                        int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                        int layout, const iolb_tile_config* cfg);
 
+/* conv_direct for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, layouts and result (bit for bit) as conv_direct, but
+ * the re-laid-out weights go into a fixed array inside the library instead of the grown workspace: the call
+ * makes no hipMalloc / hipFree and no allocating library call, and enqueues kernels only.
+ * Limit: K rounded up to 32, times C rounded up to whole stages (at most 16 extra channels), times R * S must
+ * not exceed conv_direct_noalloc_max_weight_floats() = 4194304 floats (16 MiB, held by every GPU the library
+ * has run this call on until the process ends); beyond it the call returns IOLB_EWORKSPACE and launches
+ * nothing.  All calls on one GPU share that array: calls that overlap on one GPU (two streams) race, and a
+ * captured graph must not replay concurrently with another call of this entry point on the same GPU. */
+int conv_direct_noalloc(const float* x, const float* w, float* y,
+                        int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
+size_t conv_direct_noalloc_max_weight_floats(void);
+
 /* conv_direct with its own padding per axis: pad_h rows of zeros above and below, pad_w columns left and
  * right (the 1 x 7 / 7 x 1 factorised kernels of Inception-v3 pad one axis only); P and Q follow from
  * pad_h and pad_w.  NCHW tensors, tuned tile. */

@@ -14,7 +14,7 @@ WINO_ALGO = {2: WINO_F2, 3: WINO_F3, 4: WINO_F4, 6: WINO_F6}     # algo id of F(
 PATH_FMA, PATH_MFMA, PATH_FUSED = 0, 1, 2
 LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 
-EXPORTS = ["conv_direct", "conv_direct_cfg", "conv_direct_layout", "conv_direct_pad2", "conv_winograd", "conv_winograd_pad", "conv_winograd_workspace_bytes",
+EXPORTS = ["conv_direct", "conv_direct_noalloc", "conv_direct_noalloc_max_weight_floats", "conv_direct_cfg", "conv_direct_layout", "conv_direct_pad2", "conv_winograd", "conv_winograd_pad", "conv_winograd_workspace_bytes",
            "conv_winograd_ws", "conv_winograd_kernel_bytes", "conv_winograd_transform_kernels", "conv_winograd_pre",
            "iolb_tune", "iolb_tune_bound", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
            "iolb_probe_hbm_copy", "iolb_probe_mfma_sink_bytes", "iolb_probe_mfma_f32",
@@ -69,6 +69,10 @@ def lib():
         i, vp, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
         L.conv_direct.restype = i
         L.conv_direct.argtypes = [vp, vp, vp] + [i] * 9
+        L.conv_direct_noalloc.restype = i
+        L.conv_direct_noalloc.argtypes = [vp, vp, vp] + [i] * 9
+        L.conv_direct_noalloc_max_weight_floats.restype = sz
+        L.conv_direct_noalloc_max_weight_floats.argtypes = []
         L.conv_direct_cfg.restype = i
         L.conv_direct_cfg.argtypes = [vp, vp, vp] + [i] * 9 + [ctypes.POINTER(TileConfig)]
         L.conv_direct_pad2.restype = i
@@ -260,6 +264,18 @@ def conv_direct_layout(x, w, stride=1, pad=0, layout=LAYOUT_HWC, y=None, cfg=Non
         c = ctypes.byref(cfg if isinstance(cfg, TileConfig) else TileConfig.from_dict(cfg))
     _check(lib().conv_direct_layout(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, R, S,
                                     stride, pad, int(layout), c))
+    return y
+
+
+def conv_direct_noalloc(x, w, stride, pad, y):
+    """conv_direct through the entry point that allocates nothing: y must be given (N, K, P, Q), the re-laid-out
+    weights go into the library's fixed scratch array."""
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    _use_current_stream()
+    _check(lib().conv_direct_noalloc(_dev_f32(x, "x"), _dev_f32(w, "w"), _dev_f32(y, "y"), N, C, H, W, K, R, S, stride, pad))
     return y
 
 

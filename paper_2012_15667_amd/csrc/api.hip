@@ -33,7 +33,13 @@ int hip_fail(hipError_t e)
 struct DeviceState {
     void* ws = nullptr;
     size_t ws_bytes = 0;
+    float* scratch = nullptr;      // this device's copy of the static scratch array (conv_direct_noalloc)
 };
+
+// Scratch of the entry point that allocates nothing: the re-laid-out weights of one layer.  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until the process ends.
+constexpr size_t kScratchFloats = (size_t)4 << 20;            // 16 MiB
+static __device__ __align__(256) float scratch[kScratchFloats];
 std::mutex g_mutex;
 std::map<int, DeviceState> g_devices;
 
@@ -59,6 +65,20 @@ int ensure_workspace(DeviceState* d, size_t bytes)
     }
     IOLB_HIP(hipMalloc(&d->ws, bytes));
     d->ws_bytes = bytes;
+    return IOLB_OK;
+}
+
+// Device address of this device's scratch array, looked up once per device (with that device current: the caller
+// has just asked for it with hipGetDevice).  In host code the array's name is only a handle for this lookup.
+int scratch_address(DeviceState* d, float** out)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    if (!d->scratch) {
+        void* p = nullptr;
+        IOLB_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        d->scratch = static_cast<float*>(p);
+    }
+    *out = d->scratch;
     return IOLB_OK;
 }
 
@@ -154,8 +174,10 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
 
 // layout CWH: s, P, Q describe the transposed layer (H and W, R and S exchanged) and the weights are read
 // transposed; the tensors are then plain CHW tensors of that layer.
+// wt_buf != nullptr: room for the re-laid-out weights (wt_floats floats) given by the caller, so that nothing is
+// allocated; otherwise the library's workspace is used.
 int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, int P, int Q, const iolb_tile_config& cfg,
-               int layout = IOLB_LAYOUT_CHW, int pad_w = -1)
+               int layout = IOLB_LAYOUT_CHW, int pad_w = -1, float* wt_buf = nullptr, size_t wt_floats = 0)
 {
     DeviceState* dev = nullptr;
     int rc = device_state(&dev);
@@ -179,9 +201,14 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     if (cfg.path == IOLB_PATH_MFMA) {
         const int c_padded = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;     // whole stages
         const size_t wbytes = sizeof(float) * (size_t)g.Kp * c_padded * s.R * s.S;
-        rc = ensure_workspace(dev, align256(wbytes));
-        if (rc != IOLB_OK) return rc;
-        float* wt = static_cast<float*>(dev->ws);
+        float* wt = wt_buf;
+        if (wt_buf) {
+            if (wbytes > sizeof(float) * wt_floats) return IOLB_EWORKSPACE;
+        } else {
+            rc = ensure_workspace(dev, align256(wbytes));
+            if (rc != IOLB_OK) return rc;
+            wt = static_cast<float*>(dev->ws);
+        }
         if (g.w_transposed)
             IOLB_HIP(iolb::launch_weight_relayout_transposed(w, wt, s.K, g.Kp, s.C, s.R, s.S, c_padded * s.R * s.S, st));
         else
@@ -383,6 +410,29 @@ int conv_direct(const float* x, const float* w, float* y, int N, int C, int H, i
     if (rc != IOLB_OK) return rc;
     return run_direct(x, w, y, s, P, Q, cfg);
 }
+
+int conv_direct_noalloc(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
+                        int stride, int pad)
+{
+    if (!x || !w || !y) return IOLB_EINVAL;
+    const iolb_shape s{N, C, H, W, K, R, S, stride, pad, IOLB_DIRECT};
+    int P = 0, Q = 0;
+    int rc = iolb::validate_shape(s, &P, &Q);
+    if (rc != IOLB_OK) return rc;
+    iolb_tile_config cfg;
+    rc = tuned_tile(s, &cfg);
+    if (rc != IOLB_OK) return rc;
+    DeviceState* dev = nullptr;
+    rc = device_state(&dev);
+    if (rc != IOLB_OK) return rc;
+    float* buf = nullptr;
+    rc = scratch_address(dev, &buf);
+    if (rc != IOLB_OK) return rc;
+    // the limit is checked inside run_direct, before anything is launched: IOLB_EWORKSPACE beyond it
+    return run_direct(x, w, y, s, P, Q, cfg, IOLB_LAYOUT_CHW, -1, buf, kScratchFloats);
+}
+
+size_t conv_direct_noalloc_max_weight_floats(void) { return kScratchFloats; }
 
 int conv_direct_pad2(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int R, int S,
                      int stride, int pad_h, int pad_w)
