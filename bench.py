@@ -79,15 +79,24 @@ def cpu_baseline(budget_s=15.0):
                       % (" and ".join(extra), flops / 1e9, secs)}
 
 
-def read_traffic_note():
-    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary."""
-    path = os.path.join(ROOT, "profiles", "direct_mfma_hbm_traffic.txt")
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic_by_layer.txt")
+
+
+def read_traffic_table():
+    """Measured HBM bytes per layer call, from the committed rocprofv3 counter summary (written by
+    `python -m paper_2012_15667_amd.traffic`): {(layer, algo, path): {"read": B, "written": B, "main_kernel": B}}.
+    The figures are RECORDED ones (an earlier run of the same kernels), not measured by this run."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
+    table = {}
     if not os.path.exists(path):
-        return None
+        return table
     for line in open(path):
-        if line.startswith("traffic_bytes_per_launch="):
-            return float(line.split("=", 1)[1])
-    return None
+        if not line.startswith("row "):
+            continue
+        f = dict(kv.split("=", 1) for kv in line.split()[1:])
+        table[(f["layer"], f["algo"], f["path"])] = {"read": float(f["read_bytes"]), "written": float(f["written_bytes"]),
+                                                     "main_kernel": float(f["main_kernel_bytes"])}
+    return table
 
 
 def main():
@@ -98,6 +107,14 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", default="", help="comma-separated subset of config names (profiling runs)")
     ap.add_argument("--algos", default="", help="comma-separated subset of direct,wino2,wino3,wino4,wino6 (profiling runs; wino3 and wino6 are not part of the default step)")
+    ap.add_argument("--wino-path", default="tuned", choices=["tuned", "fused", "unfused", "bound"],
+                    help="Winograd tile: the tuner's pick, the first fused block, the first unfused tile of the "
+                         "enumeration, or the bound-only pick (profiling runs)")
+    ap.add_argument("--direct-pick", default="tuned", choices=["tuned", "bound"],
+                    help="direct-convolution tile: the tuner's pick or the bound-only pick (profiling runs)")
+    ap.add_argument("--profile", action="store_true",
+                    help="run the selected layers --steps times and exit (for rocprofv3 runs: no warm-up beyond "
+                         "--warmup, no per-layer repetitions, no ceiling probes, no JSON)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (known size) to calibrate rocprofv3 FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -142,23 +159,58 @@ def main():
             jobs.append((L, a, xd, wd, yd))
     torch.cuda.synchronize()
 
-    def run(job):
+    algo_ids = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino3": B.WINO_F3, "wino4": B.WINO_F4, "wino6": B.WINO_F6}
+
+    def shape_of(L, a):
+        return B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_ids[a])
+
+    def pick_tile(L, a, which):
+        """None = let the library tune; otherwise an explicit tile."""
+        sh = shape_of(L, a)
+        if which == "tuned":
+            return None
+        if which == "bound":
+            return B.iolb_tune_bound(sh)
+        want = B.PATH_FUSED if which == "fused" else B.PATH_MFMA
+        for t in B.iolb_enumerate(sh, 0, 0, False):
+            if t["path"] == want:
+                return t
+        return None
+
+    workspaces = {}
+
+    def run(job, tile=None):
         L, a, xd, wd, yd = job
         if a == "direct":
-            B.conv_direct(xd, wd, L.stride, L.pad, y=yd)
-        else:
+            B.conv_direct(xd, wd, L.stride, L.pad, y=yd, cfg=tile)
+        elif tile is None:
             B.conv_winograd(xd, wd, int(a[4:]), y=yd)
+        else:
+            m = int(a[4:])
+            key = (L.name, m)
+            if key not in workspaces:
+                workspaces[key] = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, m), dtype=torch.uint8, device="cuda")
+            B.conv_winograd(xd, wd, m, y=yd, cfg=tile, workspace=workspaces[key])
+
+    forced = {id(j): pick_tile(j[0], j[1], args.direct_pick if j[1] == "direct" else args.wino_path) for j in jobs}
 
     def step():
         for job in jobs:
-            run(job)
+            run(job, forced[id(job)])
+
+    if args.profile:
+        for _ in range(args.warmup + args.steps):
+            step()
+        torch.cuda.synchronize()
+        print("profiled %d calls of each of: %s" % (args.warmup + args.steps, ", ".join("%s[%s]" % (j[0].name, j[1]) for j in jobs)))
+        return
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
 
     # ---- timed region: exactly --steps steps, main kernels bracketed by HIP events ------------
-    B.timing_read(B.TIME_DIRECT); B.timing_read(B.TIME_WINO_PRODUCT)
+    B.timing_read(B.TIME_DIRECT); B.timing_read(B.TIME_WINO_PRODUCT); B.timing_read(B.TIME_WINO_FUSED)
     B.timing_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -169,43 +221,67 @@ def main():
     B.timing_enable(False)
     n_direct, ms_direct = B.timing_read(B.TIME_DIRECT)
     n_wino, ms_wino = B.timing_read(B.TIME_WINO_PRODUCT)
+    n_fused, ms_fused = B.timing_read(B.TIME_WINO_FUSED)
 
     flops_step = sum(direct_flops(j[0]) for j in jobs)
     direct_alg_flops = sum(direct_flops(j[0]) for j in jobs if j[1] == "direct")
-    algo_ids = {"direct": B.DIRECT, "wino2": B.WINO_F2, "wino3": B.WINO_F3, "wino4": B.WINO_F4, "wino6": B.WINO_F6}
-
     def tile_of(L, a):
-        return B.iolb_tune(B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_ids[a]))
+        return B.iolb_tune(shape_of(L, a))
 
-    # thin Winograd layers run as one fused FMA kernel: no product launch, nothing added to its roofline
+    # Winograd layers by the kernel their tuned tile runs: unfused product, fused matrix-core kernel, or the thin
+    # one-kernel FMA path (no matrix-core launch: nothing added to a roofline)
     wino_alg_flops = sum(wino_product_flops(j[0], int(j[1][4:])) for j in jobs
                          if j[1] != "direct" and tile_of(j[0], j[1])["path"] == B.PATH_MFMA)
+    fused_alg_flops = sum(wino_product_flops(j[0], int(j[1][4:])) for j in jobs
+                          if j[1] != "direct" and tile_of(j[0], j[1])["path"] == B.PATH_FUSED)
 
     # ---- per-layer figures (outside the timed region) ------------------------------------------
-    layers = []
-    for job in jobs:
-        L, a = job[0], job[1]
-        reps = 5
-        run(job)
+    traffic = read_traffic_table()
+    path_names = {B.PATH_FMA: "fma", B.PATH_MFMA: "mfma", B.PATH_FUSED: "fused"}
+
+    def timed(job, tile, reps=5):
+        run(job, tile)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(reps):
-            run(job)
+            run(job, tile)
         e1.record()
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_ids[a])
+        return e0.elapsed_time(e1) / reps
+
+    layers = []
+    for job in jobs:
+        L, a = job[0], job[1]
+        shape = shape_of(L, a)
         tile = B.iolb_tune(shape)
+        bound_tile = B.iolb_tune_bound(shape)
+        ms = timed(job, None)
+        ms_bound = ms if bound_tile == tile else timed(job, bound_tile)
         bnd = B.iolb_bounds(shape, 40960)
-        layers.append({
+        keys = ("b", "x", "y", "z", "alpha", "threads", "path")
+        rec = {
             "layer": L.name, "algo": a, "ms": round(ms, 4),
             "tflops_direct_equiv": round(direct_flops(L) / ms / 1e9, 2),
-            "tile": {k: tile[k] for k in ("b", "x", "y", "z", "alpha", "threads", "path")},
+            "tile": {k: tile[k] for k in keys},
+            "bound_pick": {"tile": {k: bound_tile[k] for k in keys}, "ms": round(ms_bound, 4),
+                           "read_volume_over_tuned": round(bound_tile["q_read_elems"] / tile["q_read_elems"], 3)},
             "compulsory_MB": round(4 * bnd["compulsory_elems"] / 1e6, 2),
             "io_lower_bound_lead_MB_at_160KB": round(4 * bnd["q_lower_lead"] / 1e6, 2),
             "modelled_read_MB": round(4 * tile["q_read_elems"] / 1e6, 2),
-        })
+        }
+        if a != "direct":
+            # the other Winograd path beside the tuned one (fused against unfused)
+            other = pick_tile(L, a, "unfused" if tile["path"] == B.PATH_FUSED else "fused")
+            if other is not None and tile["path"] != B.PATH_FMA:
+                rec["other_path"] = {"path": path_names[other["path"]], "ms": round(timed(job, other), 4)}
+        t = traffic.get((L.name, a, path_names[tile["path"]]))
+        if t:
+            denom = max(4 * bnd["compulsory_elems"], 4 * bnd["q_lower_lead"] if a != "direct" else 0)
+            rec["hbm_MB_measured"] = round((t["read"] + t["written"]) / 1e6, 1)
+            rec["hbm_over_bound"] = round((t["read"] + t["written"]) / denom, 3)
+            rec["hbm_bound_MB"] = round(denom / 1e6, 1)
+        layers.append(rec)
 
     # ---- measured ceilings of this GPU (outside the timed region) ------------------------------
     from paper_2012_15667_amd.ceilings import measure as measure_ceilings
@@ -220,8 +296,11 @@ def main():
                     "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
                     "frac_of_measured_mfma_loop": round(achieved / ceilings["mfma_f32_TFLOPs"], 4),
-                    "avg_launch_ms": round(ms_direct / n_direct, 4), "launches": n_direct,
-                    "traffic": read_traffic_note()}
+                    "avg_launch_ms": round(ms_direct / n_direct, 4), "launches": n_direct}
+        per = [traffic[k]["main_kernel"] for k in traffic if k[1] == "direct" and any(j[0].name == k[0] and j[1] == "direct" for j in jobs)]
+        roofline["traffic"] = round(sum(per) / len(per)) if per else None
+        roofline["traffic_source"] = ("recorded: %s (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of the same "
+                                      "kernels, average over the direct launches of a step), not measured in this run" % TRAFFIC_FILE) if per else None
     wino_roofline = None
     if n_wino:
         achieved_w = wino_alg_flops * args.steps / (ms_wino * 1e-3) / 1e12
@@ -230,6 +309,14 @@ def main():
                          "frac": round(achieved_w / PEAK_FP32_MFMA_TFLOPS, 4),
                          "frac_of_measured_mfma_loop": round(achieved_w / ceilings["mfma_f32_TFLOPs"], 4),
                          "avg_launch_ms": round(ms_wino / n_wino, 4), "launches": n_wino}
+
+    fused_roofline = None
+    if n_fused:
+        achieved_f = fused_alg_flops * args.steps / (ms_fused * 1e-3) / 1e12
+        fused_roofline = {"bound": "mfma", "kernel": "wino_fused_mfma_kernel / wino_rows_kernel (fused Winograd layers of the step)",
+                          "achieved": round(achieved_f, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+                          "frac": round(achieved_f / PEAK_FP32_MFMA_TFLOPS, 4),
+                          "avg_launch_ms": round(ms_fused / n_fused, 4), "launches": n_fused}
 
     out = {
         "metric": "TFLOP/s per conv layer (direct & Winograd) + HBM bytes / I/O lower bound",
@@ -240,6 +327,8 @@ def main():
                    "convs_per_step": len(jobs), "direct_equiv_gflop_per_step": round(flops_step / 1e9, 1)},
         "roofline": roofline,
         "roofline_winograd_product": wino_roofline,
+        "roofline_winograd_fused": fused_roofline,
+        "hbm_traffic_source": "recorded in %s by rocprofv3 counters, not measured in this run" % TRAFFIC_FILE,
         "measured_ceilings": ceilings,
         "layers": layers,
     }
