@@ -36,9 +36,14 @@ DEFAULT_RUNS = (
 )
 
 
+REUSE = False      # --reuse: summarise the counter files of an earlier collection instead of running rocprofv3 again
+
+
 def _rocprof(counters, tag, bench_args, timeout=180):
     cmd = ["rocprofv3", "--pmc"] + counters + ["--output-format", "csv", "-d", OUT_DIR, "-o", tag, "--",
                                                "python3", "bench.py"] + bench_args
+    if REUSE:
+        return " ".join(cmd)
     env = dict(os.environ, TMPDIR="/tmp")
     r = subprocess.run(cmd, cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=timeout)
     if r.returncode != 0:
@@ -81,7 +86,10 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default=os.path.join("profiles", "hbm_traffic_by_layer.txt"))
     ap.add_argument("--l2", action="store_true", help="also collect the requests between the compute units and L2")
+    ap.add_argument("--reuse", action="store_true", help="summarise the counter files already under gpurun_out/traffic")
     args = ap.parse_args()
+    global REUSE
+    REUSE = args.reuse
     from . import binding as B
     from .inputs import CONFIGS
     os.makedirs(os.path.join(ROOT, OUT_DIR), exist_ok=True)
@@ -119,7 +127,7 @@ def main():
                 k = r["Kernel_Name"]
                 if "iolb::" not in k or r["Counter_Name"] not in scale:
                     continue
-                short = k.split("iolb::")[1].split("(")[0].replace("(anonymous namespace)::", "")
+                short = k.replace("(anonymous namespace)::", "").split("iolb::")[1].split("(")[0]
                 per_kernel[short][r["Counter_Name"]] += float(r["Counter_Value"]) / STEPS
         results[(layer, algo, path)] = per_kernel
 
