@@ -7,11 +7,14 @@
  * IOLB_E* code; no exception crosses this boundary and nothing aborts.  Arguments are checked
  * before anything is launched, so a call that fails validation writes nothing.
  *
- * Work is enqueued on the stream given to iolb_set_stream (the null stream by default) and
- * the calls return without waiting for it.  One stream per host thread; calls that use the
- * library's workspace and overlap on one GPU race.  A call that does not have to grow the
- * workspace enqueues kernels only (no allocation, no memset, no synchronisation), so after one
- * eager call for the same layer it can be recorded by a stream capture and replayed as a graph.
+ * Work is enqueued on the stream given to iolb_set_stream (the null stream by default; the setting is per host
+ * thread) and the calls return without waiting for it.  Thread-compatible with one stream per host thread: the
+ * library keeps one workspace per (GPU, stream), so calls on different streams do not share scratch memory;
+ * calls on one stream are ordered by the stream.  A call that does not have to grow its stream's workspace
+ * enqueues kernels only (no allocation, no memset, no synchronisation), so after one eager call for the same
+ * layer on the same stream it can be recorded by a stream capture and replayed as a graph.  A workspace that
+ * has to grow is replaced, never freed before iolb_release_workspace, so kernels in flight and graphs captured
+ * earlier keep valid addresses; iolb_release_workspace invalidates such graphs.
  *
  * Symbols (paper -> here): W_in,H_in,C_in -> W,H,C;  C_out -> K;  W_ker,H_ker -> S,R;
  * W_out,H_out -> Q,P;  mu -> stride;  e -> m.  A batch of N images shares the K kernels.
@@ -83,7 +86,7 @@ typedef struct iolb_bounds_out {
  *   y[n,k,p,q] = sum_{c,r,s} xpad[n,c,p*stride+r-pad,q*stride+s-pad] * w[k,c,r,s]
  * x: [N][C][H][W], w: [K][C][R][S], y: [N][K][P][Q]; cross-correlation, zero padding.
  * y is fully overwritten; x and y must not overlap.  The tile comes from iolb_tune with the
- * default budgets.  May grow the library's device workspace (one allocation, kept). */
+ * default budgets.  May grow the stream's workspace in the library (one allocation, kept). */
 int conv_direct(const float* x, const float* w, float* y,
                 int N, int C, int H, int W, int K, int R, int S, int stride, int pad);
 
@@ -219,7 +222,9 @@ int iolb_probe_hbm_copy(const void* src, void* dst, size_t bytes, int reps, floa
 size_t iolb_probe_mfma_sink_bytes(void);
 int iolb_probe_mfma_f32(void* sink, int iters, int reps, float* ms_per_launch, double* flop_per_launch);
 
-/* Frees the library's device workspace (it is otherwise kept until the process ends). */
+/* Waits for the current GPU and frees the library's workspaces on it (all streams, and the buffers larger ones
+ * have replaced); they are otherwise kept until the process ends.  Graphs captured from calls that used them
+ * must not be replayed afterwards. */
 int iolb_release_workspace(void);
 
 const char* iolb_strerror(int code);

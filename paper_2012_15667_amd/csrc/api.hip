@@ -30,10 +30,15 @@ int hip_fail(hipError_t e)
         if (e__ != hipSuccess) return hip_fail(e__);  \
     } while (0)
 
+struct Workspace {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+};
 struct DeviceState {
-    void* ws = nullptr;
-    size_t ws_bytes = 0;
-    float* scratch = nullptr;      // this device's copy of the static scratch array (conv_direct_noalloc)
+    std::map<hipStream_t, Workspace> ws;   // the library's workspace: one per stream that has called in
+    std::vector<void*> retired;            // buffers a larger one has replaced: kept until iolb_release_workspace,
+                                           // because launches in flight and captured graphs may still name them
+    float* scratch = nullptr;              // this device's copy of the static scratch array (conv_direct_noalloc)
 };
 
 // Scratch of the entry point that allocates nothing: the re-laid-out weights of one layer.  Every GPU the
@@ -52,19 +57,22 @@ int device_state(DeviceState** out)
     return IOLB_OK;
 }
 
-// Library-owned workspace: one allocation per device, grown on demand, kept until released.
-int ensure_workspace(DeviceState* d, size_t bytes)
+// Library-owned workspace of the calling thread's stream on the current device: grown on demand, never freed
+// before iolb_release_workspace.  One workspace per stream makes calls on different streams independent (one
+// stream per host thread); two calls on ONE stream are ordered by the stream.  A buffer that has to grow is
+// replaced, not freed: kernels already enqueued, and graphs captured earlier, keep a valid address.
+int ensure_workspace(DeviceState* d, size_t bytes, void** out)
 {
     std::lock_guard<std::mutex> lock(g_mutex);
-    if (d->ws_bytes >= bytes) return IOLB_OK;
-    if (d->ws) {
-        IOLB_HIP(hipDeviceSynchronize());      // earlier launches may still read the old buffer
-        IOLB_HIP(hipFree(d->ws));
-        d->ws = nullptr;
-        d->ws_bytes = 0;
+    Workspace& w = d->ws[t_stream];
+    if (w.bytes < bytes) {
+        void* p = nullptr;
+        IOLB_HIP(hipMalloc(&p, bytes));
+        if (w.ptr) d->retired.push_back(w.ptr);
+        w.ptr = p;
+        w.bytes = bytes;
     }
-    IOLB_HIP(hipMalloc(&d->ws, bytes));
-    d->ws_bytes = bytes;
+    *out = w.ptr;
     return IOLB_OK;
 }
 
@@ -205,9 +213,10 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
         if (wt_buf) {
             if (wbytes > sizeof(float) * wt_floats) return IOLB_EWORKSPACE;
         } else {
-            rc = ensure_workspace(dev, align256(wbytes));
+            void* ws = nullptr;
+            rc = ensure_workspace(dev, align256(wbytes), &ws);
             if (rc != IOLB_OK) return rc;
-            wt = static_cast<float*>(dev->ws);
+            wt = static_cast<float*>(ws);
         }
         if (g.w_transposed)
             IOLB_HIP(iolb::launch_weight_relayout_transposed(w, wt, s.K, g.Kp, s.C, s.R, s.S, c_padded * s.R * s.S, st));
@@ -559,9 +568,10 @@ int conv_winograd(const float* x, const float* w, float* y, int N, int C, int H,
     DeviceState* dev = nullptr;
     rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;
-    rc = ensure_workspace(dev, bytes);
+    void* ws = nullptr;
+    rc = ensure_workspace(dev, bytes, &ws);
     if (rc != IOLB_OK) return rc;
-    return run_winograd(x, w, nullptr, y, s, tile, dev->ws, dev->ws_bytes);
+    return run_winograd(x, w, nullptr, y, s, tile, ws, bytes);
 }
 
 int conv_winograd_pad(const float* x, const float* w, float* y, int N, int C, int H, int W, int K, int m, int pad)
@@ -581,9 +591,10 @@ int conv_winograd_pad(const float* x, const float* w, float* y, int N, int C, in
     DeviceState* dev = nullptr;
     rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;
-    rc = ensure_workspace(dev, bytes);
+    void* ws = nullptr;
+    rc = ensure_workspace(dev, bytes, &ws);
     if (rc != IOLB_OK) return rc;
-    return run_winograd(x, w, nullptr, y, s, tile, dev->ws, dev->ws_bytes);
+    return run_winograd(x, w, nullptr, y, s, tile, ws, bytes);
 }
 
 int iolb_winograd_matrices(int m, float* A, float* L, float* B)
@@ -669,11 +680,15 @@ int iolb_release_workspace(void)
     IOLB_HIP(hipGetDevice(&dev));
     std::lock_guard<std::mutex> lock(g_mutex);
     auto it = g_devices.find(dev);
-    if (it == g_devices.end() || !it->second.ws) return IOLB_OK;
-    IOLB_HIP(hipDeviceSynchronize());
-    IOLB_HIP(hipFree(it->second.ws));
-    it->second.ws = nullptr;
-    it->second.ws_bytes = 0;
+    if (it == g_devices.end()) return IOLB_OK;
+    DeviceState& d = it->second;
+    if (d.ws.empty() && d.retired.empty()) return IOLB_OK;
+    IOLB_HIP(hipDeviceSynchronize());          // nothing in flight may still use the buffers
+    for (auto& kv : d.ws)
+        if (kv.second.ptr) (void)hipFree(kv.second.ptr);
+    for (void* p : d.retired) (void)hipFree(p);
+    d.ws.clear();
+    d.retired.clear();
     return IOLB_OK;
 }
 

@@ -1,5 +1,6 @@
-// Direct convolution, plain fp32 FMA path (Sec. 5.2 dataflow) for layers whose tile cannot be
-// cut into 32 x 32 MFMA blocks (tiny or odd extents).
+// Direct convolution, plain fp32 FMA path (Sec. 5.2 dataflow): the fallback for layers on which no matrix-core
+// tile fits the LDS or none covers 64 pixels (very large kernels: an 11 x 11 stride-4 first layer), and for
+// callers that ask for an FMA tile.
 //
 // One workgroup owns an output sub-block of b images * ty rows * tx columns * z channels and keeps
 // its partial sums in registers for the whole channel loop.  Each stage copies alpha channels of the

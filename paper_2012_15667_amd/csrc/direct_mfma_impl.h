@@ -10,9 +10,11 @@
 // registers in between),
 //   - the weight slab  [alpha][R*S][z]  from the re-laid-out weights wt[C'][R*S][K'] (C' = C rounded up
 //     to whole stages, K' = K rounded up to whole 32-channel blocks, the extra rows and columns zero), whole rows per instruction, 16 bytes per lane;
-//   - the input tile   [alpha][b][yh][xh], one instruction per (tile row, 64-column segment, channel):
-//     the row's base address is wave-uniform, lanes add their column.  Elements outside the image are
-//     never loaded: both LDS buffers are cleared once and those positions stay zero.
+//   - the input tile   [alpha][b][yh][xh]: the tile of one channel is b*yh*xh contiguous LDS floats, staged in
+//     flat chunks of 64 whose lanes each fetch their own element (narrow tile rows share an instruction); tiles
+//     with more chunks than a wave keeps offsets for fall back to one instruction per (tile row, 64-column
+//     segment, channel).  Elements outside the image are never loaded: the LDS buffers are cleared once and
+//     those positions stay zero.
 // Two LDS buffers alternate.  The loads of stage s+1 are issued from inside the multiply phase of
 // stage s, by the two waves of a SIMD half a stage apart, so that the matrix core always has a wave
 // that is multiplying.
@@ -112,9 +114,10 @@ direct_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, fl
     const int nseg = (g.xh + 63) >> 6;                      // 64-lane segments per tile row
     const float* wslab = wt + k0;                           // row (c*RS + rs) of the slab starts at wslab + row*K
 
-    // Elements of the tile that fall outside the image are zero in every stage: clear both buffers
-    // once, then only ever load the elements that exist.
-    for (int i = tid; i < 2 * stage_floats; i += T) lds[i] = 0.f;
+    // Elements of the tile that fall outside the image are zero in every stage: clear the buffers once (two, or
+    // the single one of a layer whose channels fit one stage), then only ever load the elements that exist.
+    const int nbuffers = g.C <= g.alpha ? 1 : 2;
+    for (int i = tid; i < nbuffers * stage_floats; i += T) lds[i] = 0.f;
     __syncthreads();
 
     // Input-tile staging comes in two forms.
@@ -355,11 +358,9 @@ hipError_t launch_one(const float* x, const float* wt, float* y, const DirectGeo
                       size_t shm, hipStream_t st)
 {
     auto kern = direct_mfma_kernel<MBW, NBW, LB, RR, SS, HWC, EVEN>;
-    static bool raised = false;               // dynamic LDS above 64 KB needs an opt-in, once per kernel
-    if (shm > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (shm > 64 * 1024) {
+        const hipError_t e = allow_large_lds((const void*)kern);
         if (e != hipSuccess) return e;
-        raised = true;
     }
     const int grid = g.nbk * g.nbx * g.nby * g.nbn;
     DirectGeom gl = g;

@@ -4,9 +4,29 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 #include "iolbconv.h"
 
 namespace iolb {
+
+// Dynamic LDS above 64 KB needs an opt-in per kernel and device.  Done once for each pair; safe to call from
+// several host threads.
+inline hipError_t allow_large_lds(const void* kernel)
+{
+    static std::mutex guard;
+    static std::set<std::pair<const void*, int>> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(guard);
+    if (done.count({kernel, dev})) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess) done.insert({kernel, dev});
+    return e;
+}
 
 // Geometry of one direct-convolution launch: the layer, the output sub-block b * tx * ty * z of
 // Sec. 5.2 with its input tile xh * yh (x' * y' in the paper), and the block counts.

@@ -27,7 +27,7 @@ __device__ __forceinline__ void lds_dma_load_4(const float* base, unsigned offse
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                  :
                  : "v"(offset_bytes), "s"(base), "s"(lds_base_bytes)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // 16 bytes per lane from base + offset_bytes; both sides 16-byte aligned.
@@ -36,7 +36,7 @@ __device__ __forceinline__ void lds_dma_load_16(const float* base, unsigned offs
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(offset_bytes), "s"(base), "s"(lds_base_bytes)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // Wait until every load this wave has issued has written its data.

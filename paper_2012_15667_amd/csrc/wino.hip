@@ -337,11 +337,9 @@ hipError_t launch_product_one(const float* U, const float* V, float* Mp, const W
                               int grid, int threads, size_t shm, hipStream_t st)
 {
     auto kern = wino_product_kernel<MBW, NBW, LB, DEEP>;
-    static bool raised = false;
-    if (shm > 64 * 1024 && !raised) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (shm > 64 * 1024) {
+        const hipError_t e = allow_large_lds((const void*)kern);
         if (e != hipSuccess) return e;
-        raised = true;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), shm, st, U, V, Mp, g);
     return hipGetLastError();

@@ -22,8 +22,6 @@
 // Two LDS buffers alternate; one barrier per stage.  The output transform  Y = A Pi A^T  is split around an
 // exchange through LDS: wave i applies A^T from the right to its row, T[i][b] = sum_j Pi[i][j] A[b][j]; the wave
 // that finishes register r then reads the (m+2) x m values of its lanes, applies A from the left and stores.
-#include <mutex>
-
 #include "kernels.h"
 #include "lds_dma.h"
 #include "wino_mats.h"
@@ -367,13 +365,10 @@ hipError_t launch_fused_vec(const float* x, const float* U2, float* y, const Win
     const long long span = ((TB + tpi - 1) / tpi + 2) * (long long)g.C * g.H * g.W * 4;
     if (span >= (1LL << 32)) return hipErrorInvalidValue;
     auto kern = wino_fused_mfma_kernel<M, WT, WK, ALPHA, VEC>;
-    static std::once_flag raised;
-    static hipError_t raise_rc = hipSuccess;
-    std::call_once(raised, [&] {
-        if (shm > 64 * 1024)
-            raise_rc = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    });
-    if (raise_rc != hipSuccess) return raise_rc;
+    if (shm > 64 * 1024) {
+        const hipError_t e = allow_large_lds((const void*)kern);
+        if (e != hipSuccess) return e;
+    }
     const long long grid_ll = (long long)(g.Kp / Z) * ((g.tiles + TB - 1) / TB);
     if (grid_ll > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid_ll), dim3(T), shm, st, x, U2, y, g);

@@ -19,8 +19,6 @@
 // finishes register r then applies A from the left over the m+2 rows and stores.
 //
 // Buffers: two product stages (U2 slab + V) and two scratch buffers alternate; one barrier per stage.
-#include <mutex>
-
 #include "kernels.h"
 #include "wino_mats.h"
 #include "wino_transform.h"
@@ -329,13 +327,10 @@ hipError_t launch_rows_one(const float* x, const float* U2, float* y, const Wino
     const long long span = ((TB + tpi - 1) / tpi + 2) * (long long)g.C * g.H * g.W * 4;
     if (span >= (1LL << 32)) return hipErrorInvalidValue;
     auto kern = wino_rows_kernel<M, WT, WK, ALPHA>;
-    static std::once_flag raised;
-    static hipError_t raise_rc = hipSuccess;
-    std::call_once(raised, [&] {
-        if (shm > 64 * 1024)
-            raise_rc = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    });
-    if (raise_rc != hipSuccess) return raise_rc;
+    if (shm > 64 * 1024) {
+        const hipError_t e = allow_large_lds((const void*)kern);
+        if (e != hipSuccess) return e;
+    }
     const long long grid_ll = (long long)(g.Kp / Z) * ((g.tiles + TB - 1) / TB);
     if (grid_ll > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid_ll), dim3(T), shm, st, x, U2, y, g);

@@ -15,6 +15,11 @@ pytestmark = pytest.mark.gpu
 
 TOL_DIRECT = 1e-4
 TOL_WINO = 5e-3
+# Regression guards at about ten times the errors measured on the full-size layers (direct 3e-6; Winograd 3e-6,
+# 2e-5, 5e-5, 7e-5 for m = 2, 3, 4, 6): far inside the contract tolerances above, so a loss of accuracy that the
+# contract would still pass fails here.
+GUARD_DIRECT = 3e-5
+GUARD_WINO = {2: 5e-5, 3: 5e-4, 4: 5e-4, 6: 1e-3}
 
 
 @pytest.fixture(scope="module")
@@ -191,6 +196,51 @@ def test_direct_full_size_sampled(gpu, name):
     g = got[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
     assert rel_err(g, ref) <= TOL_DIRECT
     assert np.isfinite(got).all()
+
+
+_WHOLE_IMAGE_REFS = {}
+
+
+def _whole_image_reference(name):
+    """Oracle outputs of images 0, N/2 and N-1 of a full-size layer (3/64 of the layer: every tile row and column,
+    every channel block and every XCD slab of a workgroup grid is covered), computed once per layer."""
+    if name not in _WHOLE_IMAGE_REFS:
+        L = CONFIGS[name]
+        x, w = layer_inputs(L)
+        imgs = [0, L.N // 2, L.N - 1]
+        _WHOLE_IMAGE_REFS[name] = (x, w, imgs, conv_ref(np.ascontiguousarray(x[imgs]), w, L.stride, L.pad))
+    return _WHOLE_IMAGE_REFS[name]
+
+
+@pytest.mark.parametrize("algo", ["direct", "direct_bound", "wino2", "wino2_fused", "wino2_unfused", "wino4", "wino4_fused", "wino4_unfused"])
+@pytest.mark.parametrize("name", ["cfg5a", "cfg5b", "cfg5c", "cfg5d"])
+def test_full_size_layers_whole_images_match_oracle(gpu, name, algo):
+    """The bench configuration at full size, in the launch configuration bench.py times (the tuned tile), plus the
+    bound-only direct tile and both Winograd paths: EVERY output of three whole images against the oracle."""
+    torch, B = gpu
+    L = CONFIGS[name]
+    x, w, imgs, ref = _whole_image_reference(name)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    if algo.startswith("direct"):
+        cfg = B.iolb_tune_bound(B.make_shape(L.N, L.C, L.H, L.W, L.K)) if algo == "direct_bound" else None
+        y = B.conv_direct(xd, wd, 1, 1, cfg=cfg)
+        tol, guard = TOL_DIRECT, GUARD_DIRECT
+    else:
+        m = int(algo[4])
+        cfg = None
+        if "_" in algo:
+            want = B.PATH_FUSED if algo.endswith("_fused") else B.PATH_MFMA
+            tiles = [t for t in B.iolb_enumerate(B.make_shape(L.N, L.C, L.H, L.W, L.K, algo=B.WINO_ALGO[m]), 0, 0, False)
+                     if t["path"] == want]
+            cfg = tiles[0]
+        y = B.conv_winograd(xd, wd, m, cfg=cfg)
+        tol, guard = TOL_WINO, GUARD_WINO[m]
+    torch.cuda.synchronize()
+    got = y[imgs].cpu().numpy()
+    del y
+    err = rel_err(got, ref)
+    assert err <= tol
+    assert err <= guard, "accuracy regression: %.2e" % err
 
 
 @pytest.mark.parametrize("name", ["alex1", "alex2", "alex3", "alex4"])
@@ -602,6 +652,80 @@ def test_calls_can_be_captured_in_a_hip_graph(gpu):
         assert np.array_equal(got_d, eager), rep
         ref = conv_ref(x2, w, 1, 1)
         assert rel_err(got_d, ref) <= TOL_DIRECT and rel_err(got_w, ref) <= TOL_WINO, rep
+
+
+def test_two_host_threads_with_a_stream_each_do_not_share_scratch(gpu):
+    """One stream per host thread: the library keeps a workspace per stream, so an unfused Winograd layer (whose
+    transformed inputs and products live in the workspace) and a direct layer running concurrently from two
+    threads give what they give alone."""
+    import threading
+    torch, B = gpu
+    xa, wa = make_inputs(8, 64, 56, 56, 64, 3, 3, "u01", "he", seed=91)
+    xb, wb = make_inputs(8, 48, 40, 40, 96, 3, 3, "u01", "he", seed=92)
+    dev = [torch.from_numpy(a).cuda() for a in (xa, wa, xb, wb)]
+    shape_a = B.make_shape(8, 64, 56, 56, 64, algo=B.WINO_F4)
+    unfused = [t for t in B.iolb_enumerate(shape_a, 0, 0, False) if t["path"] == B.PATH_MFMA][0]
+    alone_a = B.conv_winograd(dev[0], dev[1], 4).clone()
+    alone_b = B.conv_winograd(dev[2], dev[3], 2).clone()
+    alone_c = B.conv_direct(dev[2], dev[3], 1, 1).clone()
+    torch.cuda.synchronize()
+    results, errors = {}, []
+
+    def worker(tag, fn, reps):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                outs = [fn().clone() for _ in range(reps)]
+            stream.synchronize()
+            results[tag] = outs
+        except Exception as e:          # noqa: BLE001 -- reported by the main thread
+            errors.append((tag, e))
+
+    threads = [threading.Thread(target=worker, args=("a", lambda: B.conv_winograd(dev[0], dev[1], 4), 6)),
+               threading.Thread(target=worker, args=("b", lambda: B.conv_winograd(dev[2], dev[3], 2), 12)),
+               threading.Thread(target=worker, args=("c", lambda: B.conv_direct(dev[2], dev[3], 1, 1), 12))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    assert unfused["path"] == B.PATH_MFMA
+    for tag, alone in (("a", alone_a), ("b", alone_b), ("c", alone_c)):
+        for out in results[tag]:
+            assert torch.equal(out, alone), tag
+
+
+def test_a_captured_graph_survives_the_growth_of_the_workspace(gpu):
+    """A workspace that has to grow is replaced, not freed: a graph captured before still replays correctly after
+    a larger layer has run on the same stream."""
+    torch, B = gpu
+    N, C, H, W, K = 2, 16, 20, 20, 32
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u01", "he", seed=95)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    yd = torch.empty((N, K, H, W), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.conv_winograd(xd, wd, 4, y=yd)                 # sizes this stream's workspace for the small layer
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.conv_winograd(xd, wd, 4, y=yd)
+    ref = conv_ref(x, w, 1, 1)
+    xl, wl = make_inputs(16, 64, 56, 56, 64, 3, 3, "u01", "he", seed=96)
+    with torch.cuda.stream(side):
+        big = B.conv_winograd(torch.from_numpy(xl).cuda(), torch.from_numpy(wl).cuda(), 4)    # grows the workspace
+    side.synchronize()
+    assert rel_err(big.cpu().numpy(), conv_ref(xl, wl, 1, 1)) <= TOL_WINO
+    for rep in range(2):
+        yd.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert rel_err(yd.cpu().numpy(), ref) <= TOL_WINO, rep
+        B.conv_direct(xd, wd, 1, 1)                      # eager work between the replays
+    torch.cuda.synchronize()
 
 
 def test_padded_and_fused_calls_can_be_captured_too(gpu):
