@@ -270,6 +270,8 @@ def tune_by_volume(N, C, P, Q, K, R, S, stride, Sb, z_step=1):
 MODEL_CONSTANTS = {
     # name: (value, unit, where it came from)
     "operand_read": (32, "cycles per LDS operand read of a wave", "fit to 300-tile sweeps on 21 layers, one MI355X"),
+    "operand_read_shared": (8, "cycles of a SIMD's matrix-core time per operand read of any of its waves",
+                            "250-tile sweeps with several wave grids per tile on cfg3, cfg5a-d, AlexNet conv2/3"),
     "load_issue": (300, "cycles per LDS-direct load instruction", "s_memtime around the issue of back-to-back loads"),
     "barrier": (100, "cycles per wave and stage", "fit to the same sweeps"),
     "startup": (15000, "cycles per workgroup", "fit to the same sweeps"),
@@ -327,11 +329,12 @@ def _pick_alpha(C, choices, per_alpha_bytes, lds_bytes, buffers=1):
     return None if best is None else best[1]
 
 
-def _wave_grids(MB, NB, vgpr_budget):
-    """All wave grids for MB x NB blocks of 32 x 32 outputs: a wave owns mbw x nbw blocks (mbw in {1,2},
-    at most 8 blocks); waves_m divides MB, waves_n = ceil(NB / nbw) -- the last wave column may own
-    blocks past the tile, which stay idle.  Ordered by idle blocks first, then workgroup size."""
-    out = []
+def _wave_grids(MB, NB, vgpr_budget, exact_only=False):
+    """Wave grids for MB x NB blocks of 32 x 32 outputs: a wave owns mbw x nbw blocks (mbw in {1,2}, at most 8
+    blocks); waves_m divides MB, waves_n = ceil(NB / nbw) -- the last wave column may own blocks past the tile,
+    which stay idle.  One grid per workgroup size (fewest idle blocks, then fewest operand reads), ascending in
+    (idle blocks, threads, ...): the first is the tightest fit."""
+    best = {}
     for wm in divisors(MB):
         mbw = MB // wm
         if mbw not in (1, 2):
@@ -340,6 +343,8 @@ def _wave_grids(MB, NB, vgpr_budget):
             if mbw * nbw > 8 or nbw > NB:
                 continue
             wn = -(-NB // nbw)
+            if exact_only and wn * nbw != NB:
+                continue
             T = 64 * wm * wn
             if T not in T_CHOICES:
                 continue
@@ -347,26 +352,48 @@ def _wave_grids(MB, NB, vgpr_budget):
                 continue
             if 16 * mbw * nbw + 64 > 131072 // T:      # register-file share of a lane, 64 kept for operands
                 continue
-            out.append((wn * nbw - NB, T, mbw + nbw, wm, wn, 16 * mbw * nbw))
-    return out
+            g = (wn * nbw - NB, T, mbw + nbw, wm, wn, 16 * mbw * nbw)
+            if T not in best or g < best[T]:
+                best[T] = g
+    return sorted(best.values())
 
 
 def _cdiv(a, b):
     return -(-a // b)
 
 
-def mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, q_read, q_write):
-    """Modelled run time (matrix-core clock cycles) of a direct-convolution tile on the matrix-core path:
-    the ranking function of the tile rule.  Per stage a wave keeps the matrix core of its SIMD busy for
-    steps * blocks * 64 cycles (one 32x32x2 MFMA per block and step, steps = alpha/2 * R*S); it also issues
-    its operand reads (32 cycles each) and its share of the stage's load instructions (300 cycles each).
-    Waves of the workgroup that share a SIMD hide that behind each other's matrix work; a barrier costs
+def block_cost(steps, mbw, nbw, loads, waves, acc, lds_used, stages, nblocks, memory_cycles):
+    """The model proper (matrix-core clock cycles), shared by direct convolution and the Winograd product: a
+    workgroup of `waves` waves, each owning mbw x nbw blocks of 32 x 32 partial sums, runs `stages` stages of
+    `steps` MFMA steps (64 cycles per block) and `loads` load instructions per wave (300 cycles each), plus 32
+    cycles per operand read; waves that share a SIMD hide that behind each other's matrix work; a barrier costs
     100 cycles per wave; a workgroup pays 15000 cycles to start and 200 per accumulator register to store.
-    Workgroups run one per compute unit (several, if they have at most four waves) in rounds over the 256
-    compute units.  The result cannot beat the
-    time the reading and writing volumes need at 4000 / 1500 bytes per cycle (a tile row counts at least one
-    128-byte request).  The constants come from
-    tile sweeps on an MI355X; everything is integer arithmetic."""
+    Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as many
+    as the LDS and the registers hold (512 per SIMD lane, acc + 64 per wave), at most 4 one-wave or 2 larger
+    ones, no more than the layer has per compute unit; waves of different workgroups overlap a little less
+    well (+10 % on the shared matrix-core time).  Rounds over the 256 compute units; never below the time the
+    memory traffic needs.  See MODEL_CONSTANTS for where the numbers come from."""
+    mfma = steps * mbw * nbw * 64
+    own = mfma + steps * (mbw + nbw) * 32 + 300 * loads
+    resident = 1
+    if waves <= 4:
+        resident = max(1, min(LDS_CU // lds_used, 4 * (512 // (acc + 64)) // waves, 4 if waves == 1 else 2,
+                              _cdiv(nblocks, N_CU)))
+    sharing = _cdiv(resident * waves, 4)                    # waves per SIMD
+    per_wave = mfma + steps * (mbw + nbw) * 8               # operand reads hold up the MFMA issue of the SIMD's other waves
+    shared = per_wave * sharing * 11 // 10 if resident > 1 else per_wave * sharing
+    stage = (max(shared, own) if sharing > 1 else own) + 100 * waves
+    workgroup = stages * stage + 15000 + 200 * acc
+    compute = _cdiv(nblocks, N_CU * resident) * workgroup
+    return max(compute, memory_cycles)
+
+
+def mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, q_read, q_write):
+    """Modelled run time of a direct-convolution tile on the matrix-core path: the ranking function of this
+    build's tile rule.  steps = alpha/2 * R*S per stage; load instructions per wave and stage: the input tile in
+    flat chunks of 64 elements when a wave owns at most 8 of them (else one per tile row and 64 columns), per
+    channel, plus its share of the weight slab in 16-byte pieces.  Memory floor: reads at 4000 and writes at 1500
+    bytes per cycle, a tile row counting at least one 128-byte request."""
     RS = s["R"] * s["S"]
     waves = T // 64
     mbw = (z // 32) // wm
@@ -379,28 +406,24 @@ def mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, q_read, q_write):
     else:
         loads_in = _cdiv(b * yp * _cdiv(xp, 64), waves) * alpha         # one per tile row and 64 columns
     loads_w = _cdiv(alpha * RS * (z // 4), 64 * waves)
-    steps = (alpha // 2) * RS
-    mfma = steps * mbw * nbw * 64
-    own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w)
-    # Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as
-    # many as the LDS holds (a single stage needs one buffer) and the registers hold (512 per SIMD lane,
-    # acc + 64 per wave), at most 4 one-wave or 2 larger workgroups, and no more than the layer has per compute
-    # unit.  Waves of different workgroups overlap a little less well than those of one (+10 % on the shared
-    # matrix-core time).  Larger workgroups are modelled one per compute unit.
-    resident = 1
-    if waves <= 4:
-        lds_used = (4 if alpha >= s["C"] else 8) * alpha * (halo + RS * z)
-        resident = max(1, min(LDS_CU // lds_used, 4 * (512 // (acc + 64)) // waves, 4 if waves == 1 else 2,
-                              _cdiv(nblocks, N_CU)))
-    sharing = _cdiv(resident * waves, 4)                    # waves per SIMD
-    shared = mfma * sharing * 11 // 10 if resident > 1 else mfma * sharing
-    stage = (max(shared, own) if sharing > 1 else own) + 100 * waves
-    workgroup = _cdiv(s["C"], alpha) * stage + 15000 + 200 * acc
-    compute = _cdiv(nblocks, N_CU * resident) * workgroup
+    lds_used = (4 if alpha >= s["C"] else 8) * alpha * (halo + RS * z)
     in_bytes = nblocks * s["C"] * b * yp * max(4 * xp, 128)     # a short tile row still costs a 128-byte request
     w_bytes = 4 * (q_read - nblocks * s["C"] * halo)
     memory = (in_bytes + w_bytes) // 4000 + (4 * q_write) // 1500
-    return max(compute, memory)
+    return block_cost((alpha // 2) * RS, mbw, nbw, loads_in + loads_w, waves, acc, lds_used, _cdiv(s["C"], alpha),
+                      nblocks, memory)
+
+
+def product_tile_cost(s, tb, z, alpha, T, wm, acc, nblocks, q_read, m_elems):
+    """The same model for a block of the unfused Winograd product: tb sub-domains by z channels of one plane, alpha
+    rows of U (z floats) and of V (tb floats) per stage in 16-byte loads, one MFMA step per channel pair."""
+    waves = T // 64
+    mbw = (z // 32) // wm
+    nbw = acc // 16 // mbw
+    loads = _cdiv(alpha * (z // 4), 64 * waves) + _cdiv(alpha * (tb // 4), 64 * waves)
+    lds_used = (4 if alpha >= s["C"] else 8) * alpha * (tb + z)
+    memory = (4 * q_read) // 4000 + (4 * m_elems) // 1500
+    return block_cost(alpha // 2, mbw, nbw, loads, waves, acc, lds_used, _cdiv(s["C"], alpha), nblocks, memory)
 
 
 def _pow2ceil(v):
@@ -440,17 +463,13 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                     if path == PATH_MFMA:
                         if z % 32:
                             continue
-                        grids = _wave_grids(z // 32, -(-npix // 32), vgpr_budget)
-                        alpha = None
-                        if grids:
-                            _, T0, _, _, _, acc0 = min(grids)
-                            budget = lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0)
-                            alpha = _pick_alpha(C, (64, 32, 16, 8, 4), 8 * (halo + R * S * z), budget, 2)
-                            # a stage too large for half the LDS (large kernels) may take all of it, provided the
-                            # smallest weight slab (4 channels of 32 kernels, two buffers) leaves half to the tile
-                            if alpha is None and not lds_bytes and 8 * 4 * R * S * 32 <= LDS_CU // 2:
-                                alpha = _pick_alpha(C, (64, 32, 16, 8, 4), 8 * (halo + R * S * z), LDS_CU, 2)
-                        lds_mult = 4 if alpha is not None and alpha >= C else 8      # one stage only: one buffer
+                        # the tightest wave grid, and the larger workgroups that idle on at most a quarter of the
+                        # tile's blocks more
+                        NB = -(-npix // 32)
+                        grids = []
+                        for g in _wave_grids(z // 32, NB, vgpr_budget):
+                            if not grids or 4 * (g[0] - grids[0][0]) <= NB:
+                                grids.append(g)
                     else:
                         if npix > 256:
                             continue
@@ -463,24 +482,34 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
                             if z % KG or z // KG > 16 or z // KG > vgpr_budget:
                                 continue
                             grids.append((0, T, 0, KG, 1, z // KG))
-                        alpha = _pick_alpha(C, (16, 8, 4, 2, 1), 4 * (halo + R * S * z), lds_bytes or 81920)
-                        lds_mult = 4
-                    if alpha is None or not grids:
-                        continue
-                    nblocks = (N // b) * (-(-Q // x)) * (-(-P // y)) * (Kz // z)
-                    qread = nblocks * C * (halo + R * S * z)
-                    _, T, _, wm, wn, acc = min(grids)
-                    if path == PATH_MFMA:
-                        cost = mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, qread, N * K * P * Q)
-                        key = (cost, qread, -npix * z, -x, z, b, y, T, 0, 0)
-                    else:
-                        key = (-_grid_efficiency_pct(nblocks), 0, qread, abs(npix * st * st - R * S * z),
-                               -npix * z, -x, z, b, y, T)
-                    cands.append((key, dict(b=b, x=x, y=y, z=z, alpha=alpha, threads=T, waves_m=wm,
-                                            waves_n=wn, path=path, wt_mode=0,
-                                            lds_bytes_used=lds_mult * alpha * (halo + R * S * z),
-                                            acc_regs_per_thread=acc, q_read_elems=qread,
-                                            q_write_elems=N * K * P * Q)))
+                            break
+                    for _, T, _, wm, wn, acc in grids:
+                        if path == PATH_MFMA:
+                            budget = lds_bytes if lds_bytes else _auto_lds_budget(T, acc)
+                            alpha = _pick_alpha(C, (64, 32, 16, 8, 4), 8 * (halo + R * S * z), budget, 2)
+                            # a stage too large for half the LDS (large kernels) may take all of it, provided the
+                            # smallest weight slab (4 channels of 32 kernels, two buffers) leaves half to the tile
+                            if alpha is None and not lds_bytes and 8 * 4 * R * S * 32 <= LDS_CU // 2:
+                                alpha = _pick_alpha(C, (64, 32, 16, 8, 4), 8 * (halo + R * S * z), LDS_CU, 2)
+                            lds_mult = 4 if alpha is not None and alpha >= C else 8      # one stage only: one buffer
+                        else:
+                            alpha = _pick_alpha(C, (16, 8, 4, 2, 1), 4 * (halo + R * S * z), lds_bytes or 81920)
+                            lds_mult = 4
+                        if alpha is None:
+                            continue
+                        nblocks = (N // b) * (-(-Q // x)) * (-(-P // y)) * (Kz // z)
+                        qread = nblocks * C * (halo + R * S * z)
+                        if path == PATH_MFMA:
+                            cost = mfma_tile_cost(s, b, x, y, z, alpha, T, wm, acc, nblocks, qread, N * K * P * Q)
+                            key = (cost, qread, -npix * z, -x, z, b, y, T, 0, 0)
+                        else:
+                            key = (-_grid_efficiency_pct(nblocks), 0, qread, abs(npix * st * st - R * S * z),
+                                   -npix * z, -x, z, b, y, T)
+                        cands.append((key, dict(b=b, x=x, y=y, z=z, alpha=alpha, threads=T, waves_m=wm,
+                                                waves_n=wn, path=path, wt_mode=0,
+                                                lds_bytes_used=lds_mult * alpha * (halo + R * S * z),
+                                                acc_regs_per_thread=acc, q_read_elems=qread,
+                                                q_write_elems=N * K * P * Q)))
     return cands
 
 
@@ -549,21 +578,19 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs=True)
                 continue
             if use_f3 and not (z * z <= sb_max and tb * tb <= sb_max):
                 continue
-            grids = [g for g in _wave_grids(z // 32, tb // 32, vgpr_budget) if g[0] == 0]   # tb is free: no idle blocks
-            if not grids:
-                continue
-            _, T0, _, _, _, acc0 = min(grids)
-            alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes if lds_bytes else _auto_lds_budget(T0, acc0), 2)
-            if alpha is None:
-                continue
-            nblocks = n2 * (-(-tiles // tb)) * (Kz // z)
-            qread = nblocks * C * (tb + z)
-            _, T, _, wm, wn, acc = min(grids)
-            key = (-_grid_efficiency_pct(nblocks), qread, abs(tb - z), -tb * z, z, T)
-            cands.append((key, dict(b=1, x=e * tb, y=e, z=z, alpha=alpha, threads=T, waves_m=wm,
-                                    waves_n=wn, path=PATH_MFMA, wt_mode=1,
-                                    lds_bytes_used=(4 if alpha >= C else 8) * alpha * (tb + z), acc_regs_per_thread=acc,
-                                    q_read_elems=qread, q_write_elems=N * K * P * Q)))
+            for _, T, _, wm, wn, acc in _wave_grids(z // 32, tb // 32, vgpr_budget, exact_only=True):   # tb is free: no idle blocks
+                alpha = _pick_alpha(C, (16, 8, 4), 8 * (tb + z), lds_bytes if lds_bytes else _auto_lds_budget(T, acc), 2)
+                if alpha is None:
+                    continue
+                ntb = -(-tiles // tb)
+                nblocks = n2 * ntb * (Kz // z)
+                qread = nblocks * C * (tb + z)
+                cost = product_tile_cost(s, tb, z, alpha, T, wm, acc, nblocks, qread, n2 * Kz * ntb * tb)
+                key = (0, cost, qread, abs(tb - z), -tb * z, z, T)
+                cands.append((key, dict(b=1, x=e * tb, y=e, z=z, alpha=alpha, threads=T, waves_m=wm,
+                                        waves_n=wn, path=PATH_MFMA, wt_mode=1,
+                                        lds_bytes_used=(4 if alpha >= C else 8) * alpha * (tb + z), acc_regs_per_thread=acc,
+                                        q_read_elems=qread, q_write_elems=N * K * P * Q)))
     return cands
 
 

@@ -95,12 +95,12 @@ struct WaveGrid {
     }
 };
 
-// Best wave grid for MB x NB blocks of 32 x 32 partial sums: a wave owns mbw x nbw blocks (mbw in {1,2},
-// at most 8 blocks = 128 accumulator registers); waves_m divides MB, waves_n = ceil(NB / nbw) -- the last
-// wave column may own blocks past the tile, which stay idle.  Fewest idle blocks first, then the smallest
-// workgroup.
-bool best_wave_grid(int MB, int NB, int vgpr_budget, bool exact_only, WaveGrid* out) {
-    bool found = false;
+// Wave grids for MB x NB blocks of 32 x 32 partial sums: a wave owns mbw x nbw blocks (mbw in {1,2}, at most 8
+// blocks = 128 accumulator registers); waves_m divides MB, waves_n = ceil(NB / nbw) -- the last wave column may
+// own blocks past the tile, which stay idle.  One grid per workgroup size: the one with the fewest idle blocks,
+// then the fewest operand reads.  Ascending in (idle, threads, ...): the first is the tightest fit.
+std::vector<WaveGrid> wave_grids(int MB, int NB, int vgpr_budget, bool exact_only) {
+    std::vector<WaveGrid> best;                       // at most one per thread count
     for (int wm = 1; wm <= MB; ++wm) {
         if (MB % wm) continue;
         const int mbw = MB / wm;
@@ -113,12 +113,18 @@ bool best_wave_grid(int MB, int NB, int vgpr_budget, bool exact_only, WaveGrid* 
             if (!allowed_threads(threads) || 16 * mbw * nbw > vgpr_budget) continue;
             // a compute unit's register file holds 131072 lane-registers; leave 64 per lane for operands
             if (16 * mbw * nbw + 64 > 131072 / threads) continue;
-            WaveGrid g{wn * nbw - NB, (int)threads, mbw + nbw, wm, wn, 16 * mbw * nbw};
-            if (!found || g < *out) *out = g;
-            found = true;
+            const WaveGrid g{wn * nbw - NB, (int)threads, mbw + nbw, wm, wn, 16 * mbw * nbw};
+            bool placed = false;
+            for (auto& o : best)
+                if (o.threads == g.threads) {
+                    if (g < o) o = g;
+                    placed = true;
+                }
+            if (!placed) best.push_back(g);
         }
     }
-    return found;
+    std::sort(best.begin(), best.end());
+    return best;
 }
 
 // Modelled run time, in matrix-core clock cycles, of a direct-convolution tile on the MFMA path.  The
@@ -129,6 +135,32 @@ bool best_wave_grid(int MB, int NB, int vgpr_budget, bool exact_only, WaveGrid* 
 // unit (several, if they have at most four waves) in rounds; the result cannot beat the time the reading and writing volumes need.  The constants were
 // fitted to tile sweeps on an MI355X.  Integers only, so that both implementations of the tuner agree bit
 // for bit.
+// The model proper, shared by direct convolution and the Winograd product: a workgroup of `waves` waves, each
+// owning mbw x nbw blocks, runs `stages` stages of `steps` MFMA steps and `loads` load instructions per wave.
+int64_t block_cost(int64_t steps, int64_t mbw, int64_t nbw, int64_t loads, int64_t waves, int64_t acc, int64_t lds_used,
+                   int64_t stages, int64_t nblocks, int64_t memory_cycles) {
+    const int64_t mfma = steps * mbw * nbw * 64;                 // cycles one wave's stage keeps the matrix core busy
+    const int64_t own = mfma + steps * (mbw + nbw) * 32 + 300 * loads;
+    // Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as many
+    // as the LDS holds and the registers hold (512 per SIMD lane, acc + 64 per wave), at most 4 one-wave or 2
+    // larger workgroups, and no more than the layer has per compute unit.  Waves of different workgroups overlap
+    // a little less well than those of one (+10 % on the shared matrix-core time).  Larger workgroups are
+    // modelled one per compute unit.
+    int64_t resident = 1;
+    if (waves <= 4)
+        resident = std::max<int64_t>(1, std::min({kLdsPerCu / lds_used, 4 * (512 / (acc + 64)) / waves,
+                                                  (int64_t)(waves == 1 ? 4 : 2), ceil_div(nblocks, kComputeUnits)}));
+    const int64_t sharing = ceil_div(resident * waves, 4);       // waves per SIMD
+    // what the waves of a SIMD cannot hide from each other: their matrix-core time, and 8 cycles of it per operand
+    // read (the reads of one wave hold up the MFMA issue of the others)
+    const int64_t per_wave = mfma + steps * (mbw + nbw) * 8;
+    const int64_t shared = resident > 1 ? per_wave * sharing * 11 / 10 : per_wave * sharing;
+    const int64_t stage = (sharing > 1 ? std::max(shared, own) : own) + 100 * waves;           // + barrier
+    const int64_t workgroup = stages * stage + 15000 + 200 * acc;                              // + start-up, stores
+    const int64_t compute = ceil_div(nblocks, kComputeUnits * resident) * workgroup;
+    return std::max(compute, memory_cycles);
+}
+
 int64_t mfma_tile_cost(const iolb_shape& s, int b, int x, int y, int z, int alpha, const WaveGrid& g,
                        int64_t nblocks, int64_t q_read, int64_t q_write) {
     const int64_t RS = (int64_t)s.R * s.S;
@@ -141,30 +173,24 @@ int64_t mfma_tile_cost(const iolb_shape& s, int b, int x, int y, int z, int alph
     const int64_t chunks_per_wave = ceil_div(ceil_div(halo, 64), waves);
     const int64_t loads_in = (chunks_per_wave <= 8 ? chunks_per_wave : ceil_div(b * yh * ceil_div(xh, 64), waves)) * alpha;
     const int64_t loads_w = ceil_div((int64_t)alpha * RS * (z / 4), 64 * waves);
-    const int64_t steps = (alpha / 2) * RS;                      // MFMA steps of a stage (two channels each)
-    const int64_t mfma = steps * mbw * nbw * 64;                 // cycles one wave's stage keeps the matrix core busy
-    const int64_t own = mfma + steps * (mbw + nbw) * 32 + 300 * (loads_in + loads_w);
-    // Workgroups of up to four waves leave room on their compute unit, so several are resident at once: as many
-    // as the LDS holds (a single stage needs one buffer) and the registers hold (512 per SIMD lane, acc + 64 per
-    // wave), at most 4 one-wave or 2 larger workgroups, and no more than the layer has per compute unit.  Waves of
-    // different workgroups overlap a little less well than those of one (+10 % on the shared matrix-core time).
-    // Larger workgroups are modelled one per compute unit.
-    int64_t resident = 1;
-    if (waves <= 4) {
-        const int64_t lds_used = (alpha >= s.C ? 4 : 8) * alpha * (halo + RS * z);
-        resident = std::max<int64_t>(1, std::min({kLdsPerCu / lds_used, 4 * (512 / ((int64_t)g.acc + 64)) / waves,
-                                                  (int64_t)(waves == 1 ? 4 : 2), ceil_div(nblocks, kComputeUnits)}));
-    }
-    const int64_t sharing = ceil_div(resident * waves, 4);       // waves per SIMD
-    const int64_t shared = resident > 1 ? mfma * sharing * 11 / 10 : mfma * sharing;
-    const int64_t stage = (sharing > 1 ? std::max(shared, own) : own) + 100 * waves;           // + barrier
-    const int64_t workgroup = ceil_div(s.C, alpha) * stage + 15000 + 200 * (int64_t)g.acc;     // + start-up, stores
-    const int64_t compute = ceil_div(nblocks, kComputeUnits * resident) * workgroup;
+    const int64_t lds_used = (alpha >= s.C ? 4 : 8) * alpha * (halo + RS * z);
     // bytes over bytes per cycle; a tile row shorter than 128 bytes still costs a whole 128-byte request
     const int64_t in_bytes = nblocks * s.C * b * yh * std::max<int64_t>(4 * xh, 128);
     const int64_t w_bytes = 4 * (q_read - nblocks * s.C * halo);
     const int64_t memory = (in_bytes + w_bytes) / 4000 + (4 * q_write) / 1500;
-    return std::max(compute, memory);
+    return block_cost((alpha / 2) * RS, mbw, nbw, loads_in + loads_w, waves, g.acc, lds_used, ceil_div(s.C, alpha), nblocks, memory);
+}
+
+// The same model for a block of the unfused Winograd product: tb sub-domains by z channels of one plane, alpha
+// rows of U (z floats) and of V (tb floats) per stage in 16-byte loads, one MFMA step per channel pair.
+int64_t product_tile_cost(const iolb_shape& s, int64_t tb, int z, int alpha, const WaveGrid& g, int64_t nblocks,
+                          int64_t q_read, int64_t m_elems) {
+    const int64_t waves = g.threads / 64;
+    const int64_t mbw = (z / 32) / g.wm, nbw = g.acc / 16 / mbw;
+    const int64_t loads = ceil_div((int64_t)alpha * (z / 4), 64 * waves) + ceil_div((int64_t)alpha * (tb / 4), 64 * waves);
+    const int64_t lds_used = (alpha >= s.C ? 4 : 8) * alpha * (tb + z);
+    const int64_t memory = (4 * q_read) / 4000 + (4 * m_elems) / 1500;
+    return block_cost(alpha / 2, mbw, nbw, loads, waves, g.acc, lds_used, ceil_div(s.C, alpha), nblocks, memory);
 }
 
 int pow2_at_least(int v) {
@@ -193,58 +219,65 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
                 for (int z : fz) {
                     if (use_box && !((int64_t)z * z * RS <= box * st2 && npix * npix * st2 <= box * RS)) continue;
                     const int64_t per_stage = halo + RS * z;
-                    WaveGrid g{};
-                    int alpha = 0;
-                    int lds_mult = 0;
+                    std::vector<WaveGrid> grids;
                     if (path == IOLB_PATH_MFMA) {
                         if (z % 32) continue;
-                        if (!best_wave_grid(z / 32, (int)((npix + 31) / 32), vgpr_budget, false, &g)) continue;
-                        alpha = choose_alpha(s.C, alphas_mfma, 5, 8 * per_stage,
-                                             lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc), 2);
-                        // automatic budget: a stage too large for half the LDS (large kernels) may take all of it,
-                        // as long as the smallest weight slab (4 channels, 32 kernels) leaves half to the input tile
-                        if (alpha == 0 && !lds_bytes && 8 * 4 * RS * 32 <= kLdsPerCu / 2)
-                            alpha = choose_alpha(s.C, alphas_mfma, 5, 8 * per_stage, kLdsPerCu, 2);
-                        lds_mult = alpha >= s.C ? 4 : 8;            // one stage only: one buffer
+                        // the tightest wave grid, and the larger workgroups that idle on at most a quarter of the
+                        // tile's blocks more: more waves per SIMD hide the loads of small layers
+                        const int NB = (int)((npix + 31) / 32);
+                        for (const WaveGrid& g : wave_grids(z / 32, NB, vgpr_budget, false))
+                            if (grids.empty() || 4 * (g.idle - grids.front().idle) <= NB) grids.push_back(g);
                     } else {
                         if (npix > 256) continue;
                         const int lanes = std::max(pow2_at_least((int)npix), 16);
-                        bool found = false;
                         for (int T : {64, 128, 256}) {
                             if (lanes > T) continue;
                             const int groups = T / lanes;
                             if (z % groups) continue;
                             const int per_thread = z / groups;
                             if (per_thread > 16 || per_thread > vgpr_budget) continue;
-                            g = WaveGrid{0, T, 0, groups, 1, per_thread};
-                            found = true;
+                            grids.push_back(WaveGrid{0, T, 0, groups, 1, per_thread});
                             break;               // ascending T: the first is the smallest
                         }
-                        if (!found) continue;
-                        alpha = choose_alpha(s.C, alphas_fma, 5, 4 * per_stage, lds_bytes ? lds_bytes : kLdsHalf);
-                        lds_mult = 4;
                     }
-                    if (alpha == 0) continue;
-                    const int64_t nblocks = (int64_t)(s.N / b) * ceil_div(Q, x) * ceil_div(P, y) * (Kz / z);
-                    Candidate c{};
-                    c.cfg.b = b; c.cfg.x = x; c.cfg.y = y; c.cfg.z = z;
-                    c.cfg.alpha = alpha;
-                    c.cfg.threads = g.threads; c.cfg.waves_m = g.wm; c.cfg.waves_n = g.wn;
-                    c.cfg.path = path; c.cfg.wt_mode = 0;
-                    c.cfg.lds_bytes_used = (int32_t)(lds_mult * alpha * per_stage);
-                    c.cfg.acc_regs_per_thread = g.acc;
-                    c.cfg.q_read_elems = nblocks * s.C * per_stage;
-                    c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
-                    c.volume = {c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z), -npix * z, -(int64_t)x, z, b, y, g.threads, -path, 0};
-                    if (path == IOLB_PATH_MFMA) {
-                        const int64_t cost = mfma_tile_cost(s, b, x, y, z, alpha, g, nblocks, c.cfg.q_read_elems,
-                                                            c.cfg.q_write_elems);
-                        c.key = {cost, c.cfg.q_read_elems, -npix * z, -(int64_t)x, z, b, y, g.threads, 0, 0};
-                    } else {
-                        c.key = {-grid_efficiency(nblocks), 0, c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z),
-                                 -npix * z, -(int64_t)x, z, b, y, g.threads};
+                    for (const WaveGrid& g : grids) {
+                        int alpha = 0;
+                        int lds_mult = 0;
+                        if (path == IOLB_PATH_MFMA) {
+                            alpha = choose_alpha(s.C, alphas_mfma, 5, 8 * per_stage,
+                                                 lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc), 2);
+                            // automatic budget: a stage too large for half the LDS (large kernels) may take all of
+                            // it, as long as the smallest weight slab (4 channels, 32 kernels) leaves half to the
+                            // input tile
+                            if (alpha == 0 && !lds_bytes && 8 * 4 * RS * 32 <= kLdsPerCu / 2)
+                                alpha = choose_alpha(s.C, alphas_mfma, 5, 8 * per_stage, kLdsPerCu, 2);
+                            lds_mult = alpha >= s.C ? 4 : 8;            // one stage only: one buffer
+                        } else {
+                            alpha = choose_alpha(s.C, alphas_fma, 5, 4 * per_stage, lds_bytes ? lds_bytes : kLdsHalf);
+                            lds_mult = 4;
+                        }
+                        if (alpha == 0) continue;
+                        const int64_t nblocks = (int64_t)(s.N / b) * ceil_div(Q, x) * ceil_div(P, y) * (Kz / z);
+                        Candidate c{};
+                        c.cfg.b = b; c.cfg.x = x; c.cfg.y = y; c.cfg.z = z;
+                        c.cfg.alpha = alpha;
+                        c.cfg.threads = g.threads; c.cfg.waves_m = g.wm; c.cfg.waves_n = g.wn;
+                        c.cfg.path = path; c.cfg.wt_mode = 0;
+                        c.cfg.lds_bytes_used = (int32_t)(lds_mult * alpha * per_stage);
+                        c.cfg.acc_regs_per_thread = g.acc;
+                        c.cfg.q_read_elems = nblocks * s.C * per_stage;
+                        c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+                        c.volume = {c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z), -npix * z, -(int64_t)x, z, b, y, g.threads, -path, 0};
+                        if (path == IOLB_PATH_MFMA) {
+                            const int64_t cost = mfma_tile_cost(s, b, x, y, z, alpha, g, nblocks, c.cfg.q_read_elems,
+                                                                c.cfg.q_write_elems);
+                            c.key = {cost, c.cfg.q_read_elems, -npix * z, -(int64_t)x, z, b, y, g.threads, 0, 0};
+                        } else {
+                            c.key = {-grid_efficiency(nblocks), 0, c.cfg.q_read_elems, std::llabs(npix * st2 - RS * z),
+                                     -npix * z, -(int64_t)x, z, b, y, g.threads};
+                        }
+                        out->push_back(c);
                     }
-                    out->push_back(c);
                 }
             }
 }
@@ -329,24 +362,26 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
         for (int z : fz) {
             if (z % 32) continue;
             if (use_box && !((int64_t)z * z <= box && tb * tb <= box)) continue;
-            WaveGrid g{};
-            if (!best_wave_grid(z / 32, (int)(tb / 32), vgpr_budget, true, &g)) continue;    // tb is free: no idle blocks
-            const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z),
-                                           lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc), 2);
-            if (alpha == 0) continue;
-            const int64_t nblocks = planes * ceil_div(tiles, tb) * (Kz / z);
-            Candidate c{};
-            c.cfg.b = 1; c.cfg.x = (int32_t)(m * tb); c.cfg.y = m; c.cfg.z = z;
-            c.cfg.alpha = alpha;
-            c.cfg.threads = g.threads; c.cfg.waves_m = g.wm; c.cfg.waves_n = g.wn;
-            c.cfg.path = IOLB_PATH_MFMA; c.cfg.wt_mode = 1;
-            c.cfg.lds_bytes_used = (int32_t)((alpha >= s.C ? 4 : 8) * alpha * (tb + z));     // one stage only: one buffer
-            c.cfg.acc_regs_per_thread = g.acc;
-            c.cfg.q_read_elems = nblocks * s.C * (tb + z);
-            c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
-            c.key = {-grid_efficiency(nblocks), 0, c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0};
-            c.volume = {0, c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0, 0};
-            out->push_back(c);
+            for (const WaveGrid& g : wave_grids(z / 32, (int)(tb / 32), vgpr_budget, true)) {    // tb is free: no idle blocks
+                const int alpha = choose_alpha(s.C, alphas, 3, 8 * (tb + z),
+                                               lds_bytes ? lds_bytes : auto_lds_budget(g.threads, g.acc), 2);
+                if (alpha == 0) continue;
+                const int64_t ntb = ceil_div(tiles, tb);
+                const int64_t nblocks = planes * ntb * (Kz / z);
+                Candidate c{};
+                c.cfg.b = 1; c.cfg.x = (int32_t)(m * tb); c.cfg.y = m; c.cfg.z = z;
+                c.cfg.alpha = alpha;
+                c.cfg.threads = g.threads; c.cfg.waves_m = g.wm; c.cfg.waves_n = g.wn;
+                c.cfg.path = IOLB_PATH_MFMA; c.cfg.wt_mode = 1;
+                c.cfg.lds_bytes_used = (int32_t)((alpha >= s.C ? 4 : 8) * alpha * (tb + z));     // one stage only: one buffer
+                c.cfg.acc_regs_per_thread = g.acc;
+                c.cfg.q_read_elems = nblocks * s.C * (tb + z);
+                c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+                const int64_t cost = product_tile_cost(s, tb, z, alpha, g, nblocks, c.cfg.q_read_elems, planes * Kz * ntb * tb);
+                c.key = {0, cost, c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0};
+                c.volume = {0, c.cfg.q_read_elems, std::llabs(tb - z), -tb * z, z, g.threads, 0, 0, 0, 0};
+                out->push_back(c);
+            }
         }
 }
 
