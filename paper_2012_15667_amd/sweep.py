@@ -52,12 +52,15 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
     algo_id = {"direct": B.DIRECT, "direct_hwc": B.DIRECT, "wino2": B.WINO_F2, "wino3": B.WINO_F3, "wino4": B.WINO_F4, "wino6": B.WINO_F6}[algo]
     shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, algo_id)
     pick = B.iolb_tune(shape)
+    bound = B.iolb_tune_bound(shape)
     tiles = B.iolb_enumerate(shape, lds_bytes, 0, use_box)
     if max_tiles and len(tiles) > max_tiles:
         step = len(tiles) / float(max_tiles)
         tiles = [tiles[int(i * step)] for i in range(max_tiles)]
     if pick not in tiles:
         tiles.insert(0, pick)
+    if bound not in tiles:
+        tiles.insert(0, bound)
     if vary_alpha:
         from .autotune import stage_depth_variant
         extra = []
@@ -96,13 +99,17 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
         rows.append((ms, t))
         print("%8.4f ms %7.2f TF  b=%d x=%d y=%d z=%d a=%d T=%d wm=%d wn=%d lds=%d qread=%d%s" % (
             ms, flops / ms / 1e9, t["b"], t["x"], t["y"], t["z"], t["alpha"], t["threads"], t["waves_m"],
-            t["waves_n"], t["lds_bytes_used"], t["q_read_elems"], "  <== tuner pick" if t == pick else ""), flush=True)
+            t["waves_n"], t["lds_bytes_used"], t["q_read_elems"],
+            ("  <== tuner pick" if t == pick else "") + ("  <== bound-only pick" if t == bound else "")), flush=True)
     rows.sort(key=lambda r: r[0])
     pick_ms = [ms for ms, t in rows if t == pick][0]
     rank = 1 + [t for _, t in rows].index(pick)
+    bound_ms = [ms for ms, t in rows if t == bound][0]
     summary = {"layer": layer_name, "algo": algo, "tiles_timed": len(rows), "pick_rank": rank,
                "pick_ms": round(pick_ms, 4), "best_ms": round(rows[0][0], 4),
-               "pick_over_best": round(pick_ms / rows[0][0], 3), "best_tile": rows[0][1], "pick": pick}
+               "pick_over_best": round(pick_ms / rows[0][0], 3), "best_tile": rows[0][1], "pick": pick,
+               "bound_pick_rank": 1 + [t for _, t in rows].index(bound), "bound_pick_ms": round(bound_ms, 4),
+               "bound_pick_over_best": round(bound_ms / rows[0][0], 3), "bound_pick": bound}
     print(json.dumps(summary))
     return summary
 
