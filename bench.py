@@ -237,7 +237,7 @@ def main():
 
     # ---- per-layer figures (outside the timed region) ------------------------------------------
     traffic = read_traffic_table()
-    path_names = {B.PATH_FMA: "fma", B.PATH_MFMA: "mfma", B.PATH_FUSED: "fused"}
+    path_names = {B.PATH_FMA: "fma", B.PATH_MFMA: "mfma", B.PATH_FUSED: "fused", B.PATH_POINT: "pointwise"}
 
     def timed(job, tile, reps=5):
         run(job, tile)

@@ -37,8 +37,10 @@ extern "C" {
 #define IOLB_EHIP         -5   /* a HIP runtime call or launch failed; see iolb_last_hip_error */
 
 enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2, IOLB_WINO_F3 = 3, IOLB_WINO_F6 = 4 };
-enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1, IOLB_PATH_FUSED = 2 };   /* FUSED: Winograd only, all four steps in
-                                                                           one matrix-core kernel (Sec. 5.3) */
+enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1, IOLB_PATH_FUSED = 2, IOLB_PATH_POINT = 3 };
+/* FUSED: Winograd only, all four steps in one matrix-core kernel (Sec. 5.3).  POINT: direct convolution with
+ * R = S = 1, stride 1, no padding, channels-outermost tensors only: the dataflow of Sec. 5.2 on the image taken as
+ * one row of H * W pixels (without a kernel window the pixels do not interact). */
 enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1, IOLB_LAYOUT_CWH = 2 };   /* per image: channels outermost, channels
                                                                            innermost, channels outermost with W before H */
 
@@ -53,13 +55,15 @@ typedef struct iolb_shape {
  * H_out, z along C_out) taken over b images, the channels per stage alpha, and the thread
  * decomposition (Table 1 of Sec. 6.2: tile sizes and thread numbers).
  * For the Winograd algos the block is a strip of x/m sub-domains of m x m outputs (b = 1,
- * y = m) of one transformed plane.  All fields are exact integers. */
+ * y = m) of one transformed plane.  For IOLB_PATH_POINT the block is x consecutive pixels of the image
+ * taken as one row of H * W pixels (b = 1, y = 1; a block may run on into the next image) by z output
+ * channels.  All fields are exact integers. */
 typedef struct iolb_tile_config {
     int32_t b, x, y, z;
     int32_t alpha;               /* input channels staged per step of the channel loop */
     int32_t threads;             /* workgroup size */
     int32_t waves_m, waves_n;    /* MFMA path: wave grid over (z, pixels); FMA path: channel groups, 1 */
-    int32_t path;                /* IOLB_PATH_FMA or IOLB_PATH_MFMA */
+    int32_t path;                /* IOLB_PATH_FMA, _MFMA, _FUSED or _POINT */
     int32_t wt_mode;             /* 0: raw R*S weights staged; 1: pre-transformed (m+2)^2 weights */
     int32_t lds_bytes_used;      /* staging bytes the tile needs */
     int32_t acc_regs_per_thread; /* partial sums held per lane */
@@ -101,7 +105,8 @@ int conv_direct_cfg(const float* x, const float* w, float* y,
  * x: [N][H][W][C], y: [N][P][Q][K].  IOLB_LAYOUT_CWH: x: [N][C][W][H], y: [N][K][Q][P] (the
  * transposed image: computed as the CHW convolution of the W x H image with the kernels
  * transposed, so tiles are those of that transposed layer).  w is [K][C][R][S] for all.  cfg may be NULL (the tuned
- * tile is used; tiles do not depend on the layout).  Other layout values: IOLB_EUNSUPPORTED. */
+ * tile is used; tiles do not depend on the layout, except that IOLB_PATH_POINT tiles exist for IOLB_LAYOUT_CHW only:
+ * IOLB_EINVAL with another layout).  Other layout values: IOLB_EUNSUPPORTED. */
 int conv_direct_layout(const float* x, const float* w, float* y,
                        int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                        int layout, const iolb_tile_config* cfg);

@@ -16,7 +16,7 @@ from math import isqrt, sqrt
 
 DIRECT, WINO_F2, WINO_F4, WINO_F3, WINO_F6 = 0, 1, 2, 3, 4
 WINO_E = {WINO_F2: 2, WINO_F3: 3, WINO_F4: 4, WINO_F6: 6}     # output tile extent e of each Winograd algo id
-PATH_FMA, PATH_MFMA, PATH_FUSED = 0, 1, 2
+PATH_FMA, PATH_MFMA, PATH_FUSED, PATH_POINT = 0, 1, 2, 3
 
 # ------------------------------------------------------------------------------------------
 # shapes
@@ -513,6 +513,61 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
     return cands
 
 
+# 1 x 1 convolution, stride 1, no padding: the pixels of an image do not interact, so the plane is one row of P Q
+# pixels.  A workgroup of the library's kernel for these layers is four waves, each on 32 nbw consecutive pixels of
+# that row (x = 128 nbw, y = 1; a workgroup may run on into the next image) by z = 32 mbw output channels; stages of
+# 16 channels, or 32 where that pads none.  POINT_SHAPES: the (mbw, nbw) the kernel is instantiated for.
+POINT_SHAPES = ((1, 1), (1, 2), (1, 4), (2, 2), (2, 4))
+
+
+def pointwise_layer(s):
+    return (s["algo"] == DIRECT and s["R"] == 1 and s["S"] == 1 and s["stride"] == 1 and s["pad"] == 0
+            and 4 * s["C"] * s["H"] * s["W"] < (1 << 32))
+
+
+def pointwise_read_volume(N, C, HW, K, x, z):
+    """Reading volume of the dataflow of Sec. 5.2 for R = S = 1 on the row of HW pixels per image: every block of x
+    pixels (made of four ranges of x / 4, dealt image after image) by z channels reads, per input channel, its x
+    inputs and z weights."""
+    ranges = N * _cdiv(HW, x // 4)
+    return _cdiv(ranges, 4) * _cdiv(K, z) * C * (x + z)
+
+
+def _pointwise_candidates(s, P, Q, vgpr_budget, use_f3):
+    """THIS BUILD'S HEURISTIC for the order among these tiles (modelled time: the waves dealt over 1024 SIMDs, a SIMD
+    runs its waves' MFMAs one after the other, 64 cycles each, and hides all but one wave's 40 cycles per step of
+    other work; never faster than the memory traffic allows, the inputs counted once because the channel blocks of
+    a pixel range share them through L2) and for ranking them before the general tiles (measured)."""
+    N, C, K = s["N"], s["C"], s["K"]
+    HW = P * Q
+    sb_max = T_MAX * vgpr_budget
+    cands = []
+    for mbw, nbw in POINT_SHAPES:
+        for alpha in (16, 32):
+            if alpha == 32 and C % 32:
+                continue
+            z, npix, acc = 32 * mbw, 128 * nbw, 16 * mbw * nbw
+            if use_f3 and not (z * z <= sb_max and npix * npix <= sb_max):
+                continue
+            if acc > vgpr_budget:
+                continue
+            nbk = _cdiv(K, z)
+            nwaves = N * _cdiv(HW, 32 * nbw)
+            qread = pointwise_read_volume(N, C, HW, K, npix, z)
+            qwrite = N * K * P * Q
+            steps = _cdiv(C, alpha) * alpha // 2
+            compute = _cdiv(nwaves * nbk, 1024) * steps * mbw * nbw * 64 + steps * 40 + 15000
+            nblocks = _cdiv(nwaves, 4) * nbk
+            memory = (4 * (N * C * HW + nblocks * C * z)) // 4000 + (4 * qwrite) // 1500
+            cost = max(compute, memory)
+            # ties: bound by memory, the smaller block (more waves, more loads in flight); else the smaller volume
+            key = (-(1 << 61), cost, npix * z if memory >= compute else 0, qread, -npix * z, z, -alpha, 0, 0, 0)
+            cands.append((key, dict(b=1, x=npix, y=1, z=z, alpha=alpha, threads=256, waves_m=1, waves_n=4,
+                                    path=PATH_POINT, wt_mode=0, lds_bytes_used=8 * alpha * z,
+                                    acc_regs_per_thread=acc, q_read_elems=qread, q_write_elems=qwrite)))
+    return cands
+
+
 # Fused matrix-core blocks (every plane of a tb x z block resident in accumulator registers, Sec. 5.3), one per
 # kernel instantiation of the library: (e, tb, z, alpha, threads, waves_m, waves_n, lds_bytes, acc)
 FUSED_BLOCKS = (
@@ -608,6 +663,8 @@ def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True, auto_regs=True)
         # modelled time: their keys start below zero and sort first.
         if max([t["b"] * t["x"] * t["y"] for _, t in c], default=0) < 64:
             c = c + _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
+        if pointwise_layer(s):
+            c = c + _pointwise_candidates(s, P, Q, vgpr_budget, use_f3)
         return c
     e = WINO_E[s["algo"]]
     return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs)
@@ -629,6 +686,9 @@ def _volume_key(shape, t):
     Sec. 5.3 before the unfused tiles, whose temporaries make a round trip through memory that q_read does not
     count; unfused tiles by read volume, then |tb - z| (the optimality condition x y = r^2 z for sub-domain
     strips), then the fuller block."""
+    if shape["algo"] == DIRECT and t["path"] == PATH_POINT:
+        # the same order on the image as one row of pixels: volume, distance from x y = R z, the fuller block ...
+        return (t["q_read_elems"], abs(t["x"] - t["z"]), -t["x"] * t["z"], -t["x"], t["z"], 1, 1, 256, -PATH_POINT, t["alpha"])
     if shape["algo"] == DIRECT:
         P, Q = out_extent(shape["H"], shape["W"], shape["R"], shape["S"], shape["stride"], shape["pad"])
         return volume_order(shape["N"], shape["C"], P, Q, -(-shape["K"] // 32) * 32 if t["path"] == PATH_MFMA else shape["K"],

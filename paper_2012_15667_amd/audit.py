@@ -22,7 +22,7 @@ MAX_TILES = 300
 
 def tile_text(t):
     return "%d,%d,%d,%d,%d,%d%s" % (t["b"], t["x"], t["y"], t["z"], t["alpha"], t["threads"],
-                                    {0: " fma", 1: "", 2: " fused"}[t["path"]])
+                                    {0: " fma", 1: "", 2: " fused", 3: " pointwise"}[t["path"]])
 
 
 def main():

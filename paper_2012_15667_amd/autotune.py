@@ -48,6 +48,9 @@ def with_stage_depths(tiles, min_alpha=4, C=None):
     out = []
     for t in tiles:
         a = t["alpha"]
+        if t["path"] not in (0, 1):          # the depths of the fused and 1 x 1 kernels are enumerated one by one
+            out.append(t)
+            continue
         while a >= min_alpha:
             out.append(stage_depth_variant(t, a, C))
             a //= 2

@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(_PKG, "libiolbconv.so")
 
 DIRECT, WINO_F2, WINO_F4, WINO_F3, WINO_F6 = 0, 1, 2, 3, 4
 WINO_ALGO = {2: WINO_F2, 3: WINO_F3, 4: WINO_F4, 6: WINO_F6}     # algo id of F(m x m, 3 x 3)
-PATH_FMA, PATH_MFMA, PATH_FUSED = 0, 1, 2
+PATH_FMA, PATH_MFMA, PATH_FUSED, PATH_POINT = 0, 1, 2, 3
 LAYOUT_CHW, LAYOUT_HWC, LAYOUT_CWH = 0, 1, 2
 
 EXPORTS = ["conv_direct", "conv_direct_noalloc", "conv_direct_noalloc_max_weight_floats", "conv_direct_cfg", "conv_direct_layout", "conv_direct_pad2", "conv_winograd", "conv_winograd_pad", "conv_winograd_workspace_bytes",

@@ -118,16 +118,28 @@ struct MainKernelTimer {
 typedef std::tuple<int, int, int, int, int, int, int, int, int, int> ShapeKey;
 std::map<ShapeKey, iolb_tile_config> g_tiles;
 
-int tuned_tile(const iolb_shape& s, iolb_tile_config* cfg)
+// pointwise_ok = false: the call cannot run an IOLB_PATH_POINT tile (another tensor layout, padding on one axis):
+// the best of the other tiles.
+int tuned_tile(const iolb_shape& s, iolb_tile_config* cfg, bool pointwise_ok = true)
 {
-    const ShapeKey key(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.algo);
+    const ShapeKey key(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.algo + (pointwise_ok ? 0 : 1000));
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         auto it = g_tiles.find(key);
         if (it != g_tiles.end()) { *cfg = it->second; return IOLB_OK; }
     }
-    const int rc = iolb::tune(s, 0, 0, cfg);
+    int rc = iolb::tune(s, 0, 0, cfg);
     if (rc != IOLB_OK) return rc;
+    if (!pointwise_ok && cfg->path == IOLB_PATH_POINT) {
+        std::vector<iolb::Candidate> all;
+        rc = iolb::enumerate(s, 0, 0, false, &all);
+        if (rc != IOLB_OK) return rc;
+        const iolb::Candidate* first = nullptr;
+        for (const auto& c : all)
+            if (c.cfg.path != IOLB_PATH_POINT) { first = &c; break; }
+        if (!first) return IOLB_ENOTILE;
+        *cfg = first->cfg;
+    }
     std::lock_guard<std::mutex> lock(g_mutex);
     g_tiles[key] = *cfg;
     return IOLB_OK;
@@ -164,8 +176,9 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
     for (const auto& c : all) {
         iolb_tile_config probe = c.cfg;
         // alpha may be any shallower stage depth than the enumeration's (a multiple of 4 on the MFMA path)
-        if (cfg.alpha >= 1 && cfg.alpha <= c.cfg.alpha && (cfg.path == IOLB_PATH_FMA || cfg.alpha % 4 == 0) &&
-            c.cfg.alpha % cfg.alpha == 0) {
+        // (the stage depths of the 1 x 1 kernel are enumerated one by one)
+        if (cfg.path != IOLB_PATH_POINT && cfg.alpha >= 1 && cfg.alpha <= c.cfg.alpha &&
+            (cfg.path == IOLB_PATH_FMA || cfg.alpha % 4 == 0) && c.cfg.alpha % cfg.alpha == 0) {
             probe.alpha = cfg.alpha;
             // a single-stage tile counts one buffer, a shallower (multi-stage) depth two
             const int64_t buffers = cfg.path == IOLB_PATH_MFMA && c.cfg.alpha >= s.C && cfg.alpha < s.C ? 2 : 1;
@@ -190,6 +203,38 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     DeviceState* dev = nullptr;
     int rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;
+    if (cfg.path == IOLB_PATH_POINT) {
+        // 1 x 1, stride 1, no padding, channels outermost: the image as one row of H * W pixels
+        if (layout != IOLB_LAYOUT_CHW || (pad_w >= 0 && pad_w != 0) || s.pad != 0 || s.R != 1 || s.S != 1 || s.stride != 1)
+            return IOLB_EINVAL;
+        iolb::PointGeom g{};
+        g.N = s.N; g.C = s.C; g.HW = s.H * s.W; g.K = s.K;
+        g.z = cfg.z; g.mbw = cfg.z / 32; g.nbw = cfg.x / 128; g.waves = 4; g.alpha = cfg.alpha;
+        if (cfg.threads != 256 || cfg.z != 32 * g.mbw || cfg.x != 128 * g.nbw || cfg.alpha < 1) return IOLB_EINVAL;
+        g.Kp = (s.K + cfg.z - 1) / cfg.z * cfg.z;
+        g.nbk = g.Kp / cfg.z;
+        g.tiles_per_image = (g.HW + 32 * g.nbw - 1) / (32 * g.nbw);
+        const int64_t ntiles = (int64_t)s.N * g.tiles_per_image;
+        if ((ntiles + 3) / 4 * g.nbk > 0x7fffffffLL) return IOLB_EINVAL;
+        g.npg = (int)((ntiles + 3) / 4);
+        const int c_padded = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;     // whole stages
+        const size_t wbytes = sizeof(float) * (size_t)g.Kp * c_padded;
+        float* wt = wt_buf;
+        if (wt_buf) {
+            if (wbytes > sizeof(float) * wt_floats) return IOLB_EWORKSPACE;
+        } else {
+            void* ws = nullptr;
+            rc = ensure_workspace(dev, align256(wbytes), &ws);
+            if (rc != IOLB_OK) return rc;
+            wt = static_cast<float*>(ws);
+        }
+        hipStream_t st = t_stream;
+        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, g.Kp, s.C, c_padded, st));
+        MainKernelTimer timer(st, IOLB_TIME_DIRECT);
+        IOLB_HIP(iolb::launch_pointwise_mfma(x, wt, y, g, st));
+        timer.stop(st);
+        return IOLB_OK;
+    }
     iolb::DirectGeom g{};
     g.N = s.N; g.C = s.C; g.H = s.H; g.W = s.W; g.K = s.K; g.R = s.R; g.S = s.S; g.stride = s.stride; g.pad = s.pad;
     g.pad_w = pad_w < 0 ? s.pad : pad_w;
@@ -457,7 +502,7 @@ int conv_direct_pad2(const float* x, const float* w, float* y, int N, int C, int
     if (rc != IOLB_OK) return rc;
     if (H < 1 || W < 1) return IOLB_EINVAL;
     iolb_tile_config cfg;
-    rc = tuned_tile(bordered, &cfg);
+    rc = tuned_tile(bordered, &cfg, pad_h == 0 && pad_w == 0);
     if (rc != IOLB_OK) return rc;
     const iolb_shape s{N, C, H, W, K, R, S, stride, pad_h, IOLB_DIRECT};
     return run_direct(x, w, y, s, P, Q, cfg, IOLB_LAYOUT_CHW, pad_w);
@@ -480,7 +525,7 @@ int conv_direct_layout(const float* x, const float* w, float* y, int N, int C, i
         if (rc != IOLB_OK) return rc;
         tile = *cfg;
     } else {
-        rc = tuned_tile(s, &tile);
+        rc = tuned_tile(s, &tile, layout == IOLB_LAYOUT_CHW);
         if (rc != IOLB_OK) return rc;
     }
     return run_direct(x, w, y, s, P, Q, tile, layout);

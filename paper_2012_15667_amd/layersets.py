@@ -182,14 +182,81 @@ def summarise(name, records):
             "skipped": SKIPPED.get(name, "")}
 
 
+def report(path, reps=5):
+    """Runs the three measurements and writes the summary (the tracked profiles/layer_sets.md)."""
+    import io
+    quiet = io.StringIO()
+    w = []
+    w.append("# Layer sets on one MI355X: whole networks' convolution layers, batch sweep, figure sweep\n")
+    w.append("Written by `python -m paper_2012_15667_amd.layersets --report profiles/layer_sets.md` (run from the repository root")
+    w.append("on the GPU box).  Timed with `torch.cuda.Event` around %d calls after 2 warm-up calls, inputs resident in HBM, fp32;" % reps)
+    w.append("TFLOP/s are direct-convolution-equivalent (2 N K P Q C R S / time); every call goes through the tuned tile.\n")
+    w.append("## Networks (batch 64; distinct convolution shapes x how often the network runs them)\n")
+    w.append("| network | conv layers | GFLOP | best algorithm per layer: ms / TFLOP/s | direct only: ms / TFLOP/s |")
+    w.append("|---|---|---|---|---|")
+    per_model = {}
+    for name in sorted(MODELS):
+        per_model[name] = run([(64, L) for L in MODELS[name]], reps, quiet)
+        r = summarise(name, per_model[name])
+        w.append("| %s | %d | %.1f | %.2f / %.1f | %.2f / %.1f |" % (r["model"], r["conv_layers"], r["gflop"], r["ms_best_per_layer"],
+                                                               r["tflops_best"], r["ms_direct_only"], r["tflops_direct_only"]))
+        print("timed " + name, flush=True)
+    w.append("\nInception-v3: all 94 convolutions of the main path; the factorised 1x7 / 7x1 / 1x3 / 3x1 kernels pad one axis only "
+             "(pad shown as h,w) and run through conv_direct_pad2; pad-0 3x3 layers reach Winograd through conv_winograd_pad.")
+    ones = [q for recs in per_model.values() for q in recs if q["R"] == 1 and q["S"] == 1 and q["stride"] == 1 and q["gflop"] >= 1.0]
+    tf = sorted(q["tflops_direct_equiv"]["direct"] for q in ones)
+    w.append("\n1 x 1, stride-1 layers of at least 1 GFLOP (%d shapes): %.1f / %.1f / %.1f TFLOP/s lowest / median / highest; "
+             "%d of them at 60 TFLOP/s or more." % (len(tf), tf[0], tf[len(tf) // 2], tf[-1], sum(1 for v in tf if v >= 60.0)))
+    w.append("\nPer layer (ms; TFLOP/s in brackets):\n")
+    w.append("| network | layer | C | H=W | K | RxS/stride/pad | count | GFLOP | direct | F(2x2) | F(4x4) |")
+    w.append("|---|---|---|---|---|---|---|---|---|---|---|")
+    for name in sorted(MODELS):
+        for q in per_model[name]:
+            f = lambda a: ("%.3f (%.0f)" % (q["ms"][a], q["tflops_direct_equiv"][a])) if a in q["ms"] else "-"
+            pad = q["pad"] if not isinstance(q["pad"], list) else "%d,%d" % tuple(q["pad"])
+            w.append("| %s | %s | %d | %d | %d | %dx%d/%d/%s | %d | %.2f | %s | %s | %s |" % (
+                name, q["layer"], q["C"], q["H"], q["K"], q["R"], q["S"], q["stride"], pad, q["count"], q["gflop"],
+                f("direct"), f("wino2"), f("wino4")))
+    b = run(batch_sweep(), reps, quiet)
+    print("timed the batch sweep", flush=True)
+    ns = (1, 2, 4, 8, 16, 32, 64, 128)
+    w.append("\n## Batch sweep (3x3, C = K = 256, stride 1, pad 1): TFLOP/s of the fastest algorithm, and of direct convolution\n")
+    w.append("| H=W | " + " | ".join("N=%d" % n for n in ns) + " |")
+    w.append("|---|" + "---|" * len(ns))
+    for hw in (14, 28, 56, 112):
+        row = [r for r in b if r["H"] == hw]
+        w.append("| %d | " % hw + " | ".join("%.0f %s (direct %.0f)" % (max(r["tflops_direct_equiv"].values()), r["best"],
+                                                                       r["tflops_direct_equiv"]["direct"]) for r in row) + " |")
+    fg = run([(32, L) for L in figure_sweep()], reps, quiet)
+    print("timed the figure sweep", flush=True)
+    w.append("\n## Figure sweep (3x3, C = 256, batch 32): direct convolution TFLOP/s, stride 1 / stride 2; best Winograd at stride 1 in brackets\n")
+    w.append("| H=W | K=64 | K=128 | K=256 | K=512 |")
+    w.append("|---|---|---|---|---|")
+    for hw in (14, 28, 56, 112):
+        cells = []
+        for k in (64, 128, 256, 512):
+            s1 = [r for r in fg if r["H"] == hw and r["K"] == k and r["stride"] == 1][0]
+            s2 = [r for r in fg if r["H"] == hw and r["K"] == k and r["stride"] == 2][0]
+            wbest = max(v for a, v in s1["tflops_direct_equiv"].items() if a != "direct")
+            cells.append("%.0f / %.0f (%.0f)" % (s1["tflops_direct_equiv"]["direct"], s2["tflops_direct_equiv"]["direct"], wbest))
+        w.append("| %d | " % hw + " | ".join(cells) + " |")
+    with open(path, "w") as f:
+        f.write("\n".join(w) + "\n")
+    print("wrote " + path)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--report", default="", help="run everything and write the markdown summary to this path")
     ap.add_argument("--model", default="", help="one of %s, or 'all'" % ", ".join(sorted(MODELS)))
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--batch-sweep", action="store_true")
     ap.add_argument("--figure-sweep", action="store_true")
     ap.add_argument("--reps", type=int, default=5)
     a = ap.parse_args()
+    if a.report:
+        report(a.report, a.reps)
+        return 0
     if a.batch_sweep:
         run(batch_sweep(), a.reps)
     if a.figure_sweep:

@@ -65,6 +65,8 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
         from .autotune import stage_depth_variant
         extra = []
         for t in tiles:
+            if t["path"] not in (B.PATH_FMA, B.PATH_MFMA):
+                continue
             a = t["alpha"] // 2
             while a >= 4:
                 extra.append(stage_depth_variant(t, a, L.C))

@@ -78,7 +78,7 @@ def _path_label(layer, algo, path):
         return "mfma" if path == "tuned" else "bound"
     if path == "tuned":
         sh = B.make_shape(L.N, L.C, L.H, L.W, L.K, algo={"wino2": B.WINO_F2, "wino4": B.WINO_F4}[algo])
-        return {B.PATH_FMA: "fma", B.PATH_MFMA: "mfma", B.PATH_FUSED: "fused"}[B.iolb_tune(sh)["path"]]
+        return {B.PATH_FMA: "fma", B.PATH_MFMA: "mfma", B.PATH_FUSED: "fused", B.PATH_POINT: "pointwise"}[B.iolb_tune(sh)["path"]]
     return {"unfused": "mfma", "fused": "fused"}[path]
 
 

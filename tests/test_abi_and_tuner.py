@@ -50,6 +50,7 @@ SHAPES = [
     # thin Winograd layers: fused one-kernel candidate when C <= 4 and C (m+2)^2 fits the register budget
     _shape(64, 3, 224, 224, 64, algo=2), _shape(2, 4, 37, 41, 33, algo=1), _shape(2, 4, 14, 14, 32, algo=2),
     _shape(2, 2, 14, 14, 32, algo=4), _shape(2, 3, 14, 14, 32, algo=4), _shape(1, 1, 9, 9, 5, algo=3),
+    _shape(64, 192, 35, 35, 64, 1, 1, 1, 0), _shape(64, 1280, 8, 8, 384, 1, 1, 1, 0), _shape(8, 20, 17, 18, 70, 1, 1, 1, 0),
 ]
 BUDGETS = [(0, 0), (32768, 64), (163840, 128), (8192, 32)]
 

@@ -257,6 +257,60 @@ def test_direct_alexnet_rows_full_size_sampled(gpu, name):
     assert np.isfinite(got).all()
 
 
+POINTWISE_CASES = [
+    # N, C, H, W, K: 1 x 1 kernels, stride 1, no padding
+    (2, 20, 35, 35, 70),        # odd pixel count (single-float accesses), C and K ragged
+    (3, 64, 7, 7, 130),         # fewer pixels per image than one wave's range; waves of a workgroup in different images
+    (2, 33, 8, 8, 48),          # one channel past two stages of 16
+    (1, 3, 5, 10, 40),          # fewer channels than a stage, fewer waves than a workgroup
+    (4, 96, 28, 28, 64),        # everything aligned: 16-byte loads and stores, stages of 32 channels too
+    (2, 130, 17, 18, 96),       # pixel count even but not a multiple of 4: 8-byte accesses for two blocks per wave only
+    (5, 48, 3, 43, 33),         # 129 pixels: a second range of one pixel
+]
+
+
+@pytest.mark.parametrize("case", POINTWISE_CASES)
+def test_pointwise_layers_every_tile_matches_oracle(gpu, case):
+    """1 x 1 layers run in a kernel of their own (inputs from memory straight into the matrix-core operands): the
+    tuned tile must be one of its tiles, and every one of them must give the layer."""
+    torch, B = gpu
+    N, C, H, W, K = case
+    x, w = make_inputs(N, C, H, W, K, 1, 1, "u11", "he", seed=300 + C + K)
+    ref = conv_ref(x, w, 1, 0)
+    shape = B.make_shape(N, C, H, W, K, 1, 1, 1, 0)
+    assert B.iolb_tune(shape)["path"] == B.PATH_POINT
+    tiles = [t for t in B.iolb_enumerate(shape, 0, 0, False) if t["path"] == B.PATH_POINT]
+    assert len(tiles) >= 5
+    for cfg in tiles:
+        got = _run_direct(gpu, x, w, 1, 0, cfg=cfg)
+        assert rel_err(got, ref) <= GUARD_DIRECT, cfg
+    # the general kernel still serves these layers (other layouts, padded calls)
+    general = [t for t in B.iolb_enumerate(shape, 0, 0, False) if t["path"] == B.PATH_MFMA]
+    assert rel_err(_run_direct(gpu, x, w, 1, 0, cfg=general[0]), ref) <= GUARD_DIRECT
+    xh = torch.from_numpy(_to_hwc(x)).cuda()
+    yh = B.conv_direct_layout(xh, torch.from_numpy(w).cuda(), 1, 0, B.LAYOUT_HWC)
+    torch.cuda.synchronize()
+    assert rel_err(yh.cpu().numpy(), _to_hwc(ref)) <= GUARD_DIRECT
+    with pytest.raises(Exception):
+        B.conv_direct_layout(xh, torch.from_numpy(w).cuda(), 1, 0, B.LAYOUT_HWC, cfg=tiles[0])
+
+
+@pytest.mark.parametrize("shape", [(64, 192, 35, 35, 64), (64, 1280, 8, 8, 384), (64, 256, 56, 56, 64)])
+def test_pointwise_full_size_sampled(gpu, shape):
+    """Network-size 1 x 1 layers at batch 64 with the tuned tile; 4096 sampled outputs recomputed by the oracle."""
+    N, C, H, W, K = shape
+    x, w = make_inputs(N, C, H, W, K, 1, 1, "u01", "he", seed=17 + C)
+    got = _run_direct(gpu, x, w, 1, 0)
+    idx = sample_output_indices(N, K, H, W, 4096, seed=C)
+    ref = conv_ref_points(x, w, idx, 1, 0)
+    g = got[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+    assert rel_err(g, ref) <= GUARD_DIRECT
+    assert np.isfinite(got).all()
+    # whole last image against the oracle: the far end of both tensors
+    last = conv_ref(x[N - 1:], w, 1, 0)
+    assert rel_err(got[N - 1:], last) <= GUARD_DIRECT
+
+
 def test_direct_large_tensor_sampled(gpu):
     """A 2^30-element input (4 GiB) and a 2^29-element output: offsets beyond 32 bits of bytes."""
     torch, B = gpu
@@ -812,7 +866,8 @@ def test_random_shapes_and_tiles_match_oracle(gpu):
         case = (N, C, H, W, K, R, S, st, pad)
         for cfg in (None, rnd.choice(tiles), rnd.choice(tiles)):
             y = B.conv_direct(xd, wd, st, pad, cfg=cfg)
-            yh = B.conv_direct_layout(xh, wd, st, pad, B.LAYOUT_HWC, cfg=cfg)
+            # the tiles of the 1 x 1 kernel exist for channels-outermost tensors only
+            yh = B.conv_direct_layout(xh, wd, st, pad, B.LAYOUT_HWC, cfg=None if cfg and cfg["path"] == B.PATH_POINT else cfg)
             torch.cuda.synchronize()
             assert rel_err(y.cpu().numpy(), ref) <= TOL_DIRECT, (case, cfg)
             assert rel_err(yh.cpu().numpy(), _to_hwc(ref)) <= TOL_DIRECT, (case, cfg)

@@ -116,6 +116,18 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
     """Constraints re-stated from the documentation of the rule, written independently."""
     P, Q = o.out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
     b, x, y, z, a, T = (cfg[k] for k in ("b", "x", "y", "z", "alpha", "threads"))
+    if cfg["path"] == o.PATH_POINT:
+        # 1 x 1 layers: four waves, each on x / 4 consecutive pixels of an image taken as one row, by z channels
+        assert (s["algo"], s["R"], s["S"], s["stride"], s["pad"]) == (o.DIRECT, 1, 1, 1, 0)
+        assert (b, y, T, cfg["waves_m"], cfg["waves_n"]) == (1, 1, 256, 1, 4) and x % 128 == 0 and z % 32 == 0
+        assert a in (16, 32) and (a == 16 or s["C"] % 32 == 0)
+        assert cfg["acc_regs_per_thread"] == 16 * (x // 128) * (z // 32) <= vgpr_budget
+        assert cfg["lds_bytes_used"] == 2 * 4 * a * z
+        ranges = sum(len(range(0, P * Q, x // 4)) for _ in range(s["N"]))          # walked image by image
+        groups = len(range(0, ranges, 4)) * len(range(0, s["K"], z))
+        assert cfg["q_read_elems"] == groups * s["C"] * (x + z)
+        assert cfg["q_write_elems"] == s["N"] * s["K"] * P * Q
+        return
     # matrix-core tiles cut K rounded up to whole 32-channel blocks
     Kz = -(-s["K"] // 32) * 32 if cfg["path"] == o.PATH_MFMA else s["K"]
     assert Kz % z == 0 and T in (64, 128, 256, 512, 1024)
