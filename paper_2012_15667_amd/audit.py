@@ -5,6 +5,9 @@
 Part 1 -- exhaustive tile sweeps (paper_2012_15667_amd.sweep) of config 3 and configs 5a-d in direct convolution,
 F(2x2) and F(4x4): how many tiles were timed, where the tuner's pick (modelled time) and the bound-only pick (least
 reading volume inside the optimality box, the paper's objective alone) rank, and how far each is from the fastest.
+Part 3 -- the fused Winograd kernels (all four steps in one kernel, Sec. 5.3) against the unfused path (four kernels
+with the transformed tensors in memory) over layer shapes: both times, and whether the tuner's choice between
+them is the faster one.
 Part 2 -- the measured auto-tuning engine of Sec. 6 (paper_2012_15667_amd.autotune) with and without the
 optimality box of Table 1: size of the searching domain, measurements until the search stops, best time found --
 the analogue of the "search space" and "iterations" columns of Table 2.
@@ -16,6 +19,9 @@ import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SWEEPS = [(l, a) for l in ("cfg3", "cfg5a", "cfg5b", "cfg5c", "cfg5d") for a in ("direct", "wino2", "wino4")]
+CROSSOVER = ["cfg2", "cfg4", "cfg5b", "cfg5c", "cfg5d", "alex3", "alex4"] + \
+            ["64,%d,56,56,%d,3,3,1,1" % (c, c) for c in (16, 32, 64, 128, 512)] + \
+            ["64,%d,14,14,%d,3,3,1,1" % (c, c) for c in (64, 128, 512)] + ["8,128,28,28,128,3,3,1,1", "1,256,56,56,256,3,3,1,1"]
 ENGINE_LAYERS = [("alex3", "direct"), ("alex2", "direct"), ("cfg3", "direct"), ("cfg5d", "direct")]
 MAX_TILES = 300
 
@@ -65,6 +71,38 @@ def main():
                     layer, "box" if use_box else "whole domain", len(dom), 100.0 * len(dom) / max(1, len(full)), seed,
                     history[-1][0], to3, best_ms, pick_ms))
             print("searched %s %s box=%s" % (layer, algo, use_box), flush=True)
+    import torch
+    from .inputs import layer_inputs
+    from .sweep import parse_layer, time_call
+    lines += ["", "## Fused against unfused Winograd", "",
+              "The first fused block and the first unfused tile of the enumeration (the tuner's order inside each path), five calls",
+              "after two warm-up calls each.  Layers are configured names or N,C,H,W,K,R,S,stride,pad.", "",
+              "| layer | F(m x m) | fused ms | unfused ms | unfused / fused | tuner picks | the faster one |",
+              "|---|---|---|---|---|---|---|"]
+    right = total = 0
+    for name in CROSSOVER:
+        L = parse_layer(name)
+        x, w = layer_inputs(L)
+        xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+        y = torch.empty((L.N, L.K, L.H, L.W), dtype=torch.float32, device="cuda")
+        for m in (2, 4):
+            shape = B.make_shape(L.N, L.C, L.H, L.W, L.K, algo=B.WINO_ALGO[m])
+            tiles = B.iolb_enumerate(shape, 0, 0, False)
+            fused = [t for t in tiles if t["path"] == B.PATH_FUSED]
+            unfused = [t for t in tiles if t["path"] == B.PATH_MFMA]
+            if not fused or not unfused:
+                continue
+            ws = torch.empty(B.winograd_workspace_bytes(L.N, L.C, L.H, L.W, L.K, m), dtype=torch.uint8, device="cuda")
+            ms = {}
+            for label, t in (("fused", fused[0]), ("unfused", unfused[0])):
+                ms[label] = time_call(torch, lambda: B.conv_winograd(xd, wd, m, y=y, cfg=t, workspace=ws), 5)
+            pick = {B.PATH_FUSED: "fused", B.PATH_MFMA: "unfused", B.PATH_FMA: "thin-layer kernel"}[B.iolb_tune(shape)["path"]]
+            faster = min(ms, key=ms.get)
+            total += 1
+            right += pick == faster
+            lines.append("| %s | %d | %.4f | %.4f | %.2f | %s | %s |" % (name, m, ms["fused"], ms["unfused"], ms["unfused"] / ms["fused"], pick, faster))
+        print("compared " + name, flush=True)
+    lines += ["", "The tuner's choice is the faster path on %d of %d rows." % (right, total)]
     with open(os.path.join(ROOT, "profiles", "tuner_vs_sweep.md"), "w") as f:
         f.write("\n".join(lines) + "\n")
     print("wrote profiles/tuner_vs_sweep.md")
