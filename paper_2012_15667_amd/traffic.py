@@ -9,7 +9,8 @@ For every (layer, algorithm, path) of the list below it runs
 
 once per counter (FETCH_SIZE, WRITE_SIZE: KiB per dispatch between L2 and the fabric, so reads served by the
 256 MB memory-side cache count like reads from HBM; optionally TCP_TCC_READ_REQ_sum / TCP_TCC_WRITE_REQ_sum:
-requests between the compute units and L2), scales the counters by what they read for a plain 1 GiB copy
+requests between the compute units and L2; with --sq the matrix-core and LDS counters SQ_INSTS_MFMA,
+SQ_VALU_MFMA_BUSY_CYCLES, SQ_LDS_BANK_CONFLICT, SQ_LDS_IDX_ACTIVE, SQ_BUSY_CYCLES, GRBM_GUI_ACTIVE), scales the counters by what they read for a plain 1 GiB copy
 (`bench.py --copy-calibration`), and sums the library's kernels (names starting with iolb::) of one call.
 
 bench.py reads the `row ...` lines of the summary for its per-layer `hbm_MB_measured`.
@@ -86,6 +87,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--out", default=os.path.join("profiles", "hbm_traffic_by_layer.txt"))
     ap.add_argument("--l2", action="store_true", help="also collect the requests between the compute units and L2")
+    ap.add_argument("--sq", action="store_true", help="also collect the matrix-core and LDS counters of the main kernels")
     ap.add_argument("--reuse", action="store_true", help="summarise the counter files already under gpurun_out/traffic")
     args = ap.parse_args()
     global REUSE
@@ -97,6 +99,8 @@ def main():
     passes = [("FETCH_SIZE", ["FETCH_SIZE"]), ("WRITE_SIZE", ["WRITE_SIZE"])]
     if args.l2:
         passes.append(("L2REQ", ["TCP_TCC_READ_REQ_sum", "TCP_TCC_WRITE_REQ_sum"]))
+    SQ = ["SQ_INSTS_MFMA", "SQ_VALU_MFMA_BUSY_CYCLES", "SQ_LDS_BANK_CONFLICT", "SQ_LDS_IDX_ACTIVE", "SQ_BUSY_CYCLES", "GRBM_GUI_ACTIVE"]
+    layer_passes = list(passes) + ([("SQ", SQ)] if args.sq else [])
 
     # ---- calibration: what the counters read for a 1 GiB copy (3 copies per run)
     GiB_KiB = 1048576.0
@@ -120,12 +124,12 @@ def main():
     results = collections.OrderedDict()
     for layer, algo, path in DEFAULT_RUNS:
         per_kernel = collections.defaultdict(lambda: collections.defaultdict(float))
-        for pname, ctrs in passes:
+        for pname, ctrs in layer_passes:
             tag = "%s_%s_%s_%s" % (layer, algo, path, pname)
             commands.append(_rocprof(ctrs, tag, _bench_args(layer, algo, path)))
             for r in _rows(tag):
                 k = r["Kernel_Name"]
-                if "iolb::" not in k or r["Counter_Name"] not in scale:
+                if "iolb::" not in k or (r["Counter_Name"] not in scale and r["Counter_Name"] not in SQ):
                     continue
                 short = k.replace("(anonymous namespace)::", "").split("iolb::")[1].split("(")[0]
                 per_kernel[short][r["Counter_Name"]] += float(r["Counter_Value"]) / STEPS
@@ -135,7 +139,7 @@ def main():
     w = lines.append
     w("HBM traffic per layer call (rocprofv3 counters FETCH_SIZE and WRITE_SIZE, one MI355X), by kernel.")
     w("")
-    w("Written by:  python -m paper_2012_15667_amd.traffic%s   (from the repository root, on the GPU box)" % (" --l2" if args.l2 else ""))
+    w("Written by:  python -m paper_2012_15667_amd.traffic%s%s   (from the repository root, on the GPU box)" % (" --l2" if args.l2 else "", " --sq" if args.sq else ""))
     w("which runs, each counter in a run of its own:")
     w("  " + commands[0])
     w("  rocprofv3 --pmc <counter> --output-format csv -d gpurun_out/traffic -o <tag> -- python3 bench.py --profile --warmup 0 "
@@ -149,6 +153,11 @@ def main():
           (scale["TCP_TCC_READ_REQ_sum"], scale["TCP_TCC_WRITE_REQ_sum"]))
     w("bound = max(compulsory bytes, leading term of the paper's lower bound at S_f = 40960 elements (160 KB)); for direct")
     w("convolution that term is below compulsory on every layer, for Winograd it is the printed expression of Sec. 4.3.")
+    if args.sq:
+        w("Matrix-core figures of a layer's main kernel: MFMA instructions against the algorithmic count (flop / 4096: one")
+        w("v_mfma_f32_32x32x2_f32 is 4096 flop; direct 2 N K P Q C R S, Winograd 2 (m+2)^2 tiles C K) shows the work the kernel")
+        w("adds (channel padding, idle slots); MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (1024 SIMDs x GRBM_GUI_ACTIVE / 8 XCDs);")
+        w("LDS conflicts = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE.")
     w("")
     rows_out = []
     for (layer, algo, path), per_kernel in results.items():
@@ -173,6 +182,21 @@ def main():
             tot_w += wr
             if rd + wr > main_bytes and ("mfma" in k or "product" in k or "rows" in k or "fused" in k):
                 main_bytes, main_name = rd + wr, k
+        if args.sq and main_name:
+            c = per_kernel[main_name]
+            m = {"direct": 0, "wino2": 2, "wino4": 4}[algo]
+            if m:
+                tiles = L.N * -(-L.H // m) * -(-L.W // m)
+                flop = 2.0 * (m + 2) ** 2 * tiles * L.C * L.K
+            else:
+                P = (L.H + 2 * L.pad - L.R) // L.stride + 1
+                Q = (L.W + 2 * L.pad - L.S) // L.stride + 1
+                flop = 2.0 * L.N * L.K * P * Q * L.C * L.R * L.S
+            if c["SQ_INSTS_MFMA"] > 0 and c["GRBM_GUI_ACTIVE"] > 0:
+                w("    main kernel: %.0f MFMA instructions = %.3f x algorithmic;  MFMA busy %.3f;  LDS conflicts %.3f" % (
+                    c["SQ_INSTS_MFMA"], c["SQ_INSTS_MFMA"] / (flop / 4096.0),
+                    c["SQ_VALU_MFMA_BUSY_CYCLES"] / (1024.0 * c["GRBM_GUI_ACTIVE"] / 8.0),
+                    c["SQ_LDS_BANK_CONFLICT"] / max(1.0, c["SQ_LDS_IDX_ACTIVE"])))
         w("    total %9.1f MB read + %9.1f MB written = %9.1f MB;  compulsory %8.1f MB (x %.2f);  bound %8.1f MB (x %.2f)" %
           (tot_r / 1e6, tot_w / 1e6, (tot_r + tot_w) / 1e6, comp / 1e6, (tot_r + tot_w) / comp, denom / 1e6, (tot_r + tot_w) / denom))
         w("")
