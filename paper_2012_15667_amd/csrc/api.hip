@@ -217,21 +217,26 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
         const int64_t ntiles = (int64_t)s.N * g.tiles_per_image;
         if ((ntiles + 3) / 4 * g.nbk > 0x7fffffffLL) return IOLB_EINVAL;
         g.npg = (int)((ntiles + 3) / 4);
-        const int c_padded = (s.C + cfg.alpha - 1) / cfg.alpha * cfg.alpha;     // whole stages
-        const size_t wbytes = sizeof(float) * (size_t)g.Kp * c_padded;
-        float* wt = wt_buf;
-        if (wt_buf) {
-            if (wbytes > sizeof(float) * wt_floats) return IOLB_EWORKSPACE;
-        } else {
-            void* ws = nullptr;
-            rc = ensure_workspace(dev, align256(wbytes), &ws);
-            if (rc != IOLB_OK) return rc;
-            wt = static_cast<float*>(ws);
-        }
+        // the kernel reads w itself when its rows are whole 16-byte pieces; otherwise a copy padded with zeros
+        g.Cw = (s.C + 3) / 4 * 4;
         hipStream_t st = t_stream;
-        IOLB_HIP(iolb::launch_weight_relayout(w, wt, s.K, g.Kp, s.C, c_padded, st));
+        const float* wk = w;
+        if (g.Cw != s.C || (reinterpret_cast<size_t>(w) & 15)) {
+            const size_t wbytes = sizeof(float) * (size_t)s.K * g.Cw;
+            float* wp = wt_buf;
+            if (wt_buf) {
+                if (wbytes > sizeof(float) * wt_floats) return IOLB_EWORKSPACE;
+            } else {
+                void* ws = nullptr;
+                rc = ensure_workspace(dev, align256(wbytes), &ws);
+                if (rc != IOLB_OK) return rc;
+                wp = static_cast<float*>(ws);
+            }
+            IOLB_HIP(iolb::launch_pointwise_weight_pad(w, wp, s.K, s.C, g.Cw, st));
+            wk = wp;
+        }
         MainKernelTimer timer(st, IOLB_TIME_DIRECT);
-        IOLB_HIP(iolb::launch_pointwise_mfma(x, wt, y, g, st));
+        IOLB_HIP(iolb::launch_pointwise_mfma(x, wk, y, g, st));
         timer.stop(st);
         return IOLB_OK;
     }

@@ -61,11 +61,12 @@ hipError_t launch_direct_mfma_hwc(const float* x, const float* wt, float* y, con
 
 // 1 x 1 convolution, stride 1, no padding (pointwise_mfma.hip): per image y[K][HW] = w[K][C] x[C][HW].  A wave owns
 // mbw x nbw blocks of 32 x 32 partial sums (z = 32 mbw channels by 32 nbw pixels of one image); a workgroup is
-// `waves` waves on consecutive pixel ranges.  wt: re-laid-out weights, ceil(C / alpha) whole
-// stages of rows (zero beyond C) of Kp floats (zero beyond K).
+// `waves` waves on consecutive pixel ranges.  w: the kernels [K][Cw], Cw a multiple of 4 and 16-byte aligned rows
+// (the caller's own w when C is a multiple of 4, else a copy with zeros in [C, Cw): launch_pointwise_weight_pad).
 struct PointGeom {
     int N, C, HW, K;
     int Kp;                    // K rounded up to a multiple of z
+    int Cw;                    // floats per kernel in w: C rounded up to a multiple of 4
     int z, mbw, nbw;
     int waves;                 // 4
     int alpha;                 // channels per stage: 16, 32 or 64 (twice the depth of the input ring)
@@ -73,7 +74,8 @@ struct PointGeom {
     int nbk;                   // Kp / z
     int npg;                   // workgroups along the pixels: ceil(N * tiles_per_image / waves)
 };
-hipError_t launch_pointwise_mfma(const float* x, const float* wt, float* y, const PointGeom& g, hipStream_t st);
+hipError_t launch_pointwise_weight_pad(const float* w, float* wp, int K, int C, int Cw, hipStream_t st);
+hipError_t launch_pointwise_mfma(const float* x, const float* w, float* y, const PointGeom& g, hipStream_t st);
 
 // Winograd F(m x m, 3 x 3), unfused: kernel transform, input transform, batched product over the
 // (m+2)^2 planes, output transform (steps 1-4 of Sec. 4.3).

@@ -9,7 +9,9 @@
 // -- no LDS, no barrier on their way -- through a ring of D channel pairs per lane that is refilled as it is
 // consumed: the loads run a whole stage (D steps) ahead of the multiplications; D is chosen per layer and wave
 // shape so that the ring covers the latency of memory even when a SIMD has a single wave.  Only the weights are
-// shared: a stage's slab of 2 D channels by z kernels goes through registers into one of two LDS buffers.
+// shared: a stage's slab of 2 D channels by z kernels goes through registers into one of two LDS buffers, read
+// from the kernels as the caller holds them (w[K][C], four consecutive channels of a kernel per load) and
+// transposed on the way, so that no re-layout pass runs before the kernel.
 //
 // A wave owns MBW x NBW blocks of 32 x 32 partial sums: z = 32 MBW channels by 32 NBW pixels.  With VEC the
 // lane's NBW pixels are neighbours (pixel l32 * NBW + nb of the wave's range): one NBW-float load per channel,
@@ -54,7 +56,7 @@ template <> struct vec_of<1> { typedef float type; };
 // D: channel pairs per stage = depth of the input ring
 template <int MBW, int NBW, int D, bool VEC>
 __global__ void __launch_bounds__(256, 1)
-pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt, float* __restrict__ y, PointGeom g)
+pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ w, float* __restrict__ y, PointGeom g)
 {
     constexpr int Z = 32 * MBW, PW_ALPHA = 2 * D;
     constexpr int SLAB = PW_ALPHA * Z;                    // floats of a stage's weights
@@ -138,25 +140,42 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt,
         else wait_loads<N>(xr[t][0], xr[t][1], xr[t][2], xr[t][3]);
     };
 
-    // weights of a stage: rows 2 D s .. 2 D s + 2 D - 1 of wt (zero rows beyond C), columns k0 .. k0 + Z - 1, in 16-byte
-    // pieces dealt over the 256 threads (with fewer pieces than threads the upper threads load a piece again and do
-    // not store it), through registers into LDS
+    // weights of a stage: channels 2 D s .. 2 D s + 2 D - 1 of kernels k0 .. k0 + Z - 1, in 16-byte pieces (four
+    // consecutive channels of one kernel: rows of w are g.Cw floats, a multiple of 4) dealt over the 256 threads --
+    // with fewer pieces than threads the upper threads load a piece again and do not store it -- through registers
+    // into LDS as [channel][kernel].  Kernels past K and, in the last stage, channels past the row are read from a
+    // piece that exists and stored as zeros.
+    constexpr int QPS = D / 2;                            // channel quads of a kernel per stage
     floatx4 wreg[WPT];
-    const int wpiece = tid % PIECES;
-    const float* wsrc = wt + (size_t)(wpiece / (Z / 4)) * g.Kp + k0 + (wpiece % (Z / 4)) * 4;      // piece i: + i * 256 / (Z / 4) rows
+    const float* wsrc[WPT];
+    bool wkernel[WPT], wlast[WPT];
+    int wdst[WPT], wquad[WPT];
+#pragma unroll
+    for (int i = 0; i < WPT; ++i) {
+        const int piece = (tid + i * 256) % PIECES;
+        const int kq = piece / QPS, cq = piece % QPS;
+        wkernel[i] = k0 + kq < g.K;
+        wlast[i] = (nstages - 1) * PW_ALPHA + 4 * cq < g.Cw;
+        wsrc[i] = w + (size_t)(wkernel[i] ? k0 + kq : g.K - 1) * g.Cw;     // the kernel's first quad always exists
+        wquad[i] = 4 * cq;
+        wdst[i] = 4 * cq * Z + kq;
+    }
     auto load_weights = [&](int s) {
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
-            const float* p = wsrc + (size_t)(s * PW_ALPHA + i * (256 / (Z / 4))) * g.Kp;
+            const float* p = wsrc[i] + ((s + 1 < nstages || wlast[i]) ? s * PW_ALPHA + wquad[i] : 0);
             asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(wreg[i]) : "v"(p));
         }
     };
-    auto store_weights = [&](float* buf) {
+    auto store_weights = [&](float* buf, int s) {
 #pragma unroll
         for (int i = 0; i < WPT; ++i) {
             wait_loads<WAIT_W>(wreg[i]);
-            const int p = tid + i * 256;
-            if (PIECES % 256 == 0 || p < PIECES) *reinterpret_cast<floatx4*>(buf + p * 4) = wreg[i];
+            if (PIECES % 256 == 0 || tid + i * 256 < PIECES) {
+                const bool keep = wkernel[i] && (s + 1 < nstages || wlast[i]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) buf[wdst[i] + j * Z] = keep ? wreg[i][j] : 0.f;
+            }
         }
     };
 
@@ -171,7 +190,7 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt,
     load_weights(0);
 #pragma unroll
     for (int t = 0; t < D; ++t) load_inputs(0, t);
-    store_weights(wlds);
+    store_weights(wlds, 0);
     __syncthreads();
 
     // One stage.  LAST: nothing is loaded any more, so a step waits for the loads of the stage's later steps only, and
@@ -208,7 +227,7 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt,
             if constexpr (!LAST) load_inputs(s + 1, t);
         });
         if constexpr (!LAST) {
-            store_weights(wlds + ((s + 1) & 1) * SLAB);   // the buffer last read in stage s - 1
+            store_weights(wlds + ((s + 1) & 1) * SLAB, s + 1);   // the buffer last read in stage s - 1
             __syncthreads();
         }
     };
@@ -253,19 +272,36 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ wt,
 }
 
 template <int MBW, int NBW, int D>
-hipError_t launch_shape(const float* x, const float* wt, float* y, const PointGeom& g, hipStream_t st)
+hipError_t launch_shape(const float* x, const float* w, float* y, const PointGeom& g, hipStream_t st)
 {
     const int grid = g.nbk * g.npg;
     if (g.HW % NBW == 0)
-        hipLaunchKernelGGL((pointwise_mfma_kernel<MBW, NBW, D, true>), dim3(grid), dim3(64 * g.waves), 0, st, x, wt, y, g);
+        hipLaunchKernelGGL((pointwise_mfma_kernel<MBW, NBW, D, true>), dim3(grid), dim3(64 * g.waves), 0, st, x, w, y, g);
     else
-        hipLaunchKernelGGL((pointwise_mfma_kernel<MBW, NBW, D, false>), dim3(grid), dim3(64 * g.waves), 0, st, x, wt, y, g);
+        hipLaunchKernelGGL((pointwise_mfma_kernel<MBW, NBW, D, false>), dim3(grid), dim3(64 * g.waves), 0, st, x, w, y, g);
     return hipGetLastError();
+}
+
+// wp[k][c] = w[k][c] for c < C, 0 for C <= c < Cw
+__global__ void pointwise_weight_pad_kernel(const float* __restrict__ w, float* __restrict__ wp, int K, int C, int Cw)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (size_t)K * Cw) return;
+    const int k = (int)(i / Cw), c = (int)(i % Cw);
+    wp[i] = c < C ? w[(size_t)k * C + c] : 0.f;
 }
 
 }  // namespace
 
-hipError_t launch_pointwise_mfma(const float* x, const float* wt, float* y, const PointGeom& g, hipStream_t st)
+hipError_t launch_pointwise_weight_pad(const float* w, float* wp, int K, int C, int Cw, hipStream_t st)
+{
+    if (K < 1 || C < 1 || Cw < C) return hipErrorInvalidValue;
+    const size_t n = (size_t)K * Cw;
+    hipLaunchKernelGGL(pointwise_weight_pad_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, w, wp, K, C, Cw);
+    return hipGetLastError();
+}
+
+hipError_t launch_pointwise_mfma(const float* x, const float* w, float* y, const PointGeom& g, hipStream_t st)
 {
     // what the kernel's indexing assumes
     if (g.N < 1 || g.C < 1 || g.HW < 1 || g.K < 1) return hipErrorInvalidValue;
@@ -277,9 +313,10 @@ hipError_t launch_pointwise_mfma(const float* x, const float* wt, float* y, cons
     if ((long long)g.nbk * g.npg > 0x7fffffffLL) return hipErrorInvalidValue;
     // a lane's byte offset inside its image is 32 bits
     if (4LL * g.C * g.HW >= (1LL << 32)) return hipErrorInvalidValue;
-    if ((reinterpret_cast<size_t>(x) | reinterpret_cast<size_t>(y) | reinterpret_cast<size_t>(wt)) & 15) return hipErrorInvalidValue;
+    if ((reinterpret_cast<size_t>(x) | reinterpret_cast<size_t>(y) | reinterpret_cast<size_t>(w)) & 15) return hipErrorInvalidValue;
+    if (g.Cw < g.C || (g.Cw & 3)) return hipErrorInvalidValue;
     // stage depths per wave shape: the fewer MFMAs a step has, the more steps cover the same time
-#define IOLB_PW(M_, N_, A_) if (g.mbw == M_ && g.nbw == N_ && g.alpha == A_) return launch_shape<M_, N_, A_ / 2>(x, wt, y, g, st);
+#define IOLB_PW(M_, N_, A_) if (g.mbw == M_ && g.nbw == N_ && g.alpha == A_) return launch_shape<M_, N_, A_ / 2>(x, w, y, g, st);
     IOLB_PW(1, 1, 16) IOLB_PW(1, 1, 32)
     IOLB_PW(1, 2, 16) IOLB_PW(1, 2, 32)
     IOLB_PW(1, 4, 16) IOLB_PW(1, 4, 32)

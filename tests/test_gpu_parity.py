@@ -293,6 +293,14 @@ def test_pointwise_layers_every_tile_matches_oracle(gpu, case):
     assert rel_err(yh.cpu().numpy(), _to_hwc(ref)) <= GUARD_DIRECT
     with pytest.raises(Exception):
         B.conv_direct_layout(xh, torch.from_numpy(w).cuda(), 1, 0, B.LAYOUT_HWC, cfg=tiles[0])
+    # kernels that do not start on a 16-byte boundary are copied first (the kernel reads them in 16-byte pieces)
+    shifted = torch.empty(w.size + 1, dtype=torch.float32, device="cuda")
+    shifted[1:] = torch.from_numpy(w).cuda().reshape(-1)
+    wd = shifted[1:].view(K, C, 1, 1)
+    assert wd.data_ptr() % 16 == 4
+    y = B.conv_direct(torch.from_numpy(x).cuda(), wd, 1, 0, cfg=tiles[0])
+    torch.cuda.synchronize()
+    assert rel_err(y.cpu().numpy(), ref) <= GUARD_DIRECT
 
 
 @pytest.mark.parametrize("shape", [(64, 192, 35, 35, 64), (64, 1280, 8, 8, 384), (64, 256, 56, 56, 64)])
