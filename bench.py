@@ -224,9 +224,14 @@ def main():
     n_fused, ms_fused = B.timing_read(B.TIME_WINO_FUSED)
 
     flops_step = sum(direct_flops(j[0]) for j in jobs)
-    direct_alg_flops = sum(direct_flops(j[0]) for j in jobs if j[1] == "direct")
     def tile_of(L, a):
         return B.iolb_tune(shape_of(L, a))
+
+    # direct layers whose tile runs the matrix-core kernel (thin layers run a plain-FMA kernel of their own, which the
+    # library does not time with them)
+    def on_matrix_cores(j):
+        return j[1] == "direct" and (forced[id(j)] or tile_of(j[0], "direct"))["path"] == B.PATH_MFMA
+    direct_alg_flops = sum(direct_flops(j[0]) for j in jobs if on_matrix_cores(j))
 
     # Winograd layers by the kernel their tuned tile runs: unfused product, fused matrix-core kernel, or the thin
     # one-kernel FMA path (no matrix-core launch: nothing added to a roofline)
@@ -297,7 +302,7 @@ def main():
                     "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
                     "frac_of_measured_mfma_loop": round(achieved / ceilings["mfma_f32_TFLOPs"], 4),
                     "avg_launch_ms": round(ms_direct / n_direct, 4), "launches": n_direct}
-        per = [traffic[k]["main_kernel"] for k in traffic if k[1] == "direct" and any(j[0].name == k[0] and j[1] == "direct" for j in jobs)]
+        per = [traffic[k]["main_kernel"] for k in traffic if k[1] == "direct" and any(j[0].name == k[0] and on_matrix_cores(j) for j in jobs)]
         roofline["traffic"] = round(sum(per) / len(per)) if per else None
         roofline["traffic_source"] = ("recorded: %s (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of the same "
                                       "kernels, average over the direct launches of a step), not measured in this run" % TRAFFIC_FILE) if per else None

@@ -64,7 +64,9 @@ typedef struct iolb_tile_config {
     int32_t threads;             /* workgroup size */
     int32_t waves_m, waves_n;    /* MFMA path: wave grid over (z, pixels); FMA path: channel groups, 1 */
     int32_t path;                /* IOLB_PATH_FMA, _MFMA, _FUSED or _POINT */
-    int32_t wt_mode;             /* 0: raw R*S weights staged; 1: pre-transformed (m+2)^2 weights */
+    int32_t wt_mode;             /* 0: raw R*S weights staged; 1: pre-transformed (m+2)^2 weights; 2: thin direct
+                                    layers (3 x 3, stride 1, C <= 4, channels-outermost tensors): one lane per x / 256
+                                    neighbouring pixels of a row and all z = K channels, kernels through the scalar unit */
     int32_t lds_bytes_used;      /* staging bytes the tile needs */
     int32_t acc_regs_per_thread; /* partial sums held per lane */
     int64_t q_read_elems;        /* modelled elements read by all workgroups (exact form of the

@@ -568,6 +568,27 @@ def _pointwise_candidates(s, P, Q, vgpr_budget, use_f3):
     return cands
 
 
+def thin_direct_layer(s):
+    return s["algo"] == DIRECT and s["R"] == 3 and s["S"] == 3 and s["stride"] == 1 and s["C"] <= 4
+
+
+def _thin_direct_candidates(s, P, Q, vgpr_budget):
+    """Thin layers in direct convolution: a lane owns tw neighbouring output pixels of a row (4 when the rows are
+    whole quads, else 1) and every output channel, its 3 x (tw + 2) input window of all C channels in registers; a
+    workgroup is 256 such lanes.  Reading volume counted as if every workgroup were one strip of a row.  Ranked
+    before every other tile in this build's order (heuristic, measured)."""
+    N, C, K = s["N"], s["C"], s["K"]
+    tw = 4 if Q % 4 == 0 else 1
+    if C * 3 * (tw + 2) > vgpr_budget:
+        return []
+    x = 256 * tw
+    nblocks = _cdiv(N * P * _cdiv(Q, tw), 256)
+    qread = nblocks * C * (3 * (x + 2) + 9 * K)
+    key = (-(1 << 62), 0, qread, 0, 0, K, 256, 0, 0, 0)
+    return [(key, dict(b=1, x=x, y=1, z=K, alpha=C, threads=256, waves_m=1, waves_n=4, path=PATH_FMA, wt_mode=2,
+                       lds_bytes_used=0, acc_regs_per_thread=tw, q_read_elems=qread, q_write_elems=N * K * P * Q))]
+
+
 # Fused matrix-core blocks (every plane of a tb x z block resident in accumulator registers, Sec. 5.3), one per
 # kernel instantiation of the library: (e, tb, z, alpha, threads, waves_m, waves_n, lds_bytes, acc)
 FUSED_BLOCKS = (
@@ -665,6 +686,8 @@ def candidates(shape, lds_bytes=0, vgpr_budget=128, use_f3=True, auto_regs=True)
             c = c + _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, PATH_FMA, use_f3)
         if pointwise_layer(s):
             c = c + _pointwise_candidates(s, P, Q, vgpr_budget, use_f3)
+        if thin_direct_layer(s):
+            c = c + _thin_direct_candidates(s, P, Q, vgpr_budget)
         return c
     e = WINO_E[s["algo"]]
     return _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs)
@@ -686,6 +709,8 @@ def _volume_key(shape, t):
     Sec. 5.3 before the unfused tiles, whose temporaries make a round trip through memory that q_read does not
     count; unfused tiles by read volume, then |tb - z| (the optimality condition x y = r^2 z for sub-domain
     strips), then the fuller block."""
+    if shape["algo"] == DIRECT and t["wt_mode"] == 2:
+        return (t["q_read_elems"], abs(t["x"] - 9 * t["z"]), -t["x"] * t["z"], -t["x"], t["z"], 1, 1, 256, 0, 2)
     if shape["algo"] == DIRECT and t["path"] == PATH_POINT:
         # the same order on the image as one row of pixels: volume, distance from x y = R z, the fuller block ...
         return (t["q_read_elems"], abs(t["x"] - t["z"]), -t["x"] * t["z"], -t["x"], t["z"], 1, 1, 256, -PATH_POINT, t["alpha"])

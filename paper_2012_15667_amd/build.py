@@ -9,7 +9,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libiolbconv.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["api.hip", "direct_fma.hip", "direct_mfma.hip", "direct_mfma_hwc.hip", "pointwise_mfma.hip", "wino.hip", "wino_fused.hip", "wino_fused_mfma.hip", "wino_fused_rows.hip", "probe.hip", "tune.cpp"]
+SOURCES = ["api.hip", "direct_fma.hip", "direct_thin.hip", "direct_mfma.hip", "direct_mfma_hwc.hip", "pointwise_mfma.hip", "wino.hip", "wino_fused.hip", "wino_fused_mfma.hip", "wino_fused_rows.hip", "probe.hip", "tune.cpp"]
 # packed fp32 VALU forms are disabled on purpose: plain v_fma_f32 only
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,

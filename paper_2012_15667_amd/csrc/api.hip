@@ -118,11 +118,14 @@ struct MainKernelTimer {
 typedef std::tuple<int, int, int, int, int, int, int, int, int, int> ShapeKey;
 std::map<ShapeKey, iolb_tile_config> g_tiles;
 
-// pointwise_ok = false: the call cannot run an IOLB_PATH_POINT tile (another tensor layout, padding on one axis):
-// the best of the other tiles.
-int tuned_tile(const iolb_shape& s, iolb_tile_config* cfg, bool pointwise_ok = true)
+// Tiles of the kernels that exist for one kind of call only: IOLB_PATH_POINT (channels-outermost tensors, no
+// padding on either axis) and the thin direct layers (wt_mode 2: channels-outermost tensors).
+bool is_thin(const iolb_tile_config& c) { return c.path == IOLB_PATH_FMA && c.wt_mode == 2; }
+
+// pointwise_ok / thin_ok = false: the call cannot run such a tile: the best of the others.
+int tuned_tile(const iolb_shape& s, iolb_tile_config* cfg, bool pointwise_ok = true, bool thin_ok = true)
 {
-    const ShapeKey key(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.algo + (pointwise_ok ? 0 : 1000));
+    const ShapeKey key(s.N, s.C, s.H, s.W, s.K, s.R, s.S, s.stride, s.pad, s.algo + (pointwise_ok ? 0 : 1000) + (thin_ok ? 0 : 2000));
     {
         std::lock_guard<std::mutex> lock(g_mutex);
         auto it = g_tiles.find(key);
@@ -130,13 +133,13 @@ int tuned_tile(const iolb_shape& s, iolb_tile_config* cfg, bool pointwise_ok = t
     }
     int rc = iolb::tune(s, 0, 0, cfg);
     if (rc != IOLB_OK) return rc;
-    if (!pointwise_ok && cfg->path == IOLB_PATH_POINT) {
+    if ((!pointwise_ok && cfg->path == IOLB_PATH_POINT) || (!thin_ok && is_thin(*cfg))) {
         std::vector<iolb::Candidate> all;
         rc = iolb::enumerate(s, 0, 0, false, &all);
         if (rc != IOLB_OK) return rc;
         const iolb::Candidate* first = nullptr;
         for (const auto& c : all)
-            if (c.cfg.path != IOLB_PATH_POINT) { first = &c; break; }
+            if ((pointwise_ok || c.cfg.path != IOLB_PATH_POINT) && (thin_ok || !is_thin(c.cfg))) { first = &c; break; }
         if (!first) return IOLB_ENOTILE;
         *cfg = first->cfg;
     }
@@ -170,7 +173,7 @@ int check_config(const iolb_shape& s, const iolb_tile_config& cfg)
         if (g_checked.count(key)) return IOLB_OK;
     }
     std::vector<iolb::Candidate> all;
-    const int rc = cfg.path == IOLB_PATH_FMA && s.algo == IOLB_DIRECT ? iolb::enumerate_fma(s, 160 * 1024, 0, &all)
+    const int rc = cfg.path == IOLB_PATH_FMA && s.algo == IOLB_DIRECT && cfg.wt_mode != 2 ? iolb::enumerate_fma(s, 160 * 1024, 0, &all)
                                                                       : iolb::enumerate(s, 160 * 1024, 0, false, &all);
     if (rc != IOLB_OK) return rc;
     for (const auto& c : all) {
@@ -244,6 +247,25 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     g.N = s.N; g.C = s.C; g.H = s.H; g.W = s.W; g.K = s.K; g.R = s.R; g.S = s.S; g.stride = s.stride; g.pad = s.pad;
     g.pad_w = pad_w < 0 ? s.pad : pad_w;
     g.P = P; g.Q = Q;
+    if (is_thin(cfg)) {
+        // 3 x 3, stride 1, C <= 4, channels outermost: one lane per few pixels and all output channels
+        if (layout != IOLB_LAYOUT_CHW || s.R != 3 || s.S != 3 || s.stride != 1 || s.C > 4 || cfg.z != s.K || cfg.alpha != s.C)
+            return IOLB_EINVAL;
+        const size_t wbytes = sizeof(float) * (size_t)s.K * iolb::direct_thin_row(s.C);
+        float* wk = wt_buf;
+        if (wt_buf) {
+            if (wbytes > sizeof(float) * wt_floats) return IOLB_EWORKSPACE;
+        } else {
+            void* ws = nullptr;
+            rc = ensure_workspace(dev, align256(wbytes), &ws);
+            if (rc != IOLB_OK) return rc;
+            wk = static_cast<float*>(ws);
+        }
+        hipStream_t st = t_stream;
+        IOLB_HIP(iolb::launch_direct_thin_rows(w, wk, s.K, s.C, st));
+        IOLB_HIP(iolb::launch_direct_thin(x, wk, y, g, st));       // a plain-FMA kernel: not timed with the matrix-core ones
+        return IOLB_OK;
+    }
     g.b = cfg.b; g.tx = cfg.x; g.ty = cfg.y; g.z = cfg.z; g.alpha = cfg.alpha;
     g.threads = cfg.threads; g.waves_m = cfg.waves_m; g.waves_n = cfg.waves_n;
     g.per_thread = cfg.acc_regs_per_thread;
@@ -530,7 +552,7 @@ int conv_direct_layout(const float* x, const float* w, float* y, int N, int C, i
         if (rc != IOLB_OK) return rc;
         tile = *cfg;
     } else {
-        rc = tuned_tile(s, &tile, layout == IOLB_LAYOUT_CHW);
+        rc = tuned_tile(s, &tile, layout == IOLB_LAYOUT_CHW, layout == IOLB_LAYOUT_CHW);
         if (rc != IOLB_OK) return rc;
     }
     return run_direct(x, w, y, s, P, Q, tile, layout);

@@ -59,6 +59,13 @@ hipError_t launch_direct_mfma(const float* x, const float* wt, float* y, const D
 // The same for the channels-innermost tensor layout (g.hwc = 1).
 hipError_t launch_direct_mfma_hwc(const float* x, const float* wt, float* y, const DirectGeom& g, hipStream_t st);
 
+// Thin layers (direct_thin.hip): 3 x 3 kernels, stride 1, C <= 4, plain NCHW tensors.  wk: K rows of
+// direct_thin_row(C) floats (the 9 C elements of a kernel, zero-padded to whole 16-float pieces), 64-byte aligned,
+// written from w by launch_direct_thin_rows.  Of g the layer, P, Q, pad and pad_w are used.
+int direct_thin_row(int C);
+hipError_t launch_direct_thin_rows(const float* w, float* wk, int K, int C, hipStream_t st);
+hipError_t launch_direct_thin(const float* x, const float* wk, float* y, const DirectGeom& g, hipStream_t st);
+
 // 1 x 1 convolution, stride 1, no padding (pointwise_mfma.hip): per image y[K][HW] = w[K][C] x[C][HW].  A wave owns
 // mbw x nbw blocks of 32 x 32 partial sums (z = 32 mbw channels by 32 nbw pixels of one image); a workgroup is
 // `waves` waves on consecutive pixel ranges.  w: the kernels [K][Cw], Cw a multiple of 4 and 16-byte aligned rows

@@ -253,7 +253,7 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ w, 
 #pragma unroll
                     for (int nb = 0; nb < NBW; ++nb) v[nb] = acc[mb][nb][i];
                 }
-                *reinterpret_cast<xvec*>(yimg + (size_t)kk * HW + p) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<xvec*>(yimg + (size_t)kk * HW + p));
             }
     } else {
 #pragma unroll
@@ -265,7 +265,7 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ w, 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int kk = mb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                    if (k0 + kk < g.K) yimg[(size_t)kk * HW + p] = acc[mb][nb][i];
+                    if (k0 + kk < g.K) __builtin_nontemporal_store(acc[mb][nb][i], yimg + (size_t)kk * HW + p);
                 }
         }
     }

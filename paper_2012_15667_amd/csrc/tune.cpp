@@ -333,6 +333,36 @@ void pointwise_candidates(const iolb_shape& s, int P, int Q, int vgpr_budget, bo
         }
 }
 
+// Thin layers in direct convolution (3 x 3 kernels, stride 1, at most four input channels; direct_thin.hip): a lane
+// owns tw neighbouring output pixels of a row (tw = 4 when the rows are whole quads, else 1) and every output
+// channel, with its 3 x (tw + 2) input window of all C channels in registers; a workgroup is 256 such lanes in
+// (image, row, column) order.  Reported as b = 1, x = 256 tw, y = 1, z = K, alpha = C, path FMA, wt_mode 2.
+// Reading volume, counted as if every workgroup were one strip of a row: C (3 (x + 2) + 9 K) per workgroup.  In
+// this build's order it comes before every other tile (measured: such layers are bound by their stores, and this
+// kernel is the one that overlaps them with its arithmetic); in the paper's order it competes by volume.
+bool thin_direct_layer(const iolb_shape& s) {
+    return s.algo == IOLB_DIRECT && s.R == 3 && s.S == 3 && s.stride == 1 && s.C <= 4;
+}
+
+void thin_direct_candidates(const iolb_shape& s, int P, int Q, int vgpr_budget, std::vector<Candidate>* out) {
+    const int tw = Q % 4 == 0 ? 4 : 1;
+    if (s.C * 3 * (tw + 2) > vgpr_budget) return;
+    const int64_t x = 256 * tw;
+    const int64_t nblocks = ceil_div((int64_t)s.N * P * ceil_div(Q, tw), 256);
+    Candidate c{};
+    c.cfg.b = 1; c.cfg.x = (int32_t)x; c.cfg.y = 1; c.cfg.z = s.K;
+    c.cfg.alpha = s.C;
+    c.cfg.threads = 256; c.cfg.waves_m = 1; c.cfg.waves_n = 4;
+    c.cfg.path = IOLB_PATH_FMA; c.cfg.wt_mode = 2;
+    c.cfg.lds_bytes_used = 0;
+    c.cfg.acc_regs_per_thread = tw;
+    c.cfg.q_read_elems = nblocks * s.C * (3 * (x + 2) + 9 * (int64_t)s.K);
+    c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
+    c.key = {-(1LL << 62), 0, c.cfg.q_read_elems, 0, 0, s.K, 256, 0, 0, 0};
+    c.volume = {c.cfg.q_read_elems, std::llabs(x - 9 * (int64_t)s.K), -x * s.K, -x, s.K, 1, 1, 256, 0, 2};
+    out->push_back(c);
+}
+
 // Winograd: the resident block is tb sub-domains by z output channels of ONE transformed plane
 // (the channel-summation temporaries of step 3); per channel it reads tb transformed inputs and
 // z transformed weights, for each of the (m+2)^2 planes.
@@ -495,6 +525,7 @@ int enumerate(const iolb_shape& s, int64_t lds_bytes, int vgpr_budget, bool use_
         const bool fma = most_pixels < 64;
         if (fma) direct_candidates(s, P, Q, lds_bytes, vgpr_budget, IOLB_PATH_FMA, use_box, out);
         if (pointwise_layer(s)) pointwise_candidates(s, P, Q, vgpr_budget, use_box, out);
+        if (thin_direct_layer(s)) thin_direct_candidates(s, P, Q, vgpr_budget, out);
     } else {
         winograd_candidates(s, P, Q, winograd_m(s.algo), lds_bytes, vgpr_budget, auto_regs, use_box, out);
     }

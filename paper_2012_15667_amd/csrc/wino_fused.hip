@@ -96,11 +96,11 @@ wino_fused_kernel(const float* __restrict__ x, const float* __restrict__ Uk, flo
                 vec q;
 #pragma unroll
                 for (int j = 0; j < M; ++j) q[j] = o[i][j];
-                if (h < g.P) *reinterpret_cast<vec*>(yk + (size_t)i * g.Q) = q;
+                if (h < g.P) __builtin_nontemporal_store(q, reinterpret_cast<vec*>(yk + (size_t)i * g.Q));
             } else {
 #pragma unroll
                 for (int j = 0; j < M; ++j)
-                    if (h < g.P && tj * M + j < g.Q) yk[(size_t)i * g.Q + j] = o[i][j];
+                    if (h < g.P && tj * M + j < g.Q) __builtin_nontemporal_store(o[i][j], yk + (size_t)i * g.Q + j);
             }
         }
     }

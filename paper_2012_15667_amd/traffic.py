@@ -75,8 +75,11 @@ def _path_label(layer, algo, path):
     from . import binding as B
     from .inputs import CONFIGS
     L = CONFIGS[layer]
+    names = {B.PATH_FMA: "fma", B.PATH_MFMA: "mfma", B.PATH_FUSED: "fused", B.PATH_POINT: "pointwise"}
     if algo == "direct":
-        return "mfma" if path == "tuned" else "bound"
+        if path != "tuned":
+            return "bound"
+        return names[B.iolb_tune(B.make_shape(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad))["path"]]
     if path == "tuned":
         sh = B.make_shape(L.N, L.C, L.H, L.W, L.K, algo={"wino2": B.WINO_F2, "wino4": B.WINO_F4}[algo])
         return {B.PATH_FMA: "fma", B.PATH_MFMA: "mfma", B.PATH_FUSED: "fused", B.PATH_POINT: "pointwise"}[B.iolb_tune(sh)["path"]]
@@ -180,7 +183,7 @@ def main():
             w("    %-46s read %9.1f MB   written %9.1f MB%s" % (k[:46], rd / 1e6, wr / 1e6, extra))
             tot_r += rd
             tot_w += wr
-            if rd + wr > main_bytes and ("mfma" in k or "product" in k or "rows" in k or "fused" in k):
+            if rd + wr > main_bytes and ("mfma" in k or "product" in k or "rows" in k or "fused" in k or "thin_kernel" in k):
                 main_bytes, main_name = rd + wr, k
         if args.sq and main_name:
             c = per_kernel[main_name]

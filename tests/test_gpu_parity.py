@@ -170,7 +170,7 @@ def test_direct_tiles_that_hang_over_the_edge(gpu, shape):
 @pytest.mark.parametrize("shape", [(2, 8, 17, 17, 32, 1, 7, 1, 0, 3), (2, 8, 17, 17, 32, 7, 1, 1, 3, 0),
                                    (2, 16, 8, 8, 64, 1, 3, 1, 0, 1), (2, 16, 8, 8, 64, 3, 1, 1, 1, 0),
                                    (3, 5, 20, 13, 16, 3, 5, 2, 0, 2), (1, 3, 35, 35, 32, 11, 11, 4, 2, 0),
-                                   (2, 6, 9, 9, 32, 3, 3, 1, 2, 1)])
+                                   (2, 6, 9, 9, 32, 3, 3, 1, 2, 1), (2, 3, 12, 14, 16, 3, 3, 1, 2, 0), (2, 1, 1, 5, 1, 1, 1, 1, 0, 2)])
 def test_direct_with_its_own_padding_per_axis(gpu, shape):
     """pad_h rows and pad_w columns of zeros: against the oracle run on the explicitly bordered image."""
     torch, B = gpu
@@ -255,6 +255,40 @@ def test_direct_alexnet_rows_full_size_sampled(gpu, name):
     g = got[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
     assert rel_err(g, ref) <= TOL_DIRECT
     assert np.isfinite(got).all()
+
+
+THIN_DIRECT_CASES = [
+    # N, C, H, W, K, pad: 3 x 3 kernels, stride 1, at most four input channels
+    (2, 3, 16, 16, 32, 1),       # rows of whole quads: 16-byte stores
+    (1, 4, 64, 64, 32, 0),       # no padding: 62-pixel rows, single-float stores
+    (3, 1, 9, 11, 6, 1),         # one channel, odd extents, K = 6
+    (2, 2, 13, 17, 40, 2),       # two rings of zeros
+    (4, 3, 28, 28, 64, 1),
+    (2, 4, 7, 8, 5, 1),          # fewer lanes than a workgroup
+]
+
+
+@pytest.mark.parametrize("case", THIN_DIRECT_CASES)
+def test_thin_direct_layers_match_oracle(gpu, case):
+    """3 x 3 layers with at most four input channels run in a kernel of their own (one lane per few pixels and every
+    output channel); the matrix-core tiles still serve them, also for the other layouts."""
+    torch, B = gpu
+    N, C, H, W, K, pad = case
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u11", "he", seed=400 + C + W)
+    ref = conv_ref(x, w, 1, pad)
+    shape = B.make_shape(N, C, H, W, K, 3, 3, 1, pad)
+    tuned = B.iolb_tune(shape)
+    assert tuned["path"] == B.PATH_FMA and tuned["wt_mode"] == 2
+    assert rel_err(_run_direct(gpu, x, w, 1, pad), ref) <= GUARD_DIRECT
+    assert rel_err(_run_direct(gpu, x, w, 1, pad, cfg=tuned), ref) <= GUARD_DIRECT
+    general = [t for t in B.iolb_enumerate(shape, 0, 0, False) if t["wt_mode"] != 2]
+    assert rel_err(_run_direct(gpu, x, w, 1, pad, cfg=general[0]), ref) <= GUARD_DIRECT
+    xh = torch.from_numpy(_to_hwc(x)).cuda()
+    yh = B.conv_direct_layout(xh, torch.from_numpy(w).cuda(), 1, pad, B.LAYOUT_HWC)
+    torch.cuda.synchronize()
+    assert rel_err(yh.cpu().numpy(), _to_hwc(ref)) <= GUARD_DIRECT
+    with pytest.raises(Exception):
+        B.conv_direct_layout(xh, torch.from_numpy(w).cuda(), 1, pad, B.LAYOUT_HWC, cfg=tuned)
 
 
 POINTWISE_CASES = [

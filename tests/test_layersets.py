@@ -42,6 +42,10 @@ def test_every_layer_has_a_tile(model):
             assert (L.R, L.S, L.stride, ph, pw) == (1, 1, 1, 0, 0)
             assert cfg["x"] in (128, 256, 512) and cfg["y"] == 1 and cfg["b"] == 1 and cfg["z"] in (32, 64)
             continue
+        if cfg["path"] == B.PATH_FMA and cfg["wt_mode"] == 2:     # thin 3 x 3 layers: 256 lanes of 1 or 4 pixels each
+            assert (L.R, L.S, L.stride) == (3, 3, 1) and L.C <= 4
+            assert cfg["x"] == (1024 if Q % 4 == 0 else 256) and cfg["y"] == 1 and cfg["z"] == L.K
+            continue
         Kz = -(-L.K // 32) * 32 if cfg["path"] == B.PATH_MFMA else L.K
         # tile extents: factors of the output extent or a balanced cut into up to 8 tiles
         fits = lambda n, t: n % t == 0 or any(t == -(-n // k) for k in range(1, 9))

@@ -116,6 +116,16 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
     """Constraints re-stated from the documentation of the rule, written independently."""
     P, Q = o.out_extent(s["H"], s["W"], s["R"], s["S"], s["stride"], s["pad"])
     b, x, y, z, a, T = (cfg[k] for k in ("b", "x", "y", "z", "alpha", "threads"))
+    if cfg["path"] == o.PATH_FMA and cfg["wt_mode"] == 2:
+        # thin direct layers: 256 lanes, each tw neighbouring pixels of a row and every output channel
+        assert (s["algo"], s["R"], s["S"], s["stride"]) == (o.DIRECT, 3, 3, 1) and s["C"] <= 4
+        tw = 4 if Q % 4 == 0 else 1
+        assert (b, x, y, z, a, T) == (1, 256 * tw, 1, s["K"], s["C"], 256) and cfg["lds_bytes_used"] == 0
+        assert s["C"] * 3 * (tw + 2) <= vgpr_budget and cfg["acc_regs_per_thread"] == tw
+        lanes = sum(len(range(0, Q, tw)) for _ in range(s["N"] * P))                # walked row by row
+        assert cfg["q_read_elems"] == len(range(0, lanes, 256)) * s["C"] * (3 * (x + 2) + 9 * s["K"])
+        assert cfg["q_write_elems"] == s["N"] * s["K"] * P * Q
+        return
     if cfg["path"] == o.PATH_POINT:
         # 1 x 1 layers: four waves, each on x / 4 consecutive pixels of an image taken as one row, by z channels
         assert (s["algo"], s["R"], s["S"], s["stride"], s["pad"]) == (o.DIRECT, 1, 1, 1, 0)
