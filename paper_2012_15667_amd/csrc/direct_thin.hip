@@ -93,7 +93,7 @@ direct_thin_kernel(const float* __restrict__ x, const float* __restrict__ wk, fl
         } else {
 #pragma unroll
             for (int j = 0; j < TW; ++j)
-                if (q0 + j < g.Q) __builtin_nontemporal_store(o[j], yk + j);
+                if (q0 + j < g.Q) yk[j] = o[j];
         }
     }
 }

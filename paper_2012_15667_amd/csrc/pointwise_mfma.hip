@@ -253,7 +253,10 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ w, 
 #pragma unroll
                     for (int nb = 0; nb < NBW; ++nb) v[nb] = acc[mb][nb][i];
                 }
-                __builtin_nontemporal_store(v, reinterpret_cast<xvec*>(yimg + (size_t)kk * HW + p));
+                // written once and not read again here: past the caches, when a lane stores 8 or 16 bytes (measured:
+                // single-float nontemporal stores are up to twice as slow as plain ones)
+                if constexpr (NBW > 1) __builtin_nontemporal_store(v, reinterpret_cast<xvec*>(yimg + (size_t)kk * HW + p));
+                else *reinterpret_cast<xvec*>(yimg + (size_t)kk * HW + p) = v;
             }
     } else {
 #pragma unroll
@@ -265,7 +268,7 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ w, 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int kk = mb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                    if (k0 + kk < g.K) __builtin_nontemporal_store(acc[mb][nb][i], yimg + (size_t)kk * HW + p);
+                    if (k0 + kk < g.K) yimg[(size_t)kk * HW + p] = acc[mb][nb][i];
                 }
         }
     }

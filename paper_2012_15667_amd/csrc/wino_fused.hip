@@ -100,7 +100,7 @@ wino_fused_kernel(const float* __restrict__ x, const float* __restrict__ Uk, flo
             } else {
 #pragma unroll
                 for (int j = 0; j < M; ++j)
-                    if (h < g.P && tj * M + j < g.Q) __builtin_nontemporal_store(o[i][j], yk + (size_t)i * g.Q + j);
+                    if (h < g.P && tj * M + j < g.Q) yk[(size_t)i * g.Q + j] = o[i][j];
             }
         }
     }

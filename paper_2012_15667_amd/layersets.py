@@ -149,10 +149,14 @@ def time_layer(N, L, reps=5, seed=0):
     w = torch.randn((L.K, L.C, L.R, L.S), generator=g, device="cuda", dtype=torch.float32) * (2.0 / (L.R * L.S * L.C)) ** 0.5
     P, Q = out_extents(L)
     y = torch.empty((N, L.K, P, Q), device="cuda", dtype=torch.float32)
-    out = {"direct": time_call(torch, lambda: B.conv_direct(x, w, L.stride, L.pad, y=y), reps)}
+    def timed(fn):
+        # short layers are timed over more calls: about two milliseconds of work, at least `reps` calls
+        first = time_call(torch, fn, 3)
+        return time_call(torch, fn, max(reps, min(100, int(2.0 / max(first, 1e-3)))), warmup=0)
+    out = {"direct": timed(lambda: B.conv_direct(x, w, L.stride, L.pad, y=y))}
     if winograd_applies(L):
         for m in (2, 4):
-            out["wino%d" % m] = time_call(torch, lambda: B.conv_winograd(x, w, m, y=y, pad=L.pad), reps)
+            out["wino%d" % m] = timed(lambda m=m: B.conv_winograd(x, w, m, y=y, pad=L.pad))
     return out
 
 
@@ -189,7 +193,7 @@ def report(path, reps=5):
     w = []
     w.append("# Layer sets on one MI355X: whole networks' convolution layers, batch sweep, figure sweep\n")
     w.append("Written by `python -m paper_2012_15667_amd.layersets --report profiles/layer_sets.md` (run from the repository root")
-    w.append("on the GPU box).  Timed with `torch.cuda.Event` around %d calls after 2 warm-up calls, inputs resident in HBM, fp32;" % reps)
+    w.append("on the GPU box).  Timed with `torch.cuda.Event` around at least %d calls (about 2 ms of work for short layers) after warm-up calls, inputs resident in HBM, fp32;" % reps)
     w.append("TFLOP/s are direct-convolution-equivalent (2 N K P Q C R S / time); every call goes through the tuned tile.\n")
     w.append("## Networks (batch 64; distinct convolution shapes x how often the network runs them)\n")
     w.append("| network | conv layers | GFLOP | best algorithm per layer: ms / TFLOP/s | direct only: ms / TFLOP/s |")
