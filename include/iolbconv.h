@@ -39,8 +39,8 @@ extern "C" {
 enum { IOLB_DIRECT = 0, IOLB_WINO_F2 = 1, IOLB_WINO_F4 = 2, IOLB_WINO_F3 = 3, IOLB_WINO_F6 = 4 };
 enum { IOLB_PATH_FMA = 0, IOLB_PATH_MFMA = 1, IOLB_PATH_FUSED = 2, IOLB_PATH_POINT = 3 };
 /* FUSED: Winograd only, all four steps in one matrix-core kernel (Sec. 5.3).  POINT: direct convolution with
- * R = S = 1, stride 1, no padding, channels-outermost tensors only: the dataflow of Sec. 5.2 on the image taken as
- * one row of H * W pixels (without a kernel window the pixels do not interact). */
+ * R = S = 1, no padding, channels-outermost tensors only: the dataflow of Sec. 5.2 on the output plane taken as
+ * one row of P * Q pixels (without a kernel window the pixels do not interact). */
 enum { IOLB_LAYOUT_CHW = 0, IOLB_LAYOUT_HWC = 1, IOLB_LAYOUT_CWH = 2 };   /* per image: channels outermost, channels
                                                                            innermost, channels outermost with W before H */
 
@@ -56,7 +56,7 @@ typedef struct iolb_shape {
  * decomposition (Table 1 of Sec. 6.2: tile sizes and thread numbers).
  * For the Winograd algos the block is a strip of x/m sub-domains of m x m outputs (b = 1,
  * y = m) of one transformed plane.  For IOLB_PATH_POINT the block is x consecutive pixels of the image
- * taken as one row of H * W pixels (b = 1, y = 1; a block may run on into the next image) by z output
+ * taken as one row of P * Q pixels (b = 1, y = 1; a block may run on into the next image) by z output
  * channels.  All fields are exact integers. */
 typedef struct iolb_tile_config {
     int32_t b, x, y, z;

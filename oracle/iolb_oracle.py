@@ -513,15 +513,15 @@ def _direct_candidates(s, P, Q, lds_bytes, vgpr_budget, path, use_f3):
     return cands
 
 
-# 1 x 1 convolution, stride 1, no padding: the pixels of an image do not interact, so the plane is one row of P Q
-# pixels.  A workgroup of the library's kernel for these layers is four waves, each on 32 nbw consecutive pixels of
+# 1 x 1 convolution, no padding (any stride: an output pixel reads one input pixel): the pixels of an image do not
+# interact, so the output plane is one row of P Q pixels.  A workgroup of the library's kernel for these layers is four waves, each on 32 nbw consecutive pixels of
 # that row (x = 128 nbw, y = 1; a workgroup may run on into the next image) by z = 32 mbw output channels; stages of
 # 16 channels, or 32 where that pads none.  POINT_SHAPES: the (mbw, nbw) the kernel is instantiated for.
 POINT_SHAPES = ((1, 1), (1, 2), (1, 4), (2, 2), (2, 4))
 
 
 def pointwise_layer(s):
-    return (s["algo"] == DIRECT and s["R"] == 1 and s["S"] == 1 and s["stride"] == 1 and s["pad"] == 0
+    return (s["algo"] == DIRECT and s["R"] == 1 and s["S"] == 1 and s["pad"] == 0
             and 4 * s["C"] * s["H"] * s["W"] < (1 << 32))
 
 
@@ -558,7 +558,7 @@ def _pointwise_candidates(s, P, Q, vgpr_budget, use_f3):
             steps = _cdiv(C, alpha) * alpha // 2
             compute = _cdiv(nwaves * nbk, 1024) * steps * mbw * nbw * 64 + steps * 40 + 15000
             nblocks = _cdiv(nwaves, 4) * nbk
-            memory = (4 * (N * C * HW + nblocks * C * z)) // 4000 + (4 * qwrite) // 1500
+            memory = (4 * (N * C * HW * s["stride"] + nblocks * C * z)) // 4000 + (4 * qwrite) // 1500
             cost = max(compute, memory)
             # ties: bound by memory, the smaller block (more waves, more loads in flight); else the smaller volume
             key = (-(1 << 61), cost, npix * z if memory >= compute else 0, qread, -npix * z, z, -alpha, 0, 0, 0)

@@ -207,11 +207,12 @@ int run_direct(const float* x, const float* w, float* y, const iolb_shape& s, in
     int rc = device_state(&dev);
     if (rc != IOLB_OK) return rc;
     if (cfg.path == IOLB_PATH_POINT) {
-        // 1 x 1, stride 1, no padding, channels outermost: the image as one row of H * W pixels
-        if (layout != IOLB_LAYOUT_CHW || (pad_w >= 0 && pad_w != 0) || s.pad != 0 || s.R != 1 || s.S != 1 || s.stride != 1)
+        // 1 x 1, no padding, channels outermost: the output plane as one row of P * Q pixels
+        if (layout != IOLB_LAYOUT_CHW || (pad_w >= 0 && pad_w != 0) || s.pad != 0 || s.R != 1 || s.S != 1)
             return IOLB_EINVAL;
         iolb::PointGeom g{};
-        g.N = s.N; g.C = s.C; g.HW = s.H * s.W; g.K = s.K;
+        g.N = s.N; g.C = s.C; g.HW = P * Q; g.K = s.K;
+        g.HWin = s.H * s.W; g.Win = s.W; g.Q = Q; g.stride = s.stride;
         g.z = cfg.z; g.mbw = cfg.z / 32; g.nbw = cfg.x / 128; g.waves = 4; g.alpha = cfg.alpha;
         if (cfg.threads != 256 || cfg.z != 32 * g.mbw || cfg.x != 128 * g.nbw || cfg.alpha < 1) return IOLB_EINVAL;
         g.Kp = (s.K + cfg.z - 1) / cfg.z * cfg.z;

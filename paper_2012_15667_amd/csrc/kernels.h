@@ -66,12 +66,14 @@ int direct_thin_row(int C);
 hipError_t launch_direct_thin_rows(const float* w, float* wk, int K, int C, hipStream_t st);
 hipError_t launch_direct_thin(const float* x, const float* wk, float* y, const DirectGeom& g, hipStream_t st);
 
-// 1 x 1 convolution, stride 1, no padding (pointwise_mfma.hip): per image y[K][HW] = w[K][C] x[C][HW].  A wave owns
+// 1 x 1 convolution, no padding (pointwise_mfma.hip): per image y[K][HW] = w[K][C] x[C][HW] over the HW = P Q output
+// pixels, whose inputs are the pixels (stride p, stride q) of the H x W planes.  A wave owns
 // mbw x nbw blocks of 32 x 32 partial sums (z = 32 mbw channels by 32 nbw pixels of one image); a workgroup is
 // `waves` waves on consecutive pixel ranges.  w: the kernels [K][Cw], Cw a multiple of 4 and 16-byte aligned rows
 // (the caller's own w when C is a multiple of 4, else a copy with zeros in [C, Cw): launch_pointwise_weight_pad).
 struct PointGeom {
-    int N, C, HW, K;
+    int N, C, HW, K;           // HW: output pixels per image
+    int HWin, Win, Q, stride;  // input plane size and row length, output row length, stride (HWin = HW for stride 1)
     int Kp;                    // K rounded up to a multiple of z
     int Cw;                    // floats per kernel in w: C rounded up to a multiple of 4
     int z, mbw, nbw;

@@ -1,4 +1,4 @@
-// 1 x 1 convolution (stride 1, no padding) on the fp32 matrix cores: the dataflow of Sec. 5.2 for R = S = 1.
+// 1 x 1 convolution (no padding) on the fp32 matrix cores: the dataflow of Sec. 5.2 for R = S = 1.
 //
 // Without a kernel window the pixels of an image do not interact: the H x W plane is one row of HW pixels, the
 // input tile of an output sub-block is the sub-block itself (x' = x, y' = y), and the layer is, per image, the
@@ -18,6 +18,8 @@
 // one NBW-float store per output channel; this needs HW to be a multiple of NBW.  Without it block nb holds
 // pixels nb * 32 + l32 and all accesses are single floats.  As everywhere in this library the two k-slices of
 // an MFMA are fed by the lane halves: lanes 0-31 take channel c, lanes 32-63 channel c + D of the stage.
+// With a stride the output pixel (p, q) reads input pixel (stride p, stride q): the same kernel with the lane's
+// input offsets computed from its output pixels (single-float accesses); "pixels" below are output pixels.
 #include "kernels.h"
 
 #include <hip/hip_runtime.h>
@@ -87,16 +89,17 @@ pointwise_mfma_kernel(const float* __restrict__ x, const float* __restrict__ w, 
 
     // byte offset of the lane's first pixel in channel 0 of its image, per block when the blocks are strided;
     // pixels past the image read pixel 0 of the range (always inside) and store nothing
-    const unsigned HWb = 4u * (unsigned)g.HW;
+    const unsigned HWb = 4u * (unsigned)g.HWin;                  // bytes of an input channel plane
     unsigned poff[VEC ? 1 : NBW];
-    if constexpr (VEC) {
+    if constexpr (VEC) {                                         // stride 1: input pixel = output pixel
         const int p = pbase + l32 * NBW;
         poff[0] = 4u * (unsigned)(p < g.HW ? p : pbase);
     } else {
 #pragma unroll
         for (int nb = 0; nb < NBW; ++nb) {
-            const int p = pbase + nb * 32 + l32;
-            poff[nb] = 4u * (unsigned)(p < g.HW ? p : pbase);
+            int p = pbase + nb * 32 + l32;
+            if (p >= g.HW) p = pbase;
+            poff[nb] = 4u * (unsigned)(g.stride == 1 ? p : (p / g.Q) * g.stride * g.Win + (p % g.Q) * g.stride);
         }
     }
     const char* ximg = reinterpret_cast<const char*>(x) + (size_t)img * g.C * HWb;    // wave-uniform
@@ -278,7 +281,7 @@ template <int MBW, int NBW, int D>
 hipError_t launch_shape(const float* x, const float* w, float* y, const PointGeom& g, hipStream_t st)
 {
     const int grid = g.nbk * g.npg;
-    if (g.HW % NBW == 0)
+    if (g.stride == 1 && g.HW % NBW == 0)
         hipLaunchKernelGGL((pointwise_mfma_kernel<MBW, NBW, D, true>), dim3(grid), dim3(64 * g.waves), 0, st, x, w, y, g);
     else
         hipLaunchKernelGGL((pointwise_mfma_kernel<MBW, NBW, D, false>), dim3(grid), dim3(64 * g.waves), 0, st, x, w, y, g);
@@ -315,7 +318,9 @@ hipError_t launch_pointwise_mfma(const float* x, const float* w, float* y, const
     if (g.npg != (ntiles + g.waves - 1) / g.waves) return hipErrorInvalidValue;
     if ((long long)g.nbk * g.npg > 0x7fffffffLL) return hipErrorInvalidValue;
     // a lane's byte offset inside its image is 32 bits
-    if (4LL * g.C * g.HW >= (1LL << 32)) return hipErrorInvalidValue;
+    if (4LL * g.C * g.HWin >= (1LL << 32)) return hipErrorInvalidValue;
+    if (g.stride < 1 || g.Q < 1 || g.HW % g.Q || g.Win < (g.Q - 1) * g.stride + 1 ||
+        (long long)g.HWin < ((long long)(g.HW / g.Q - 1) * g.stride) * g.Win + (g.Q - 1) * g.stride + 1) return hipErrorInvalidValue;
     if ((reinterpret_cast<size_t>(x) | reinterpret_cast<size_t>(y) | reinterpret_cast<size_t>(w)) & 15) return hipErrorInvalidValue;
     if (g.Cw < g.C || (g.Cw & 3)) return hipErrorInvalidValue;
     // stage depths per wave shape: the fewer MFMAs a step has, the more steps cover the same time

@@ -282,8 +282,8 @@ void direct_candidates(const iolb_shape& s, int P, int Q, int64_t lds_bytes, int
             }
 }
 
-// 1 x 1 convolution, stride 1, no padding: the pixels of an image do not interact, so the plane is one row of
-// P Q pixels and a workgroup of pointwise_mfma.hip covers four waves' ranges of 32 nbw consecutive pixels of that
+// 1 x 1 convolution, no padding (any stride: output pixel (p, q) reads input pixel (stride p, stride q) only): the
+// pixels of an image do not interact, so the output plane is one row of P Q pixels and a workgroup of pointwise_mfma.hip covers four waves' ranges of 32 nbw consecutive pixels of that
 // row (x = 128 nbw pixels, y = 1; the ranges of a workgroup may lie in neighbouring images) by z = 32 mbw output
 // channels.  Each entry of kPointShapes is a wave shape the kernel is instantiated for, with stages of 16
 // channels, or 32 where that pads no channel.  Reading volume: per workgroup and channel x inputs and z weights.
@@ -297,7 +297,7 @@ struct PointShape { int mbw, nbw; };
 constexpr PointShape kPointShapes[] = {{1, 1}, {1, 2}, {1, 4}, {2, 2}, {2, 4}};
 
 bool pointwise_layer(const iolb_shape& s) {
-    return s.algo == IOLB_DIRECT && s.R == 1 && s.S == 1 && s.stride == 1 && s.pad == 0 &&
+    return s.algo == IOLB_DIRECT && s.R == 1 && s.S == 1 && s.pad == 0 &&
            4LL * s.C * s.H * s.W < (1LL << 32);          // a lane's byte offset inside its image is 32 bits
 }
 
@@ -324,7 +324,9 @@ void pointwise_candidates(const iolb_shape& s, int P, int Q, int vgpr_budget, bo
             c.cfg.q_write_elems = (int64_t)s.N * s.K * P * Q;
             const int64_t steps = ceil_div(s.C, alpha) * alpha / 2;
             const int64_t compute = ceil_div(nwaves * nbk, 1024) * steps * w.mbw * w.nbw * 64 + steps * 40 + 15000;
-            const int64_t memory = (4 * ((int64_t)s.N * s.C * HW + nblocks * s.C * z)) / 4000 + (4 * c.cfg.q_write_elems) / 1500;
+            // (with a stride the rows between the output rows are never touched, the pixels between the output
+            // pixels come along in the same memory lines)
+            const int64_t memory = (4 * ((int64_t)s.N * s.C * HW * s.stride + nblocks * s.C * z)) / 4000 + (4 * c.cfg.q_write_elems) / 1500;
             const int64_t cost = std::max(compute, memory);
             // ties: bound by memory, the smaller block (more waves, more loads in flight); else the smaller volume
             c.key = {-(1LL << 61), cost, memory >= compute ? npix * z : 0, c.cfg.q_read_elems, -npix * z, z, -alpha, 0, 0, 0};

@@ -337,6 +337,20 @@ def test_pointwise_layers_every_tile_matches_oracle(gpu, case):
     assert rel_err(y.cpu().numpy(), ref) <= GUARD_DIRECT
 
 
+@pytest.mark.parametrize("case", [(2, 20, 35, 35, 70, 2), (3, 64, 7, 8, 40, 2), (2, 33, 28, 28, 48, 3), (4, 64, 56, 56, 128, 2)])
+def test_pointwise_strided_layers_match_oracle(gpu, case):
+    """1 x 1 kernels with a stride (projection shortcuts): the same kernel gathers every stride-th pixel."""
+    torch, B = gpu
+    N, C, H, W, K, stride = case
+    x, w = make_inputs(N, C, H, W, K, 1, 1, "u11", "he", seed=350 + C + stride)
+    ref = conv_ref(x, w, stride, 0)
+    shape = B.make_shape(N, C, H, W, K, 1, 1, stride, 0)
+    assert B.iolb_tune(shape)["path"] == B.PATH_POINT
+    assert rel_err(_run_direct(gpu, x, w, stride, 0), ref) <= GUARD_DIRECT
+    for cfg in [t for t in B.iolb_enumerate(shape, 0, 0, False) if t["path"] == B.PATH_POINT]:
+        assert rel_err(_run_direct(gpu, x, w, stride, 0, cfg=cfg), ref) <= GUARD_DIRECT, cfg
+
+
 @pytest.mark.parametrize("shape", [(64, 192, 35, 35, 64), (64, 1280, 8, 8, 384), (64, 256, 56, 56, 64)])
 def test_pointwise_full_size_sampled(gpu, shape):
     """Network-size 1 x 1 layers at batch 64 with the tuned tile; 4096 sampled outputs recomputed by the oracle."""

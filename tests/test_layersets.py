@@ -39,7 +39,7 @@ def test_every_layer_has_a_tile(model):
         else:       # per-axis padding: the library tunes the layer whose image already holds the zero borders
             cfg = B.iolb_tune(B.make_shape(8, L.C, L.H + 2 * ph, L.W + 2 * pw, L.K, L.R, L.S, L.stride, 0))
         if cfg["path"] == B.PATH_POINT:     # 1 x 1 layers: a block of the image taken as one row of pixels
-            assert (L.R, L.S, L.stride, ph, pw) == (1, 1, 1, 0, 0)
+            assert (L.R, L.S, ph, pw) == (1, 1, 0, 0)
             assert cfg["x"] in (128, 256, 512) and cfg["y"] == 1 and cfg["b"] == 1 and cfg["z"] in (32, 64)
             continue
         if cfg["path"] == B.PATH_FMA and cfg["wt_mode"] == 2:     # thin 3 x 3 layers: 256 lanes of 1 or 4 pixels each

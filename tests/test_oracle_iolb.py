@@ -128,7 +128,7 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
         return
     if cfg["path"] == o.PATH_POINT:
         # 1 x 1 layers: four waves, each on x / 4 consecutive pixels of an image taken as one row, by z channels
-        assert (s["algo"], s["R"], s["S"], s["stride"], s["pad"]) == (o.DIRECT, 1, 1, 1, 0)
+        assert (s["algo"], s["R"], s["S"], s["pad"]) == (o.DIRECT, 1, 1, 0)
         assert (b, y, T, cfg["waves_m"], cfg["waves_n"]) == (1, 1, 256, 1, 4) and x % 128 == 0 and z % 32 == 0
         assert a in (16, 32) and (a == 16 or s["C"] % 32 == 0)
         assert cfg["acc_regs_per_thread"] == 16 * (x // 128) * (z // 32) <= vgpr_budget
