@@ -107,8 +107,8 @@ int conv_direct_cfg(const float* x, const float* w, float* y,
  * x: [N][H][W][C], y: [N][P][Q][K].  IOLB_LAYOUT_CWH: x: [N][C][W][H], y: [N][K][Q][P] (the
  * transposed image: computed as the CHW convolution of the W x H image with the kernels
  * transposed, so tiles are those of that transposed layer).  w is [K][C][R][S] for all.  cfg may be NULL (the tuned
- * tile is used; tiles do not depend on the layout, except that IOLB_PATH_POINT tiles exist for IOLB_LAYOUT_CHW only:
- * IOLB_EINVAL with another layout).  Other layout values: IOLB_EUNSUPPORTED. */
+ * tile is used; tiles do not depend on the layout, except that IOLB_PATH_POINT tiles and the thin-layer tiles
+ * (wt_mode 2) exist for IOLB_LAYOUT_CHW only: IOLB_EINVAL with another layout; with cfg NULL the best other tile is used).  Other layout values: IOLB_EUNSUPPORTED. */
 int conv_direct_layout(const float* x, const float* w, float* y,
                        int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                        int layout, const iolb_tile_config* cfg);

@@ -59,7 +59,9 @@ def with_stage_depths(tiles, min_alpha=4, C=None):
 
 def with_layouts(tiles):
     """Each configuration in both tensor layouts (0: channels outermost, 1: channels innermost)."""
-    return [dict(t, layout=l) for t in tiles for l in (0, 1)]
+    # (the tiles of the 1 x 1 kernel and of the thin-layer kernel exist for channels-outermost tensors only)
+    chw_only = lambda t: t["path"] == 3 or (t["path"] == 0 and t["wt_mode"] == 2)
+    return [dict(t, layout=l) for t in tiles for l in (0, 1) if l == 0 or not chw_only(t)]
 
 
 PARAMS = ("b", "x", "y", "z", "alpha", "layout")

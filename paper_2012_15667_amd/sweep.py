@@ -54,6 +54,11 @@ def sweep(layer_name, algo="direct", max_tiles=0, reps=5, vary_alpha=False, use_
     pick = B.iolb_tune(shape)
     bound = B.iolb_tune_bound(shape)
     tiles = B.iolb_enumerate(shape, lds_bytes, 0, use_box)
+    if hwc:      # the tiles of the 1 x 1 kernel and of the thin-layer kernel exist for channels-outermost tensors only
+        chw_only = lambda t: t["path"] == B.PATH_POINT or (t["path"] == B.PATH_FMA and t["wt_mode"] == 2)
+        tiles = [t for t in tiles if not chw_only(t)]
+        pick = tiles[0] if chw_only(pick) else pick
+        bound = tiles[0] if chw_only(bound) else bound
     if max_tiles and len(tiles) > max_tiles:
         step = len(tiles) / float(max_tiles)
         tiles = [tiles[int(i * step)] for i in range(max_tiles)]
