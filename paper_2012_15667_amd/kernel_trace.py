@@ -2,7 +2,7 @@
 
     python -m paper_2012_15667_amd.kernel_trace        (on a box with an MI355X, from the repository root)
 
-runs  rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof -o bench -- python3 bench.py --steps 5
+runs  rocprofv3 --kernel-trace --stats --output-format csv -d rocprof_out/prof -o bench -- python3 bench.py --steps 5
 --warmup 1 --no-cpu-baseline  and tabulates rocprofv3's per-kernel durations beside the HIP-event figures that the
 same bench.py run printed (the average launch durations of the dominant kernels must agree).
 """
@@ -14,7 +14,7 @@ import subprocess
 import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-CMD = ["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", os.path.join("gpurun_out", "prof"), "-o", "bench",
+CMD = ["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", os.path.join("rocprof_out", "prof"), "-o", "bench",
        "--", "python3", "bench.py", "--steps", "5", "--warmup", "1", "--no-cpu-baseline"]
 
 
@@ -24,7 +24,7 @@ def main():
     if r.returncode != 0:
         raise RuntimeError("rocprofv3 failed:\n" + r.stderr[-2000:])
     d = json.loads([l for l in r.stdout.splitlines() if l.startswith("{")][-1])
-    stats = glob.glob(os.path.join(ROOT, "gpurun_out", "prof", "**", "bench_kernel_stats.csv"), recursive=True)[0]
+    stats = glob.glob(os.path.join(ROOT, "rocprof_out", "prof", "**", "bench_kernel_stats.csv"), recursive=True)[0]
     rows = list(csv.DictReader(open(stats)))
     with open(out, "w") as f:
         f.write("# rocprofv3 kernel-trace summary: bench.py step (configs 2-5, direct + Winograd F2/F4), one MI355X\n\n")

@@ -4,7 +4,7 @@
 
 For every (layer, algorithm, path) of the list below it runs
 
-    rocprofv3 --pmc <counter> --output-format csv -d gpurun_out/traffic -o <tag> -- \
+    rocprofv3 --pmc <counter> --output-format csv -d rocprof_out/traffic -o <tag> -- \
         python3 bench.py --profile --warmup 0 --steps 2 --layers <layer> --algos <algo> [--wino-path <path>] [--direct-pick <pick>]
 
 once per counter (FETCH_SIZE, WRITE_SIZE: KiB per dispatch between L2 and the fabric, so reads served by the
@@ -24,7 +24,7 @@ import subprocess
 import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-OUT_DIR = os.path.join("gpurun_out", "traffic")
+OUT_DIR = os.path.join("rocprof_out", "traffic")
 STEPS = 2
 
 # (layer, algo, path): path "tuned"/"bound" for direct; "fused"/"unfused" for Winograd (thin layers: "tuned")
@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--out", default=os.path.join("profiles", "hbm_traffic_by_layer.txt"))
     ap.add_argument("--l2", action="store_true", help="also collect the requests between the compute units and L2")
     ap.add_argument("--sq", action="store_true", help="also collect the matrix-core and LDS counters of the main kernels")
-    ap.add_argument("--reuse", action="store_true", help="summarise the counter files already under gpurun_out/traffic")
+    ap.add_argument("--reuse", action="store_true", help="summarise the counter files already under rocprof_out/traffic")
     args = ap.parse_args()
     global REUSE
     REUSE = args.reuse
@@ -145,7 +145,7 @@ def main():
     w("Written by:  python -m paper_2012_15667_amd.traffic%s%s   (from the repository root, on the GPU box)" % (" --l2" if args.l2 else "", " --sq" if args.sq else ""))
     w("which runs, each counter in a run of its own:")
     w("  " + commands[0])
-    w("  rocprofv3 --pmc <counter> --output-format csv -d gpurun_out/traffic -o <tag> -- python3 bench.py --profile --warmup 0 "
+    w("  rocprofv3 --pmc <counter> --output-format csv -d rocprof_out/traffic -o <tag> -- python3 bench.py --profile --warmup 0 "
       "--steps %d --layers <layer> --algos <algo> [--wino-path fused|unfused] [--direct-pick tuned]" % STEPS)
     w("")
     w("Calibration: a plain 1 GiB device copy (1048576 KiB each way) reads FETCH_SIZE = %.0f and WRITE_SIZE = %.0f," % (raw["FETCH_SIZE"], raw["WRITE_SIZE"]))
