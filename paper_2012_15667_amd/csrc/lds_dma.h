@@ -39,8 +39,32 @@ __device__ __forceinline__ void lds_dma_load_16(const float* base, unsigned offs
                  : "memory", "m0");
 }
 
-// Wait until every load this wave has issued has written its data.
-__device__ __forceinline__ void lds_dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Wait until every load this wave has issued has written its data.  Written with the builtin, not as assembly, so
+// that the compiler's own wait-count bookkeeping sees it: after an assembly wait it still believes its earlier
+// loads to registers are in flight, and its next wait for them (or before it reuses their registers) then also
+// waits for the LDS-direct loads issued in between -- a full memory latency in the middle of a stage.
+// s_waitcnt immediate of gfx9: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[15:14]; 0x0F70 = vmcnt(0) only.
+__device__ __forceinline__ void lds_dma_wait_all()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
+}
+
+// Wait until at most N of the wave's loads are still in flight (loads complete in the order they were issued).  The
+// registers the awaited loads write are operands, so that no use of them is moved above the wait.  For loads that
+// were themselves issued from assembly: the compiler knows of neither.
+template <int N, class V>
+__device__ __forceinline__ void wait_loads(V& a) { asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N)); }
+template <int N, class V>
+__device__ __forceinline__ void wait_loads(V& a, V& b) { asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N)); }
+template <int N, class V>
+__device__ __forceinline__ void wait_loads(V& a, V& b, V& c, V& d)
+{
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+// The same without registers to tie: for data that lands in LDS.
+template <int N>
+__device__ __forceinline__ void wait_loads_lds() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
 // Stages `nrows` rows of 4*row4 contiguous floats (row r starts at src + r * pitch floats) into LDS,
 // packed row after row from lds_dst.  src, lds_dst and every size are wave-uniform; src, pitch and

@@ -21,6 +21,7 @@
 // With a stride the output pixel (p, q) reads input pixel (stride p, stride q): the same kernel with the lane's
 // input offsets computed from its output pixels (single-float accesses); "pixels" below are output pixels.
 #include "kernels.h"
+#include "lds_dma.h"
 
 #include <hip/hip_runtime.h>
 
@@ -39,18 +40,6 @@ template <int... I, class F>
 __device__ __forceinline__ void static_for_each(std::integer_sequence<int, I...>, F&& f) { (f(std::integral_constant<int, I>{}), ...); }
 template <int N, class F>
 __device__ __forceinline__ void static_for(F&& f) { static_for_each(std::make_integer_sequence<int, N>{}, f); }
-
-// Wait until at most N of the wave's loads are still in flight.  The registers the awaited loads write are
-// operands, so that no use of them is moved above the wait.
-template <int N, class V>
-__device__ __forceinline__ void wait_loads(V& a) { asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(N)); }
-template <int N, class V>
-__device__ __forceinline__ void wait_loads(V& a, V& b) { asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N)); }
-template <int N, class V>
-__device__ __forceinline__ void wait_loads(V& a, V& b, V& c, V& d)
-{
-    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
-}
 
 template <int N> struct vec_of { typedef float type __attribute__((ext_vector_type(N))); };
 template <> struct vec_of<1> { typedef float type; };
