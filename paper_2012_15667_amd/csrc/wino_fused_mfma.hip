@@ -121,106 +121,96 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
     const int k0 = kb * Z, t0 = tbk * TB;
 
     // ---- this lane's transform task: sub-domain t0 + lane, channel `wave` of every stage ---------------------
+    // The windows are read with buffer loads: an element outside the image (zero padding, a sub-domain past the
+    // last one, a channel past C) gets a byte offset at or beyond the descriptor's size, for which the hardware
+    // returns zero -- no masking arithmetic.  A lane's offset is a row part plus a column part; either may carry
+    // the out-of-range mark, and two marks still add up to less than 2^32 (valid offsets stay below 2^30: checked
+    // by the launcher).
     const bool task = wave < ALPHA && lane < TB;
     const int tpi = g.th * g.tw;                                   // sub-domains per image
     const int img0 = t0 / tpi;
     const int HW = g.H * g.W;
     typedef float vecm __attribute__((ext_vector_type(M)));
-    unsigned voff[VEC ? 1 : n][VEC ? 1 : n];                       // scalar path: byte offsets of the window elements
-    unsigned vrow[VEC ? n : 1];                                    // vector path: byte offsets of the own columns per row
-    bool rv[n], cv[n];
-    bool edge_lane = false;
-    int edge_delta = 0;
+    typedef unsigned uvecm __attribute__((ext_vector_type(M)));
+    constexpr unsigned OUTSIDE = 0x40000000u;
+    constexpr int NCOL = VEC ? 3 : n;                              // VEC: left border, the M own columns, right border
+    unsigned vrow[n], vcol[NCOL];                                  // byte offsets from channel 0 of the block's first image
     {
         int t = t0 + lane;
         const bool tv = task && t < g.tiles;
         if (!tv) t = t0;
         const int img = t / tpi, rem = t - img * tpi, ti = rem / g.tw, tj = rem - ti * g.tw;
         const int h0 = ti * M - g.pad, w0 = tj * M - g.pad;
-        unsigned ro[n], co[n];
 #pragma unroll
         for (int i = 0; i < n; ++i) {
-            const int h = h0 + i, ww = w0 + i;
-            rv[i] = tv && h >= 0 && h < g.H;
-            cv[i] = ww >= 0 && ww < g.W;
-            ro[i] = (unsigned)((img - img0) * g.C * HW + (h < 0 ? 0 : (h >= g.H ? g.H - 1 : h)) * g.W);
-            co[i] = (unsigned)(ww < 0 ? 0 : (ww >= g.W ? g.W - 1 : ww));
+            const int h = h0 + i;
+            vrow[i] = (tv && h >= 0 && h < g.H) ? 4u * (unsigned)((img - img0) * g.C * HW + h * g.W) : OUTSIDE;
         }
         if constexpr (VEC) {
-#pragma unroll
-            for (int i = 0; i < n; ++i) vrow[i] = 4u * (ro[i] + (unsigned)(tj * M));
-            // the block's first lane has no left neighbour in the wave, its last lane no right one
-            const bool first = lane == 0 && tj > 0, last = lane == TB - 1 && tj + 1 < g.tw;
-            edge_lane = tv && (first || last);
-            edge_delta = first ? -4 : 4 * M;
+            // pad = 1 and W a multiple of M: the own columns tj M .. tj M + M - 1 always lie inside the image
+            vcol[0] = tj > 0 ? 4u * (unsigned)(tj * M - 1) : OUTSIDE;
+            vcol[1] = 4u * (unsigned)(tj * M);
+            vcol[2] = tj + 1 < g.tw ? 4u * (unsigned)(tj * M + M) : OUTSIDE;
         } else {
 #pragma unroll
-            for (int i = 0; i < n; ++i)
-#pragma unroll
-                for (int j = 0; j < n; ++j) voff[i][j] = 4u * (ro[i] + co[j]);
+            for (int j = 0; j < n; ++j) {
+                const int ww = w0 + j;
+                vcol[j] = (ww >= 0 && ww < g.W) ? 4u * (unsigned)ww : OUTSIDE;
+            }
         }
     }
     const float* xblk = x + (size_t)img0 * g.C * HW;
 
     float win[VEC ? 1 : n][VEC ? 1 : n];
     vecm mid[VEC ? n : 1];
-    float edge[VEC ? n : 1];
-    // channels at or beyond C (the last stage of a C that is not a multiple of ALPHA) read channel C - 1 and
-    // are zeroed in the transform
+    float wl[VEC ? n : 1], wr[VEC ? n : 1];
     auto load_windows = [&](int c0) {
         if (!task) return;
         const int c = c0 + wave;
-        const char* xc = reinterpret_cast<const char*>(xblk + (size_t)(c < g.C ? c : g.C - 1) * HW);
+        // the channel goes into the descriptor's base; a channel at or beyond C (the last stage of a C that is not a
+        // multiple of ALPHA) gets a descriptor of size zero: every load returns zero
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(xblk + (size_t)(c < g.C ? c : 0) * HW), 0, c < g.C ? (int)OUTSIDE : 0, 0x00020000);
         if constexpr (VEC) {
 #pragma unroll
-            for (int i = 0; i < n; ++i) mid[i] = *reinterpret_cast<const vecm*>(xc + vrow[i]);
-            if (edge_lane) {
+            for (int i = 0; i < n; ++i) {
+                wl[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, vrow[i] + vcol[0], 0, 0));
+                if constexpr (M == 2) {
+                    const uvecm q = __builtin_amdgcn_raw_buffer_load_b64(rs, vrow[i] + vcol[1], 0, 0);
+                    mid[i][0] = __uint_as_float(q[0]);
+                    mid[i][1] = __uint_as_float(q[1]);
+                } else {
+                    const uvecm q = __builtin_amdgcn_raw_buffer_load_b128(rs, vrow[i] + vcol[1], 0, 0);
 #pragma unroll
-                for (int i = 0; i < n; ++i) edge[i] = *reinterpret_cast<const float*>(xc + vrow[i] + edge_delta);
+                    for (int e = 0; e < M; ++e) mid[i][e] = __uint_as_float(q[e]);
+                }
+                wr[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, vrow[i] + vcol[2], 0, 0));
             }
         } else {
 #pragma unroll
             for (int i = 0; i < n; ++i)
 #pragma unroll
-                for (int j = 0; j < n; ++j) win[i][j] = *reinterpret_cast<const float*>(xc + voff[i][j]);
+                for (int j = 0; j < n; ++j)
+                    win[i][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, vrow[i] + vcol[j], 0, 0));
         }
     };
-    // Written for few live registers (the accumulators leave little room when four waves share a SIMD): first
-    // B d column by column, then (B d) B^T row by row, each row stored as soon as it is complete.
-    auto transform_windows = [&](int c0, float* vbuf) {
+    // B d column by column, then (B d) B^T row by row, each row stored as soon as it is complete.  Plain VALU
+    // instructions run on the same pipeline as the fp32 MFMAs of the SIMD's other waves and wait for them, so the
+    // transform is kept to its additions: no masks, no exchanges between lanes.
+    auto transform_windows = [&](float* vbuf) {
         if (!task) return;
-        const bool cvalid = c0 + wave < g.C;
         float tmp[n][n];
         static_for<n>([&](auto jc) {
             constexpr int j = decltype(jc)::value;
             float col[n], out[n];
 #pragma unroll
             for (int i = 0; i < n; ++i) {
-                float vin;
-                if constexpr (VEC) {
-                    // border columns: the value of the lane below / above (ds_bpermute: a lane reads the lane
-                    // whose byte index it gives).  The component is copied to a scalar first: a bit cast
-                    // applied directly to a vector element reads element 0.
-                    if constexpr (j == 0) {
-                        const float own_last = mid[i][M - 1];
-                        vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane - 1), __float_as_int(own_last)));
-                        if (lane == 0) vin = edge[i];
-                    } else if constexpr (j == n - 1) {
-                        const float own_first = mid[i][0];
-                        vin = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (lane + 1), __float_as_int(own_first)));
-                        if (lane == TB - 1) vin = edge[i];
-                    } else {
-                        vin = mid[i][j - 1];
-                    }
-                } else {
-                    vin = win[i][j];
-                }
-                col[i] = (cvalid && rv[i] && cv[j]) ? vin : 0.f;
+                if constexpr (VEC) col[i] = j == 0 ? wl[i] : (j == n - 1 ? wr[i] : mid[i][j == 0 || j == n - 1 ? 0 : j - 1]);
+                else col[i] = win[i][j];
             }
             mat_vec<M, UseB, n, n>(col, out);
 #pragma unroll
             for (int i = 0; i < n; ++i) tmp[i][j] = out[i];
-            __builtin_amdgcn_sched_barrier(0);
         });
         float* vp = vbuf + ((size_t)(wave >> 1) * NP * TB + lane) * 2 + (wave & 1);
         static_for<n>([&](auto ic) {
@@ -229,13 +219,23 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
             mat_vec<M, UseB, n, n>(tmp[i], out);
 #pragma unroll
             for (int j = 0; j < n; ++j) vp[(i * n + j) * TB * 2] = out[j];
-            __builtin_amdgcn_sched_barrier(0);
         });
     };
     // the stage's slab of U2: NCP * NP rows of 2 Z floats, pitch 2 Kp
     const float* Ublk = U2 + (size_t)k0 * 2;
+    // Every wave issues one load instruction: with nothing of its own in flight its LDS-base write does not wait.
+    // The rest of the slab is left to the waves without a transform task: each further LDS-base write waits for the
+    // load before it, and they wait while the others transform.
     auto issue_kernels = [&](int c0, float* ubuf) {
-        stage_rows(Ublk + (size_t)(c0 >> 1) * NP * g.Kp * 2, g.Kp * 2, Z / 2, NCP * NP, ubuf, wave, NWAVES, lane);
+        constexpr int ROWS = NCP * NP, RPI = (Z / 2 <= 64 && 64 % (Z / 2) == 0) ? 64 / (Z / 2) : 1;
+        constexpr int FIRST = (NWAVES * RPI < ROWS && ALPHA < NWAVES) ? NWAVES * RPI : ROWS;
+        const float* src = Ublk + (size_t)(c0 >> 1) * NP * g.Kp * 2;
+        stage_rows(src, g.Kp * 2, Z / 2, FIRST, ubuf, wave, NWAVES, lane);
+        if constexpr (FIRST < ROWS) {
+            if (wave >= ALPHA)
+                stage_rows(src + (size_t)FIRST * g.Kp * 2, g.Kp * 2, Z / 2, ROWS - FIRST, ubuf + FIRST * Z * 2, wave - ALPHA,
+                           NWAVES - ALPHA, lane);
+        }
     };
 
     floatx16 acc[n];
@@ -252,7 +252,7 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
     load_windows(0);
     issue_kernels(0, lds);
     lds_dma_wait_all();
-    transform_windows(0, lds + UFLOATS);
+    transform_windows(lds + UFLOATS);
     if (nstages > 1) load_windows(ALPHA);
     for (int s = 0; s < nstages; ++s) {
         lds_dma_wait_all();                 // this wave's part of U(s) has landed; so have the windows of stage s + 1
@@ -261,7 +261,7 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
         float* nxt = lds + ((s + 1) & 1) * STAGE;
         if (s + 1 < nstages) {
             issue_kernels((s + 1) * ALPHA, nxt);
-            transform_windows((s + 1) * ALPHA, nxt + UFLOATS);
+            transform_windows(nxt + UFLOATS);
         }
         if (s + 2 < nstages) load_windows((s + 2) * ALPHA);
         // the n planes of this wave's row, per group of four channels: operands of the next group are fetched
@@ -359,11 +359,11 @@ hipError_t launch_fused_vec(const float* x, const float* U2, float* y, const Win
     constexpr size_t shm = 2 * stage > xch ? 2 * stage : xch;
     static_assert(shm <= 160 * 1024, "block does not fit the LDS");
     if (g.tb != TB || g.z != Z || g.alpha != ALPHA || g.Kp % Z || g.Cp % ALPHA || g.Cp < g.C) return hipErrorInvalidValue;
-    // per-lane byte offsets are 32 bits from the first image of the block: a block spans at most
-    // TB / (sub-domains per image) + 2 images
+    // per-lane byte offsets count from the first image of the block and stay below the out-of-range mark of the
+    // window loads (2^30): a block spans at most TB / (sub-domains per image) + 2 images
     const long long tpi = (long long)g.th * g.tw;
     const long long span = ((TB + tpi - 1) / tpi + 2) * (long long)g.C * g.H * g.W * 4;
-    if (span >= (1LL << 32)) return hipErrorInvalidValue;
+    if (span >= (1LL << 30)) return hipErrorInvalidValue;
     auto kern = wino_fused_mfma_kernel<M, WT, WK, ALPHA, VEC>;
     if (shm > 64 * 1024) {
         const hipError_t e = allow_large_lds((const void*)kern);
