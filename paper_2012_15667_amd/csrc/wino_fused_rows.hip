@@ -80,9 +80,14 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
     const float* xblk = x + (size_t)img0 * g.C * HW;
 
     // ---- pass 1 geometry: task q = tid + it * T  ->  (channel q / (n TB), sub-domain (q / n) % TB, column q % n) ----
-    unsigned coff[NT][n];              // byte offset of the column's pixel in window row i, from the channel base
-    unsigned cmask[NT];                // bit i: pixel i of the column lies inside the image (and the sub-domain exists)
+    // The pixels are read with buffer loads: one outside the image (zero padding, a sub-domain past the last one, a
+    // channel past C) gets a byte offset at or beyond the descriptor's size, for which the hardware returns zero --
+    // no masking arithmetic (plain VALU instructions share the pipeline of the fp32 MFMAs: each one costs the SIMD
+    // matrix time).  Valid offsets stay below the mark (checked by the launcher).
+    constexpr unsigned OUTSIDE = 0x40000000u;
+    unsigned coff[NT][n];              // byte offset of the column's pixel in window row i, from channel 0 of the block's first image
     int p1_dst[NT];                    // scratch offset of (window, column)
+    int p1_ch[NT];                     // channel of the task within its stage (the same for all lanes of a wave)
 #pragma unroll
     for (int it = 0; it < NT; ++it) {
         const int q = tid + it * T;
@@ -93,16 +98,13 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
         const int img = t / tpi, rem = t - img * tpi, ti = rem / g.tw, tj = rem - ti * g.tw;
         const int h0 = ti * M - g.pad, ww = tj * M - g.pad + j;
         const bool cvalid = tv && ww >= 0 && ww < g.W;
-        const unsigned cw = (unsigned)(ww < 0 ? 0 : (ww >= g.W ? g.W - 1 : ww));
-        unsigned mask = 0;
 #pragma unroll
         for (int i = 0; i < n; ++i) {
             const int h = h0 + i;
-            if (cvalid && h >= 0 && h < g.H) mask |= 1u << i;
-            coff[it][i] = 4u * ((unsigned)((img - img0) * g.C * HW + (h < 0 ? 0 : (h >= g.H ? g.H - 1 : h)) * g.W) + cw);
+            coff[it][i] = (cvalid && h >= 0 && h < g.H) ? 4u * (unsigned)((img - img0) * g.C * HW + h * g.W + ww) : OUTSIDE;
         }
-        cmask[it] = mask;
         p1_dst[it] = ((q / (n * TB)) * TB + tl) * SP + j;
+        p1_ch[it] = __builtin_amdgcn_readfirstlane(q / (n * TB));
     }
     // ---- pass 2 geometry: task q -> (channel q / (n TB), window row (q / TB) % n, sub-domain q % TB) --------------
     int p2_src[NT], p2_dst[NT];
@@ -115,26 +117,23 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
     }
 
     float colv[NT][n];
-    // channels at or beyond C (the last stage of a C that is not a multiple of ALPHA) read channel C - 1 and are
-    // zeroed in pass 1
+    // the channel goes into the descriptor's base; a channel at or beyond C (the last stage of a C that is not a
+    // multiple of ALPHA) gets a descriptor of size zero: every load returns zero
     auto load_columns = [&](int c0) {
 #pragma unroll
         for (int it = 0; it < NT; ++it) {
-            const int c = c0 + __builtin_amdgcn_readfirstlane((tid + it * T) / (n * TB));
-            const char* xc = reinterpret_cast<const char*>(xblk + (size_t)(c < g.C ? c : g.C - 1) * HW);
+            const int c = c0 + p1_ch[it];
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float*>(xblk + (size_t)(c < g.C ? c : 0) * HW), 0, c < g.C ? (int)OUTSIDE : 0, 0x00020000);
 #pragma unroll
-            for (int i = 0; i < n; ++i) colv[it][i] = *reinterpret_cast<const float*>(xc + coff[it][i]);
+            for (int i = 0; i < n; ++i) colv[it][i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, coff[it][i], 0, 0));
         }
     };
-    auto pass1 = [&](int c0, float* sbuf) {
+    auto pass1 = [&](float* sbuf) {
 #pragma unroll
         for (int it = 0; it < NT; ++it) {
-            const int c = c0 + __builtin_amdgcn_readfirstlane((tid + it * T) / (n * TB));
-            const unsigned mask = c < g.C ? cmask[it] : 0u;
-            float col[n], out[n];
-#pragma unroll
-            for (int i = 0; i < n; ++i) col[i] = (mask >> i) & 1u ? colv[it][i] : 0.f;
-            rows_mat_vec<M, UseB, n, n>(col, out);
+            float out[n];
+            rows_mat_vec<M, UseB, n, n>(colv[it], out);
             float* dst = sbuf + p1_dst[it];
 #pragma unroll
             for (int i = 0; i < n; ++i) dst[i * n] = out[i];
@@ -166,10 +165,18 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
     }
     const float* Ublk = U2 + (size_t)k0 * 2;
     floatx4 ureg[NU];
+    // (buffer loads: the stage's base is a scalar and the lane's offset goes in as it is -- no 64-bit address
+    // arithmetic on the vector unit)
+    typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
     auto load_kernels = [&](int c0) {
-        const char* up = reinterpret_cast<const char*>(Ublk + (size_t)(c0 >> 1) * NP * g.Kp * 2);
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float*>(Ublk + (size_t)(c0 >> 1) * NP * g.Kp * 2), 0, 0x7fffffff, 0x00020000);
 #pragma unroll
-        for (int it = 0; it < NU; ++it) ureg[it] = *reinterpret_cast<const floatx4*>(up + uoff[it]);
+        for (int it = 0; it < NU; ++it) {
+            const uintx4 q = __builtin_amdgcn_raw_buffer_load_b128(rs, uoff[it], 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ureg[it][e] = __uint_as_float(q[e]);
+        }
     };
     auto store_kernels = [&](float* ubuf) {
 #pragma unroll
@@ -200,7 +207,7 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
             pass2(scratch0 + (k & 1) * SCRATCH, buf + UFLOATS);
         }
         if (k >= 1 && k + 1 < nstages) load_kernels((k + 1) * ALPHA);
-        if (k >= 1 && k + 1 < nstages) pass1((k + 1) * ALPHA, scratch0 + ((k + 1) & 1) * SCRATCH);
+        if (k >= 1 && k + 1 < nstages) pass1(scratch0 + ((k + 1) & 1) * SCRATCH);
         if (k >= 1 && k + 2 < nstages) load_columns((k + 2) * ALPHA);
     };
     // the n planes of this wave's row, per group of four channels: operands of the next group are fetched while
@@ -234,13 +241,13 @@ wino_rows_kernel(const float* __restrict__ x, const float* __restrict__ U2, floa
     // prologue: stage 0 prepared by everybody in the same order
     load_columns(0);
     load_kernels(0);
-    pass1(0, scratch0);
+    pass1(scratch0);
     if (nstages > 1) load_columns(ALPHA);
     store_kernels(lds);
     if (nstages > 1) load_kernels(ALPHA);
     __syncthreads();
     pass2(scratch0, lds + UFLOATS);
-    if (nstages > 1) pass1(ALPHA, scratch0 + SCRATCH);
+    if (nstages > 1) pass1(scratch0 + SCRATCH);
     if (nstages > 2) load_columns(2 * ALPHA);
     for (int s = 0; s < nstages; ++s) {
         // the barrier that opens interval s: everything stage s needs is complete, stage s - 1 is consumed
@@ -321,11 +328,12 @@ hipError_t launch_rows_one(const float* x, const float* U2, float* y, const Wino
     constexpr size_t shm = main_bytes > xch ? main_bytes : xch;
     static_assert(shm <= 160 * 1024, "block does not fit the LDS");
     if (g.tb != TB || g.z != Z || g.alpha != ALPHA || g.Kp % Z || g.Cp % ALPHA || g.Cp < g.C) return hipErrorInvalidValue;
-    // per-lane byte offsets are 32 bits from the first image of the block: a block spans at most
+    // per-lane byte offsets count from the first image of the block and stay below the out-of-range mark of the
+    // window loads (2^30): a block spans at most
     // TB / (sub-domains per image) + 2 images
     const long long tpi = (long long)g.th * g.tw;
     const long long span = ((TB + tpi - 1) / tpi + 2) * (long long)g.C * g.H * g.W * 4;
-    if (span >= (1LL << 32)) return hipErrorInvalidValue;
+    if (span >= (1LL << 30)) return hipErrorInvalidValue;
     auto kern = wino_rows_kernel<M, WT, WK, ALPHA>;
     if (shm > 64 * 1024) {
         const hipError_t e = allow_large_lds((const void*)kern);
