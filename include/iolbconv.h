@@ -229,6 +229,18 @@ int iolb_probe_hbm_copy(const void* src, void* dst, size_t bytes, int reps, floa
 size_t iolb_probe_mfma_sink_bytes(void);
 int iolb_probe_mfma_f32(void* sink, int iters, int reps, float* ms_per_launch, double* flop_per_launch);
 
+/* Probe of how the waves of one SIMD share its fp32 pipeline (the fused Winograd kernels of Sec. 5.3 mix matrix
+ * and plain vector arithmetic in one workgroup; this measures what that costs).  One launch of 256 workgroups of
+ * 4 * slots waves, so that every SIMD holds `slots` waves (1..4); the waves of slot s run roles[s] (a host array):
+ * IOLB_PROBE_ROLE_MFMA = `iters` rounds of 8 v_mfma_f32_32x32x2_f32 (512 matrix cycles per round),
+ * IOLB_PROBE_ROLE_VALU = `iters` rounds of 64 v_fma_f32.  `scratch` is a device buffer of at least
+ * iolb_probe_share_scratch_bytes() bytes.  *ms gets the duration of the launch, ticks_per_slot[s] (host, `slots`
+ * doubles) the average clock ticks a wave of slot s spent in its loop.  Runs on the set stream and waits for it.
+ * IOLB_EINVAL for null pointers, slots outside 1..4, an unknown role, iters < 1. */
+enum { IOLB_PROBE_ROLE_MFMA = 0, IOLB_PROBE_ROLE_VALU = 1 };
+size_t iolb_probe_share_scratch_bytes(void);
+int iolb_probe_pipeline_share(void* scratch, int slots, const int* roles, int iters, float* ms, double* ticks_per_slot);
+
 /* Waits for the current GPU and frees the library's workspaces on it (all streams, and the buffers larger ones
  * have replaced); they are otherwise kept until the process ends.  Graphs captured from calls that used them
  * must not be replayed afterwards. */

@@ -282,7 +282,7 @@ MODEL_CONSTANTS = {
     "unfused_flop_rate": (105000, "flop per ns, Winograd product kernel", "bench step, eight layers"),
     "transform_rate": (5200, "bytes per ns, Winograd transform kernels", "cfg5c transforms, rocprofv3 durations"),
     "launch": (3000, "ns per kernel launch", "cfg2, back-to-back launches"),
-    "fused_rate": ({2: 328, 4: 242}, "flop per ns and compute unit, fused Winograd kernels", "cfg5b-d, 84 / 62 Tflop/s"),
+    "fused_rate": ({2: 370, 4: 295}, "flop per ns and compute unit, fused Winograd kernels", "cfg5b-d, 95 / 75 Tflop/s"),
 }
 
 N_CU = 256
@@ -609,7 +609,7 @@ def fused_faster(s, P, Q, e, ftb, fz, falpha):
                 (4 * (N * C * s["H"] * s["W"] + n2 * tiles_p * (Cp16 + Kz) + N * K * P * Q)) // 5200 + 4 * 3000
     Cf = -(-C // falpha) * falpha
     nblocks = (-(-tiles // ftb)) * (-(-K // fz))
-    t_fused = (-(-nblocks // N_CU)) * ((2 * n2 * ftb * fz * Cf) // (328 if e == 2 else 242)) + 2 * 3000
+    t_fused = (-(-nblocks // N_CU)) * ((2 * n2 * ftb * fz * Cf) // (370 if e == 2 else 295)) + 2 * 3000
     return t_fused < t_unfused
 
 

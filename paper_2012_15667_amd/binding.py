@@ -18,6 +18,7 @@ EXPORTS = ["conv_direct", "conv_direct_noalloc", "conv_direct_noalloc_max_weight
            "conv_winograd_ws", "conv_winograd_kernel_bytes", "conv_winograd_transform_kernels", "conv_winograd_pre",
            "iolb_tune", "iolb_tune_bound", "iolb_enumerate", "iolb_bounds", "iolb_winograd_matrices", "iolb_set_stream",
            "iolb_probe_hbm_copy", "iolb_probe_mfma_sink_bytes", "iolb_probe_mfma_f32",
+           "iolb_probe_share_scratch_bytes", "iolb_probe_pipeline_share",
            "iolb_timing_enable", "iolb_timing_read", "iolb_release_workspace", "iolb_strerror",
            "iolb_last_hip_error"]
 
@@ -115,6 +116,11 @@ def lib():
         L.iolb_probe_mfma_sink_bytes.argtypes = []
         L.iolb_probe_mfma_f32.restype = i
         L.iolb_probe_mfma_f32.argtypes = [vp, i, i, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)]
+        L.iolb_probe_share_scratch_bytes.restype = sz
+        L.iolb_probe_share_scratch_bytes.argtypes = []
+        L.iolb_probe_pipeline_share.restype = i
+        L.iolb_probe_pipeline_share.argtypes = [vp, i, ctypes.POINTER(ctypes.c_int), i, ctypes.POINTER(ctypes.c_float),
+                                                ctypes.POINTER(ctypes.c_double)]
         L.iolb_release_workspace.restype = i
         L.iolb_release_workspace.argtypes = []
         L.iolb_strerror.restype = ctypes.c_char_p
@@ -403,6 +409,22 @@ def probe_mfma_f32(sink, iters=20000, reps=3):
     flop = ctypes.c_double(0)
     _check(lib().iolb_probe_mfma_f32(_dev_f32(sink, "sink"), iters, reps, ctypes.byref(ms), ctypes.byref(flop)))
     return ms.value, flop.value
+
+
+PROBE_ROLE_MFMA, PROBE_ROLE_VALU = 0, 1
+
+
+def probe_pipeline_share(roles, iters=2000):
+    """(milliseconds, [average clock ticks of a wave of each slot]) of one launch in which every SIMD holds
+    len(roles) waves, slot s running roles[s] (PROBE_ROLE_MFMA / PROBE_ROLE_VALU)."""
+    import torch
+    _use_current_stream()
+    scratch = torch.zeros(lib().iolb_probe_share_scratch_bytes() // 4 + 1, dtype=torch.float32, device="cuda")
+    arr = (ctypes.c_int * len(roles))(*roles)
+    ms = ctypes.c_float(0)
+    ticks = (ctypes.c_double * len(roles))()
+    _check(lib().iolb_probe_pipeline_share(_dev_f32(scratch, "scratch"), len(roles), arr, iters, ctypes.byref(ms), ticks))
+    return ms.value, list(ticks)
 
 
 def release_workspace():

@@ -4,6 +4,11 @@
 
 prints one JSON line.  bench.py quotes its roofline fractions against the published peaks and, beside them,
 against these.
+
+    python -m paper_2012_15667_amd.ceilings --share
+
+prints, as a table, how waves that issue fp32 MFMAs and waves that issue plain VALU instructions share one SIMD:
+the clock ticks per instruction of each wave when it runs alone and beside the others.
 """
 import json
 import sys
@@ -28,6 +33,30 @@ def measure(copy_bytes=1 << 30, copy_reps=5, mfma_iters=20000, mfma_reps=3):
             "copy_bytes": copy_bytes, "mfma_ms": round(ms_mfma, 3)}
 
 
+def pipeline_share(iters=2000):
+    """Rows of (mix, ms, [(role, ticks per instruction)]) for the wave mixes below; an MFMA round is 8
+    instructions, a VALU round 64."""
+    from . import binding as B
+    M, V = B.PROBE_ROLE_MFMA, B.PROBE_ROLE_VALU
+    mixes = [[M], [M, M], [M, M, M, M], [V], [V, V], [M, V], [V, M], [M, M, V], [M, V, V], [M, M, M, V], [M, M, V, V]]
+    rows = []
+    for roles in mixes:
+        ms, ticks = B.probe_pipeline_share(roles, iters)
+        rows.append(("+".join("MFMA" if r == M else "VALU" for r in roles), ms,
+                     [("MFMA" if r == M else "VALU", t / (iters * (8.0 if r == M else 64.0))) for r, t in zip(roles, ticks)]))
+    return rows
+
+
+def share_report(rows):
+    lines = ["| waves of one SIMD | launch ms | ticks per instruction, wave by wave |", "|---|---|---|"]
+    for name, ms, per in rows:
+        lines.append("| %s | %.3f | %s |" % (name, ms, ", ".join("%s %.1f" % (r, t) for r, t in per)))
+    return "\n".join(lines)
+
+
 if __name__ == "__main__":
-    print(json.dumps(measure()))
+    if "--share" in sys.argv[1:]:
+        print(share_report(pipeline_share()))
+    else:
+        print(json.dumps(measure()))
     sys.exit(0)

@@ -747,6 +747,35 @@ int iolb_probe_mfma_f32(void* sink, int iters, int reps, float* ms_per_launch, d
                       [&] { return iolb::launch_probe_mfma(static_cast<float*>(sink), iters, t_stream); });
 }
 
+size_t iolb_probe_share_scratch_bytes(void)
+{
+    return sizeof(unsigned long long) * 16 * (size_t)iolb::PROBE_SHARE_BLOCKS + 64;
+}
+
+int iolb_probe_pipeline_share(void* scratch, int slots, const int* roles, int iters, float* ms, double* ticks_per_slot)
+{
+    if (!scratch || !roles || !ms || !ticks_per_slot || slots < 1 || slots > 4 || iters < 1) return IOLB_EINVAL;
+    unsigned packed = 0;
+    for (int s = 0; s < slots; ++s) {
+        if (roles[s] != IOLB_PROBE_ROLE_MFMA && roles[s] != IOLB_PROBE_ROLE_VALU) return IOLB_EINVAL;
+        packed |= (unsigned)roles[s] << (2 * s);
+    }
+    auto* ticks = static_cast<unsigned long long*>(scratch);
+    float* sink = reinterpret_cast<float*>(ticks + 16 * (size_t)iolb::PROBE_SHARE_BLOCKS);
+    const int rc = time_probe(1, ms, [&] { return iolb::launch_probe_share(ticks, sink, slots, packed, iters, t_stream); });
+    if (rc != IOLB_OK) return rc;
+    std::vector<unsigned long long> host(16 * (size_t)iolb::PROBE_SHARE_BLOCKS);
+    IOLB_HIP(hipMemcpyAsync(host.data(), ticks, host.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost, t_stream));
+    IOLB_HIP(hipStreamSynchronize(t_stream));
+    for (int s = 0; s < slots; ++s) {
+        double sum = 0;
+        for (int b = 0; b < iolb::PROBE_SHARE_BLOCKS; ++b)
+            for (int w = 0; w < 4; ++w) sum += (double)host[(size_t)b * 16 + s * 4 + w];
+        ticks_per_slot[s] = sum / (4.0 * iolb::PROBE_SHARE_BLOCKS);
+    }
+    return IOLB_OK;
+}
+
 int iolb_release_workspace(void)
 {
     int dev = 0;

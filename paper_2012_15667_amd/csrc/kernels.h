@@ -129,6 +129,11 @@ constexpr int PROBE_MFMA_BLOCKS = 1024;
 constexpr int PROBE_ACC = 8;
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
 hipError_t launch_probe_mfma(float* sink, int iters, hipStream_t st);
+// Waves of two kinds side by side on every SIMD: `slots` waves per SIMD, slot s playing role (roles >> 2 s) & 3;
+// ticks gets PROBE_SHARE_BLOCKS * 16 clock counts (one per wave, unused ones untouched), sink one float.
+constexpr int PROBE_SHARE_BLOCKS = 256;
+constexpr unsigned PROBE_ROLE_MFMA = 0, PROBE_ROLE_VALU = 1;
+hipError_t launch_probe_share(unsigned long long* ticks, float* sink, int slots, unsigned roles, int iters, hipStream_t st);
 
 }  // namespace iolb
 

@@ -42,7 +42,54 @@ probe_mfma_kernel(float* __restrict__ sink, int iters)
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// How the waves of one SIMD share its fp32 pipeline.  A workgroup has 4 * slots waves, so every SIMD gets `slots`
+// of them; the waves of slot s (waves 4 s .. 4 s + 3) all play role (roles >> 2 s) & 3:
+//   PROBE_ROLE_MFMA  iters rounds of 8 v_mfma_f32_32x32x2_f32 on four accumulators (512 matrix cycles per round);
+//   PROBE_ROLE_VALU  iters rounds of 64 v_fma_f32 on four dependent chains.
+// Each wave writes the clock ticks it took (s_memtime around its loop) to ticks[block * 16 + wave].
+__global__ void __launch_bounds__(1024)
+probe_share_kernel(unsigned long long* __restrict__ ticks, float* __restrict__ sink, unsigned roles, int iters)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const unsigned role = (roles >> (2 * (wave >> 2))) & 3u;
+    floatx16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    const float a = lane * 0.001f, b = 1.0f, c1 = 0.5f;
+    float v[4] = {1.f, 2.f, 3.f, 4.f};
+    __syncthreads();
+    const unsigned long long t0 = __builtin_amdgcn_s_memtime();
+    if (role == PROBE_ROLE_MFMA) {
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j & 3], 0, 0, 0);
+        }
+    } else if (role == PROBE_ROLE_VALU) {
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int j = 0; j < 64; ++j) asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(v[j & 3]) : "v"(c1));
+        }
+    }
+    const unsigned long long t1 = __builtin_amdgcn_s_memtime();
+    if (lane == 0) ticks[(size_t)blockIdx.x * 16 + wave] = t1 - t0;
+    float s = v[0] + v[1] + v[2] + v[3];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[j][i];
+    if (s == 123.456f) sink[0] = s;                       // keeps the loops alive; never true
+}
+
 }  // namespace
+
+hipError_t launch_probe_share(unsigned long long* ticks, float* sink, int slots, unsigned roles, int iters, hipStream_t st)
+{
+    if (slots < 1 || slots > 4) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(probe_share_kernel, dim3(PROBE_SHARE_BLOCKS), dim3(256 * slots), 0, st, ticks, sink, roles, iters);
+    return hipGetLastError();
+}
 
 hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st)
 {

@@ -411,8 +411,8 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
     // build's order a fused block comes first only where a time model says it beats the unfused path (heuristic;
     // constants measured on an MI355X, in nanoseconds):
     //   unfused: product flop at 105 Tflop/s + (x + V + M + y) bytes at 5.2 TB/s + 4 launches of 3 us;
-    //   fused:   rounds of 256 workgroups, each its own flop at the rate of one compute unit (328 flop/ns for
-    //            F(2x2), 242 for F(4x4)) + 2 launches.
+    //   fused:   rounds of 256 workgroups, each its own flop at the rate of one compute unit (370 flop/ns for
+    //            F(2x2), 295 for F(4x4)) + 2 launches.
     {
         const int64_t Cp16 = ceil_div(s.C, 16) * 16;
         const int64_t tiles_p = ceil_div(tiles, 32) * 32;
@@ -425,7 +425,7 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             if (!auto_regs && f.acc > vgpr_budget) continue;
             const int64_t Kf = ceil_div(s.K, f.z) * f.z, Cf = ceil_div(s.C, f.alpha) * f.alpha;
             const int64_t nblocks = ceil_div(tiles, f.tb) * (Kf / f.z);
-            const int64_t t_fused = ceil_div(nblocks, kComputeUnits) * (2 * planes * f.tb * f.z * Cf / (m == 2 ? 328 : 242)) + 2 * 3000;
+            const int64_t t_fused = ceil_div(nblocks, kComputeUnits) * (2 * planes * f.tb * f.z * Cf / (m == 2 ? 370 : 295)) + 2 * 3000;
             Candidate c{};
             c.cfg.b = 1; c.cfg.x = m * f.tb; c.cfg.y = m; c.cfg.z = f.z;
             c.cfg.alpha = f.alpha;

@@ -138,6 +138,18 @@ def _check_feasible(s, cfg, lds_bytes, vgpr_budget):
         assert cfg["q_read_elems"] == groups * s["C"] * (x + z)
         assert cfg["q_write_elems"] == s["N"] * s["K"] * P * Q
         return
+    if cfg["path"] == o.PATH_FUSED:
+        # fused Winograd blocks (Sec. 5.3): every plane of a tb x z block in accumulator registers, one per kernel built
+        e = o.WINO_E[s["algo"]]
+        tb, planes = x // e, (e + 2) ** 2
+        assert (e, tb, z, a, T) in ((2, 64, 64, 8, 1024), (4, 32, 64, 4, 768)) and (b, y) == (1, e)
+        assert planes * tb * z == cfg["acc_regs_per_thread"] * T and cfg["acc_regs_per_thread"] <= vgpr_budget
+        assert 2 * 4 * a * planes * (tb + z) <= cfg["lds_bytes_used"] <= (lds_bytes or o.LDS_CU)
+        tiles = s["N"] * -(-P // e) * -(-Q // e)
+        blocks = len(range(0, tiles, tb)) * len(range(0, s["K"], z))
+        assert cfg["q_read_elems"] == blocks * s["C"] * ((e * tb + 2) * (e + 2) + planes * z)
+        assert cfg["q_write_elems"] == s["N"] * s["K"] * P * Q
+        return
     # matrix-core tiles cut K rounded up to whole 32-channel blocks
     Kz = -(-s["K"] // 32) * 32 if cfg["path"] == o.PATH_MFMA else s["K"]
     assert Kz % z == 0 and T in (64, 128, 256, 512, 1024)
