@@ -48,7 +48,15 @@ def pipeline_share(iters=2000):
 
 
 def share_report(rows):
-    lines = ["| waves of one SIMD | launch ms | ticks per instruction, wave by wave |", "|---|---|---|"]
+    lines = ["# How fp32 MFMA waves and VALU waves share one SIMD (one MI355X)", "",
+             "Written by `python -m paper_2012_15667_amd.ceilings --share > profiles/pipeline_share.md` (from the repository root",
+             "on the GPU box).  One launch of 256 workgroups; every SIMD holds the waves listed; an MFMA wave issues 16000",
+             "`v_mfma_f32_32x32x2_f32` (64 matrix cycles each), a VALU wave 128000 `v_fma_f32`; ticks = `s_memtime` counts (core",
+             "clock) per instruction of that wave.  Reading: a wave of MFMAs runs at its full rate whatever runs beside it; a",
+             "VALU wave beside it needs the MFMA wave's whole time plus its own solo time (about (16000 x 64 + 128000 x 5.3) /",
+             "128000 = 13.3 ticks per instruction): plain vector instructions make no progress while another wave of the SIMD",
+             "streams fp32 MFMAs -- the two share one pipeline, and vector work next to matrix work is paid in full.", "",
+             "| waves of one SIMD | launch ms | ticks per instruction, wave by wave |", "|---|---|---|"]
     for name, ms, per in rows:
         lines.append("| %s | %.3f | %s |" % (name, ms, ", ".join("%s %.1f" % (r, t) for r, t in per)))
     return "\n".join(lines)

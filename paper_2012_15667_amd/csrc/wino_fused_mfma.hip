@@ -8,15 +8,19 @@
 //
 // Wave layout.  A 32 x 32 block (32 sub-domains by 32 channels) of one plane is one v_mfma_f32_32x32x2_f32
 // accumulator of 16 registers.  A wave owns one ROW of m+2 planes of one 32 x 32 block, so a compute unit
-// runs (m+2) * blocks light waves (16 for F(2x2) with 2 x 2 blocks) that fill each other's gaps.
+// runs (m+2) * blocks light waves (16 for F(2x2) with 2 x 2 blocks).  What they can hide for each other is memory
+// and LDS latency, not arithmetic: plain VALU instructions and fp32 MFMAs share one pipeline per SIMD, and a wave
+// that streams MFMAs keeps the VALU instructions of the SIMD's other waves waiting, so every vector instruction
+// of the transforms is paid in matrix time and the transform is kept to its additions.
 //
 // This file holds the variant in which a LANE transforms a whole window (used for m = 2, whose 4 x 4 windows
 // are small; wino_fused_rows.hip shares the transform out differently for m = 4).  Per stage the workgroup
-//   - loads the (m+2) x (m+2) input windows of its sub-domains from global memory into registers (issued one
-//     stage ahead; one lane per (sub-domain, channel), the waves 0 .. ALPHA-1 take one channel each), transforms
-//     them (B d B^T) and writes them to LDS as V[channel pair][plane][sub-domain][2];
+//   - loads the (m+2) x (m+2) input windows of its sub-domains from global memory into registers (buffer loads
+//     issued one stage ahead, elements outside the image zero-filled by the hardware's range check; one lane per
+//     (sub-domain, channel), the waves 0 .. ALPHA-1 take one channel each), transforms them (B d B^T) and writes
+//     them to LDS as V[channel pair][plane][sub-domain][2];
 //   - copies the stage's slab of the transformed kernels, U2[channel pair][plane][k][2], to LDS with LDS-direct
-//     loads (issued one stage ahead);
+//     loads (issued one stage ahead: one by every wave, the rest by the waves without a transform task);
 //   - multiplies: per plane and group of four channels one 8-byte LDS read per operand feeds two MFMAs (lane
 //     halves take channel pairs 2j and 2j + 1, so both halves use the same offsets).
 // Two LDS buffers alternate; one barrier per stage.  The output transform  Y = A Pi A^T  is split around an
@@ -91,10 +95,8 @@ __device__ __forceinline__ void mat_vec(const float (&in)[IN], float (&out)[ROWS
 // M: output tile edge.  WT x WK: 32 x 32 blocks of the workgroup along sub-domains and channels (tb = 32 WT,
 // z = 32 WK).  ALPHA: channels per stage, one transform wave each.
 // VEC (pad = 1, W a multiple of M, x aligned to 4 M bytes): a lane loads the M columns under its own
-// sub-domain as one aligned vector per window row and takes the two border columns from its neighbour lanes
-// (the sub-domains left and right of it; a border column outside the image is zero anyway), which replaces
-// (M+2)^2 four-byte loads per window by M+2 wide ones; the first and the last lane of a block, whose
-// neighbours belong to other workgroups, load their outer border column themselves.
+// sub-domain as one aligned vector per window row and the two border columns as single floats, which replaces
+// (M+2)^2 four-byte loads per window by 3 (M+2).
 template <int M, int WT, int WK, int ALPHA, bool VEC>
 __global__ void __launch_bounds__(64 * (M + 2) * WT * WK, 1)
 wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2, float* __restrict__ y, WinoGeom g)

@@ -1,7 +1,9 @@
 // Winograd F(m x m, 3 x 3) fused on the matrix cores (dataflow of Sec. 5.3), "row waves" variant: the workgroup
 // keeps all (m+2)^2 planes of its tb x z block of channel-summation temporaries in accumulator registers, ONE
 // WAVE PER PLANE ROW and 32 x 32 block, so that a compute unit runs 12 to 16 light waves (3 or 4 per SIMD) that
-// hide each other's transform arithmetic, LDS traffic and barriers behind matrix-core work.
+// hide each other's LDS traffic, loads and barriers behind matrix-core work.  (Not the transform arithmetic:
+// plain VALU instructions and fp32 MFMAs share one pipeline per SIMD, so every vector instruction is paid in
+// matrix time -- hence buffer loads whose range check supplies the zero padding, and scalar stage bases.)
 //
 // Every thread takes an equal share of the input transform (step 1 of Sec. 4.3), which runs in two halves
 // through an LDS scratch buffer so that no thread ever holds a whole window:

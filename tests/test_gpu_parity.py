@@ -988,3 +988,28 @@ def test_ceiling_probes(gpu):
     f = ctypes.c_float(0)
     assert L.iolb_probe_hbm_copy(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()), 24, 1, ctypes.byref(f)) == -1
     assert L.iolb_probe_hbm_copy(None, ctypes.c_void_p(dst.data_ptr()), 16, 1, ctypes.byref(f)) == -1
+
+
+def test_pipeline_share_probe(gpu):
+    """A wave of fp32 MFMAs alone issues one every 64 clock ticks (32 x 32 x 2 x 2 flop at 64 flop per cycle and
+    SIMD); the probe reports ticks per slot, rejects bad arguments, and a VALU wave that shares a SIMD with an
+    MFMA wave is never faster than alone."""
+    torch, B = gpu
+    iters = 500
+    ms, ticks = B.probe_pipeline_share([B.PROBE_ROLE_MFMA], iters)
+    assert ms > 0 and len(ticks) == 1 and 60.0 <= ticks[0] / (8 * iters) <= 80.0
+    _, alone = B.probe_pipeline_share([B.PROBE_ROLE_VALU], iters)
+    _, both = B.probe_pipeline_share([B.PROBE_ROLE_MFMA, B.PROBE_ROLE_VALU], iters)
+    assert len(both) == 2 and both[1] >= alone[0]
+    L = B.lib()
+    scratch = torch.zeros(L.iolb_probe_share_scratch_bytes() // 4 + 1, device="cuda", dtype=torch.float32)
+    sp = ctypes.c_void_p(scratch.data_ptr())
+    f = ctypes.c_float(0)
+    t = (ctypes.c_double * 4)()
+    roles = (ctypes.c_int * 4)(0, 1, 0, 0)
+    assert L.iolb_probe_pipeline_share(sp, 5, roles, 10, ctypes.byref(f), t) == -1          # five slots
+    assert L.iolb_probe_pipeline_share(sp, 0, roles, 10, ctypes.byref(f), t) == -1
+    assert L.iolb_probe_pipeline_share(None, 2, roles, 10, ctypes.byref(f), t) == -1
+    assert L.iolb_probe_pipeline_share(sp, 2, roles, 0, ctypes.byref(f), t) == -1
+    bad = (ctypes.c_int * 4)(0, 3, 0, 0)
+    assert L.iolb_probe_pipeline_share(sp, 2, bad, 10, ctypes.byref(f), t) == -1            # unknown role
