@@ -641,6 +641,11 @@ def _wino_candidates(s, P, Q, e, lds_bytes, vgpr_budget, use_f3, auto_regs=True)
     for fe, ftb, fz, falpha, fT, fwm, fwn, flds, facc in FUSED_BLOCKS:
         if fe != e or (lds_bytes and flds > lds_bytes) or (not auto_regs and facc > vgpr_budget):
             continue
+        # byte offsets of a block's windows, counted from its first image, must stay below 2^30; a block of ftb
+        # sub-domains touches at most ftb / (sub-domains per image) + 2 images
+        per_image = (-(-P // e)) * (-(-Q // e))
+        if (-(-ftb // per_image) + 2) * C * s["H"] * s["W"] * 4 >= 1 << 30:
+            continue
         nblocks = (-(-tiles // ftb)) * (-(-K // fz))
         qread = nblocks * C * ((e * ftb + 2) * (e + 2) + n2 * fz)
         first = fused_faster(s, P, Q, e, ftb, fz, falpha)

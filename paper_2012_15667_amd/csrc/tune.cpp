@@ -423,6 +423,10 @@ void winograd_candidates(const iolb_shape& s, int P, int Q, int m, int64_t lds_b
             if (f.m != m) continue;
             if (lds_bytes && f.lds_bytes > lds_bytes) continue;
             if (!auto_regs && f.acc > vgpr_budget) continue;
+            // the kernels address a block's windows with byte offsets below 2^30 from the block's first image; a
+            // block of tb sub-domains touches at most tb / (sub-domains per image) + 2 images
+            const int64_t tpi = (int64_t)ceil_div(P, m) * ceil_div(Q, m);
+            if ((ceil_div(f.tb, tpi) + 2) * (int64_t)s.C * s.H * s.W * 4 >= (1LL << 30)) continue;
             const int64_t Kf = ceil_div(s.K, f.z) * f.z, Cf = ceil_div(s.C, f.alpha) * f.alpha;
             const int64_t nblocks = ceil_div(tiles, f.tb) * (Kf / f.z);
             const int64_t t_fused = ceil_div(nblocks, kComputeUnits) * (2 * planes * f.tb * f.z * Cf / (m == 2 ? 370 : 295)) + 2 * 3000;

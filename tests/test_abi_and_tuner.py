@@ -192,3 +192,18 @@ def test_maximum_tensor_sizes():
         with pytest.raises(B.IolbError) as e:
             B.iolb_tune(bad)
         assert e.value.code == -1
+
+
+def test_fused_blocks_leave_the_domain_where_their_offsets_would_not_fit():
+    """The fused Winograd kernels address a block's input windows with byte offsets below 2^30 from the block's first
+    image (a block touches at most tb / (sub-domains per image) + 2 images): a layer whose images are larger than
+    that gets no fused block, in either implementation, and still gets a tile."""
+    small = _shape(2, 64, 512, 512, 64, 3, 3, 1, 1, algo=o.WINO_F4)       # 3 images of 64 MiB
+    large = _shape(2, 96, 1024, 1024, 64, 3, 3, 1, 1, algo=o.WINO_F4)     # 3 images of 384 MiB
+    for s, has in ((small, True), (large, False)):
+        got = B.iolb_enumerate(B.make_shape(**s), 0, 0, False)
+        want = [c for _, c in sorted(o.candidates(s, use_f3=False), key=lambda kc: kc[0])]
+        assert got == want
+        assert any(t["path"] == o.PATH_FUSED for t in got) == has
+        assert B.iolb_tune(B.make_shape(**s)) == o.tune(s)
+
