@@ -189,11 +189,19 @@ wino_fused_mfma_kernel(const float* __restrict__ x, const float* __restrict__ U2
                 wr[i] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, vrow[i] + vcol[2], 0, 0));
             }
         } else {
+            // (the column parts pass through an empty asm statement so that the n * n sums are made here, stage by
+            // stage, and not kept in n * n registers across the channel loop, where they would spill)
+            unsigned col[n];
+#pragma unroll
+            for (int j = 0; j < n; ++j) {
+                col[j] = vcol[j];
+                asm volatile("" : "+v"(col[j]));
+            }
 #pragma unroll
             for (int i = 0; i < n; ++i)
 #pragma unroll
                 for (int j = 0; j < n; ++j)
-                    win[i][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, vrow[i] + vcol[j], 0, 0));
+                    win[i][j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, vrow[i] + col[j], 0, 0));
         }
     };
     // B d column by column, then (B d) B^T row by row, each row stored as soon as it is complete.  Plain VALU
