@@ -1,4 +1,6 @@
 """The entry point that allocates nothing (conv_direct_noalloc) against conv_direct, through the C ABI."""
+import gc
+
 import numpy as np
 import pytest
 
@@ -14,16 +16,29 @@ def test_noalloc_entry_point_matches_conv_direct_on_two_calls_in_a_row():
     B.lib()
     # two calls in a row, the second with a smaller layer: what the first left in the shared scratch array
     # must not leak into the second
+    first = True
     for (N, C, H, W, K, R, S, stride, pad) in [(4, 40, 28, 28, 96, 3, 3, 1, 1), (2, 12, 14, 14, 32, 3, 3, 1, 1),
                                                (2, 5, 9, 11, 6, 3, 3, 2, 1), (3, 16, 16, 16, 64, 1, 1, 1, 0)]:
         x, w = make_inputs(N, C, H, W, K, R, S, "u11", "he", seed=900 + C)
         xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
         ref = B.conv_direct(xd, wd, stride, pad)
         y = torch.full_like(ref, float("nan"))
-        before = torch.cuda.memory_allocated()
+        if first:
+            # set-up on the first call on a device: the code object with the static array is loaded, its address
+            # looked up; device memory is taken then, not by later calls
+            B.conv_direct_noalloc(xd, wd, stride, pad, y)
+            y.fill_(float("nan"))
+            first = False
+        # nothing may be allocated by the call: neither through torch (its count of allocations made so far, which
+        # frees by the garbage collector do not change) nor behind its back (free device memory does not shrink)
+        gc.collect()
+        torch.cuda.synchronize()
+        allocations = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
+        free_before = torch.cuda.mem_get_info()[0]
         B.conv_direct_noalloc(xd, wd, stride, pad, y)
         torch.cuda.synchronize()
-        assert torch.cuda.memory_allocated() == before
+        assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == allocations
+        assert torch.cuda.mem_get_info()[0] >= free_before
         assert torch.equal(y, ref), (N, C, H, W, K)
 
 
