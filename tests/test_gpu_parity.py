@@ -561,6 +561,22 @@ def test_winograd_other_paddings_match_direct_oracle(gpu, case):
     assert rel_err(y.cpu().numpy(), ref) <= TOL_WINO
 
 
+@pytest.mark.parametrize("case", [(2, 16, 16, 56, 56, 16, 0), (2, 16, 16, 56, 56, 16, 2), (4, 16, 16, 56, 56, 16, 0),
+                                  (4, 16, 16, 57, 55, 16, 2), (2, 3, 9, 7, 5, 33, 0)])
+def test_fused_matrix_core_blocks_with_other_paddings(gpu, case):
+    """Layers whose tuned tile is a fused block (large images, few channels), with paddings other than 1: the window
+    loads of the fused kernels then take their general form (single floats, zero padding from the range check)."""
+    torch, B = gpu
+    m, N, C, H, W, K, pad = case
+    assert B.iolb_tune(B.make_shape(N, C, H, W, K, 3, 3, 1, pad, algo=B.WINO_ALGO[m]))["path"] == B.PATH_FUSED
+    x, w = make_inputs(N, C, H, W, K, 3, 3, "u11", "he", seed=450 + m + pad)
+    ref = conv_ref(x, w, 1, pad)
+    y = B.conv_winograd(torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda(), m, pad=pad)
+    torch.cuda.synchronize()
+    assert tuple(y.shape) == ref.shape
+    assert rel_err(y.cpu().numpy(), ref) <= TOL_WINO
+
+
 def test_winograd_config2_and_config4(gpu):
     for name, m in (("cfg2", 2), ("cfg4", 4)):
         L = CONFIGS[name]
